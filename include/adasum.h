@@ -1,0 +1,206 @@
+/*
+ * libadasum -- the Adasum tree combiner on one AMD MI355X (gfx950).
+ *
+ * Operation (arXiv 2006.02924):
+ *   - two-gradient operator, Section 1 / Section 3:
+ *       Adasum(g1, g2) = (1 - g1.g2 / (2 |g1|^2)) g1 + (1 - g1.g2 / (2 |g2|^2)) g2
+ *   - K gradients: recursive halving, Section 3.4 (second recursion) -- a
+ *     balanced binary tree whose level-0 pairs are workers (2j, 2j+1);
+ *   - the operator's scalars are taken per layer of the fused gradient buffer,
+ *     Section 3.6 (last paragraph) and Section 4.4.3 (boundary bookkeeping);
+ *   - dot products and squared norms: each lane accumulates a short run in fp32,
+ *     everything above a lane's run is summed in fp64 (Section 4.4.1 asks for
+ *     double accumulation).
+ * Reading where the paper is silent: an operand whose squared norm is exactly 0
+ * gets coefficient 1, so Adasum(0, g) = g and Adasum(0, 0) = 0.
+ *
+ * Conventions for every entry point
+ *   - returns ADASUM_OK (0) or a negative ADASUM_ERR_* code; never throws,
+ *     aborts or prints.  All argument validation happens before any device
+ *     work, so the error paths need no GPU.
+ *   - "HOST" / "DEVICE" says where a pointer must live.  DEVICE pointers must be
+ *     16-byte aligned.  The caller owns every buffer it passes; inputs are never
+ *     modified; host arrays are copied during the call and may be freed at return.
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns without synchronising.  Calls that
+ *     share a plan (same K, dtypes, radix and layer table) must be issued on one
+ *     stream or be externally ordered: they share the plan's workspace.
+ *   - results are deterministic: identical inputs give bit-identical outputs
+ *     (no atomics anywhere on the path).
+ */
+#ifndef ADASUM_H
+#define ADASUM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element storage types */
+#define ADASUM_F32  0   /* IEEE binary32 */
+#define ADASUM_BF16 1   /* bfloat16; stores round to nearest even */
+
+/* error codes */
+#define ADASUM_OK                 0
+#define ADASUM_ERR_INVALID_ARG   -1  /* null pointer, K < 1, n_layers < 0, bad layer table, bad option */
+#define ADASUM_ERR_UNSUPPORTED   -2  /* K not a power of two (Algorithm 1 requires one), unknown dtype/radix */
+#define ADASUM_ERR_MISALIGNED    -3  /* a DEVICE pointer is not 16-byte aligned */
+#define ADASUM_ERR_OUT_OF_MEMORY -4  /* device or host allocation failed */
+#define ADASUM_ERR_HIP           -5  /* a HIP call failed; see adasum_last_hip_error() */
+#define ADASUM_ERR_WORKSPACE     -6  /* caller-provided workspace too small or misaligned */
+#define ADASUM_ERR_ALIAS         -7  /* `out` overlaps an input buffer */
+
+/* tree order (Section 3.4 gives both recursions; they give different results) */
+#define ADASUM_ORDER_TREE   0   /* recursive halving -- the one the paper uses in practice */
+#define ADASUM_ORDER_LINEAR 1   /* left-to-right fold */
+
+/*
+ * Options for adasum_reduce_ex.  Zero-initialise, set struct_bytes = sizeof,
+ * then set what differs from the defaults.
+ */
+typedef struct adasum_options {
+    uint32_t struct_bytes;     /* sizeof(adasum_options) as the caller compiled it */
+    int32_t  out_dtype;        /* ADASUM_F32 | ADASUM_BF16; -1 = same as the input dtype */
+    int32_t  radix;            /* how many binary tree levels one pass over the data fuses:
+                                  2 = one level per pass (reduce pass + combine pass per level),
+                                  4 / 8 = two / three levels per pass (the pass computes the
+                                  group's Gram matrix, the tree's scalars follow from it);
+                                  0 = library default.  The result is the same binary tree. */
+    int32_t  order;            /* ADASUM_ORDER_TREE (default) | ADASUM_ORDER_LINEAR */
+    int32_t  use_graph;        /* 1 = replay the level ladder as one hipGraph launch */
+    int32_t  reserved0;
+    void*    workspace;        /* DEVICE, 256-byte aligned, or NULL = library-owned, cached per plan */
+    size_t   workspace_bytes;  /* size of `workspace`; see adasum_workspace_bytes */
+    double*  layer_stats;      /* DEVICE or NULL: n_layers x 2 doubles written per call,
+                                  [l][0] = |Adasum(g_1..g_K)|^2 of layer l (of the fp32 value
+                                  before the output store), [l][1] = sum_i |g_i|^2; their ratio
+                                  is the orthogonality metric of Section 3.6 */
+} adasum_options;
+
+/*
+ * The combiner.  Reduces K per-worker gradients to one, per layer, up the
+ * binary tree (Sections 3, 3.4, 3.6).
+ *
+ *   grads          HOST array of K DEVICE pointers; grads[k] is worker k's flat
+ *                  fused buffer of N = layer_offsets[n_layers] elements of `dtype`
+ *   K              number of workers; a power of two >= 1 (K = 1 copies)
+ *   layer_offsets  HOST, n_layers + 1 entries in element units, [0] = 0,
+ *                  non-decreasing; layer l is [layer_offsets[l], layer_offsets[l+1]);
+ *                  empty layers are allowed; N = 0 is a no-op
+ *   dtype          ADASUM_F32 | ADASUM_BF16: storage type of grads AND of out
+ *   out            DEVICE, N elements of `dtype`; must not overlap any input
+ *   stream         hipStream_t
+ *
+ * Intermediate tree nodes are kept in fp32 whatever the storage type; the only
+ * rounding to bf16 is the final store.  Uses a library-owned workspace cached
+ * per (K, dtype, layer table); the first call with a new shape allocates.
+ */
+int adasum_reduce(const void* const* grads, int K,
+                  const int64_t* layer_offsets, int n_layers,
+                  int dtype, void* out, void* stream);
+
+/* Same operation with options (output dtype, radix, order, caller workspace,
+ * per-layer statistics).  opts == NULL means all defaults. */
+int adasum_reduce_ex(const void* const* grads, int K,
+                     const int64_t* layer_offsets, int n_layers,
+                     int dtype, void* out, const adasum_options* opts, void* stream);
+
+/* Bytes of DEVICE workspace adasum_reduce_ex needs for this problem (intermediate
+ * fp32 tree nodes, per-tile partial sums, coefficient tables).  Host-only. */
+int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
+                           int dtype, const adasum_options* opts, size_t* bytes);
+
+/* ---- the steps of one tree level, exposed so that each can be checked alone ---- */
+
+/*
+ * Step 1 (Algorithm 1, "partial dot products"): per layer, the Gram matrix of R
+ * operands, G[i][j] = x_i . x_j (the pair case R = 2 is the triple
+ * [a.b, a.a, b.b]).
+ *   x      HOST array of R DEVICE pointers (N elements of `dtype` each)
+ *   R      2, 4 or 8
+ *   gram   DEVICE, n_layers x R x R doubles, row-major per layer, symmetric
+ */
+int adasum_group_gram(const void* const* x, int R,
+                      const int64_t* layer_offsets, int n_layers,
+                      int dtype, double* gram, void* stream);
+
+/*
+ * Step 2 (Algorithm 1, "finish dot products" + the scalars of "apply Adasum"):
+ * per layer, the weights w with  tree(x_0..x_{R-1}) = sum_r w_r x_r,  obtained
+ * from the Gram matrix by walking the binary tree over the R leaves bottom-up;
+ * R = 2 gives w = (1 - d/(2 n1), 1 - d/(2 n2)).  fp64 arithmetic, fp32 result.
+ *   gram     DEVICE, n_layers x R x R doubles (as written by adasum_group_gram)
+ *   weights  DEVICE, n_layers x R floats
+ */
+int adasum_group_weights(const double* gram, int R, int n_layers, int order,
+                         float* weights, void* stream);
+
+/*
+ * Step 3 (Algorithm 1, "apply Adasum"): out = sum_r w[layer][r] * x_r element
+ * by element (fp32 fused multiply-adds, one rounding at the store), and in the
+ * same pass the squared norm of the result per layer.
+ *   weights    DEVICE, n_layers x R floats
+ *   out        DEVICE, N elements of out_dtype; may be x[0] itself (in place)
+ *              when out_dtype == dtype, must not overlap any other operand
+ *   sqnorm     DEVICE, n_layers doubles, or NULL
+ */
+int adasum_group_combine(const void* const* x, int R,
+                         const int64_t* layer_offsets, int n_layers,
+                         int dtype, const float* weights,
+                         void* out, int out_dtype, double* sqnorm, void* stream);
+
+/* ---- host-side planning, exposed for inspection and tests (no GPU needed) ---- */
+
+typedef struct adasum_tile {
+    int64_t start;   /* first element (global index into the fused buffer) */
+    int32_t len;     /* 1 .. tile capacity; a tile never crosses a layer boundary */
+    int32_t layer;
+} adasum_tile;
+
+/* Elements one workgroup covers at most (tile boundaries fall on global
+ * multiples of it and on layer boundaries). */
+int adasum_tile_capacity(void);
+
+/* Writes the tile table for a layer table.  *n_tiles receives the number of
+ * tiles; at most `cap` entries are written to `tiles` (tiles may be NULL with
+ * cap = 0 to query the count).  Tiles are ordered by start; empty layers get
+ * no tile. */
+int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers,
+                      adasum_tile* tiles, int64_t cap, int64_t* n_tiles);
+
+/* Writes the radix of every pass for K workers (their product is K), e.g.
+ * K = 64, radix 8 -> {8, 8}; K = 128 -> {8, 8, 2}.  *n_levels receives the
+ * count; at most `cap` entries are written. */
+int adasum_plan_levels(int K, int radix, int* radices, int cap, int* n_levels);
+
+/* ---- per-kernel timing (HIP events on the caller's stream) ---- */
+
+typedef struct adasum_kernel_profile {
+    char     name[48];        /* e.g. "combine<bf16,f32,R=2>" */
+    int64_t  launches;
+    double   total_ms;        /* sum of event-measured durations */
+    double   bytes;           /* algorithmic bytes summed over those launches:
+                                 operands read once + outputs written once */
+} adasum_kernel_profile;
+
+/* on != 0: every kernel launched by adasum_reduce(_ex) is bracketed by a pair
+ * of HIP events on its stream.  Off by default. */
+int adasum_profile_enable(int on);
+/* Synchronises the recorded events, aggregates by kernel name, writes at most
+ * `cap` entries, sets *n to the number of distinct kernels, and clears the log. */
+int adasum_profile_collect(adasum_kernel_profile* out, int cap, int* n);
+
+/* ---- housekeeping ---- */
+const char* adasum_strerror(int code);
+int         adasum_last_hip_error(void);   /* hipError_t of the last failing HIP call in this thread */
+const char* adasum_version(void);
+/* Frees every cached plan and library-owned workspace.  The caller must have
+ * synchronised the streams it used. */
+int adasum_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADASUM_H */

@@ -1,0 +1,648 @@
+// C-ABI layer of libadasum: argument validation, plan cache, the level
+// scheduler that walks the binary tree of Section 3.4 (arXiv 2006.02924) one
+// pass per group of `radix` siblings, and per-kernel event timing.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "adasum_host.h"
+
+namespace adasum {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+#define ADASUM_HIP(call)                                        \
+    do {                                                        \
+        hipError_t e_ = (call);                                 \
+        if (e_ != hipSuccess) {                                 \
+            g_last_hip_error = static_cast<int>(e_);            \
+            return e_ == hipErrorOutOfMemory ? ADASUM_ERR_OUT_OF_MEMORY : ADASUM_ERR_HIP; \
+        }                                                       \
+    } while (0)
+
+#define ADASUM_LAUNCH(expr)                                     \
+    do {                                                        \
+        int e_ = (expr);                                        \
+        if (e_ != 0) {                                          \
+            g_last_hip_error = e_;                              \
+            return ADASUM_ERR_HIP;                              \
+        }                                                       \
+    } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+struct Opts {
+    int out_dtype;
+    int radix;
+    int order;
+    int use_graph;
+    void* workspace;
+    size_t workspace_bytes;
+    double* layer_stats;
+};
+
+int read_opts(const adasum_options* o, int dtype, Opts& r) {
+    r.out_dtype = dtype;
+    r.radix = 0;
+    r.order = ADASUM_ORDER_TREE;
+    r.use_graph = 0;
+    r.workspace = nullptr;
+    r.workspace_bytes = 0;
+    r.layer_stats = nullptr;
+    if (o != nullptr) {
+        if (o->struct_bytes < sizeof(adasum_options)) return ADASUM_ERR_INVALID_ARG;
+        if (o->out_dtype >= 0) r.out_dtype = o->out_dtype;
+        r.radix = o->radix;
+        r.order = o->order;
+        r.use_graph = o->use_graph;
+        r.workspace = o->workspace;
+        r.workspace_bytes = o->workspace_bytes;
+        r.layer_stats = o->layer_stats;
+    }
+    if (r.out_dtype != ADASUM_F32 && r.out_dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8) return ADASUM_ERR_UNSUPPORTED;
+    if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
+    if (r.order == ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;   // scheduler: tree only
+    if (r.workspace != nullptr && (reinterpret_cast<uintptr_t>(r.workspace) & 255u) != 0)
+        return ADASUM_ERR_WORKSPACE;
+    if (r.layer_stats != nullptr && (reinterpret_cast<uintptr_t>(r.layer_stats) & 7u) != 0)
+        return ADASUM_ERR_MISALIGNED;
+    return ADASUM_OK;
+}
+
+// ---- plans -------------------------------------------------------------------
+
+struct Plan {
+    int device = 0;
+    int K = 0;
+    int radix = 0;
+    std::vector<int64_t> offsets;
+    std::vector<adasum_tile> tiles;
+    std::vector<int32_t> layer_tile_begin;
+    std::vector<int> radices;
+    Layout lay;
+    adasum_tile* d_tiles = nullptr;
+    int32_t* d_ltb = nullptr;
+    char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
+
+    ~Plan() {
+        if (d_tiles) (void)hipFree(d_tiles);
+        if (d_ltb) (void)hipFree(d_ltb);
+        if (d_ws) (void)hipFree(d_ws);
+    }
+};
+
+std::mutex g_mutex;
+std::vector<std::unique_ptr<Plan>> g_plans;
+
+int find_or_make_plan(int K, int radix, const int64_t* offsets, int n_layers, Plan** out) {
+    int device = 0;
+    ADASUM_HIP(hipGetDevice(&device));
+    for (auto& p : g_plans) {
+        if (p->device == device && p->K == K && p->radix == radix &&
+            static_cast<int>(p->offsets.size()) == n_layers + 1 &&
+            std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
+            *out = p.get();
+            return ADASUM_OK;
+        }
+    }
+    std::unique_ptr<Plan> p(new (std::nothrow) Plan());
+    if (!p) return ADASUM_ERR_OUT_OF_MEMORY;
+    try {
+        p->device = device;
+        p->K = K;
+        p->radix = radix;
+        p->offsets.assign(offsets, offsets + n_layers + 1);
+        build_tiles(offsets, n_layers, p->tiles, p->layer_tile_begin);
+        int rc = build_levels(K, radix, p->radices);
+        if (rc != ADASUM_OK) return rc;
+        p->lay = make_layout(K, offsets[n_layers], n_layers, static_cast<int64_t>(p->tiles.size()), p->radices);
+    } catch (const std::bad_alloc&) {
+        return ADASUM_ERR_OUT_OF_MEMORY;
+    }
+    if (!p->tiles.empty()) {
+        ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_tiles), p->tiles.size() * sizeof(adasum_tile)));
+        ADASUM_HIP(hipMemcpy(p->d_tiles, p->tiles.data(), p->tiles.size() * sizeof(adasum_tile),
+                             hipMemcpyHostToDevice));
+    }
+    ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_ltb), p->layer_tile_begin.size() * sizeof(int32_t)));
+    ADASUM_HIP(hipMemcpy(p->d_ltb, p->layer_tile_begin.data(), p->layer_tile_begin.size() * sizeof(int32_t),
+                         hipMemcpyHostToDevice));
+    *out = p.get();
+    g_plans.push_back(std::move(p));
+    return ADASUM_OK;
+}
+
+int plan_workspace(Plan* p, const Opts& o, char** ws) {
+    if (o.workspace != nullptr) {
+        if (o.workspace_bytes < p->lay.total) return ADASUM_ERR_WORKSPACE;
+        *ws = static_cast<char*>(o.workspace);
+        return ADASUM_OK;
+    }
+    if (p->d_ws == nullptr && p->lay.total > 0) {
+        ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_ws), p->lay.total));
+    }
+    *ws = p->d_ws;
+    return ADASUM_OK;
+}
+
+// ---- per-kernel timing ---------------------------------------------------------
+
+struct ProfRecord {
+    std::string name;
+    hipEvent_t start, stop;
+    double bytes;
+};
+bool g_profile = false;
+std::vector<ProfRecord> g_records;
+std::vector<hipEvent_t> g_event_pool;
+
+int take_event(hipEvent_t* e) {
+    if (!g_event_pool.empty()) {
+        *e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return ADASUM_OK;
+    }
+    ADASUM_HIP(hipEventCreate(e));
+    return ADASUM_OK;
+}
+
+// Brackets one launch with events when profiling is on.
+struct Timed {
+    bool active = false;
+    ProfRecord rec;
+    hipStream_t st;
+    int begin(const char* name, double bytes, void* stream) {
+        st = static_cast<hipStream_t>(stream);
+        if (!g_profile) return ADASUM_OK;
+        int rc = take_event(&rec.start);
+        if (rc != ADASUM_OK) return rc;
+        rc = take_event(&rec.stop);
+        if (rc != ADASUM_OK) return rc;
+        rec.name = name;
+        rec.bytes = bytes;
+        ADASUM_HIP(hipEventRecord(rec.start, st));
+        active = true;
+        return ADASUM_OK;
+    }
+    int end() {
+        if (!active) return ADASUM_OK;
+        ADASUM_HIP(hipEventRecord(rec.stop, st));
+        g_records.push_back(rec);
+        active = false;
+        return ADASUM_OK;
+    }
+};
+
+#define ADASUM_TIMED(name, bytes, stream, launch_expr)          \
+    do {                                                        \
+        Timed t_;                                               \
+        int rc_ = t_.begin(name, bytes, stream);                \
+        if (rc_ != ADASUM_OK) return rc_;                       \
+        ADASUM_LAUNCH(launch_expr);                             \
+        rc_ = t_.end();                                         \
+        if (rc_ != ADASUM_OK) return rc_;                       \
+    } while (0)
+
+// ---- common validation ---------------------------------------------------------
+
+int check_operands(const void* const* ptrs, int count, int64_t N, int dtype) {
+    if (ptrs == nullptr) return ADASUM_ERR_INVALID_ARG;
+    for (int k = 0; k < count; ++k) {
+        if (ptrs[k] == nullptr && N > 0) return ADASUM_ERR_INVALID_ARG;
+        if (!aligned16(ptrs[k])) return ADASUM_ERR_MISALIGNED;
+    }
+    (void)dtype;
+    return ADASUM_OK;
+}
+
+// ---- the level scheduler -------------------------------------------------------
+
+int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
+    const Layout& lay = p->lay;
+    const int L = lay.n_layers;
+    const int64_t N = lay.N;
+    const int64_t T = lay.n_tiles;
+    char* slots = ws + lay.off_slots;
+    double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
+    double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
+    double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
+    float* weights = reinterpret_cast<float*>(ws + lay.off_weights);
+    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
+    char namebuf[48];
+
+    int nodes = p->K;        // tree nodes alive before this pass
+    int stride = 1;          // slot distance between consecutive alive nodes (passes >= 1)
+    const int n_levels = static_cast<int>(p->radices.size());
+    for (int lv = 0; lv < n_levels; ++lv) {
+        const int R = p->radices[lv];
+        const int groups = nodes / R;
+        const bool first = lv == 0, last = lv == n_levels - 1;
+        const int in_dtype = first ? dtype : ADASUM_F32;
+        const int st_dtype = last ? o.out_dtype : ADASUM_F32;
+        const int np = gram_entries(R, first);
+        const bool want_norm = !last || o.layer_stats != nullptr;
+
+        LevelArgs a;
+        a.tiles = p->d_tiles;
+        a.layer_tile_begin = p->d_ltb;
+        a.n_tiles = T;
+        a.n_layers = L;
+        a.R = R;
+
+        // groups per launch: explicit operand pointers travel by value
+        const int batch = first ? std::max(1, kMaxPack / R) : groups;
+        const double gram_bytes_per_group = static_cast<double>(R) * N * elem_bytes(in_dtype);
+        const double comb_bytes_per_group =
+            static_cast<double>(N) * (static_cast<double>(R) * elem_bytes(in_dtype) + elem_bytes(st_dtype));
+
+        // step 1: partial Gram entries
+        for (int g0 = 0; g0 < groups; g0 += batch) {
+            const int ng = std::min(batch, groups - g0);
+            Operands ops;
+            std::memset(&ops, 0, sizeof(ops));
+            if (first) {
+                ops.use_pack = 1;
+                for (int i = 0; i < ng * R; ++i) ops.pack[i] = grads[g0 * R + i];
+            } else {
+                ops.base = slots;
+                ops.slot_bytes = slot_bytes;
+                ops.stride = stride;
+            }
+            a.n_groups = ng;
+            kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
+            ADASUM_TIMED(namebuf, gram_bytes_per_group * ng, stream,
+                         launch_gram(in_dtype, first, ops, a, partials + static_cast<int64_t>(g0) * np * T, stream));
+        }
+        // step 2: finish the sums, then the tree's scalars
+        a.n_groups = groups;
+        kernel_name("gram_finish", 0, 0, R, first, namebuf, sizeof(namebuf));
+        ADASUM_TIMED(namebuf, 0.0, stream, launch_gram_finish(first, a, partials, normparts, gram, stream));
+        if (first && o.layer_stats != nullptr) {
+            ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, o.layer_stats + 1, 2, stream));
+        }
+        kernel_name("weights", 0, 0, R, first, namebuf, sizeof(namebuf));
+        ADASUM_TIMED(namebuf, 0.0, stream,
+                     launch_weights(gram, R, static_cast<int64_t>(groups) * L, o.order, weights, stream));
+        // step 3: apply
+        for (int g0 = 0; g0 < groups; g0 += batch) {
+            const int ng = std::min(batch, groups - g0);
+            Operands ops;
+            std::memset(&ops, 0, sizeof(ops));
+            if (first) {
+                ops.use_pack = 1;
+                for (int i = 0; i < ng * R; ++i) ops.pack[i] = grads[g0 * R + i];
+            } else {
+                ops.base = slots;
+                ops.slot_bytes = slot_bytes;
+                ops.stride = stride;
+            }
+            Outputs outs;
+            if (last) {
+                outs.base = static_cast<char*>(out);
+                outs.slot_bytes = 0;
+                outs.stride = 0;
+            } else {
+                const int ostride = first ? 1 : R * stride;
+                outs.base = slots + static_cast<long long>(g0) * ostride * slot_bytes;
+                outs.slot_bytes = slot_bytes;
+                outs.stride = ostride;
+            }
+            a.n_groups = ng;
+            kernel_name("combine", in_dtype, st_dtype, R, false, namebuf, sizeof(namebuf));
+            ADASUM_TIMED(namebuf, comb_bytes_per_group * ng, stream,
+                         launch_combine(in_dtype, st_dtype, ops, outs, a,
+                                        weights + static_cast<int64_t>(g0) * L * R,
+                                        want_norm ? normparts + static_cast<int64_t>(g0) * T : nullptr, stream));
+        }
+        stride = first ? 1 : R * stride;
+        nodes = groups;
+    }
+    if (o.layer_stats != nullptr) {
+        LevelArgs a;
+        a.tiles = p->d_tiles;
+        a.layer_tile_begin = p->d_ltb;
+        a.n_tiles = T;
+        a.n_layers = L;
+        a.n_groups = 1;
+        a.R = 1;
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, o.layer_stats, 2, stream));
+    }
+    return ADASUM_OK;
+}
+
+// K = 1: the result is the gradient itself, converted to the output dtype.
+int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
+    const Layout& lay = p->lay;
+    double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
+    LevelArgs a;
+    a.tiles = p->d_tiles;
+    a.layer_tile_begin = p->d_ltb;
+    a.n_tiles = lay.n_tiles;
+    a.n_layers = lay.n_layers;
+    a.n_groups = 1;
+    a.R = 1;
+    Operands ops;
+    std::memset(&ops, 0, sizeof(ops));
+    ops.use_pack = 1;
+    ops.pack[0] = grads[0];
+    Outputs outs;
+    outs.base = static_cast<char*>(out);
+    outs.slot_bytes = 0;
+    outs.stride = 0;
+    char namebuf[48];
+    kernel_name("combine", dtype, o.out_dtype, 1, false, namebuf, sizeof(namebuf));
+    ADASUM_TIMED(namebuf, static_cast<double>(lay.N) * (elem_bytes(dtype) + elem_bytes(o.out_dtype)), stream,
+                 launch_combine(dtype, o.out_dtype, ops, outs, a, nullptr,
+                                o.layer_stats ? normparts : nullptr, stream));
+    if (o.layer_stats != nullptr) {
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, o.layer_stats + 1, 2, stream));
+    }
+    return ADASUM_OK;
+}
+
+int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                void* out, const adasum_options* opts, void* stream) {
+    if (K < 1) return ADASUM_ERR_INVALID_ARG;
+    int rc = check_layer_table(layer_offsets, n_layers);
+    if (rc != ADASUM_OK) return rc;
+    if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    Opts o;
+    rc = read_opts(opts, dtype, o);
+    if (rc != ADASUM_OK) return rc;
+    if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
+    if (K > (1 << 20)) return ADASUM_ERR_UNSUPPORTED;
+    const int64_t N = layer_offsets[n_layers];
+    rc = check_operands(grads, K, N, dtype);
+    if (rc != ADASUM_OK) return rc;
+    if (out == nullptr && N > 0) return ADASUM_ERR_INVALID_ARG;
+    if (!aligned16(out)) return ADASUM_ERR_MISALIGNED;
+    if (N == 0) return ADASUM_OK;
+    const size_t in_bytes = static_cast<size_t>(N) * elem_bytes(dtype);
+    const size_t out_bytes = static_cast<size_t>(N) * elem_bytes(o.out_dtype);
+    for (int k = 0; k < K; ++k)
+        if (overlaps(grads[k], in_bytes, out, out_bytes)) return ADASUM_ERR_ALIAS;
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Plan* p = nullptr;
+    rc = find_or_make_plan(K, o.radix == 0 ? 2 : o.radix, layer_offsets, n_layers, &p);
+    if (rc != ADASUM_OK) return rc;
+    char* ws = nullptr;
+    rc = plan_workspace(p, o, &ws);
+    if (rc != ADASUM_OK) return rc;
+    if (K == 1) return run_copy(p, ws, grads, dtype, out, o, stream);
+    return run_tree(p, ws, grads, dtype, out, o, stream);
+}
+
+}  // namespace
+}  // namespace adasum
+
+using namespace adasum;
+
+extern "C" {
+
+int adasum_reduce(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                  void* out, void* stream) {
+    return reduce_impl(grads, K, layer_offsets, n_layers, dtype, out, nullptr, stream);
+}
+
+int adasum_reduce_ex(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                     void* out, const adasum_options* opts, void* stream) {
+    return reduce_impl(grads, K, layer_offsets, n_layers, dtype, out, opts, stream);
+}
+
+int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                           const adasum_options* opts, size_t* bytes) {
+    if (bytes == nullptr || K < 1) return ADASUM_ERR_INVALID_ARG;
+    int rc = check_layer_table(layer_offsets, n_layers);
+    if (rc != ADASUM_OK) return rc;
+    if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    Opts o;
+    rc = read_opts(opts, dtype, o);
+    if (rc != ADASUM_OK && rc != ADASUM_ERR_WORKSPACE) return rc;
+    try {
+        std::vector<int> radices;
+        rc = build_levels(K, o.radix, radices);
+        if (rc != ADASUM_OK) return rc;
+        std::vector<adasum_tile> tiles;
+        std::vector<int32_t> ltb;
+        build_tiles(layer_offsets, n_layers, tiles, ltb);
+        const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers,
+                                       static_cast<int64_t>(tiles.size()), radices);
+        *bytes = lay.total;
+    } catch (const std::bad_alloc&) {
+        return ADASUM_ERR_OUT_OF_MEMORY;
+    }
+    return ADASUM_OK;
+}
+
+static int step_common(const void* const* x, int R, const int64_t* layer_offsets, int n_layers, int dtype) {
+    if (R != 2 && R != 4 && R != 8) return ADASUM_ERR_UNSUPPORTED;
+    int rc = check_layer_table(layer_offsets, n_layers);
+    if (rc != ADASUM_OK) return rc;
+    if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    return check_operands(x, R, layer_offsets[n_layers], dtype);
+}
+
+int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets, int n_layers, int dtype,
+                      double* gram, void* stream) {
+    int rc = step_common(x, R, layer_offsets, n_layers, dtype);
+    if (rc != ADASUM_OK) return rc;
+    if (gram == nullptr && n_layers > 0) return ADASUM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(gram) & 7u) != 0) return ADASUM_ERR_MISALIGNED;
+    if (n_layers == 0) return ADASUM_OK;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Plan* p = nullptr;
+    rc = find_or_make_plan(R, R, layer_offsets, n_layers, &p);
+    if (rc != ADASUM_OK) return rc;
+    Opts o{};
+    char* ws = nullptr;
+    rc = plan_workspace(p, o, &ws);
+    if (rc != ADASUM_OK) return rc;
+    double* partials = reinterpret_cast<double*>(ws + p->lay.off_partials);
+    LevelArgs a;
+    a.tiles = p->d_tiles;
+    a.layer_tile_begin = p->d_ltb;
+    a.n_tiles = p->lay.n_tiles;
+    a.n_layers = n_layers;
+    a.n_groups = 1;
+    a.R = R;
+    Operands ops;
+    std::memset(&ops, 0, sizeof(ops));
+    ops.use_pack = 1;
+    for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
+    ADASUM_LAUNCH(launch_gram(dtype, true, ops, a, partials, stream));
+    ADASUM_LAUNCH(launch_gram_finish(true, a, partials, nullptr, gram, stream));
+    return ADASUM_OK;
+}
+
+int adasum_group_weights(const double* gram, int R, int n_layers, int order, float* weights, void* stream) {
+    if (R != 2 && R != 4 && R != 8) return ADASUM_ERR_UNSUPPORTED;
+    if (n_layers < 0) return ADASUM_ERR_INVALID_ARG;
+    if (order != ADASUM_ORDER_TREE && order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
+    if ((gram == nullptr || weights == nullptr) && n_layers > 0) return ADASUM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(gram) & 7u) != 0 || (reinterpret_cast<uintptr_t>(weights) & 3u) != 0)
+        return ADASUM_ERR_MISALIGNED;
+    if (n_layers == 0) return ADASUM_OK;
+    ADASUM_LAUNCH(launch_weights(gram, R, n_layers, order, weights, stream));
+    return ADASUM_OK;
+}
+
+int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offsets, int n_layers, int dtype,
+                         const float* weights, void* out, int out_dtype, double* sqnorm, void* stream) {
+    int rc = step_common(x, R, layer_offsets, n_layers, dtype);
+    if (rc != ADASUM_OK) return rc;
+    if (out_dtype != ADASUM_F32 && out_dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    const int64_t N = layer_offsets[n_layers];
+    if ((weights == nullptr && n_layers > 0) || (out == nullptr && N > 0)) return ADASUM_ERR_INVALID_ARG;
+    if (!aligned16(out) || (reinterpret_cast<uintptr_t>(weights) & 3u) != 0 ||
+        (reinterpret_cast<uintptr_t>(sqnorm) & 7u) != 0)
+        return ADASUM_ERR_MISALIGNED;
+    if (n_layers == 0) return ADASUM_OK;
+    const size_t in_bytes = static_cast<size_t>(N) * elem_bytes(dtype);
+    const size_t out_bytes = static_cast<size_t>(N) * elem_bytes(out_dtype);
+    for (int r = 0; r < R; ++r) {
+        if (r == 0 && x[0] == out && dtype == out_dtype) continue;   // in place on operand 0
+        if (N > 0 && overlaps(x[r], in_bytes, out, out_bytes)) return ADASUM_ERR_ALIAS;
+    }
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Plan* p = nullptr;
+    rc = find_or_make_plan(R, R, layer_offsets, n_layers, &p);
+    if (rc != ADASUM_OK) return rc;
+    Opts o{};
+    char* ws = nullptr;
+    rc = plan_workspace(p, o, &ws);
+    if (rc != ADASUM_OK) return rc;
+    double* normparts = reinterpret_cast<double*>(ws + p->lay.off_normparts);
+    LevelArgs a;
+    a.tiles = p->d_tiles;
+    a.layer_tile_begin = p->d_ltb;
+    a.n_tiles = p->lay.n_tiles;
+    a.n_layers = n_layers;
+    a.n_groups = 1;
+    a.R = R;
+    Operands ops;
+    std::memset(&ops, 0, sizeof(ops));
+    ops.use_pack = 1;
+    for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
+    Outputs outs;
+    outs.base = static_cast<char*>(out);
+    outs.slot_bytes = 0;
+    outs.stride = 0;
+    ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, a, weights, sqnorm ? normparts : nullptr, stream));
+    if (sqnorm != nullptr) ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, sqnorm, 1, stream));
+    return ADASUM_OK;
+}
+
+int adasum_tile_capacity(void) { return kTile; }
+
+int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, adasum_tile* tiles, int64_t cap,
+                      int64_t* n_tiles) {
+    if (n_tiles == nullptr || cap < 0 || (tiles == nullptr && cap > 0)) return ADASUM_ERR_INVALID_ARG;
+    int rc = check_layer_table(layer_offsets, n_layers);
+    if (rc != ADASUM_OK) return rc;
+    try {
+        std::vector<adasum_tile> t;
+        std::vector<int32_t> ltb;
+        build_tiles(layer_offsets, n_layers, t, ltb);
+        *n_tiles = static_cast<int64_t>(t.size());
+        const int64_t n = std::min<int64_t>(cap, static_cast<int64_t>(t.size()));
+        for (int64_t i = 0; i < n; ++i) tiles[i] = t[i];
+    } catch (const std::bad_alloc&) {
+        return ADASUM_ERR_OUT_OF_MEMORY;
+    }
+    return ADASUM_OK;
+}
+
+int adasum_plan_levels(int K, int radix, int* radices, int cap, int* n_levels) {
+    if (n_levels == nullptr || cap < 0 || (radices == nullptr && cap > 0)) return ADASUM_ERR_INVALID_ARG;
+    std::vector<int> r;
+    int rc = build_levels(K, radix, r);
+    if (rc != ADASUM_OK) return rc;
+    *n_levels = static_cast<int>(r.size());
+    for (int i = 0; i < std::min<int>(cap, static_cast<int>(r.size())); ++i) radices[i] = r[i];
+    return ADASUM_OK;
+}
+
+int adasum_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_profile = on != 0;
+    return ADASUM_OK;
+}
+
+int adasum_profile_collect(adasum_kernel_profile* out, int cap, int* n) {
+    if (n == nullptr || cap < 0 || (out == nullptr && cap > 0)) return ADASUM_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    std::vector<adasum_kernel_profile> agg;
+    for (auto& r : g_records) {
+        ADASUM_HIP(hipEventSynchronize(r.stop));
+        float ms = 0.f;
+        ADASUM_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+        size_t i = 0;
+        for (; i < agg.size(); ++i)
+            if (r.name == agg[i].name) break;
+        if (i == agg.size()) {
+            adasum_kernel_profile k;
+            std::memset(&k, 0, sizeof(k));
+            std::snprintf(k.name, sizeof(k.name), "%s", r.name.c_str());
+            agg.push_back(k);
+        }
+        agg[i].launches += 1;
+        agg[i].total_ms += ms;
+        agg[i].bytes += r.bytes;
+        g_event_pool.push_back(r.start);
+        g_event_pool.push_back(r.stop);
+    }
+    g_records.clear();
+    *n = static_cast<int>(agg.size());
+    for (int i = 0; i < std::min<int>(cap, *n); ++i) out[i] = agg[i];
+    return ADASUM_OK;
+}
+
+const char* adasum_strerror(int code) {
+    switch (code) {
+        case ADASUM_OK: return "ok";
+        case ADASUM_ERR_INVALID_ARG: return "invalid argument";
+        case ADASUM_ERR_UNSUPPORTED: return "unsupported (K must be a power of two; dtype f32/bf16; radix 2/4/8)";
+        case ADASUM_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
+        case ADASUM_ERR_OUT_OF_MEMORY: return "out of memory";
+        case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";
+        case ADASUM_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
+        case ADASUM_ERR_ALIAS: return "output overlaps an input";
+        default: return "unknown error";
+    }
+}
+
+int adasum_last_hip_error(void) { return g_last_hip_error; }
+
+const char* adasum_version(void) { return "libadasum 0.1.0 (gfx950)"; }
+
+int adasum_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_plans.clear();
+    for (auto& r : g_records) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_records.clear();
+    for (auto e : g_event_pool) (void)hipEventDestroy(e);
+    g_event_pool.clear();
+    return ADASUM_OK;
+}
+
+}  // extern "C"

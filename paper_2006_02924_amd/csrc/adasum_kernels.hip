@@ -1,0 +1,615 @@
+// gfx950 (CDNA4) kernels of the Adasum tree combiner (arXiv 2006.02924).
+//
+// One pass over a group of R sibling tree nodes does what Algorithm 1 does for
+// a pair: "partial dot products" (gram_kernel), "finish dot products"
+// (gram_finish_kernel), the scalars of the Section 3 operator walked up the
+// binary tree of Section 3.4 over the group's R leaves (weights_kernel), and
+// "apply Adasum" (combine_kernel), which also accumulates the squared norm of
+// what it writes so the next pass needs only the cross dot products.
+//
+// The work is HBM-bound streaming: no matrix cores.  Every workgroup owns one
+// tile (at most kTile consecutive elements inside one layer); 64-wide waves
+// issue 16-byte loads that cover 1 KiB of one operand per instruction; loads of
+// several granules are issued before any is consumed so that enough bytes are
+// in flight; partial sums go lane (fp32) -> wave (fp32 shuffles) -> workgroup
+// (fp64 via LDS) -> per-tile fp64 partial in memory; no atomics anywhere.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "adasum_host.h"
+
+namespace adasum {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct bf16_t { unsigned short v; };
+
+template <typename T> struct Traits;
+template <> struct Traits<float>  { static constexpr int VEC = 4; };
+template <> struct Traits<bf16_t> { static constexpr int VEC = 8; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned int hi_aligned) {
+    return __uint_as_float(hi_aligned);
+}
+
+// round to nearest even; NaN stays NaN (quiet), overflow rounds to infinity
+__device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// G consecutive elements of T held as raw 16-byte quads
+template <typename T, int G>
+struct Granule {
+    static constexpr int NQ = G * (int)sizeof(T) / 16;
+    u32x4 q[NQ];
+};
+
+template <typename T, int G>
+__device__ __forceinline__ void load_raw(Granule<T, G>& r, const T* p) {
+    const u32x4* s = reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < Granule<T, G>::NQ; ++i) r.q[i] = s[i];
+}
+
+template <int G>
+__device__ __forceinline__ void unpack(const Granule<float, G>& r, float (&v)[G]) {
+#pragma unroll
+    for (int i = 0; i < G / 4; ++i) {
+        v[4 * i + 0] = __uint_as_float(r.q[i].x);
+        v[4 * i + 1] = __uint_as_float(r.q[i].y);
+        v[4 * i + 2] = __uint_as_float(r.q[i].z);
+        v[4 * i + 3] = __uint_as_float(r.q[i].w);
+    }
+}
+
+__device__ __forceinline__ void unpack(const Granule<bf16_t, 8>& r, float (&v)[8]) {
+    const unsigned int w[4] = {r.q[0].x, r.q[0].y, r.q[0].z, r.q[0].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i + 0] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+template <int G>
+__device__ __forceinline__ void store_granule(float* p, const float (&v)[G]) {
+    u32x4* d = reinterpret_cast<u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < G / 4; ++i) {
+        u32x4 q;
+        q.x = __float_as_uint(v[4 * i + 0]);
+        q.y = __float_as_uint(v[4 * i + 1]);
+        q.z = __float_as_uint(v[4 * i + 2]);
+        q.w = __float_as_uint(v[4 * i + 3]);
+        d[i] = q;
+    }
+}
+
+__device__ __forceinline__ void store_granule(bf16_t* p, const float (&v)[8]) {
+    u32x4 q;
+    q.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+    q.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+    q.z = f32_to_bf16_rne(v[4]) | (f32_to_bf16_rne(v[5]) << 16);
+    q.w = f32_to_bf16_rne(v[6]) | (f32_to_bf16_rne(v[7]) << 16);
+    *reinterpret_cast<u32x4*>(p) = q;
+}
+
+__device__ __forceinline__ float load_elem(const float* p) { return *p; }
+__device__ __forceinline__ float load_elem(const bf16_t* p) {
+    return __uint_as_float(static_cast<unsigned int>(p->v) << 16);
+}
+__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(bf16_t* p, float v) {
+    p->v = static_cast<unsigned short>(f32_to_bf16_rne(v));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+template <int R>
+__device__ __forceinline__ const void* operand_ptr(const Operands& ops, int g, int r) {
+    const int idx = g * R + r;
+    if (ops.use_pack) return ops.pack[idx];
+    return ops.base + static_cast<long long>(idx) * ops.stride * ops.slot_bytes;
+}
+
+// The tile split every kernel uses: [start, hs) scalar head, [bs, be) whole
+// granules aligned to G elements of the global index, [ts, end) scalar tail.
+struct Split {
+    long long start, end, bs, hs, ts;
+    int ng, nh, nt;
+};
+
+template <int G>
+__device__ __forceinline__ Split split_tile(const adasum_tile& t) {
+    Split s;
+    s.start = t.start;
+    s.end = t.start + t.len;
+    s.bs = (s.start + (G - 1)) / G * G;
+    const long long be = s.end / G * G;
+    s.hs = s.bs < s.end ? s.bs : s.end;
+    s.ts = be > s.hs ? be : s.hs;
+    s.ng = be > s.bs ? static_cast<int>((be - s.bs) / G) : 0;
+    s.nh = static_cast<int>(s.hs - s.start);
+    s.nt = static_cast<int>(s.end - s.ts);
+    return s;
+}
+
+// ---------------------------------------------------------------------------
+// Step 1: per-tile partial Gram entries of R operands.
+// Entry order: for i < R, for j from (DIAG ? i : i+1) to R-1.
+// partials[(group * NP + entry) * n_tiles + tile]
+// ---------------------------------------------------------------------------
+template <typename T, int R, bool DIAG>
+__global__ void __launch_bounds__(kThreads)
+gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_tiles,
+            double* __restrict__ partials) {
+    constexpr int G = Traits<T>::VEC;
+    constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
+    constexpr int ITERS = kTile / G / kThreads;
+    constexpr int U = (R * (G * (int)sizeof(T) / 16) >= 8) ? 1 : (8 / R);   // granule-steps loaded ahead
+    static_assert(ITERS % U == 0, "unroll must divide the trip count");
+
+    const int tid = threadIdx.x;
+    const int tile_id = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_tiles));
+    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_tiles));
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
+
+    const T* x[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) x[r] = static_cast<const T*>(operand_ptr<R>(ops, g, r));
+
+    float acc[NP];
+#pragma unroll
+    for (int e = 0; e < NP; ++e) acc[e] = 0.f;
+
+    auto consume = [&](const Granule<T, G> (&raw)[R]) {
+        float v[R][G];
+#pragma unroll
+        for (int r = 0; r < R; ++r) unpack(raw[r], v[r]);
+        int e = 0;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+#pragma unroll
+            for (int j = (DIAG ? i : i + 1); j < R; ++j) {
+#pragma unroll
+                for (int k = 0; k < G; ++k) acc[e] = __builtin_fmaf(v[i][k], v[j][k], acc[e]);
+                ++e;
+            }
+        }
+    };
+
+    if (s.ng == kTile / G) {
+        for (int it0 = 0; it0 < ITERS; it0 += U) {
+            Granule<T, G> raw[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long idx = s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G;
+#pragma unroll
+                for (int r = 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) consume(raw[u]);
+        }
+    } else {
+        for (int j = tid; j < s.ng; j += kThreads) {
+            Granule<T, G> raw[R];
+            const long long idx = s.bs + static_cast<long long>(j) * G;
+#pragma unroll
+            for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+            consume(raw);
+        }
+    }
+    if (tid < s.nh + s.nt) {
+        const long long idx = tid < s.nh ? s.start + tid : s.ts + (tid - s.nh);
+        float v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = load_elem(x[r] + idx);
+        int e = 0;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+#pragma unroll
+            for (int j = (DIAG ? i : i + 1); j < R; ++j) {
+                acc[e] = __builtin_fmaf(v[i], v[j], acc[e]);
+                ++e;
+            }
+        }
+    }
+
+    __shared__ double sh[kThreads / 64][NP];
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int e = 0; e < NP; ++e) {
+        const float w = wave_sum(acc[e]);
+        if (lane == 0) sh[wave][e] = static_cast<double>(w);
+    }
+    __syncthreads();
+    if (tid < NP) {
+        double tot = sh[0][tid];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) tot += sh[w][tid];
+        partials[(static_cast<long long>(g) * NP + tid) * n_tiles + tile_id] = tot;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Step 2a: sum the per-tile partials of every (group, layer) into a full
+// symmetric R x R Gram matrix, in a fixed order.  When !DIAG the diagonal comes
+// from the squared norms the previous combine left per (node, tile).
+// One workgroup per (group, layer).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double block_sum(double v, double* sh) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = wave_sum(v);
+    __syncthreads();                 // sh may still be read from the previous call
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    double tot = sh[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) tot += sh[w];
+    return tot;
+}
+
+template <int R, bool DIAG>
+__global__ void __launch_bounds__(kThreads)
+gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts,
+                   const int32_t* __restrict__ layer_tile_begin, int n_tiles, int n_layers,
+                   double* __restrict__ gram) {
+    constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
+    __shared__ double sh[kThreads / 64];
+    const int tid = threadIdx.x;
+    const int l = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_layers));
+    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_layers));
+    const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
+    double* out = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
+
+    int e = 0;
+    for (int i = 0; i < R; ++i) {
+        for (int j = (DIAG ? i : i + 1); j < R; ++j) {
+            const double* row = partials + (static_cast<long long>(g) * NP + e) * n_tiles;
+            double v = 0.0;
+            for (int t = tb + tid; t < te; t += kThreads) v += row[t];
+            v = block_sum(v, sh);
+            if (tid == 0) {
+                out[i * R + j] = v;
+                out[j * R + i] = v;
+            }
+            ++e;
+        }
+    }
+    if (!DIAG) {
+        for (int i = 0; i < R; ++i) {
+            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_tiles;
+            double v = 0.0;
+            for (int t = tb + tid; t < te; t += kThreads) v += row[t];
+            v = block_sum(v, sh);
+            if (tid == 0) out[i * R + i] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Step 2b: Gram matrix -> weights of the tree over R leaves.
+// Every node of the tree is a combination of its leaves, node = sum_p w_p x_p;
+// for two sibling nodes A and B the operator of Section 3 needs
+//   d = A.B = sum_{p in A, q in B} w_p w_q G_pq,  n1 = |A|^2,  n2 = |B|^2
+// and scales A's weights by 1 - d/(2 n1) and B's by 1 - d/(2 n2).  A zero
+// squared norm gives coefficient 1.  fp64 throughout, fp32 at the end.
+// ---------------------------------------------------------------------------
+template <int R>
+__device__ __forceinline__ void merge_nodes(const double* G, double (&w)[R], int a0, int a1, int b0, int b1) {
+    double d = 0.0, n1 = 0.0, n2 = 0.0;
+    for (int p = a0; p < a1; ++p)
+        for (int q = a0; q < a1; ++q) n1 += w[p] * w[q] * G[p * R + q];
+    for (int p = b0; p < b1; ++p)
+        for (int q = b0; q < b1; ++q) n2 += w[p] * w[q] * G[p * R + q];
+    for (int p = a0; p < a1; ++p)
+        for (int q = b0; q < b1; ++q) d += w[p] * w[q] * G[p * R + q];
+    const double ca = n1 > 0.0 ? 1.0 - d / (2.0 * n1) : 1.0;
+    const double cb = n2 > 0.0 ? 1.0 - d / (2.0 * n2) : 1.0;
+    for (int p = a0; p < a1; ++p) w[p] *= ca;
+    for (int q = b0; q < b1; ++q) w[q] *= cb;
+}
+
+template <int R>
+__global__ void __launch_bounds__(64)
+weights_kernel(const double* __restrict__ gram, long long n_items, int order, float* __restrict__ weights) {
+    const long long item = static_cast<long long>(blockIdx.x) * 64 + threadIdx.x;
+    if (item >= n_items) return;
+    const double* G = gram + item * (R * R);
+    double w[R];
+    for (int p = 0; p < R; ++p) w[p] = 1.0;
+    if (order == ADASUM_ORDER_LINEAR) {
+        for (int k = 1; k < R; ++k) merge_nodes<R>(G, w, 0, k, k, k + 1);
+    } else {
+        for (int span = 1; span < R; span *= 2)
+            for (int j = 0; j < R; j += 2 * span) merge_nodes<R>(G, w, j, j + span, j + span, j + 2 * span);
+    }
+    for (int p = 0; p < R; ++p) weights[item * R + p] = static_cast<float>(w[p]);
+}
+
+// ---------------------------------------------------------------------------
+// Step 3: out = sum_r w_r x_r per element, squared norm of the result per tile.
+// normparts[group * n_tiles + tile].  `weights == nullptr` means unit weights.
+// ---------------------------------------------------------------------------
+template <typename TI, typename TO, int R>
+__global__ void __launch_bounds__(kThreads)
+combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
+               int n_tiles, int n_layers, const float* __restrict__ weights,
+               double* __restrict__ normparts) {
+    constexpr int G = (sizeof(TI) == 2 || sizeof(TO) == 2) ? 8 : 4;
+    constexpr int ITERS = kTile / G / kThreads;
+    constexpr int NQ = Granule<TI, G>::NQ;
+    constexpr int U = (R * NQ >= 8) ? 1 : (8 / (R * NQ));
+    static_assert(ITERS % U == 0, "unroll must divide the trip count");
+
+    const int tid = threadIdx.x;
+    const int tile_id = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_tiles));
+    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_tiles));
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
+
+    const TI* x[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
+    TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
+
+    float w[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        w[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0f;
+
+    float nacc = 0.f;
+
+    auto emit = [&](const Granule<TI, G> (&raw)[R], long long idx) {
+        float z[G];
+        {
+            float v[G];
+            unpack(raw[0], v);
+#pragma unroll
+            for (int k = 0; k < G; ++k) z[k] = w[0] * v[k];
+        }
+#pragma unroll
+        for (int r = 1; r < R; ++r) {
+            float v[G];
+            unpack(raw[r], v);
+#pragma unroll
+            for (int k = 0; k < G; ++k) z[k] = __builtin_fmaf(w[r], v[k], z[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < G; ++k) nacc = __builtin_fmaf(z[k], z[k], nacc);
+        store_granule(out + idx, z);
+    };
+
+    if (s.ng == kTile / G) {
+        for (int it0 = 0; it0 < ITERS; it0 += U) {
+            Granule<TI, G> raw[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long idx = s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G;
+#pragma unroll
+                for (int r = 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const long long idx = s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G;
+                emit(raw[u], idx);
+            }
+        }
+    } else {
+        for (int j = tid; j < s.ng; j += kThreads) {
+            Granule<TI, G> raw[R];
+            const long long idx = s.bs + static_cast<long long>(j) * G;
+#pragma unroll
+            for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+            emit(raw, idx);
+        }
+    }
+    if (tid < s.nh + s.nt) {
+        const long long idx = tid < s.nh ? s.start + tid : s.ts + (tid - s.nh);
+        float z = w[0] * load_elem(x[0] + idx);
+#pragma unroll
+        for (int r = 1; r < R; ++r) z = __builtin_fmaf(w[r], load_elem(x[r] + idx), z);
+        nacc = __builtin_fmaf(z, z, nacc);
+        store_elem(out + idx, z);
+    }
+
+    if (normparts != nullptr) {
+        __shared__ double sh[kThreads / 64];
+        const int lane = tid & 63, wave = tid >> 6;
+        const float ws = wave_sum(nacc);
+        if (lane == 0) sh[wave] = static_cast<double>(ws);
+        __syncthreads();
+        if (tid == 0) {
+            double tot = sh[0];
+#pragma unroll
+            for (int k = 1; k < kThreads / 64; ++k) tot += sh[k];
+            normparts[static_cast<long long>(g) * n_tiles + tile_id] = tot;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-layer statistics helpers (orthogonality metric of Section 3.6).
+// ---------------------------------------------------------------------------
+// out[l * out_stride] = sum over rows and the tiles of layer l of parts[row][tile]
+__global__ void __launch_bounds__(kThreads)
+layer_sums_kernel(const double* __restrict__ parts, int n_rows,
+                  const int32_t* __restrict__ layer_tile_begin, int n_tiles,
+                  double* __restrict__ out, int out_stride) {
+    __shared__ double sh[kThreads / 64];
+    const int l = blockIdx.x;
+    const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
+    double v = 0.0;
+    for (int r = 0; r < n_rows; ++r) {
+        const double* row = parts + static_cast<long long>(r) * n_tiles;
+        for (int t = tb + threadIdx.x; t < te; t += kThreads) v += row[t];
+    }
+    v = block_sum(v, sh);
+    if (threadIdx.x == 0) out[static_cast<long long>(l) * out_stride] = v;
+}
+
+// out[l * out_stride] = sum over groups of trace(gram[group][l])
+__global__ void __launch_bounds__(64)
+trace_sums_kernel(const double* __restrict__ gram, int R, int n_groups, int n_layers,
+                  double* __restrict__ out, int out_stride) {
+    const int l = blockIdx.x * 64 + threadIdx.x;
+    if (l >= n_layers) return;
+    double v = 0.0;
+    for (int g = 0; g < n_groups; ++g) {
+        const double* G = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
+        for (int i = 0; i < R; ++i) v += G[i * R + i];
+    }
+    out[static_cast<long long>(l) * out_stride] = v;
+}
+
+inline int check_launch() { return static_cast<int>(hipGetLastError()); }
+
+inline bool grid_fits(long long blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
+
+template <typename T, bool DIAG>
+int launch_gram_r(const Operands& ops, const LevelArgs& a, double* partials, hipStream_t st) {
+    const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups);
+    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const int nt = static_cast<int>(a.n_tiles);
+    switch (a.R) {
+        case 2: hipLaunchKernelGGL((gram_kernel<T, 2, DIAG>), grid, block, 0, st, ops, a.tiles, nt, partials); break;
+        case 4: hipLaunchKernelGGL((gram_kernel<T, 4, DIAG>), grid, block, 0, st, ops, a.tiles, nt, partials); break;
+        case 8: hipLaunchKernelGGL((gram_kernel<T, 8, DIAG>), grid, block, 0, st, ops, a.tiles, nt, partials); break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+    return check_launch();
+}
+
+template <typename TI, typename TO>
+int launch_combine_r(const Operands& ops, const Outputs& outs, const LevelArgs& a, const float* weights,
+                     double* normparts, hipStream_t st) {
+    const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups);
+    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const int nt = static_cast<int>(a.n_tiles);
+#define ADASUM_COMBINE(RR)                                                                           \
+    hipLaunchKernelGGL((combine_kernel<TI, TO, RR>), grid, block, 0, st, ops, outs, a.tiles, nt,     \
+                       a.n_layers, weights, normparts)
+    switch (a.R) {
+        case 1: ADASUM_COMBINE(1); break;
+        case 2: ADASUM_COMBINE(2); break;
+        case 4: ADASUM_COMBINE(4); break;
+        case 8: ADASUM_COMBINE(8); break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+#undef ADASUM_COMBINE
+    return check_launch();
+}
+
+}  // namespace
+
+int launch_gram(int dtype, bool diag, const Operands& ops, const LevelArgs& a, double* partials, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_tiles == 0 || a.n_groups == 0) return 0;
+    if (dtype == ADASUM_BF16) {
+        return diag ? launch_gram_r<bf16_t, true>(ops, a, partials, st)
+                    : launch_gram_r<bf16_t, false>(ops, a, partials, st);
+    }
+    return diag ? launch_gram_r<float, true>(ops, a, partials, st)
+                : launch_gram_r<float, false>(ops, a, partials, st);
+}
+
+int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials, const double* normparts,
+                       double* gram, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const long long blocks = static_cast<long long>(a.n_groups) * a.n_layers;
+    if (blocks == 0) return 0;
+    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const int nt = static_cast<int>(a.n_tiles);
+#define ADASUM_FINISH(RR, DD)                                                                      \
+    hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
+                       a.layer_tile_begin, nt, a.n_layers, gram)
+    switch (a.R) {
+        case 2: if (diag) ADASUM_FINISH(2, true); else ADASUM_FINISH(2, false); break;
+        case 4: if (diag) ADASUM_FINISH(4, true); else ADASUM_FINISH(4, false); break;
+        case 8: if (diag) ADASUM_FINISH(8, true); else ADASUM_FINISH(8, false); break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+#undef ADASUM_FINISH
+    return check_launch();
+}
+
+int launch_weights(const double* gram, int R, int64_t n_items, int order, float* weights, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_items == 0) return 0;
+    const long long blocks = (n_items + 63) / 64;
+    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(64);
+    const long long n = n_items;
+    switch (R) {
+        case 2: hipLaunchKernelGGL((weights_kernel<2>), grid, block, 0, st, gram, n, order, weights); break;
+        case 4: hipLaunchKernelGGL((weights_kernel<4>), grid, block, 0, st, gram, n, order, weights); break;
+        case 8: hipLaunchKernelGGL((weights_kernel<8>), grid, block, 0, st, gram, n, order, weights); break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+    return check_launch();
+}
+
+int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const LevelArgs& a,
+                   const float* weights, double* normparts, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_tiles == 0 || a.n_groups == 0) return 0;
+    if (dtype == ADASUM_BF16) {
+        return out_dtype == ADASUM_BF16 ? launch_combine_r<bf16_t, bf16_t>(ops, out, a, weights, normparts, st)
+                                        : launch_combine_r<bf16_t, float>(ops, out, a, weights, normparts, st);
+    }
+    return out_dtype == ADASUM_BF16 ? launch_combine_r<float, bf16_t>(ops, out, a, weights, normparts, st)
+                                    : launch_combine_r<float, float>(ops, out, a, weights, normparts, st);
+}
+
+int launch_layer_sums(const double* parts, int n_rows, const LevelArgs& a, double* layer_sum, int out_stride,
+                      void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_layers == 0) return 0;
+    hipLaunchKernelGGL(layer_sums_kernel, dim3(a.n_layers), dim3(kThreads), 0, st, parts, n_rows,
+                       a.layer_tile_begin, static_cast<int>(a.n_tiles), layer_sum, out_stride);
+    return check_launch();
+}
+
+int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, double* out, int out_stride,
+                      void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_layers == 0) return 0;
+    hipLaunchKernelGGL(trace_sums_kernel, dim3((n_layers + 63) / 64), dim3(64), 0, st, gram, R, n_groups,
+                       n_layers, out, out_stride);
+    return check_launch();
+}
+
+const char* kernel_name(const char* kind, int dtype, int out_dtype, int R, bool diag, char* buf, size_t n) {
+    const char* in = dtype == ADASUM_BF16 ? "bf16" : "f32";
+    const char* out = out_dtype == ADASUM_BF16 ? "bf16" : "f32";
+    if (std::strcmp(kind, "gram") == 0) {
+        std::snprintf(buf, n, "gram<%s,R=%d,%s>", in, R, diag ? "diag" : "offdiag");
+    } else if (std::strcmp(kind, "combine") == 0) {
+        std::snprintf(buf, n, "combine<%s,%s,R=%d>", in, out, R);
+    } else {
+        std::snprintf(buf, n, "%s<R=%d>", kind, R);
+    }
+    return buf;
+}
+
+}  // namespace adasum

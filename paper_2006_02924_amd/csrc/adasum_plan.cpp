@@ -1,0 +1,96 @@
+// Host-side planning for the Adasum tree combiner: layer-table validation, the
+// tile table (the bookkeeping of tensor boundaries inside the fused buffer,
+// Section 4.4.3 of arXiv 2006.02924), the pass schedule over the binary tree of
+// Section 3.4, and the device workspace layout.  Pure C++, no GPU calls.
+#include "adasum_host.h"
+
+#include <algorithm>
+
+namespace adasum {
+
+int check_layer_table(const int64_t* layer_offsets, int n_layers) {
+    if (n_layers < 0) return ADASUM_ERR_INVALID_ARG;
+    if (layer_offsets == nullptr) return ADASUM_ERR_INVALID_ARG;
+    if (layer_offsets[0] != 0) return ADASUM_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l) {
+        if (layer_offsets[l + 1] < layer_offsets[l]) return ADASUM_ERR_INVALID_ARG;
+    }
+    return ADASUM_OK;
+}
+
+void build_tiles(const int64_t* layer_offsets, int n_layers,
+                 std::vector<adasum_tile>& tiles, std::vector<int32_t>& layer_tile_begin) {
+    tiles.clear();
+    layer_tile_begin.assign(static_cast<size_t>(n_layers) + 1, 0);
+    for (int l = 0; l < n_layers; ++l) {
+        layer_tile_begin[l] = static_cast<int32_t>(tiles.size());
+        int64_t pos = layer_offsets[l];
+        const int64_t end = layer_offsets[l + 1];
+        while (pos < end) {
+            // next global multiple of kTile strictly above pos, clipped to the layer
+            int64_t stop = (pos / kTile + 1) * static_cast<int64_t>(kTile);
+            if (stop > end) stop = end;
+            adasum_tile t;
+            t.start = pos;
+            t.len = static_cast<int32_t>(stop - pos);
+            t.layer = l;
+            tiles.push_back(t);
+            pos = stop;
+        }
+    }
+    layer_tile_begin[n_layers] = static_cast<int32_t>(tiles.size());
+}
+
+int build_levels(int K, int radix, std::vector<int>& radices) {
+    radices.clear();
+    if (K < 1) return ADASUM_ERR_INVALID_ARG;
+    if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
+    if (radix == 0) radix = 2;
+    if (radix != 2 && radix != 4 && radix != 8) return ADASUM_ERR_UNSUPPORTED;
+    int rest = K;
+    while (rest > 1) {
+        int r = std::min(rest, radix);
+        radices.push_back(r);
+        rest /= r;
+    }
+    return ADASUM_OK;
+}
+
+Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, const std::vector<int>& radices) {
+    Layout lay;
+    lay.N = N;
+    lay.n_tiles = n_tiles;
+    lay.n_layers = n_layers;
+    lay.slot_elems = static_cast<int64_t>(align_up(static_cast<size_t>(N), 64));
+    // nodes written by the first pass, unless that pass is already the root
+    lay.n_slots = radices.size() > 1 ? K / radices[0] : 0;
+
+    size_t max_partials = 0, max_gram = 0, max_weights = 0, max_nodes = 1;
+    int groups = K;
+    for (size_t lv = 0; lv < radices.size(); ++lv) {
+        const int R = radices[lv];
+        groups /= R;
+        const size_t np = static_cast<size_t>(gram_entries(R, lv == 0));
+        max_partials = std::max(max_partials, static_cast<size_t>(groups) * np * static_cast<size_t>(n_tiles));
+        max_gram = std::max(max_gram, static_cast<size_t>(groups) * n_layers * R * R);
+        max_weights = std::max(max_weights, static_cast<size_t>(groups) * n_layers * R);
+        max_nodes = std::max(max_nodes, static_cast<size_t>(groups));
+    }
+    size_t off = 0;
+    lay.off_slots = off;
+    off = align_up(off + static_cast<size_t>(lay.n_slots) * lay.slot_elems * sizeof(float), 256);
+    lay.off_partials = off;
+    off = align_up(off + max_partials * sizeof(double), 256);
+    lay.off_normparts = off;
+    off = align_up(off + max_nodes * static_cast<size_t>(n_tiles) * sizeof(double), 256);
+    lay.off_gram = off;
+    off = align_up(off + max_gram * sizeof(double), 256);
+    lay.off_weights = off;
+    off = align_up(off + max_weights * sizeof(float), 256);
+    lay.off_leafnorm = off;
+    off = align_up(off + static_cast<size_t>(n_layers) * sizeof(double), 256);
+    lay.total = off;
+    return lay;
+}
+
+}  // namespace adasum

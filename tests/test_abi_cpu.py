@@ -1,0 +1,126 @@
+"""The C-ABI library loads, exports what include/adasum.h declares, and rejects
+bad arguments before touching a device (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2006_02924_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "adasum.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adasum_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_version_and_strerror(lib):
+    assert b"libadasum" in lib.adasum_version()
+    for code in range(0, -8, -1):
+        assert lib.adasum_strerror(code)
+    assert lib.adasum_strerror(-99) == b"unknown error"
+
+
+def _call_reduce(lib, ptrs, K, offs, dtype, out, opts=None):
+    arr = (C.c_void_p * max(1, len(ptrs)))(*ptrs) if ptrs is not None else None
+    o = (C.c_int64 * len(offs))(*offs) if offs is not None else None
+    L = len(offs) - 1 if offs is not None else 0
+    if opts is None:
+        return lib.adasum_reduce(arr, K, o, L, dtype, out, None)
+    return lib.adasum_reduce_ex(arr, K, o, L, dtype, out, C.byref(opts), None)
+
+
+def _opts(**kw):
+    o = B.Options()
+    o.struct_bytes = C.sizeof(B.Options)
+    o.out_dtype = -1
+    for k, v in kw.items():
+        setattr(o, k, v)
+    return o
+
+
+def test_reduce_rejects_bad_arguments(lib):
+    good = [0x1000, 0x2000, 0x3000, 0x4000]
+    offs = [0, 10, 30]
+    assert _call_reduce(lib, None, 4, offs, B.F32, 0x9000) == B.ERR_INVALID_ARG
+    assert _call_reduce(lib, good, 0, offs, B.F32, 0x9000) == B.ERR_INVALID_ARG
+    assert _call_reduce(lib, good, 4, None, B.F32, 0x9000) == B.ERR_INVALID_ARG
+    assert _call_reduce(lib, good, 4, [1, 10, 30], B.F32, 0x9000) == B.ERR_INVALID_ARG
+    assert _call_reduce(lib, good, 4, [0, 30, 10], B.F32, 0x9000) == B.ERR_INVALID_ARG
+    assert _call_reduce(lib, good, 4, offs, 7, 0x9000) == B.ERR_UNSUPPORTED
+    # Algorithm 1 requires a power-of-two number of workers
+    assert _call_reduce(lib, good[:3], 3, offs, B.F32, 0x9000) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, [0x1000, 0x2004, 0x3000, 0x4000], 4, offs, B.F32, 0x9000) == B.ERR_MISALIGNED
+    assert _call_reduce(lib, good, 4, offs, B.F32, 0x9008) == B.ERR_MISALIGNED
+    assert _call_reduce(lib, [0x1000, 0, 0x3000, 0x4000], 4, offs, B.F32, 0x9000) == B.ERR_INVALID_ARG
+    assert _call_reduce(lib, good, 4, offs, B.F32, None) == B.ERR_INVALID_ARG
+    # out overlapping worker 1's buffer (30 fp32 = 120 bytes from 0x2000)
+    assert _call_reduce(lib, good, 4, offs, B.F32, 0x2040) == B.ERR_ALIAS
+
+
+def test_empty_problem_is_a_no_op(lib):
+    assert _call_reduce(lib, [0x1000, 0x2000], 2, [0], B.F32, 0x9000) == B.OK
+    assert _call_reduce(lib, [0x1000, 0x2000], 2, [0, 0, 0], B.BF16, 0x9000) == B.OK
+    assert _call_reduce(lib, [0, 0], 2, [0, 0], B.BF16, None) == B.OK
+
+
+def test_options_validation(lib):
+    good = [0x1000, 0x2000]
+    offs = [0, 8]
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(out_dtype=5)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(radix=3)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(order=9)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(workspace=0x10010, workspace_bytes=1 << 20)) \
+        == B.ERR_WORKSPACE
+    bad = _opts()
+    bad.struct_bytes = 8
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, bad) == B.ERR_INVALID_ARG
+
+
+def test_step_entry_points_validate(lib):
+    offs = (C.c_int64 * 3)(0, 10, 30)
+    x = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert lib.adasum_group_gram(x, 3, offs, 2, B.F32, 0x9000, None) == B.ERR_UNSUPPORTED
+    assert lib.adasum_group_gram(x, 2, offs, 2, 9, 0x9000, None) == B.ERR_UNSUPPORTED
+    assert lib.adasum_group_gram(x, 2, offs, 2, B.F32, None, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_group_gram(None, 2, offs, 2, B.F32, 0x9000, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_group_weights(0x9000, 5, 2, 0, 0xa000, None) == B.ERR_UNSUPPORTED
+    assert lib.adasum_group_weights(None, 2, 2, 0, 0xa000, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_group_weights(0x9000, 2, 0, 0, 0xa000, None) == B.OK
+    assert lib.adasum_group_combine(x, 2, offs, 2, B.F32, None, 0x9000, B.F32, None, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_group_combine(x, 2, offs, 2, B.F32, 0xa000, 0x2010, B.F32, None, None) == B.ERR_ALIAS
+    assert lib.adasum_group_combine(x, 2, offs, 2, B.F32, 0xa000, 0x9000, 3, None, None) == B.ERR_UNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    g = [torch.zeros(8), torch.zeros(8)]
+    with pytest.raises(ValueError):
+        B.adasum_reduce(g, [0, 8])
+
+
+def test_workspace_bytes(lib):
+    offs = [0, 1000, 5096, 70632]
+    n2 = B.adasum_workspace_bytes(4, offs, B.F32, radix=2)
+    # two fp32 intermediate nodes of N elements (rounded up to 64) dominate
+    assert n2 >= 2 * 70656 * 4
+    assert n2 < 2 * 70656 * 4 + (1 << 20)
+    # one pass over all four workers needs no intermediate node
+    n4 = B.adasum_workspace_bytes(4, offs, B.F32, radix=4)
+    assert n4 < (1 << 20)
+    n = C.c_size_t(0)
+    o = (C.c_int64 * 4)(*offs)
+    assert lib.adasum_workspace_bytes(3, o, 3, B.F32, None, C.byref(n)) == B.ERR_UNSUPPORTED
+    assert lib.adasum_workspace_bytes(4, o, 3, B.F32, None, None) == B.ERR_INVALID_ARG

@@ -1,0 +1,279 @@
+"""GPU parity: the HIP library (through the C-ABI) against the fp64 CPU oracle,
+element by element on the same stored inputs.
+
+Tolerances (per layer, relative L2): 1e-5 for fp32 output, 2e-3 for bf16 output.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import adasum_oracle as O
+from paper_2006_02924_amd import binding as B
+from paper_2006_02924_amd import workloads as W
+from tests.gpu_util import (TOL_BF16, TOL_F32, assert_parity, bf16_ulp_distance, oracle_reduce, to_f64)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------------------
+# step level
+# ---------------------------------------------------------------------------
+
+RAGGED = [0, 1, 2, 9, 9, 40, 41, 1064, 1064 + 16384, 1064 + 16384 + 33000, 60000, 60001]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("R", [2, 4, 8])
+def test_group_gram_matches_dot_products(R, dtype):
+    say(f"group_gram R={R} {dtype}")
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=11)
+    gram = B.adasum_group_gram(w.grads, w.layer_offsets)
+    torch.cuda.synchronize()
+    got = gram.cpu().numpy()
+    X = np.stack([to_f64(g) for g in w.grads])
+    for l in range(w.n_layers):
+        lo, hi = RAGGED[l], RAGGED[l + 1]
+        want = X[:, lo:hi] @ X[:, lo:hi].T
+        scale = np.sqrt(np.outer(np.diag(want), np.diag(want))) + 1e-300
+        assert np.max(np.abs(got[l] - want) / scale) < 2e-6, (l, got[l], want)
+        if hi == lo:
+            assert np.all(got[l] == 0.0)
+    if R == 2:
+        # Algorithm 1's triple [a.b, a.a, b.b] per layer
+        lo, hi = RAGGED[-3], RAGGED[-2]
+        d, n1, n2 = O.pair_scalars(X[0, lo:hi], X[1, lo:hi])
+        np.testing.assert_allclose([got[-2][0, 1], got[-2][0, 0], got[-2][1, 1]], [d, n1, n2], rtol=2e-6)
+
+
+@pytest.mark.parametrize("R", [2, 4, 8])
+def test_group_weights_reproduce_the_tree(R):
+    say(f"group_weights R={R}")
+    rng = np.random.default_rng(R)
+    L, n = 12, 50
+    X = rng.standard_normal((L, R, n))
+    X[3, 1] = 0.0                      # a zero leaf
+    X[4] = 0.0                         # an all-zero layer
+    X[5, : R // 2] = 0.0               # a zero subtree
+    X[6, 1] = -X[6, 0]                 # exactly cancelling siblings
+    X[7] = X[7, 0]                     # all leaves identical
+    G = np.einsum("lri,lsi->lrs", X, X)
+    wt = B.adasum_group_weights(torch.from_numpy(G).to(DEV))
+    torch.cuda.synchronize()
+    wt = wt.cpu().numpy().astype(np.float64)
+    for l in range(L):
+        want = O.adasum_tree([X[l, r] for r in range(R)])
+        got = wt[l] @ X[l]
+        den = np.linalg.norm(want)
+        if den == 0:
+            assert np.linalg.norm(got) == 0
+        else:
+            assert np.linalg.norm(got - want) / den < 1e-6, l
+    if R == 2:
+        for l in (0, 1, 2):
+            a, b = O.pair_coefficients(G[l, 0, 1], G[l, 0, 0], G[l, 1, 1])
+            np.testing.assert_allclose(wt[l], [a, b], rtol=1e-7)
+    # left-to-right order (Section 3.4, first recursion)
+    wl = B.adasum_group_weights(torch.from_numpy(G).to(DEV), order=B.ORDER_LINEAR)
+    torch.cuda.synchronize()
+    wl = wl.cpu().numpy().astype(np.float64)
+    for l in (0, 1, 2, 3, 5):
+        want = O.adasum_linear([X[l, r] for r in range(R)])
+        assert np.linalg.norm(wl[l] @ X[l] - want) / np.linalg.norm(want) < 1e-6
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("R", [2, 4, 8])
+def test_group_combine_matches_weighted_sum(R, dtype, out_dtype):
+    say(f"group_combine R={R} {dtype}->{out_dtype}")
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=12)
+    L = w.n_layers
+    wt = torch.randn(L, R, generator=torch.Generator().manual_seed(5)).to(DEV)
+    before = [g.clone() for g in w.grads]
+    out, sq = B.adasum_group_combine(w.grads, w.layer_offsets, wt, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    for g, b in zip(w.grads, before):
+        assert torch.equal(g, b), "inputs must not be modified"
+    X = np.stack([to_f64(g) for g in w.grads])
+    wt64 = wt.cpu().numpy().astype(np.float64)
+    ref = np.zeros(w.N)
+    for l in range(L):
+        lo, hi = RAGGED[l], RAGGED[l + 1]
+        ref[lo:hi] = wt64[l] @ X[:, lo:hi]
+    assert_parity(out, ref, w.layer_offsets, tol=2e-6 if out_dtype == torch.float32 else TOL_BF16)
+    want_sq = np.array([np.dot(ref[RAGGED[l]:RAGGED[l + 1]], ref[RAGGED[l]:RAGGED[l + 1]]) for l in range(L)])
+    np.testing.assert_allclose(sq.cpu().numpy(), want_sq, rtol=2e-6, atol=0)
+    if out_dtype == torch.bfloat16:
+        assert bf16_ulp_distance(out, ref).max() <= 1
+
+
+def test_group_combine_in_place_on_first_operand():
+    say("group_combine in place")
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), 4, dtype=torch.float32, device=DEV, seed=13)
+    wt = torch.rand(w.n_layers, 4, generator=torch.Generator().manual_seed(6)).to(DEV)
+    ref, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt)
+    got, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt, out=w.grads[0])
+    torch.cuda.synchronize()
+    assert got.data_ptr() == w.grads[0].data_ptr()
+    assert torch.equal(got, ref)
+
+
+# ---------------------------------------------------------------------------
+# whole tree
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("radix", [0, 2, 4, 8])
+def test_config1(radix):
+    say(f"config1 radix={radix}")
+    w = W.config1(DEV)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix)
+    torch.cuda.synchronize()
+    err = assert_parity(out, ref, w.layer_offsets, what=f"config1 radix {radix}")
+    say(f"  max rel-L2 {err.max():.2e}")
+
+
+@pytest.mark.parametrize("radix", [2, 4, 8])
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K", [1, 2, 4, 8, 16, 32])
+def test_ragged_tables(K, dtype, out_dtype, radix):
+    if K == 1 and radix != 2:
+        pytest.skip("K=1 has no passes")
+    say(f"ragged K={K} {dtype}->{out_dtype} radix={radix}")
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), K, dtype=dtype, device=DEV, seed=100 + K)
+    before = [g.clone() for g in w.grads]
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix)
+    torch.cuda.synchronize()
+    for g, b in zip(w.grads, before):
+        assert torch.equal(g, b), "inputs must not be modified"
+    assert_parity(out, ref, w.layer_offsets, what="ragged")
+    if out_dtype == torch.bfloat16:
+        assert bf16_ulp_distance(out, ref).max() <= 1
+
+
+def test_empty_and_degenerate_tables():
+    say("empty tables")
+    for offs in ([0], [0, 0], [0, 0, 0, 5, 5], [0, 1], [0, 7, 7, 8]):
+        N = offs[-1]
+        g = [torch.randn(max(N, 1), device=DEV)[:N].contiguous() for _ in range(4)]
+        if N == 0:
+            g = [torch.empty(0, device=DEV) for _ in range(4)]
+        out = B.adasum_reduce(g, offs)
+        torch.cuda.synchronize()
+        if N:
+            assert_parity(out, oracle_reduce(g, offs), offs, what=str(offs))
+
+
+def test_deterministic_and_workspace_from_caller():
+    say("determinism")
+    sizes = W.scaled_down(W.resnet50_layer_sizes(), 16, floor=3)
+    w = W.correlated_gaussian(sizes, 8, dtype=torch.bfloat16, device=DEV, seed=21)
+    a = B.adasum_reduce(w.grads, w.layer_offsets, radix=2)
+    b = B.adasum_reduce(w.grads, w.layer_offsets, radix=2)
+    nbytes = B.adasum_workspace_bytes(8, w.layer_offsets, B.BF16, radix=2)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    assert ws.data_ptr() % 256 == 0
+    c = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    small = torch.empty(nbytes - 256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(w.grads, w.layer_offsets, radix=2, workspace=small)
+    assert e.value.code == B.ERR_WORKSPACE
+
+
+def test_layer_stats_orthogonality_metric():
+    say("layer stats")
+    # Section 3.6: |Adasum|^2 / sum |g_i|^2 is 1 for orthogonal and 1/K for identical gradients
+    K, n = 8, 4096
+    q, _ = torch.linalg.qr(torch.randn(n, K, dtype=torch.float64, generator=torch.Generator().manual_seed(1)))
+    base = torch.randn(n, generator=torch.Generator().manual_seed(2))
+    rnd = W.correlated_gaussian([3000], K, device="cpu", seed=3, corr=0.5)
+    grads = []
+    for i in range(K):
+        grads.append(torch.cat([q[:, i].float() * (i + 1), base, rnd.grads[i]]).to(DEV))
+    offs = [0, n, 2 * n, 2 * n + 3000]
+    for radix in (2, 8):
+        stats = torch.zeros(3, 2, dtype=torch.float64, device=DEV)
+        out = B.adasum_reduce(grads, offs, radix=radix, layer_stats=stats)
+        torch.cuda.synchronize()
+        s = stats.cpu().numpy()
+        metric = s[:, 0] / s[:, 1]
+        want = O.orthogonality([to_f64(g) for g in grads], offs)
+        np.testing.assert_allclose(metric, want, rtol=1e-5)
+        assert abs(metric[0] - 1.0) < 1e-5 and abs(metric[1] - 1.0 / K) < 1e-5
+        got = to_f64(out)
+        np.testing.assert_allclose(s[:, 0], [got[offs[l]:offs[l + 1]] @ got[offs[l]:offs[l + 1]] for l in range(3)],
+                                   rtol=1e-5)
+
+
+def test_config2_resnet50_full():
+    say("config2 (K=8, fp32, ResNet-50 shapes, full size)")
+    w = W.config2(DEV)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    for radix in (2, 8):
+        out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix)
+        torch.cuda.synchronize()
+        err = assert_parity(out, ref, w.layer_offsets, what=f"config2 radix {radix}")
+        say(f"  radix {radix}: max rel-L2 {err.max():.2e}")
+
+
+def test_config3_bert_fp32_scaled():
+    say("config3 (K=16, fp32, BERT-Large shapes / 16)")
+    sizes = W.scaled_down(W.bert_large_layer_sizes(), 16, floor=64)
+    w = W.config3(DEV, sizes=sizes)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    for radix in (2, 4, 8):
+        out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix)
+        torch.cuda.synchronize()
+        err = assert_parity(out, ref, w.layer_offsets, what=f"config3 radix {radix}")
+        say(f"  radix {radix}: max rel-L2 {err.max():.2e}")
+
+
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_config4_bert_bf16_scaled(out_dtype):
+    say(f"config4 (K=64, bf16->{out_dtype}, BERT-Large shapes / 32)")
+    sizes = W.scaled_down(W.bert_large_layer_sizes(), 32, floor=32)
+    w = W.config4(DEV, sizes=sizes)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    for radix in (2, 4, 8):
+        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix)
+        torch.cuda.synchronize()
+        err = assert_parity(out, ref, w.layer_offsets, what=f"config4 radix {radix}")
+        say(f"  radix {radix}: max rel-L2 {err.max():.2e}")
+        if out_dtype == torch.bfloat16:
+            assert bf16_ulp_distance(out, ref).max() <= 1
+
+
+def test_config5_edge_cases_scaled():
+    say("config5 (K=128, bf16, degenerate layers, BERT-Large shapes / 64)")
+    sizes = W.scaled_down(W.bert_large_layer_sizes(), 64, floor=16)
+    w = W.config5(DEV, sizes=sizes)
+    offs = w.layer_offsets
+    ref = oracle_reduce(w.grads, offs)
+    kinds = w.meta["kind"]
+    for radix in (2, 8):
+        for out_dtype in (torch.bfloat16, torch.float32):
+            out = B.adasum_reduce(w.grads, offs, out_dtype=out_dtype, radix=radix)
+            torch.cuda.synchronize()
+            err = assert_parity(out, ref, offs, what=f"config5 radix {radix} {out_dtype}")
+            say(f"  radix {radix} {out_dtype}: max rel-L2 {err.max():.2e} at layer {int(err.argmax())} "
+                f"({kinds[int(err.argmax())]}, size {offs[int(err.argmax()) + 1] - offs[int(err.argmax())]})")
+    got = to_f64(out)
+    for l, k in enumerate(kinds):
+        lo, hi = offs[l], offs[l + 1]
+        if hi - lo == 1:
+            # one-element layer: collinear operands everywhere => arithmetic mean of the K scalars
+            vals = np.array([float(g[lo]) for g in w.grads])
+            if np.all(vals != 0):
+                assert abs(got[lo] - ref[lo]) <= 1e-5 * abs(ref[lo])
+    for l, mode in w.meta["zero_modes"]:
+        if mode == 0:
+            assert np.all(got[offs[l]:offs[l + 1]] == 0.0)

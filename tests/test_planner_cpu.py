@@ -1,0 +1,77 @@
+"""Host planner: tile table and pass schedule (no GPU needed)."""
+import numpy as np
+import pytest
+
+from paper_2006_02924_amd import binding as B
+from paper_2006_02924_amd import workloads as W
+
+
+def check_tiles(offsets):
+    cap = B.tile_capacity()
+    t = B.plan_tiles(offsets)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    N = int(offsets[-1])
+    # cover [0, N) exactly, in order, without overlap
+    if N == 0:
+        assert len(t) == 0
+        return t
+    ends = t["start"] + t["len"]
+    assert t["start"][0] == 0 and ends[-1] == N
+    assert np.array_equal(t["start"][1:], ends[:-1])
+    assert t["len"].min() >= 1 and t["len"].max() <= cap
+    # never cross a layer boundary; layer ids are right
+    lo = offsets[t["layer"]]
+    hi = offsets[t["layer"] + 1]
+    assert np.all(t["start"] >= lo) and np.all(ends <= hi)
+    # interior boundaries fall on global multiples of the capacity or on layer boundaries
+    inner = t["start"][1:]
+    assert np.all((inner % cap == 0) | np.isin(inner, offsets))
+    # full tiles are aligned to the capacity
+    full = t["len"] == cap
+    assert np.all(t["start"][full] % cap == 0)
+    return t
+
+
+def test_tiles_config1():
+    t = check_tiles([0, 1000, 5096, 70632])
+    assert list(t["layer"][:3]) == [0, 1, 2]
+
+
+def test_tiles_ragged_and_empty_layers():
+    cap = B.tile_capacity()
+    check_tiles([0])
+    check_tiles([0, 0, 0])
+    check_tiles([0, 1])
+    check_tiles([0, 1, 2, 3, 3, 3 + cap, 4 + 2 * cap, 4 + 2 * cap, 5 * cap + 17])
+    rng = np.random.default_rng(0)
+    sizes = rng.integers(0, 3 * cap, size=200)
+    check_tiles(np.concatenate([[0], np.cumsum(sizes)]))
+
+
+def test_tiles_bert_large():
+    offs = W.offsets_from_sizes(W.bert_large_layer_sizes())
+    t = check_tiles(offs)
+    cap = B.tile_capacity()
+    assert len(t) <= offs[-1] // cap + 2 * 391
+
+
+def test_levels():
+    assert B.plan_levels(1) == []
+    assert B.plan_levels(2) == [2]
+    assert B.plan_levels(64) == [2] * 6
+    assert B.plan_levels(64, 2) == [2] * 6
+    assert B.plan_levels(64, 8) == [8, 8]
+    assert B.plan_levels(64, 4) == [4, 4, 4]
+    assert B.plan_levels(128, 8) == [8, 8, 2]
+    assert B.plan_levels(32, 8) == [8, 4]
+    assert B.plan_levels(4, 8) == [4]
+    for K in (2, 4, 8, 16, 32, 64, 128, 256):
+        for r in (2, 4, 8):
+            assert int(np.prod(B.plan_levels(K, r))) == K
+    with pytest.raises(B.AdasumError) as e:
+        B.plan_levels(12)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.AdasumError):
+        B.plan_levels(8, 3)
+    with pytest.raises(B.AdasumError):
+        B.plan_levels(0)
