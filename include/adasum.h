@@ -9,8 +9,9 @@
  *   - the operator's scalars are taken per layer of the fused gradient buffer,
  *     Section 3.6 (last paragraph) and Section 4.4.3 (boundary bookkeeping);
  *   - dot products and squared norms: each lane accumulates a short run in fp32,
- *     everything above a lane's run is summed in fp64 (Section 4.4.1 asks for
- *     double accumulation).
+ *     a wave adds its lanes in fp32, everything above that (and the ragged
+ *     head/tail elements of a layer) is summed in fp64; the operator's scalars
+ *     are computed in fp64 (Section 4.4.1 asks for double accumulation).
  * Reading where the paper is silent: an operand whose squared norm is exactly 0
  * gets coefficient 1, so Adasum(0, g) = g and Adasum(0, 0) = 0.
  *
@@ -130,25 +131,26 @@ int adasum_group_gram(const void* const* x, int R,
  * Step 2 (Algorithm 1, "finish dot products" + the scalars of "apply Adasum"):
  * per layer, the weights w with  tree(x_0..x_{R-1}) = sum_r w_r x_r,  obtained
  * from the Gram matrix by walking the binary tree over the R leaves bottom-up;
- * R = 2 gives w = (1 - d/(2 n1), 1 - d/(2 n2)).  fp64 arithmetic, fp32 result.
+ * R = 2 gives w = (1 - d/(2 n1), 1 - d/(2 n2)).  fp64 arithmetic and result.
  *   gram     DEVICE, n_layers x R x R doubles (as written by adasum_group_gram)
- *   weights  DEVICE, n_layers x R floats
+ *   weights  DEVICE, n_layers x R doubles
  */
 int adasum_group_weights(const double* gram, int R, int n_layers, int order,
-                         float* weights, void* stream);
+                         double* weights, void* stream);
 
 /*
  * Step 3 (Algorithm 1, "apply Adasum"): out = sum_r w[layer][r] * x_r element
- * by element (fp32 fused multiply-adds, one rounding at the store), and in the
- * same pass the squared norm of the result per layer.
- *   weights    DEVICE, n_layers x R floats
+ * by element (fp32 fused multiply-adds with the weights rounded to fp32, one
+ * rounding at the store; the few elements of a layer's ragged head and tail are
+ * done in fp64), and in the same pass the squared norm of the result per layer.
+ *   weights    DEVICE, n_layers x R doubles
  *   out        DEVICE, N elements of out_dtype; may be x[0] itself (in place)
  *              when out_dtype == dtype, must not overlap any other operand
  *   sqnorm     DEVICE, n_layers doubles, or NULL
  */
 int adasum_group_combine(const void* const* x, int R,
                          const int64_t* layer_offsets, int n_layers,
-                         int dtype, const float* weights,
+                         int dtype, const double* weights,
                          void* out, int out_dtype, double* sqnorm, void* stream);
 
 /* ---- host-side planning, exposed for inspection and tests (no GPU needed) ---- */

@@ -227,11 +227,11 @@ def adasum_group_gram(xs: Sequence, layer_offsets: Sequence[int], stream=None):
 
 
 def adasum_group_weights(gram, order: int = ORDER_TREE, stream=None):
-    """[L, R, R] float64 Gram matrices -> [L, R] float32 tree weights."""
+    """[L, R, R] float64 Gram matrices -> [L, R] float64 tree weights."""
     import torch
     lib = load()
     L, R, _ = gram.shape
-    w = torch.empty((L, R), dtype=torch.float32, device=gram.device)
+    w = torch.empty((L, R), dtype=torch.float64, device=gram.device)
     check(lib.adasum_group_weights(C.c_void_p(gram.data_ptr()), R, L, order, C.c_void_p(w.data_ptr()),
                                    _stream(stream)))
     return w
@@ -247,6 +247,8 @@ def adasum_group_combine(xs: Sequence, layer_offsets: Sequence[int], weights, *,
     _check_inputs(xs, N)
     in_code = _dtype_code(xs[0])
     out_code = in_code if out_dtype is None else (F32 if out_dtype == torch.float32 else BF16)
+    if weights.dtype != torch.float64 or weights.numel() != L * len(xs) or not weights.is_contiguous():
+        raise ValueError("weights must be a contiguous float64 tensor of n_layers x R")
     if out is None:
         out = torch.empty(N, dtype=_torch_dtype(out_code), device=xs[0].device)
     sq = torch.empty(L, dtype=torch.float64, device=xs[0].device) if want_sqnorm else None

@@ -241,7 +241,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
     double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
-    float* weights = reinterpret_cast<float*>(ws + lay.off_weights);
+    double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
     const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
     char namebuf[48];
 
@@ -491,12 +491,12 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     return ADASUM_OK;
 }
 
-int adasum_group_weights(const double* gram, int R, int n_layers, int order, float* weights, void* stream) {
+int adasum_group_weights(const double* gram, int R, int n_layers, int order, double* weights, void* stream) {
     if (R != 2 && R != 4 && R != 8) return ADASUM_ERR_UNSUPPORTED;
     if (n_layers < 0) return ADASUM_ERR_INVALID_ARG;
     if (order != ADASUM_ORDER_TREE && order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if ((gram == nullptr || weights == nullptr) && n_layers > 0) return ADASUM_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(gram) & 7u) != 0 || (reinterpret_cast<uintptr_t>(weights) & 3u) != 0)
+    if ((reinterpret_cast<uintptr_t>(gram) & 7u) != 0 || (reinterpret_cast<uintptr_t>(weights) & 7u) != 0)
         return ADASUM_ERR_MISALIGNED;
     if (n_layers == 0) return ADASUM_OK;
     ADASUM_LAUNCH(launch_weights(gram, R, n_layers, order, weights, stream));
@@ -504,13 +504,13 @@ int adasum_group_weights(const double* gram, int R, int n_layers, int order, flo
 }
 
 int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offsets, int n_layers, int dtype,
-                         const float* weights, void* out, int out_dtype, double* sqnorm, void* stream) {
+                         const double* weights, void* out, int out_dtype, double* sqnorm, void* stream) {
     int rc = step_common(x, R, layer_offsets, n_layers, dtype);
     if (rc != ADASUM_OK) return rc;
     if (out_dtype != ADASUM_F32 && out_dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
     const int64_t N = layer_offsets[n_layers];
     if ((weights == nullptr && n_layers > 0) || (out == nullptr && N > 0)) return ADASUM_ERR_INVALID_ARG;
-    if (!aligned16(out) || (reinterpret_cast<uintptr_t>(weights) & 3u) != 0 ||
+    if (!aligned16(out) || (reinterpret_cast<uintptr_t>(weights) & 7u) != 0 ||
         (reinterpret_cast<uintptr_t>(sqnorm) & 7u) != 0)
         return ADASUM_ERR_MISALIGNED;
     if (n_layers == 0) return ADASUM_OK;

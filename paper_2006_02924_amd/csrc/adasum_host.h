@@ -53,7 +53,7 @@ struct Layout {
     size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
     size_t  off_normparts = 0;// doubles [node][tile]: squared norm of every node a combine wrote
     size_t  off_gram = 0;     // doubles [group][layer][R*R] (finished Gram matrices)
-    size_t  off_weights = 0;  // floats  [group][layer][R]
+    size_t  off_weights = 0;  // doubles [group][layer][R]
     size_t  off_leafnorm = 0; // doubles [layer]: sum over workers of the input squared norms
     size_t  total = 0;
 };
@@ -96,9 +96,9 @@ int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials,
                        const double* normparts, double* gram, void* stream);
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
 int launch_weights(const double* gram, int R, int64_t n_items, int order,
-                   float* weights, void* stream);
+                   double* weights, void* stream);
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out,
-                   const LevelArgs& a, const float* weights /* or null: unit weights */,
+                   const LevelArgs& a, const double* weights /* or null: unit weights */,
                    double* normparts /* [group][tile] or null */, void* stream);
 // layer_sum[l] (+)= sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
 int launch_layer_sums(const double* parts, int n_rows, const LevelArgs& a,

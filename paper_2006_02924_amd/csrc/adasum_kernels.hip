@@ -216,24 +216,34 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
             consume(raw);
         }
     }
-    if (tid < s.nh + s.nt) {
-        const long long idx = tid < s.nh ? s.start + tid : s.ts + (tid - s.nh);
+    // Whole granules went through fp32 lanes.  The at most 2*(G-1) elements of a
+    // ragged head/tail are multiplied and summed in fp64 by wave 0: layers of a
+    // few elements (which are all head/tail) then get exact products, so the
+    // scalars of nearly cancelling tiny layers do not lose digits here.
+    __shared__ double sh[kThreads / 64][NP];
+    __shared__ double sh_edge[NP];
+    const int lane = tid & 63, wave = tid >> 6;
+    const int nedge = s.nh + s.nt;
+    if (nedge > 0 && wave == 0) {
         float v[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) v[r] = load_elem(x[r] + idx);
+        for (int r = 0; r < R; ++r) v[r] = 0.f;
+        if (lane < nedge) {
+            const long long idx = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[r] = load_elem(x[r] + idx);
+        }
         int e = 0;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
 #pragma unroll
             for (int j = (DIAG ? i : i + 1); j < R; ++j) {
-                acc[e] = __builtin_fmaf(v[i], v[j], acc[e]);
+                const double p = wave_sum(static_cast<double>(v[i]) * static_cast<double>(v[j]));
+                if (lane == 0) sh_edge[e] = p;
                 ++e;
             }
         }
     }
-
-    __shared__ double sh[kThreads / 64][NP];
-    const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int e = 0; e < NP; ++e) {
         const float w = wave_sum(acc[e]);
@@ -244,6 +254,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
         double tot = sh[0][tid];
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) tot += sh[w][tid];
+        if (nedge > 0) tot += sh_edge[tid];
         partials[(static_cast<long long>(g) * NP + tid) * n_tiles + tile_id] = tot;
     }
 }
@@ -310,7 +321,7 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
 // for two sibling nodes A and B the operator of Section 3 needs
 //   d = A.B = sum_{p in A, q in B} w_p w_q G_pq,  n1 = |A|^2,  n2 = |B|^2
 // and scales A's weights by 1 - d/(2 n1) and B's by 1 - d/(2 n2).  A zero
-// squared norm gives coefficient 1.  fp64 throughout, fp32 at the end.
+// squared norm gives coefficient 1.  fp64 throughout.
 // ---------------------------------------------------------------------------
 template <int R>
 __device__ __forceinline__ void merge_nodes(const double* G, double (&w)[R], int a0, int a1, int b0, int b1) {
@@ -329,7 +340,7 @@ __device__ __forceinline__ void merge_nodes(const double* G, double (&w)[R], int
 
 template <int R>
 __global__ void __launch_bounds__(64)
-weights_kernel(const double* __restrict__ gram, long long n_items, int order, float* __restrict__ weights) {
+weights_kernel(const double* __restrict__ gram, long long n_items, int order, double* __restrict__ weights) {
     const long long item = static_cast<long long>(blockIdx.x) * 64 + threadIdx.x;
     if (item >= n_items) return;
     const double* G = gram + item * (R * R);
@@ -341,7 +352,7 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, fl
         for (int span = 1; span < R; span *= 2)
             for (int j = 0; j < R; j += 2 * span) merge_nodes<R>(G, w, j, j + span, j + span, j + 2 * span);
     }
-    for (int p = 0; p < R; ++p) weights[item * R + p] = static_cast<float>(w[p]);
+    for (int p = 0; p < R; ++p) weights[item * R + p] = w[p];
 }
 
 // ---------------------------------------------------------------------------
@@ -351,7 +362,7 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, fl
 template <typename TI, typename TO, int R>
 __global__ void __launch_bounds__(kThreads)
 combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
-               int n_tiles, int n_layers, const float* __restrict__ weights,
+               int n_tiles, int n_layers, const double* __restrict__ weights,
                double* __restrict__ normparts) {
     constexpr int G = (sizeof(TI) == 2 || sizeof(TO) == 2) ? 8 : 4;
     constexpr int ITERS = kTile / G / kThreads;
@@ -370,10 +381,14 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
 
+    // fp64 weights as computed; the streaming body uses them rounded to fp32
+    double wd[R];
     float w[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
-        w[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0f;
+    for (int r = 0; r < R; ++r) {
+        wd[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0;
+        w[r] = static_cast<float>(wd[r]);
+    }
 
     float nacc = 0.f;
 
@@ -421,18 +436,25 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
             emit(raw, idx);
         }
     }
-    if (tid < s.nh + s.nt) {
-        const long long idx = tid < s.nh ? s.start + tid : s.ts + (tid - s.nh);
-        float z = w[0] * load_elem(x[0] + idx);
+    // ragged head/tail elements: fp64 arithmetic, one rounding at the store
+    const int lane = tid & 63, wave = tid >> 6;
+    const int nedge = s.nh + s.nt;
+    double enorm = 0.0;
+    if (nedge > 0 && wave == 0) {
+        if (lane < nedge) {
+            const long long idx = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
+            double z = wd[0] * static_cast<double>(load_elem(x[0] + idx));
 #pragma unroll
-        for (int r = 1; r < R; ++r) z = __builtin_fmaf(w[r], load_elem(x[r] + idx), z);
-        nacc = __builtin_fmaf(z, z, nacc);
-        store_elem(out + idx, z);
+            for (int r = 1; r < R; ++r) z = __builtin_fma(wd[r], static_cast<double>(load_elem(x[r] + idx)), z);
+            const float zf = static_cast<float>(z);
+            store_elem(out + idx, zf);
+            enorm = static_cast<double>(zf) * static_cast<double>(zf);
+        }
+        if (normparts != nullptr) enorm = wave_sum(enorm);
     }
 
     if (normparts != nullptr) {
         __shared__ double sh[kThreads / 64];
-        const int lane = tid & 63, wave = tid >> 6;
         const float ws = wave_sum(nacc);
         if (lane == 0) sh[wave] = static_cast<double>(ws);
         __syncthreads();
@@ -440,6 +462,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
             double tot = sh[0];
 #pragma unroll
             for (int k = 1; k < kThreads / 64; ++k) tot += sh[k];
+            if (nedge > 0) tot += enorm;
             normparts[static_cast<long long>(g) * n_tiles + tile_id] = tot;
         }
     }
@@ -499,7 +522,7 @@ int launch_gram_r(const Operands& ops, const LevelArgs& a, double* partials, hip
 }
 
 template <typename TI, typename TO>
-int launch_combine_r(const Operands& ops, const Outputs& outs, const LevelArgs& a, const float* weights,
+int launch_combine_r(const Operands& ops, const Outputs& outs, const LevelArgs& a, const double* weights,
                      double* normparts, hipStream_t st) {
     const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups);
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
@@ -553,7 +576,7 @@ int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials, co
     return check_launch();
 }
 
-int launch_weights(const double* gram, int R, int64_t n_items, int order, float* weights, void* stream) {
+int launch_weights(const double* gram, int R, int64_t n_items, int order, double* weights, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_items == 0) return 0;
     const long long blocks = (n_items + 63) / 64;
@@ -570,7 +593,7 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order, float*
 }
 
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const LevelArgs& a,
-                   const float* weights, double* normparts, void* stream) {
+                   const double* weights, double* normparts, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_tiles == 0 || a.n_groups == 0) return 0;
     if (dtype == ADASUM_BF16) {

@@ -86,7 +86,7 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, const std::v
     lay.off_gram = off;
     off = align_up(off + max_gram * sizeof(double), 256);
     lay.off_weights = off;
-    off = align_up(off + max_weights * sizeof(float), 256);
+    off = align_up(off + max_weights * sizeof(double), 256);
     lay.off_leafnorm = off;
     off = align_up(off + static_cast<size_t>(n_layers) * sizeof(double), 256);
     lay.total = off;

@@ -7,6 +7,14 @@ from oracle import adasum_oracle as O
 
 TOL_F32 = 1e-5    # per-layer relative L2 error, fp32 output
 TOL_BF16 = 2e-3   # per-layer relative L2 error, bf16 output
+# One round-to-nearest-even store to bf16 has relative error up to 2^-8 per
+# element (about 1.66e-3 in relative L2 over many Gaussian elements, which is
+# what the 2e-3 bound is sized for).  A layer of a few elements can therefore
+# exceed 2e-3 with a correctly rounded result; such layers (< 256 elements) are
+# held to the format's unit roundoff instead, and every bf16 test also checks
+# each element against RNE(oracle) to within one ulp.
+TOL_BF16_TINY = 2.0 ** -8 * 1.001
+TINY_LAYER = 256
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
@@ -35,6 +43,10 @@ def tol_for(dtype: torch.dtype) -> float:
 def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None, tol=None, what=""):
     tol = tol_for(out.dtype) if tol is None else tol
     offs = list(layer_offsets)
+    tols = np.full(len(offs) - 1, tol)
+    if out.dtype == torch.bfloat16:
+        sizes = np.diff(np.asarray(offs))
+        tols[sizes < TINY_LAYER] = max(tol, TOL_BF16_TINY)
     got = to_f64(out)
     if layers is None:
         err = O.rel_l2_per_layer(got, ref, offs)
@@ -43,19 +55,27 @@ def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None
         for l in layers:
             lo, hi = offs[l], offs[l + 1]
             err[l] = O.rel_l2_per_layer(got[lo:hi], ref[lo:hi], [0, hi - lo])[0]
-    worst = int(np.argmax(err))
+    worst = int(np.argmax(err / tols))
     assert np.all(np.isfinite(got)), f"{what}: non-finite output"
-    assert err[worst] <= tol, (f"{what}: layer {worst} (size {offs[worst + 1] - offs[worst]}) "
-                               f"rel-L2 {err[worst]:.3e} > {tol:.1e}")
+    assert err[worst] <= tols[worst], (f"{what}: layer {worst} (size {offs[worst + 1] - offs[worst]}) "
+                                       f"rel-L2 {err[worst]:.3e} > {tols[worst]:.1e}")
     return err
 
 
-def bf16_ulp_distance(out_bf16: torch.Tensor, ref: np.ndarray) -> np.ndarray:
-    """|out - RNE_bf16(ref)| in units of bf16 ulps of the reference value."""
-    r = torch.from_numpy(ref).to(torch.float32).to(torch.bfloat16)
-    a = out_bf16.detach().cpu().view(torch.int16).to(torch.int32)
-    b = r.view(torch.int16).to(torch.int32)
-    # sign-magnitude -> monotone integer line
-    a = torch.where(a < 0, -(a & 0x7FFF), a)
-    b = torch.where(b < 0, -(b & 0x7FFF), b)
-    return (a - b).abs().numpy()
+def assert_bf16_rounding(out_bf16: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None):
+    """Sharper than relative L2: every stored bf16 element is the oracle value
+    rounded once -- within half a bf16 ulp of it (relative 2^-8), plus the fp32
+    noise of the computation, which is relative to the layer's magnitude (an
+    element that nearly cancels is small against its own rounding noise)."""
+    offs = list(layer_offsets)
+    got = to_f64(out_bf16)
+    todo = range(len(offs) - 1) if layers is None else layers
+    for l in todo:
+        lo, hi = offs[l], offs[l + 1]
+        if hi == lo:
+            continue
+        r = ref[lo:hi]
+        bound = 2.0 ** -8 * np.abs(r) + 2e-6 * np.abs(r).max() + 1e-45
+        bad = np.abs(got[lo:hi] - r) > bound
+        assert not bad.any(), (f"layer {l}: {int(bad.sum())} elements off by more than one rounding, "
+                               f"first at {int(np.argmax(bad))}: got {got[lo:hi][bad][0]!r} want {r[bad][0]!r}")

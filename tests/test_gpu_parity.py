@@ -10,7 +10,7 @@ import torch
 from oracle import adasum_oracle as O
 from paper_2006_02924_amd import binding as B
 from paper_2006_02924_amd import workloads as W
-from tests.gpu_util import (TOL_BF16, TOL_F32, assert_parity, bf16_ulp_distance, oracle_reduce, to_f64)
+from tests.gpu_util import (TOL_BF16, TOL_F32, assert_parity, assert_bf16_rounding, oracle_reduce, to_f64)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -64,19 +64,21 @@ def test_group_weights_reproduce_the_tree(R):
     G = np.einsum("lri,lsi->lrs", X, X)
     wt = B.adasum_group_weights(torch.from_numpy(G).to(DEV))
     torch.cuda.synchronize()
-    wt = wt.cpu().numpy().astype(np.float64)
+    wt = wt.cpu().numpy()
+    assert wt.dtype == np.float64
     for l in range(L):
         want = O.adasum_tree([X[l, r] for r in range(R)])
         got = wt[l] @ X[l]
         den = np.linalg.norm(want)
         if den == 0:
-            assert np.linalg.norm(got) == 0
+            # weights that cancel in exact arithmetic; the host-side product rounds
+            assert np.linalg.norm(got) <= 1e-12 * (1.0 + np.abs(wt[l]) @ np.linalg.norm(X[l], axis=1))
         else:
             assert np.linalg.norm(got - want) / den < 1e-6, l
     if R == 2:
         for l in (0, 1, 2):
             a, b = O.pair_coefficients(G[l, 0, 1], G[l, 0, 0], G[l, 1, 1])
-            np.testing.assert_allclose(wt[l], [a, b], rtol=1e-7)
+            np.testing.assert_allclose(wt[l], [a, b], rtol=1e-13)
     # left-to-right order (Section 3.4, first recursion)
     wl = B.adasum_group_weights(torch.from_numpy(G).to(DEV), order=B.ORDER_LINEAR)
     torch.cuda.synchronize()
@@ -93,7 +95,7 @@ def test_group_combine_matches_weighted_sum(R, dtype, out_dtype):
     say(f"group_combine R={R} {dtype}->{out_dtype}")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=12)
     L = w.n_layers
-    wt = torch.randn(L, R, generator=torch.Generator().manual_seed(5)).to(DEV)
+    wt = torch.randn(L, R, generator=torch.Generator().manual_seed(5), dtype=torch.float64).to(DEV)
     before = [g.clone() for g in w.grads]
     out, sq = B.adasum_group_combine(w.grads, w.layer_offsets, wt, out_dtype=out_dtype)
     torch.cuda.synchronize()
@@ -107,15 +109,15 @@ def test_group_combine_matches_weighted_sum(R, dtype, out_dtype):
         ref[lo:hi] = wt64[l] @ X[:, lo:hi]
     assert_parity(out, ref, w.layer_offsets, tol=2e-6 if out_dtype == torch.float32 else TOL_BF16)
     want_sq = np.array([np.dot(ref[RAGGED[l]:RAGGED[l + 1]], ref[RAGGED[l]:RAGGED[l + 1]]) for l in range(L)])
-    np.testing.assert_allclose(sq.cpu().numpy(), want_sq, rtol=2e-6, atol=0)
+    np.testing.assert_allclose(sq.cpu().numpy(), want_sq, rtol=1e-5, atol=0)
     if out_dtype == torch.bfloat16:
-        assert bf16_ulp_distance(out, ref).max() <= 1
+        assert_bf16_rounding(out, ref, w.layer_offsets)
 
 
 def test_group_combine_in_place_on_first_operand():
     say("group_combine in place")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), 4, dtype=torch.float32, device=DEV, seed=13)
-    wt = torch.rand(w.n_layers, 4, generator=torch.Generator().manual_seed(6)).to(DEV)
+    wt = torch.rand(w.n_layers, 4, generator=torch.Generator().manual_seed(6), dtype=torch.float64).to(DEV)
     ref, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt)
     got, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt, out=w.grads[0])
     torch.cuda.synchronize()
@@ -155,7 +157,7 @@ def test_ragged_tables(K, dtype, out_dtype, radix):
         assert torch.equal(g, b), "inputs must not be modified"
     assert_parity(out, ref, w.layer_offsets, what="ragged")
     if out_dtype == torch.bfloat16:
-        assert bf16_ulp_distance(out, ref).max() <= 1
+        assert_bf16_rounding(out, ref, w.layer_offsets)
 
 
 def test_empty_and_degenerate_tables():
@@ -249,7 +251,7 @@ def test_config4_bert_bf16_scaled(out_dtype):
         err = assert_parity(out, ref, w.layer_offsets, what=f"config4 radix {radix}")
         say(f"  radix {radix}: max rel-L2 {err.max():.2e}")
         if out_dtype == torch.bfloat16:
-            assert bf16_ulp_distance(out, ref).max() <= 1
+            assert_bf16_rounding(out, ref, w.layer_offsets)
 
 
 def test_config5_edge_cases_scaled():
