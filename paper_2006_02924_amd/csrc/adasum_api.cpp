@@ -400,7 +400,7 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(K, o.radix == 0 ? 2 : o.radix, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(K, o.radix == 0 ? kDefaultRadix : o.radix, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);

@@ -18,6 +18,8 @@ constexpr int kThreads = 256;
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
 constexpr int kMaxRadix = 8;
+// Radix used when the caller asks for 0: the widest pass moves the fewest bytes.
+constexpr int kDefaultRadix = 8;
 
 inline int elem_bytes(int dtype) { return dtype == ADASUM_BF16 ? 2 : 4; }
 inline bool is_pow2(long long v) { return v > 0 && (v & (v - 1)) == 0; }

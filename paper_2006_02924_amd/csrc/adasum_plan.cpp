@@ -45,7 +45,7 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     radices.clear();
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
     if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
-    if (radix == 0) radix = 2;
+    if (radix == 0) radix = kDefaultRadix;
     if (radix != 2 && radix != 4 && radix != 8) return ADASUM_ERR_UNSUPPORTED;
     int rest = K;
     while (rest > 1) {

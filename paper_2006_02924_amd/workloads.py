@@ -124,9 +124,10 @@ def correlated_gaussian(sizes: Sequence[int], K: int, *, dtype=torch.float32,
     ``a_l ~ U(0,1)`` (``scale``: 1).  The arithmetic is done in fp32 and the
     result is rounded to ``dtype`` (round-to-nearest-even for bf16).
 
-    Draw order, per layer: ``c``, then ``n_0 .. n_{K-1}``; the per-layer
-    parameters come from a separate host generator so that they do not depend
-    on the device.
+    Draw order: ``c`` for the whole fused buffer (N values), then ``n_0``,
+    ``n_1``, ... (N values each); ``g_i = c * (a_l scale_l) + n_i * (sqrt(1 -
+    a_l^2) scale_l)`` element by element.  The per-layer parameters come from a
+    separate host generator so that they do not depend on the device.
     """
     L = len(sizes)
     hg = _host_gen(seed)
@@ -144,18 +145,22 @@ def correlated_gaussian(sizes: Sequence[int], K: int, *, dtype=torch.float32,
         scale_l = [float(s) for s in scale]
     offs = offsets_from_sizes(sizes)
     N = offs[-1]
-    grads = [torch.empty(N, dtype=dtype, device=device) for _ in range(K)]
     dg = _gen(device, seed)
-    for l, n in enumerate(sizes):
-        if n == 0:
-            continue
-        a = corr_l[l]
-        b = math.sqrt(max(0.0, 1.0 - a * a))
-        c = torch.randn(n, generator=dg, device=device, dtype=torch.float32)
-        for i in range(K):
-            ni = torch.randn(n, generator=dg, device=device, dtype=torch.float32)
-            g = (c * a + ni * b) * scale_l[l]
-            grads[i][offs[l]:offs[l + 1]] = g.to(dtype)
+    # per-element multipliers of the shared and the private component
+    reps = torch.tensor([int(x) for x in sizes], dtype=torch.int64)
+    coef_c = torch.tensor([a * sc for a, sc in zip(corr_l, scale_l)], dtype=torch.float32)
+    coef_n = torch.tensor([math.sqrt(max(0.0, 1.0 - a * a)) * sc for a, sc in zip(corr_l, scale_l)],
+                          dtype=torch.float32)
+    coef_c = torch.repeat_interleave(coef_c, reps).to(device)
+    coef_n = torch.repeat_interleave(coef_n, reps).to(device)
+    shared = torch.randn(N, generator=dg, device=device, dtype=torch.float32) * coef_c
+    del coef_c
+    grads = []
+    for _ in range(K):
+        g = torch.randn(N, generator=dg, device=device, dtype=torch.float32)
+        g.mul_(coef_n).add_(shared)
+        grads.append(g.to(dtype) if dtype != torch.float32 else g)
+    del shared, coef_n
     return Workload(name, K, dtype, offs, grads,
                     {"corr": corr_l, "scale": scale_l, "kind": ["gauss"] * L})
 

@@ -58,7 +58,7 @@ def test_tiles_bert_large():
 def test_levels():
     assert B.plan_levels(1) == []
     assert B.plan_levels(2) == [2]
-    assert B.plan_levels(64) == [2] * 6
+    assert B.plan_levels(64) == [8, 8]
     assert B.plan_levels(64, 2) == [2] * 6
     assert B.plan_levels(64, 8) == [8, 8]
     assert B.plan_levels(64, 4) == [4, 4, 4]
