@@ -14,7 +14,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libadasum.so")
+# ADASUM_LIB overrides the library file (e.g. a build with other tuning knobs)
+LIB_PATH = os.environ.get("ADASUM_LIB") or os.path.join(HERE, "libadasum.so")
 
 F32, BF16 = 0, 1
 ORDER_TREE, ORDER_LINEAR = 0, 1

@@ -29,15 +29,15 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = True, extra_flags=()) -> str:
+def build_library(verbose: bool = True, extra_flags=(), out_path: str = LIB_PATH) -> str:
     cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-command-line-argument",
            *DEVICE_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra_flags]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB_PATH]
+    cmd += ["-o", out_path]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

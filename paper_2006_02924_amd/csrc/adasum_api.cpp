@@ -247,6 +247,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 
     int nodes = p->K;        // tree nodes alive before this pass
     int stride = 1;          // slot distance between consecutive alive nodes (passes >= 1)
+    int norm_sub = 1;        // parts per tile in the squared norms the previous combine left
     const int n_levels = static_cast<int>(p->radices.size());
     for (int lv = 0; lv < n_levels; ++lv) {
         const int R = p->radices[lv];
@@ -291,7 +292,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         // step 2: finish the sums, then the tree's scalars
         a.n_groups = groups;
         kernel_name("gram_finish", 0, 0, R, first, namebuf, sizeof(namebuf));
-        ADASUM_TIMED(namebuf, 0.0, stream, launch_gram_finish(first, a, partials, normparts, gram, stream));
+        ADASUM_TIMED(namebuf, 0.0, stream, launch_gram_finish(first, a, partials, normparts, norm_sub, gram, stream));
         if (first && o.layer_stats != nullptr) {
             ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, o.layer_stats + 1, 2, stream));
         }
@@ -299,6 +300,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         ADASUM_TIMED(namebuf, 0.0, stream,
                      launch_weights(gram, R, static_cast<int64_t>(groups) * L, o.order, weights, stream));
         // step 3: apply
+        const int sub = combine_parts_per_tile(in_dtype, st_dtype);
         for (int g0 = 0; g0 < groups; g0 += batch) {
             const int ng = std::min(batch, groups - g0);
             Operands ops;
@@ -327,10 +329,11 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
             ADASUM_TIMED(namebuf, comb_bytes_per_group * ng, stream,
                          launch_combine(in_dtype, st_dtype, ops, outs, a,
                                         weights + static_cast<int64_t>(g0) * L * R,
-                                        want_norm ? normparts + static_cast<int64_t>(g0) * T : nullptr, stream));
+                                        want_norm ? normparts + static_cast<int64_t>(g0) * T * sub : nullptr, stream));
         }
         stride = first ? 1 : R * stride;
         nodes = groups;
+        norm_sub = sub;
     }
     if (o.layer_stats != nullptr) {
         LevelArgs a;
@@ -340,7 +343,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         a.n_layers = L;
         a.n_groups = 1;
         a.R = 1;
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, norm_sub, a, o.layer_stats, 2, stream));
     }
     return ADASUM_OK;
 }
@@ -370,8 +373,9 @@ int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                  launch_combine(dtype, o.out_dtype, ops, outs, a, nullptr,
                                 o.layer_stats ? normparts : nullptr, stream));
     if (o.layer_stats != nullptr) {
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, o.layer_stats, 2, stream));
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, o.layer_stats + 1, 2, stream));
+        const int sub = combine_parts_per_tile(dtype, o.out_dtype);
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, sub, a, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, sub, a, o.layer_stats + 1, 2, stream));
     }
     return ADASUM_OK;
 }
@@ -487,7 +491,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     ops.use_pack = 1;
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
     ADASUM_LAUNCH(launch_gram(dtype, true, ops, a, partials, stream));
-    ADASUM_LAUNCH(launch_gram_finish(true, a, partials, nullptr, gram, stream));
+    ADASUM_LAUNCH(launch_gram_finish(true, a, partials, nullptr, 1, gram, stream));
     return ADASUM_OK;
 }
 
@@ -545,7 +549,8 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     outs.slot_bytes = 0;
     outs.stride = 0;
     ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, a, weights, sqnorm ? normparts : nullptr, stream));
-    if (sqnorm != nullptr) ADASUM_LAUNCH(launch_layer_sums(normparts, 1, a, sqnorm, 1, stream));
+    if (sqnorm != nullptr)
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, combine_parts_per_tile(dtype, out_dtype), a, sqnorm, 1, stream));
     return ADASUM_OK;
 }
 

@@ -13,8 +13,14 @@ namespace adasum {
 
 // Elements one workgroup covers at most.  A multiple of every granule
 // (4 fp32 or 8 bf16 elements per 16-byte access) times the workgroup size.
-constexpr int kTile = 16384;
-constexpr int kThreads = 256;
+#ifndef ADASUM_TILE
+#define ADASUM_TILE 16384
+#endif
+#ifndef ADASUM_THREADS
+#define ADASUM_THREADS 256
+#endif
+constexpr int kTile = ADASUM_TILE;
+constexpr int kThreads = ADASUM_THREADS;
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
 constexpr int kMaxRadix = 8;
@@ -53,7 +59,7 @@ struct Layout {
     int     n_layers = 0;
     size_t  off_slots = 0;    // n_slots x slot_elems floats
     size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
-    size_t  off_normparts = 0;// doubles [node][tile]: squared norm of every node a combine wrote
+    size_t  off_normparts = 0;// doubles [node][tile][part]: squared norm of every node a combine wrote
     size_t  off_gram = 0;     // doubles [group][layer][R*R] (finished Gram matrices)
     size_t  off_weights = 0;  // doubles [group][layer][R]
     size_t  off_leafnorm = 0; // doubles [layer]: sum over workers of the input squared norms
@@ -95,15 +101,19 @@ int launch_gram(int dtype, bool diag, const Operands& ops, const LevelArgs& a,
 // Sums the per-tile partials (and, when !diag, the carried squared norms of the
 // operand nodes) into full R x R Gram matrices gram[group][layer][R*R].
 int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials,
-                       const double* normparts, double* gram, void* stream);
+                       const double* normparts, int norm_sub, double* gram, void* stream);
+// Workgroups ("parts") a combine of these dtypes spends on one tile; the squared
+// norms it leaves are indexed [node][tile * parts + part].
+int combine_parts_per_tile(int dtype, int out_dtype);
+constexpr int kMaxCombineParts = 16;
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
 int launch_weights(const double* gram, int R, int64_t n_items, int order,
                    double* weights, void* stream);
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out,
                    const LevelArgs& a, const double* weights /* or null: unit weights */,
                    double* normparts /* [group][tile] or null */, void* stream);
-// layer_sum[l] (+)= sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
-int launch_layer_sums(const double* parts, int n_rows, const LevelArgs& a,
+// layer_sum[l] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile * sub + part].
+int launch_layer_sums(const double* parts, int n_rows, int sub, const LevelArgs& a,
                       double* layer_sum, int out_stride, void* stream);
 // leafnorm[l] = sum over groups of trace(gram[group][l]).
 int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers,

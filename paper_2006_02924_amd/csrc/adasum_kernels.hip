@@ -20,20 +20,36 @@
 
 #include "adasum_host.h"
 
+// Tuning knobs (compile-time): 16-byte loads a lane issues before consuming any,
+// and whether streaming loads / stores carry the non-temporal hint.
+#ifndef ADASUM_INFLIGHT
+#define ADASUM_INFLIGHT 8
+#endif
+#ifndef ADASUM_NT_LOAD
+#define ADASUM_NT_LOAD 1
+#endif
+#ifndef ADASUM_NT_STORE
+#define ADASUM_NT_STORE 1
+#endif
+#ifndef ADASUM_MIXED_G
+#define ADASUM_MIXED_G 0
+#endif
+// granule-steps one combine workgroup does (a tile has 8 or 16 of them)
+#ifndef ADASUM_COMBINE_IPW
+#define ADASUM_COMBINE_IPW 1
+#endif
+
 namespace adasum {
 namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 struct bf16_t { unsigned short v; };
 
 template <typename T> struct Traits;
 template <> struct Traits<float>  { static constexpr int VEC = 4; };
 template <> struct Traits<bf16_t> { static constexpr int VEC = 8; };
-
-__device__ __forceinline__ float bf16_bits_to_f32(unsigned int hi_aligned) {
-    return __uint_as_float(hi_aligned);
-}
 
 // round to nearest even; NaN stays NaN (quiet), overflow rounds to infinity
 __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
@@ -43,61 +59,101 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
     return u >> 16;
 }
 
-// G consecutive elements of T held as raw 16-byte quads
+// G consecutive elements of T held as raw 32-bit words (8, 16 or 32 bytes)
 template <typename T, int G>
 struct Granule {
-    static constexpr int NQ = G * (int)sizeof(T) / 16;
-    u32x4 q[NQ];
+    static constexpr int NW = G * (int)sizeof(T) / 4;
+    static_assert(NW == 2 || NW == 4 || NW == 8, "granule must be 8, 16 or 32 bytes");
+    unsigned int w[NW];
 };
 
+template <typename V>
+__device__ __forceinline__ V stream_load(const V* p) {
+#if ADASUM_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
+template <typename V>
+__device__ __forceinline__ void stream_store(V v, V* p) {
+#if ADASUM_NT_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// p must be aligned to the granule size (to 16 bytes for a 32-byte granule)
 template <typename T, int G>
 __device__ __forceinline__ void load_raw(Granule<T, G>& r, const T* p) {
-    const u32x4* s = reinterpret_cast<const u32x4*>(p);
+    constexpr int NW = Granule<T, G>::NW;
+    if constexpr (NW == 2) {
+        const u32x2 q = stream_load(reinterpret_cast<const u32x2*>(p));
+        r.w[0] = q.x;
+        r.w[1] = q.y;
+    } else {
 #pragma unroll
-    for (int i = 0; i < Granule<T, G>::NQ; ++i) r.q[i] = s[i];
+        for (int i = 0; i < NW / 4; ++i) {
+            const u32x4 q = stream_load(reinterpret_cast<const u32x4*>(p) + i);
+            r.w[4 * i + 0] = q.x;
+            r.w[4 * i + 1] = q.y;
+            r.w[4 * i + 2] = q.z;
+            r.w[4 * i + 3] = q.w;
+        }
+    }
 }
 
 template <int G>
 __device__ __forceinline__ void unpack(const Granule<float, G>& r, float (&v)[G]) {
 #pragma unroll
-    for (int i = 0; i < G / 4; ++i) {
-        v[4 * i + 0] = __uint_as_float(r.q[i].x);
-        v[4 * i + 1] = __uint_as_float(r.q[i].y);
-        v[4 * i + 2] = __uint_as_float(r.q[i].z);
-        v[4 * i + 3] = __uint_as_float(r.q[i].w);
+    for (int i = 0; i < G; ++i) v[i] = __uint_as_float(r.w[i]);
+}
+
+template <int G>
+__device__ __forceinline__ void unpack(const Granule<bf16_t, G>& r, float (&v)[G]) {
+#pragma unroll
+    for (int i = 0; i < G / 2; ++i) {
+        v[2 * i + 0] = __uint_as_float(r.w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(r.w[i] & 0xffff0000u);
     }
 }
 
-__device__ __forceinline__ void unpack(const Granule<bf16_t, 8>& r, float (&v)[8]) {
-    const unsigned int w[4] = {r.q[0].x, r.q[0].y, r.q[0].z, r.q[0].w};
+template <int NW>
+__device__ __forceinline__ void store_words(void* p, const unsigned int (&w)[NW]) {
+    if constexpr (NW == 2) {
+        u32x2 q;
+        q.x = w[0];
+        q.y = w[1];
+        stream_store(q, reinterpret_cast<u32x2*>(p));
+    } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        v[2 * i + 0] = __uint_as_float(w[i] << 16);
-        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        for (int i = 0; i < NW / 4; ++i) {
+            u32x4 q;
+            q.x = w[4 * i + 0];
+            q.y = w[4 * i + 1];
+            q.z = w[4 * i + 2];
+            q.w = w[4 * i + 3];
+            stream_store(q, reinterpret_cast<u32x4*>(p) + i);
+        }
     }
 }
 
 template <int G>
 __device__ __forceinline__ void store_granule(float* p, const float (&v)[G]) {
-    u32x4* d = reinterpret_cast<u32x4*>(p);
+    unsigned int w[G];
 #pragma unroll
-    for (int i = 0; i < G / 4; ++i) {
-        u32x4 q;
-        q.x = __float_as_uint(v[4 * i + 0]);
-        q.y = __float_as_uint(v[4 * i + 1]);
-        q.z = __float_as_uint(v[4 * i + 2]);
-        q.w = __float_as_uint(v[4 * i + 3]);
-        d[i] = q;
-    }
+    for (int i = 0; i < G; ++i) w[i] = __float_as_uint(v[i]);
+    store_words(p, w);
 }
 
-__device__ __forceinline__ void store_granule(bf16_t* p, const float (&v)[8]) {
-    u32x4 q;
-    q.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
-    q.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
-    q.z = f32_to_bf16_rne(v[4]) | (f32_to_bf16_rne(v[5]) << 16);
-    q.w = f32_to_bf16_rne(v[6]) | (f32_to_bf16_rne(v[7]) << 16);
-    *reinterpret_cast<u32x4*>(p) = q;
+template <int G>
+__device__ __forceinline__ void store_granule(bf16_t* p, const float (&v)[G]) {
+    unsigned int w[G / 2];
+#pragma unroll
+    for (int i = 0; i < G / 2; ++i) w[i] = f32_to_bf16_rne(v[2 * i]) | (f32_to_bf16_rne(v[2 * i + 1]) << 16);
+    store_words(p, w);
 }
 
 __device__ __forceinline__ float load_elem(const float* p) { return *p; }
@@ -162,7 +218,8 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     constexpr int G = Traits<T>::VEC;
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
     constexpr int ITERS = kTile / G / kThreads;
-    constexpr int U = (R * (G * (int)sizeof(T) / 16) >= 8) ? 1 : (8 / R);   // granule-steps loaded ahead
+    constexpr int U0 = (R >= ADASUM_INFLIGHT) ? 1 : (ADASUM_INFLIGHT / R);   // granule-steps loaded ahead
+    constexpr int U = U0 > ITERS ? ITERS : U0;
     static_assert(ITERS % U == 0, "unroll must divide the trip count");
 
     const int tid = threadIdx.x;
@@ -279,7 +336,7 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
 
 template <int R, bool DIAG>
 __global__ void __launch_bounds__(kThreads)
-gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts,
+gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts, int norm_sub,
                    const int32_t* __restrict__ layer_tile_begin, int n_tiles, int n_layers,
                    double* __restrict__ gram) {
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
@@ -306,9 +363,9 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
     }
     if (!DIAG) {
         for (int i = 0; i < R; ++i) {
-            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_tiles;
+            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_tiles * norm_sub;
             double v = 0.0;
-            for (int t = tb + tid; t < te; t += kThreads) v += row[t];
+            for (int t = tb * norm_sub + tid; t < te * norm_sub; t += kThreads) v += row[t];
             v = block_sum(v, sh);
             if (tid == 0) out[i * R + i] = v;
         }
@@ -356,23 +413,45 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, do
 }
 
 // ---------------------------------------------------------------------------
-// Step 3: out = sum_r w_r x_r per element, squared norm of the result per tile.
-// normparts[group * n_tiles + tile].  `weights == nullptr` means unit weights.
+// Step 3: out = sum_r w_r x_r per element, squared norm of the result per part.
+// A tile is split over CombineShape::SUB workgroups ("parts"), each doing IPW
+// consecutive granule-steps: short-lived workgroups that walk memory in launch
+// order keep the mixed read/write stream close to sequential, which is worth
+// ~10 % of bandwidth over one long-lived workgroup per tile.
+// normparts[(group * n_tiles + tile) * SUB + part].  weights == nullptr: unit weights.
 // ---------------------------------------------------------------------------
+template <typename TI, typename TO>
+struct CombineShape {
+    // one 16-byte load per lane, operand and step: lanes read consecutive addresses
+    static constexpr int G = ADASUM_MIXED_G == 0 ? 16 / (int)sizeof(TI)
+                           : ADASUM_MIXED_G == 8 ? ((sizeof(TI) == 2 || sizeof(TO) == 2) ? 8 : 4)
+                                                 : ((sizeof(TI) == 2 && sizeof(TO) == 2) ? 8 : 4);
+    static constexpr int ITERS = kTile / G / kThreads;
+    static constexpr int IPW = ADASUM_COMBINE_IPW < ITERS ? ADASUM_COMBINE_IPW : ITERS;
+    static constexpr int SUB = ITERS / IPW;
+    static_assert(ITERS % IPW == 0, "steps per workgroup must divide the tile");
+    static_assert(SUB <= kMaxCombineParts, "workspace is sized for at most kMaxCombineParts parts per tile");
+};
+
 template <typename TI, typename TO, int R>
 __global__ void __launch_bounds__(kThreads)
 combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
                int n_tiles, int n_layers, const double* __restrict__ weights,
                double* __restrict__ normparts) {
-    constexpr int G = (sizeof(TI) == 2 || sizeof(TO) == 2) ? 8 : 4;
-    constexpr int ITERS = kTile / G / kThreads;
-    constexpr int NQ = Granule<TI, G>::NQ;
-    constexpr int U = (R * NQ >= 8) ? 1 : (8 / (R * NQ));
-    static_assert(ITERS % U == 0, "unroll must divide the trip count");
+    using Shape = CombineShape<TI, TO>;
+    constexpr int G = Shape::G;
+    constexpr int IPW = Shape::IPW;
+    constexpr int SUB = Shape::SUB;
+    constexpr int STEP_BYTES = R * G * (int)sizeof(TI);
+    constexpr int U0 = (STEP_BYTES >= 16 * ADASUM_INFLIGHT) ? 1 : (16 * ADASUM_INFLIGHT / STEP_BYTES);
+    constexpr int U = U0 > IPW ? IPW : U0;
+    static_assert(IPW % U == 0, "unroll must divide the trip count");
 
     const int tid = threadIdx.x;
-    const int tile_id = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_tiles));
-    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_tiles));
+    const unsigned part_tile = blockIdx.x / SUB;
+    const int part = static_cast<int>(blockIdx.x % SUB);
+    const int tile_id = static_cast<int>(part_tile % static_cast<unsigned>(n_tiles));
+    const int g = static_cast<int>(part_tile / static_cast<unsigned>(n_tiles));
     const adasum_tile t = tiles[tile_id];
     const Split s = split_tile<G>(t);
 
@@ -412,23 +491,26 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         store_granule(out + idx, z);
     };
 
+    // this part's granule steps: [part * IPW, (part + 1) * IPW) of the tile
+    const int step0 = part * IPW;
     if (s.ng == kTile / G) {
-        for (int it0 = 0; it0 < ITERS; it0 += U) {
+        for (int it0 = 0; it0 < IPW; it0 += U) {
             Granule<TI, G> raw[U][R];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const long long idx = s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G;
+                const long long idx = s.bs + (static_cast<long long>(step0 + it0 + u) * kThreads + tid) * G;
 #pragma unroll
                 for (int r = 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const long long idx = s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G;
+                const long long idx = s.bs + (static_cast<long long>(step0 + it0 + u) * kThreads + tid) * G;
                 emit(raw[u], idx);
             }
         }
     } else {
-        for (int j = tid; j < s.ng; j += kThreads) {
+        const int jend = (step0 + IPW) * kThreads < s.ng ? (step0 + IPW) * kThreads : s.ng;
+        for (int j = step0 * kThreads + tid; j < jend; j += kThreads) {
             Granule<TI, G> raw[R];
             const long long idx = s.bs + static_cast<long long>(j) * G;
 #pragma unroll
@@ -436,9 +518,10 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
             emit(raw, idx);
         }
     }
-    // ragged head/tail elements: fp64 arithmetic, one rounding at the store
+
+    // ragged head/tail elements (part 0 only): fp64 arithmetic, one rounding at the store
     const int lane = tid & 63, wave = tid >> 6;
-    const int nedge = s.nh + s.nt;
+    const int nedge = part == 0 ? s.nh + s.nt : 0;
     double enorm = 0.0;
     if (nedge > 0 && wave == 0) {
         if (lane < nedge) {
@@ -453,7 +536,11 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         if (normparts != nullptr) enorm = wave_sum(enorm);
     }
 
+#ifdef ADASUM_TIMING_ONLY_SKIP_NORM
+    if (false) {
+#else
     if (normparts != nullptr) {
+#endif
         __shared__ double sh[kThreads / 64];
         const float ws = wave_sum(nacc);
         if (lane == 0) sh[wave] = static_cast<double>(ws);
@@ -463,7 +550,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 #pragma unroll
             for (int k = 1; k < kThreads / 64; ++k) tot += sh[k];
             if (nedge > 0) tot += enorm;
-            normparts[static_cast<long long>(g) * n_tiles + tile_id] = tot;
+            normparts[(static_cast<long long>(g) * n_tiles + tile_id) * SUB + part] = tot;
         }
     }
 }
@@ -473,7 +560,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 // ---------------------------------------------------------------------------
 // out[l * out_stride] = sum over rows and the tiles of layer l of parts[row][tile]
 __global__ void __launch_bounds__(kThreads)
-layer_sums_kernel(const double* __restrict__ parts, int n_rows,
+layer_sums_kernel(const double* __restrict__ parts, int n_rows, int sub,
                   const int32_t* __restrict__ layer_tile_begin, int n_tiles,
                   double* __restrict__ out, int out_stride) {
     __shared__ double sh[kThreads / 64];
@@ -481,8 +568,8 @@ layer_sums_kernel(const double* __restrict__ parts, int n_rows,
     const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
     double v = 0.0;
     for (int r = 0; r < n_rows; ++r) {
-        const double* row = parts + static_cast<long long>(r) * n_tiles;
-        for (int t = tb + threadIdx.x; t < te; t += kThreads) v += row[t];
+        const double* row = parts + static_cast<long long>(r) * n_tiles * sub;
+        for (int t = tb * sub + threadIdx.x; t < te * sub; t += kThreads) v += row[t];
     }
     v = block_sum(v, sh);
     if (threadIdx.x == 0) out[static_cast<long long>(l) * out_stride] = v;
@@ -524,7 +611,7 @@ int launch_gram_r(const Operands& ops, const LevelArgs& a, double* partials, hip
 template <typename TI, typename TO>
 int launch_combine_r(const Operands& ops, const Outputs& outs, const LevelArgs& a, const double* weights,
                      double* normparts, hipStream_t st) {
-    const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups);
+    const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups) * CombineShape<TI, TO>::SUB;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const int nt = static_cast<int>(a.n_tiles);
@@ -555,8 +642,14 @@ int launch_gram(int dtype, bool diag, const Operands& ops, const LevelArgs& a, d
                 : launch_gram_r<float, false>(ops, a, partials, st);
 }
 
+int combine_parts_per_tile(int dtype, int out_dtype) {
+    if (dtype == ADASUM_BF16)
+        return out_dtype == ADASUM_BF16 ? CombineShape<bf16_t, bf16_t>::SUB : CombineShape<bf16_t, float>::SUB;
+    return out_dtype == ADASUM_BF16 ? CombineShape<float, bf16_t>::SUB : CombineShape<float, float>::SUB;
+}
+
 int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials, const double* normparts,
-                       double* gram, void* stream) {
+                       int norm_sub, double* gram, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const long long blocks = static_cast<long long>(a.n_groups) * a.n_layers;
     if (blocks == 0) return 0;
@@ -565,7 +658,7 @@ int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials, co
     const int nt = static_cast<int>(a.n_tiles);
 #define ADASUM_FINISH(RR, DD)                                                                      \
     hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
-                       a.layer_tile_begin, nt, a.n_layers, gram)
+                       norm_sub, a.layer_tile_begin, nt, a.n_layers, gram)
     switch (a.R) {
         case 2: if (diag) ADASUM_FINISH(2, true); else ADASUM_FINISH(2, false); break;
         case 4: if (diag) ADASUM_FINISH(4, true); else ADASUM_FINISH(4, false); break;
@@ -604,11 +697,11 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
                                     : launch_combine_r<float, float>(ops, out, a, weights, normparts, st);
 }
 
-int launch_layer_sums(const double* parts, int n_rows, const LevelArgs& a, double* layer_sum, int out_stride,
-                      void* stream) {
+int launch_layer_sums(const double* parts, int n_rows, int sub, const LevelArgs& a, double* layer_sum,
+                      int out_stride, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_layers == 0) return 0;
-    hipLaunchKernelGGL(layer_sums_kernel, dim3(a.n_layers), dim3(kThreads), 0, st, parts, n_rows,
+    hipLaunchKernelGGL(layer_sums_kernel, dim3(a.n_layers), dim3(kThreads), 0, st, parts, n_rows, sub,
                        a.layer_tile_begin, static_cast<int>(a.n_tiles), layer_sum, out_stride);
     return check_launch();
 }

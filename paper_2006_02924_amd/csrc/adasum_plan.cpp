@@ -82,7 +82,7 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, const std::v
     lay.off_partials = off;
     off = align_up(off + max_partials * sizeof(double), 256);
     lay.off_normparts = off;
-    off = align_up(off + max_nodes * static_cast<size_t>(n_tiles) * sizeof(double), 256);
+    off = align_up(off + max_nodes * static_cast<size_t>(n_tiles) * kMaxCombineParts * sizeof(double), 256);
     lay.off_gram = off;
     off = align_up(off + max_gram * sizeof(double), 256);
     lay.off_weights = off;
