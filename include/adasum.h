@@ -161,15 +161,17 @@ typedef struct adasum_tile {
     int32_t layer;
 } adasum_tile;
 
-/* Elements one workgroup covers at most (tile boundaries fall on global
- * multiples of it and on layer boundaries). */
+/* Elements one workgroup of the Gram pass covers at most.  (The combine pass
+ * uses finer tables of 256 x 4 or 256 x 8 elements: one 16-byte load per lane.) */
 int adasum_tile_capacity(void);
 
-/* Writes the tile table for a layer table.  *n_tiles receives the number of
- * tiles; at most `cap` entries are written to `tiles` (tiles may be NULL with
- * cap = 0 to query the count).  Tiles are ordered by start; empty layers get
- * no tile. */
-int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers,
+/* Writes the tile table for a layer table: consecutive runs of at most
+ * `capacity` elements (0 = adasum_tile_capacity()) whose boundaries fall on
+ * global multiples of the capacity and on layer boundaries, so a tile never
+ * crosses a layer.  *n_tiles receives the number of tiles; at most `cap` entries
+ * are written to `tiles` (tiles may be NULL with cap = 0 to query the count).
+ * Tiles are ordered by start; empty layers get no tile. */
+int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
                       adasum_tile* tiles, int64_t cap, int64_t* n_tiles);
 
 /* Writes the radix of every pass for K workers (their product is K), e.g.

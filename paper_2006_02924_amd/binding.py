@@ -87,7 +87,7 @@ def load() -> C.CDLL:
     lib.adasum_group_combine.argtypes = [pp, C.c_int, i64p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                          C.c_int, C.c_void_p, C.c_void_p]
     lib.adasum_tile_capacity.argtypes = []
-    lib.adasum_plan_tiles.argtypes = [i64p, C.c_int, C.POINTER(Tile), C.c_int64, i64p]
+    lib.adasum_plan_tiles.argtypes = [i64p, C.c_int, C.c_int64, C.POINTER(Tile), C.c_int64, i64p]
     lib.adasum_plan_levels.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int, C.POINTER(C.c_int)]
     lib.adasum_profile_enable.argtypes = [C.c_int]
     lib.adasum_profile_collect.argtypes = [C.POINTER(KernelProfile), C.c_int, C.POINTER(C.c_int)]
@@ -265,14 +265,15 @@ def tile_capacity() -> int:
     return int(load().adasum_tile_capacity())
 
 
-def plan_tiles(layer_offsets: Sequence[int]) -> np.ndarray:
-    """Tile table as a structured array with fields start, len, layer."""
+def plan_tiles(layer_offsets: Sequence[int], capacity: int = 0) -> np.ndarray:
+    """Tile table (capacity 0 = the Gram pass's) as a structured array with
+    fields start, len, layer."""
     lib = load()
     offs, L = _offsets(layer_offsets)
     n = C.c_int64(0)
-    check(lib.adasum_plan_tiles(offs, L, None, 0, C.byref(n)))
+    check(lib.adasum_plan_tiles(offs, L, capacity, None, 0, C.byref(n)))
     buf = (Tile * max(1, n.value))()
-    check(lib.adasum_plan_tiles(offs, L, buf, n.value, C.byref(n)))
+    check(lib.adasum_plan_tiles(offs, L, capacity, buf, n.value, C.byref(n)))
     arr = np.frombuffer(buf, dtype=np.dtype([("start", "<i8"), ("len", "<i4"), ("layer", "<i4")]),
                         count=n.value)
     return arr.copy()

@@ -86,22 +86,56 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
 
 // ---- plans -------------------------------------------------------------------
 
+// One tile table on the host and on the device.
+struct TileTable {
+    std::vector<adasum_tile> tiles;
+    std::vector<int32_t> layer_begin;
+    adasum_tile* d_tiles = nullptr;
+    int32_t* d_layer_begin = nullptr;
+
+    TileSet view() const {
+        TileSet t;
+        t.tiles = d_tiles;
+        t.layer_begin = d_layer_begin;
+        t.n_tiles = static_cast<int64_t>(tiles.size());
+        return t;
+    }
+    int upload() {
+        if (!tiles.empty()) {
+            ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&d_tiles), tiles.size() * sizeof(adasum_tile)));
+            ADASUM_HIP(hipMemcpy(d_tiles, tiles.data(), tiles.size() * sizeof(adasum_tile), hipMemcpyHostToDevice));
+        }
+        ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&d_layer_begin), layer_begin.size() * sizeof(int32_t)));
+        ADASUM_HIP(hipMemcpy(d_layer_begin, layer_begin.data(), layer_begin.size() * sizeof(int32_t),
+                             hipMemcpyHostToDevice));
+        return ADASUM_OK;
+    }
+    void release() {
+        if (d_tiles) (void)hipFree(d_tiles);
+        if (d_layer_begin) (void)hipFree(d_layer_begin);
+        d_tiles = nullptr;
+        d_layer_begin = nullptr;
+    }
+};
+
 struct Plan {
     int device = 0;
     int K = 0;
     int radix = 0;
     std::vector<int64_t> offsets;
-    std::vector<adasum_tile> tiles;
-    std::vector<int32_t> layer_tile_begin;
+    TileTable gram_tiles;        // capacity kTile
+    TileTable comb_tiles_f32;    // capacity combine_tile_capacity(ADASUM_F32)
+    TileTable comb_tiles_bf16;   // capacity combine_tile_capacity(ADASUM_BF16)
     std::vector<int> radices;
     Layout lay;
-    adasum_tile* d_tiles = nullptr;
-    int32_t* d_ltb = nullptr;
     char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
 
+    const TileTable& comb_tiles(int dtype) const { return dtype == ADASUM_BF16 ? comb_tiles_bf16 : comb_tiles_f32; }
+
     ~Plan() {
-        if (d_tiles) (void)hipFree(d_tiles);
-        if (d_ltb) (void)hipFree(d_ltb);
+        gram_tiles.release();
+        comb_tiles_f32.release();
+        comb_tiles_bf16.release();
         if (d_ws) (void)hipFree(d_ws);
     }
 };
@@ -127,21 +161,22 @@ int find_or_make_plan(int K, int radix, const int64_t* offsets, int n_layers, Pl
         p->K = K;
         p->radix = radix;
         p->offsets.assign(offsets, offsets + n_layers + 1);
-        build_tiles(offsets, n_layers, p->tiles, p->layer_tile_begin);
+        build_tiles(offsets, n_layers, kTile, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
+        build_tiles(offsets, n_layers, combine_tile_capacity(ADASUM_F32), p->comb_tiles_f32.tiles,
+                    p->comb_tiles_f32.layer_begin);
+        build_tiles(offsets, n_layers, combine_tile_capacity(ADASUM_BF16), p->comb_tiles_bf16.tiles,
+                    p->comb_tiles_bf16.layer_begin);
         int rc = build_levels(K, radix, p->radices);
         if (rc != ADASUM_OK) return rc;
-        p->lay = make_layout(K, offsets[n_layers], n_layers, static_cast<int64_t>(p->tiles.size()), p->radices);
+        p->lay = make_layout(K, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
+                             static_cast<int64_t>(p->comb_tiles_f32.tiles.size()), p->radices);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
-    if (!p->tiles.empty()) {
-        ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_tiles), p->tiles.size() * sizeof(adasum_tile)));
-        ADASUM_HIP(hipMemcpy(p->d_tiles, p->tiles.data(), p->tiles.size() * sizeof(adasum_tile),
-                             hipMemcpyHostToDevice));
-    }
-    ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_ltb), p->layer_tile_begin.size() * sizeof(int32_t)));
-    ADASUM_HIP(hipMemcpy(p->d_ltb, p->layer_tile_begin.data(), p->layer_tile_begin.size() * sizeof(int32_t),
-                         hipMemcpyHostToDevice));
+    int rc = p->gram_tiles.upload();
+    if (rc == ADASUM_OK) rc = p->comb_tiles_f32.upload();
+    if (rc == ADASUM_OK) rc = p->comb_tiles_bf16.upload();
+    if (rc != ADASUM_OK) return rc;
     *out = p.get();
     g_plans.push_back(std::move(p));
     return ADASUM_OK;
@@ -236,7 +271,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     const Layout& lay = p->lay;
     const int L = lay.n_layers;
     const int64_t N = lay.N;
-    const int64_t T = lay.n_tiles;
+    const TileSet gt = p->gram_tiles.view();
+    const int64_t T = gt.n_tiles;
     char* slots = ws + lay.off_slots;
     double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
@@ -247,7 +283,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 
     int nodes = p->K;        // tree nodes alive before this pass
     int stride = 1;          // slot distance between consecutive alive nodes (passes >= 1)
-    int norm_sub = 1;        // parts per tile in the squared norms the previous combine left
+    TileSet norm_tiles;      // the table the previous combine indexed its squared norms by
     const int n_levels = static_cast<int>(p->radices.size());
     for (int lv = 0; lv < n_levels; ++lv) {
         const int R = p->radices[lv];
@@ -257,42 +293,35 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         const int st_dtype = last ? o.out_dtype : ADASUM_F32;
         const int np = gram_entries(R, first);
         const bool want_norm = !last || o.layer_stats != nullptr;
+        const TileSet ct = p->comb_tiles(in_dtype).view();
 
-        LevelArgs a;
-        a.tiles = p->d_tiles;
-        a.layer_tile_begin = p->d_ltb;
-        a.n_tiles = T;
-        a.n_layers = L;
-        a.R = R;
-
-        // groups per launch: explicit operand pointers travel by value
-        const int batch = first ? std::max(1, kMaxPack / R) : groups;
+        // groups per launch: the operand pointers travel by value in the kernel arguments
+        const int batch = std::max(1, kMaxPack / R);
         const double gram_bytes_per_group = static_cast<double>(R) * N * elem_bytes(in_dtype);
         const double comb_bytes_per_group =
             static_cast<double>(N) * (static_cast<double>(R) * elem_bytes(in_dtype) + elem_bytes(st_dtype));
+
+        auto fill_operands = [&](Operands& ops, int g0, int ng) {
+            std::memset(&ops, 0, sizeof(ops));
+            for (int i = 0; i < ng * R; ++i)
+                ops.pack[i] = first ? grads[g0 * R + i]
+                                    : slots + static_cast<long long>(g0 * R + i) * stride * slot_bytes;
+        };
 
         // step 1: partial Gram entries
         for (int g0 = 0; g0 < groups; g0 += batch) {
             const int ng = std::min(batch, groups - g0);
             Operands ops;
-            std::memset(&ops, 0, sizeof(ops));
-            if (first) {
-                ops.use_pack = 1;
-                for (int i = 0; i < ng * R; ++i) ops.pack[i] = grads[g0 * R + i];
-            } else {
-                ops.base = slots;
-                ops.slot_bytes = slot_bytes;
-                ops.stride = stride;
-            }
-            a.n_groups = ng;
+            fill_operands(ops, g0, ng);
             kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
             ADASUM_TIMED(namebuf, gram_bytes_per_group * ng, stream,
-                         launch_gram(in_dtype, first, ops, a, partials + static_cast<int64_t>(g0) * np * T, stream));
+                         launch_gram(in_dtype, first, ops, gt, ng, R, partials + static_cast<int64_t>(g0) * np * T,
+                                     stream));
         }
         // step 2: finish the sums, then the tree's scalars
-        a.n_groups = groups;
         kernel_name("gram_finish", 0, 0, R, first, namebuf, sizeof(namebuf));
-        ADASUM_TIMED(namebuf, 0.0, stream, launch_gram_finish(first, a, partials, normparts, norm_sub, gram, stream));
+        ADASUM_TIMED(namebuf, 0.0, stream,
+                     launch_gram_finish(first, gt, norm_tiles, L, groups, R, partials, normparts, gram, stream));
         if (first && o.layer_stats != nullptr) {
             ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, o.layer_stats + 1, 2, stream));
         }
@@ -300,19 +329,10 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         ADASUM_TIMED(namebuf, 0.0, stream,
                      launch_weights(gram, R, static_cast<int64_t>(groups) * L, o.order, weights, stream));
         // step 3: apply
-        const int sub = combine_parts_per_tile(in_dtype, st_dtype);
         for (int g0 = 0; g0 < groups; g0 += batch) {
             const int ng = std::min(batch, groups - g0);
             Operands ops;
-            std::memset(&ops, 0, sizeof(ops));
-            if (first) {
-                ops.use_pack = 1;
-                for (int i = 0; i < ng * R; ++i) ops.pack[i] = grads[g0 * R + i];
-            } else {
-                ops.base = slots;
-                ops.slot_bytes = slot_bytes;
-                ops.stride = stride;
-            }
+            fill_operands(ops, g0, ng);
             Outputs outs;
             if (last) {
                 outs.base = static_cast<char*>(out);
@@ -324,26 +344,19 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                 outs.slot_bytes = slot_bytes;
                 outs.stride = ostride;
             }
-            a.n_groups = ng;
             kernel_name("combine", in_dtype, st_dtype, R, false, namebuf, sizeof(namebuf));
             ADASUM_TIMED(namebuf, comb_bytes_per_group * ng, stream,
-                         launch_combine(in_dtype, st_dtype, ops, outs, a,
+                         launch_combine(in_dtype, st_dtype, ops, outs, ct, L, ng, R,
                                         weights + static_cast<int64_t>(g0) * L * R,
-                                        want_norm ? normparts + static_cast<int64_t>(g0) * T * sub : nullptr, stream));
+                                        want_norm ? normparts + static_cast<int64_t>(g0) * ct.n_tiles : nullptr,
+                                        stream));
         }
         stride = first ? 1 : R * stride;
         nodes = groups;
-        norm_sub = sub;
+        norm_tiles = ct;
     }
     if (o.layer_stats != nullptr) {
-        LevelArgs a;
-        a.tiles = p->d_tiles;
-        a.layer_tile_begin = p->d_ltb;
-        a.n_tiles = T;
-        a.n_layers = L;
-        a.n_groups = 1;
-        a.R = 1;
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, norm_sub, a, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, norm_tiles, L, o.layer_stats, 2, stream));
     }
     return ADASUM_OK;
 }
@@ -352,16 +365,9 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
     const Layout& lay = p->lay;
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
-    LevelArgs a;
-    a.tiles = p->d_tiles;
-    a.layer_tile_begin = p->d_ltb;
-    a.n_tiles = lay.n_tiles;
-    a.n_layers = lay.n_layers;
-    a.n_groups = 1;
-    a.R = 1;
+    const TileSet ct = p->comb_tiles(dtype).view();
     Operands ops;
     std::memset(&ops, 0, sizeof(ops));
-    ops.use_pack = 1;
     ops.pack[0] = grads[0];
     Outputs outs;
     outs.base = static_cast<char*>(out);
@@ -370,12 +376,11 @@ int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     char namebuf[48];
     kernel_name("combine", dtype, o.out_dtype, 1, false, namebuf, sizeof(namebuf));
     ADASUM_TIMED(namebuf, static_cast<double>(lay.N) * (elem_bytes(dtype) + elem_bytes(o.out_dtype)), stream,
-                 launch_combine(dtype, o.out_dtype, ops, outs, a, nullptr,
+                 launch_combine(dtype, o.out_dtype, ops, outs, ct, lay.n_layers, 1, 1, nullptr,
                                 o.layer_stats ? normparts : nullptr, stream));
     if (o.layer_stats != nullptr) {
-        const int sub = combine_parts_per_tile(dtype, o.out_dtype);
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, sub, a, o.layer_stats, 2, stream));
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, sub, a, o.layer_stats + 1, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, ct, lay.n_layers, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, ct, lay.n_layers, o.layer_stats + 1, 2, stream));
     }
     return ADASUM_OK;
 }
@@ -443,11 +448,12 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
         std::vector<int> radices;
         rc = build_levels(K, o.radix, radices);
         if (rc != ADASUM_OK) return rc;
-        std::vector<adasum_tile> tiles;
+        std::vector<adasum_tile> tiles, ctiles;
         std::vector<int32_t> ltb;
-        build_tiles(layer_offsets, n_layers, tiles, ltb);
-        const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers,
-                                       static_cast<int64_t>(tiles.size()), radices);
+        build_tiles(layer_offsets, n_layers, kTile, tiles, ltb);
+        build_tiles(layer_offsets, n_layers, combine_tile_capacity(ADASUM_F32), ctiles, ltb);
+        const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers, static_cast<int64_t>(tiles.size()),
+                                       static_cast<int64_t>(ctiles.size()), radices);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -479,19 +485,12 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
     double* partials = reinterpret_cast<double*>(ws + p->lay.off_partials);
-    LevelArgs a;
-    a.tiles = p->d_tiles;
-    a.layer_tile_begin = p->d_ltb;
-    a.n_tiles = p->lay.n_tiles;
-    a.n_layers = n_layers;
-    a.n_groups = 1;
-    a.R = R;
+    const TileSet gt = p->gram_tiles.view();
     Operands ops;
     std::memset(&ops, 0, sizeof(ops));
-    ops.use_pack = 1;
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
-    ADASUM_LAUNCH(launch_gram(dtype, true, ops, a, partials, stream));
-    ADASUM_LAUNCH(launch_gram_finish(true, a, partials, nullptr, 1, gram, stream));
+    ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, stream));
+    ADASUM_LAUNCH(launch_gram_finish(true, gt, TileSet(), n_layers, 1, R, partials, nullptr, gram, stream));
     return ADASUM_OK;
 }
 
@@ -533,38 +532,33 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
     double* normparts = reinterpret_cast<double*>(ws + p->lay.off_normparts);
-    LevelArgs a;
-    a.tiles = p->d_tiles;
-    a.layer_tile_begin = p->d_ltb;
-    a.n_tiles = p->lay.n_tiles;
-    a.n_layers = n_layers;
-    a.n_groups = 1;
-    a.R = R;
+    const TileSet ct = p->comb_tiles(dtype).view();
     Operands ops;
     std::memset(&ops, 0, sizeof(ops));
-    ops.use_pack = 1;
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
     Outputs outs;
     outs.base = static_cast<char*>(out);
     outs.slot_bytes = 0;
     outs.stride = 0;
-    ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, a, weights, sqnorm ? normparts : nullptr, stream));
-    if (sqnorm != nullptr)
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, combine_parts_per_tile(dtype, out_dtype), a, sqnorm, 1, stream));
+    ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, ct, n_layers, 1, R, weights,
+                                 sqnorm ? normparts : nullptr, stream));
+    if (sqnorm != nullptr) ADASUM_LAUNCH(launch_layer_sums(normparts, 1, ct, n_layers, sqnorm, 1, stream));
     return ADASUM_OK;
 }
 
 int adasum_tile_capacity(void) { return kTile; }
 
-int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, adasum_tile* tiles, int64_t cap,
-                      int64_t* n_tiles) {
+int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity, adasum_tile* tiles,
+                      int64_t cap, int64_t* n_tiles) {
     if (n_tiles == nullptr || cap < 0 || (tiles == nullptr && cap > 0)) return ADASUM_ERR_INVALID_ARG;
+    if (capacity == 0) capacity = kTile;
+    if (capacity < 1 || capacity > 0x7fffffff) return ADASUM_ERR_INVALID_ARG;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
     try {
         std::vector<adasum_tile> t;
         std::vector<int32_t> ltb;
-        build_tiles(layer_offsets, n_layers, t, ltb);
+        build_tiles(layer_offsets, n_layers, capacity, t, ltb);
         *n_tiles = static_cast<int64_t>(t.size());
         const int64_t n = std::min<int64_t>(cap, static_cast<int64_t>(t.size()));
         for (int64_t i = 0; i < n; ++i) tiles[i] = t[i];

@@ -11,16 +11,21 @@
 
 namespace adasum {
 
-// Elements one workgroup covers at most.  A multiple of every granule
-// (4 fp32 or 8 bf16 elements per 16-byte access) times the workgroup size.
+// Elements one Gram workgroup covers at most (a long tile amortises the
+// workgroup's start-up and its 36-value reduction).  A multiple of every
+// granule (4 fp32 or 8 bf16 elements per 16-byte access) times the workgroup size.
 #ifndef ADASUM_TILE
-#define ADASUM_TILE 16384
+#define ADASUM_TILE 65536
 #endif
 #ifndef ADASUM_THREADS
 #define ADASUM_THREADS 256
 #endif
 constexpr int kTile = ADASUM_TILE;
 constexpr int kThreads = ADASUM_THREADS;
+// A combine workgroup covers one 16-byte load per lane and operand: short-lived
+// workgroups that walk memory in launch order keep the mixed read/write stream
+// close to sequential.  Its tile capacity therefore depends on the input type.
+inline int combine_tile_capacity(int dtype) { return kThreads * (dtype == ADASUM_BF16 ? 8 : 4); }
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
 constexpr int kMaxRadix = 8;
@@ -36,9 +41,9 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Validates a layer table; returns ADASUM_OK or an error code.
 int check_layer_table(const int64_t* layer_offsets, int n_layers);
 
-// Tile table: boundaries at layer boundaries and at global multiples of kTile.
+// Tile table: boundaries at layer boundaries and at global multiples of `capacity`.
 // layer_tile_begin[l] .. layer_tile_begin[l+1] are the tiles of layer l.
-void build_tiles(const int64_t* layer_offsets, int n_layers,
+void build_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
                  std::vector<adasum_tile>& tiles, std::vector<int32_t>& layer_tile_begin);
 
 // Radix of every pass; product equals K.  Largest radices first (the first pass
@@ -55,28 +60,27 @@ struct Layout {
     int64_t N = 0;            // elements per gradient
     int64_t slot_elems = 0;   // N rounded up so that fp32 slots stay 256-byte aligned
     int64_t n_slots = 0;      // fp32 intermediate tree nodes after the first pass
-    int64_t n_tiles = 0;
+    int64_t n_tiles = 0;      // Gram tiles
+    int64_t n_ctiles = 0;     // combine tiles of the finest table (fp32 input)
     int     n_layers = 0;
     size_t  off_slots = 0;    // n_slots x slot_elems floats
     size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
-    size_t  off_normparts = 0;// doubles [node][tile][part]: squared norm of every node a combine wrote
+    size_t  off_normparts = 0;// doubles [node][combine tile]: squared norm of every node a combine wrote
     size_t  off_gram = 0;     // doubles [group][layer][R*R] (finished Gram matrices)
     size_t  off_weights = 0;  // doubles [group][layer][R]
     size_t  off_leafnorm = 0; // doubles [layer]: sum over workers of the input squared norms
     size_t  total = 0;
 };
-Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, const std::vector<int>& radices);
+Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t n_ctiles,
+                   const std::vector<int>& radices);
 
 // ---- kernel launchers (adasum_kernels.hip) -----------------------------------
 
-// How a kernel finds operand r of group g: either an explicit pointer
-// (index g*R + r into `pack`), or slot (g*R + r)*stride of a strided fp32 arena.
+// Operand r of group g is pack[g * R + r]: explicit device pointers carried by
+// value in the kernel arguments (one contiguous run of R pointers per group, so a
+// workgroup fetches its operands with one wide scalar load).
 struct Operands {
     const void* pack[kMaxPack];
-    const char* base;
-    long long   slot_bytes;
-    int         stride;
-    int         use_pack;
 };
 
 // Same idea for where a combine writes group g's result.
@@ -86,36 +90,34 @@ struct Outputs {
     int       stride;      // group g writes slot g*stride
 };
 
-struct LevelArgs {
-    const adasum_tile* tiles;          // device
-    const int32_t* layer_tile_begin;   // device, n_layers + 1
-    int64_t n_tiles;
-    int     n_layers;
-    int     n_groups;
-    int     R;
+// Device-side view of one tile table.
+struct TileSet {
+    const adasum_tile* tiles = nullptr;      // device
+    const int32_t* layer_begin = nullptr;    // device, n_layers + 1
+    int64_t n_tiles = 0;
 };
 
 // All launchers return a hipError_t as int (0 = success) and enqueue on `stream`.
-int launch_gram(int dtype, bool diag, const Operands& ops, const LevelArgs& a,
+// partials[(group * entries + entry) * gt.n_tiles + tile]
+int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
                 double* partials, void* stream);
-// Sums the per-tile partials (and, when !diag, the carried squared norms of the
-// operand nodes) into full R x R Gram matrices gram[group][layer][R*R].
-int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials,
-                       const double* normparts, int norm_sub, double* gram, void* stream);
-// Workgroups ("parts") a combine of these dtypes spends on one tile; the squared
-// norms it leaves are indexed [node][tile * parts + part].
-int combine_parts_per_tile(int dtype, int out_dtype);
-constexpr int kMaxCombineParts = 16;
+// Sums the per-tile partials (and, when !diag, the squared norms the previous
+// combine left per (node, tile of `nt`)) into full R x R Gram matrices
+// gram[group][layer][R*R].
+int launch_gram_finish(bool diag, const TileSet& gt, const TileSet& nt, int n_layers, int n_groups, int R,
+                       const double* partials, const double* normparts, double* gram, void* stream);
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
 int launch_weights(const double* gram, int R, int64_t n_items, int order,
                    double* weights, void* stream);
+// `ct` must be the table of capacity combine_tile_capacity(dtype);
+// normparts[group * ct.n_tiles + tile] (or null).
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out,
-                   const LevelArgs& a, const double* weights /* or null: unit weights */,
-                   double* normparts /* [group][tile] or null */, void* stream);
-// layer_sum[l] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile * sub + part].
-int launch_layer_sums(const double* parts, int n_rows, int sub, const LevelArgs& a,
+                   const TileSet& ct, int n_layers, int n_groups, int R,
+                   const double* weights /* or null: unit weights */, double* normparts, void* stream);
+// layer_sum[l * out_stride] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
+int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers,
                       double* layer_sum, int out_stride, void* stream);
-// leafnorm[l] = sum over groups of trace(gram[group][l]).
+// out[l * out_stride] = sum over groups of trace(gram[group][l]).
 int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers,
                       double* out, int out_stride, void* stream);
 

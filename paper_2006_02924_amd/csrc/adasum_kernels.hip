@@ -8,11 +8,14 @@
 // what it writes so the next pass needs only the cross dot products.
 //
 // The work is HBM-bound streaming: no matrix cores.  Every workgroup owns one
-// tile (at most kTile consecutive elements inside one layer); 64-wide waves
-// issue 16-byte loads that cover 1 KiB of one operand per instruction; loads of
-// several granules are issued before any is consumed so that enough bytes are
-// in flight; partial sums go lane (fp32) -> wave (fp32 shuffles) -> workgroup
-// (fp64 via LDS) -> per-tile fp64 partial in memory; no atomics anywhere.
+// tile (consecutive elements inside one layer): a long one (kTile elements) in
+// the read-only Gram pass, where a workgroup's start-up and its reduction must
+// be amortised, and a short one (one 16-byte load per lane and operand) in the
+// combine pass, where short-lived workgroups keep the mixed read/write stream
+// near sequential.  64-wide waves issue 16-byte non-temporal loads that cover
+// 1 KiB of one operand per instruction; partial sums go lane (fp32) -> wave
+// (fp32 shuffles) -> workgroup (fp64 via LDS) -> per-tile fp64 partial in
+// memory, summed later in a fixed order; no atomics anywhere.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -31,12 +34,9 @@
 #ifndef ADASUM_NT_STORE
 #define ADASUM_NT_STORE 1
 #endif
-#ifndef ADASUM_MIXED_G
-#define ADASUM_MIXED_G 0
-#endif
-// granule-steps one combine workgroup does (a tile has 8 or 16 of them)
-#ifndef ADASUM_COMBINE_IPW
-#define ADASUM_COMBINE_IPW 1
+// bf16 Gram entries through v_dot2c_f32_bf16 (1) or unpack + fp32 FMA (0)
+#ifndef ADASUM_BF16_DOT2
+#define ADASUM_BF16_DOT2 1
 #endif
 
 namespace adasum {
@@ -44,6 +44,7 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct bf16_t { unsigned short v; };
 
@@ -76,13 +77,13 @@ __device__ __forceinline__ V stream_load(const V* p) {
 #endif
 }
 
-template <typename V>
+template <bool NT, typename V>
 __device__ __forceinline__ void stream_store(V v, V* p) {
-#if ADASUM_NT_STORE
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
+    if constexpr (NT && ADASUM_NT_STORE) {
+        __builtin_nontemporal_store(v, p);
+    } else {
+        *p = v;
+    }
 }
 
 // p must be aligned to the granule size (to 16 bytes for a 32-byte granule)
@@ -120,13 +121,13 @@ __device__ __forceinline__ void unpack(const Granule<bf16_t, G>& r, float (&v)[G
     }
 }
 
-template <int NW>
+template <bool NT, int NW>
 __device__ __forceinline__ void store_words(void* p, const unsigned int (&w)[NW]) {
     if constexpr (NW == 2) {
         u32x2 q;
         q.x = w[0];
         q.y = w[1];
-        stream_store(q, reinterpret_cast<u32x2*>(p));
+        stream_store<NT>(q, reinterpret_cast<u32x2*>(p));
     } else {
 #pragma unroll
         for (int i = 0; i < NW / 4; ++i) {
@@ -135,25 +136,25 @@ __device__ __forceinline__ void store_words(void* p, const unsigned int (&w)[NW]
             q.y = w[4 * i + 1];
             q.z = w[4 * i + 2];
             q.w = w[4 * i + 3];
-            stream_store(q, reinterpret_cast<u32x4*>(p) + i);
+            stream_store<NT>(q, reinterpret_cast<u32x4*>(p) + i);
         }
     }
 }
 
-template <int G>
+template <bool NT, int G>
 __device__ __forceinline__ void store_granule(float* p, const float (&v)[G]) {
     unsigned int w[G];
 #pragma unroll
     for (int i = 0; i < G; ++i) w[i] = __float_as_uint(v[i]);
-    store_words(p, w);
+    store_words<NT>(p, w);
 }
 
-template <int G>
+template <bool NT, int G>
 __device__ __forceinline__ void store_granule(bf16_t* p, const float (&v)[G]) {
     unsigned int w[G / 2];
 #pragma unroll
     for (int i = 0; i < G / 2; ++i) w[i] = f32_to_bf16_rne(v[2 * i]) | (f32_to_bf16_rne(v[2 * i + 1]) << 16);
-    store_words(p, w);
+    store_words<NT>(p, w);
 }
 
 __device__ __forceinline__ float load_elem(const float* p) { return *p; }
@@ -179,9 +180,7 @@ __device__ __forceinline__ double wave_sum(double v) {
 
 template <int R>
 __device__ __forceinline__ const void* operand_ptr(const Operands& ops, int g, int r) {
-    const int idx = g * R + r;
-    if (ops.use_pack) return ops.pack[idx];
-    return ops.base + static_cast<long long>(idx) * ops.stride * ops.slot_bytes;
+    return ops.pack[g * R + r];
 }
 
 // The tile split every kernel uses: [start, hs) scalar head, [bs, be) whole
@@ -237,17 +236,35 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     for (int e = 0; e < NP; ++e) acc[e] = 0.f;
 
     auto consume = [&](const Granule<T, G> (&raw)[R]) {
-        float v[R][G];
+        if constexpr (sizeof(T) == 2 && ADASUM_BF16_DOT2) {
+            // two bf16 products and the fp32 accumulate in one instruction, straight
+            // from the packed words (bf16 x bf16 is exact in fp32)
+            int e = 0;
 #pragma unroll
-        for (int r = 0; r < R; ++r) unpack(raw[r], v[r]);
-        int e = 0;
+            for (int i = 0; i < R; ++i) {
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
+                for (int j = (DIAG ? i : i + 1); j < R; ++j) {
 #pragma unroll
-            for (int j = (DIAG ? i : i + 1); j < R; ++j) {
+                    for (int k = 0; k < Granule<T, G>::NW; ++k)
+                        acc[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw[i].w[k]),
+                                                                 __builtin_bit_cast(bf16x2_t, raw[j].w[k]),
+                                                                 acc[e], false);
+                    ++e;
+                }
+            }
+        } else {
+            float v[R][G];
 #pragma unroll
-                for (int k = 0; k < G; ++k) acc[e] = __builtin_fmaf(v[i][k], v[j][k], acc[e]);
-                ++e;
+            for (int r = 0; r < R; ++r) unpack(raw[r], v[r]);
+            int e = 0;
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+#pragma unroll
+                for (int j = (DIAG ? i : i + 1); j < R; ++j) {
+#pragma unroll
+                    for (int k = 0; k < G; ++k) acc[e] = __builtin_fmaf(v[i][k], v[j][k], acc[e]);
+                    ++e;
+                }
             }
         }
     };
@@ -336,8 +353,9 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
 
 template <int R, bool DIAG>
 __global__ void __launch_bounds__(kThreads)
-gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts, int norm_sub,
-                   const int32_t* __restrict__ layer_tile_begin, int n_tiles, int n_layers,
+gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts,
+                   const int32_t* __restrict__ layer_tile_begin, int n_tiles,
+                   const int32_t* __restrict__ norm_layer_begin, int n_norm_tiles, int n_layers,
                    double* __restrict__ gram) {
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
     __shared__ double sh[kThreads / 64];
@@ -362,10 +380,11 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
         }
     }
     if (!DIAG) {
+        const int nb = norm_layer_begin[l], ne = norm_layer_begin[l + 1];
         for (int i = 0; i < R; ++i) {
-            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_tiles * norm_sub;
+            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_norm_tiles;
             double v = 0.0;
-            for (int t = tb * norm_sub + tid; t < te * norm_sub; t += kThreads) v += row[t];
+            for (int t = nb + tid; t < ne; t += kThreads) v += row[t];
             v = block_sum(v, sh);
             if (tid == 0) out[i * R + i] = v;
         }
@@ -413,45 +432,27 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, do
 }
 
 // ---------------------------------------------------------------------------
-// Step 3: out = sum_r w_r x_r per element, squared norm of the result per part.
-// A tile is split over CombineShape::SUB workgroups ("parts"), each doing IPW
-// consecutive granule-steps: short-lived workgroups that walk memory in launch
-// order keep the mixed read/write stream close to sequential, which is worth
-// ~10 % of bandwidth over one long-lived workgroup per tile.
-// normparts[(group * n_tiles + tile) * SUB + part].  weights == nullptr: unit weights.
+// Step 3: out = sum_r w_r x_r per element, squared norm of the result per tile.
+// One workgroup per combine tile: kThreads granules of 16 input bytes, i.e. one
+// 16-byte load per lane and operand, then the workgroup ends.  Short-lived
+// workgroups that walk memory in launch order keep the mixed read/write stream
+// close to sequential, worth 10-20 % of bandwidth over long-lived workgroups.
+// normparts[group * n_tiles + tile].  weights == nullptr: unit weights.
 // ---------------------------------------------------------------------------
-template <typename TI, typename TO>
-struct CombineShape {
-    // one 16-byte load per lane, operand and step: lanes read consecutive addresses
-    static constexpr int G = ADASUM_MIXED_G == 0 ? 16 / (int)sizeof(TI)
-                           : ADASUM_MIXED_G == 8 ? ((sizeof(TI) == 2 || sizeof(TO) == 2) ? 8 : 4)
-                                                 : ((sizeof(TI) == 2 && sizeof(TO) == 2) ? 8 : 4);
-    static constexpr int ITERS = kTile / G / kThreads;
-    static constexpr int IPW = ADASUM_COMBINE_IPW < ITERS ? ADASUM_COMBINE_IPW : ITERS;
-    static constexpr int SUB = ITERS / IPW;
-    static_assert(ITERS % IPW == 0, "steps per workgroup must divide the tile");
-    static_assert(SUB <= kMaxCombineParts, "workspace is sized for at most kMaxCombineParts parts per tile");
-};
-
 template <typename TI, typename TO, int R>
 __global__ void __launch_bounds__(kThreads)
 combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
                int n_tiles, int n_layers, const double* __restrict__ weights,
                double* __restrict__ normparts) {
-    using Shape = CombineShape<TI, TO>;
-    constexpr int G = Shape::G;
-    constexpr int IPW = Shape::IPW;
-    constexpr int SUB = Shape::SUB;
-    constexpr int STEP_BYTES = R * G * (int)sizeof(TI);
-    constexpr int U0 = (STEP_BYTES >= 16 * ADASUM_INFLIGHT) ? 1 : (16 * ADASUM_INFLIGHT / STEP_BYTES);
-    constexpr int U = U0 > IPW ? IPW : U0;
-    static_assert(IPW % U == 0, "unroll must divide the trip count");
+    constexpr int G = 16 / (int)sizeof(TI);   // tile capacity is kThreads * G
+    // Non-temporal stores pay off except where the output is half of the traffic
+    // and every lane issues two of them (bf16 pair -> fp32): measured, 13.4 vs 16.4 ms.
+    constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);
 
     const int tid = threadIdx.x;
-    const unsigned part_tile = blockIdx.x / SUB;
-    const int part = static_cast<int>(blockIdx.x % SUB);
-    const int tile_id = static_cast<int>(part_tile % static_cast<unsigned>(n_tiles));
-    const int g = static_cast<int>(part_tile / static_cast<unsigned>(n_tiles));
+    const unsigned v = blockIdx.x;
+    const int tile_id = static_cast<int>(v % static_cast<unsigned>(n_tiles));
+    const int g = static_cast<int>(v / static_cast<unsigned>(n_tiles));
     const adasum_tile t = tiles[tile_id];
     const Split s = split_tile<G>(t);
 
@@ -460,7 +461,15 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
 
+    const long long idx = s.bs + static_cast<long long>(tid) * G;
+    Granule<TI, G> raw[R];
+    if (tid < s.ng) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+    }
+
     // fp64 weights as computed; the streaming body uses them rounded to fp32
+    // (fetched after the operand loads are in flight)
     double wd[R];
     float w[R];
 #pragma unroll
@@ -470,8 +479,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     }
 
     float nacc = 0.f;
-
-    auto emit = [&](const Granule<TI, G> (&raw)[R], long long idx) {
+    if (tid < s.ng) {
         float z[G];
         {
             float v[G];
@@ -488,40 +496,12 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         }
 #pragma unroll
         for (int k = 0; k < G; ++k) nacc = __builtin_fmaf(z[k], z[k], nacc);
-        store_granule(out + idx, z);
-    };
-
-    // this part's granule steps: [part * IPW, (part + 1) * IPW) of the tile
-    const int step0 = part * IPW;
-    if (s.ng == kTile / G) {
-        for (int it0 = 0; it0 < IPW; it0 += U) {
-            Granule<TI, G> raw[U][R];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const long long idx = s.bs + (static_cast<long long>(step0 + it0 + u) * kThreads + tid) * G;
-#pragma unroll
-                for (int r = 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const long long idx = s.bs + (static_cast<long long>(step0 + it0 + u) * kThreads + tid) * G;
-                emit(raw[u], idx);
-            }
-        }
-    } else {
-        const int jend = (step0 + IPW) * kThreads < s.ng ? (step0 + IPW) * kThreads : s.ng;
-        for (int j = step0 * kThreads + tid; j < jend; j += kThreads) {
-            Granule<TI, G> raw[R];
-            const long long idx = s.bs + static_cast<long long>(j) * G;
-#pragma unroll
-            for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
-            emit(raw, idx);
-        }
+        store_granule<NTS>(out + idx, z);
     }
 
-    // ragged head/tail elements (part 0 only): fp64 arithmetic, one rounding at the store
+    // ragged head/tail elements: fp64 arithmetic, one rounding at the store
     const int lane = tid & 63, wave = tid >> 6;
-    const int nedge = part == 0 ? s.nh + s.nt : 0;
+    const int nedge = s.nh + s.nt;
     double enorm = 0.0;
     if (nedge > 0 && wave == 0) {
         if (lane < nedge) {
@@ -536,11 +516,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         if (normparts != nullptr) enorm = wave_sum(enorm);
     }
 
-#ifdef ADASUM_TIMING_ONLY_SKIP_NORM
-    if (false) {
-#else
     if (normparts != nullptr) {
-#endif
         __shared__ double sh[kThreads / 64];
         const float ws = wave_sum(nacc);
         if (lane == 0) sh[wave] = static_cast<double>(ws);
@@ -550,7 +526,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 #pragma unroll
             for (int k = 1; k < kThreads / 64; ++k) tot += sh[k];
             if (nedge > 0) tot += enorm;
-            normparts[(static_cast<long long>(g) * n_tiles + tile_id) * SUB + part] = tot;
+            normparts[static_cast<long long>(g) * n_tiles + tile_id] = tot;
         }
     }
 }
@@ -560,7 +536,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 // ---------------------------------------------------------------------------
 // out[l * out_stride] = sum over rows and the tiles of layer l of parts[row][tile]
 __global__ void __launch_bounds__(kThreads)
-layer_sums_kernel(const double* __restrict__ parts, int n_rows, int sub,
+layer_sums_kernel(const double* __restrict__ parts, int n_rows,
                   const int32_t* __restrict__ layer_tile_begin, int n_tiles,
                   double* __restrict__ out, int out_stride) {
     __shared__ double sh[kThreads / 64];
@@ -568,8 +544,8 @@ layer_sums_kernel(const double* __restrict__ parts, int n_rows, int sub,
     const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
     double v = 0.0;
     for (int r = 0; r < n_rows; ++r) {
-        const double* row = parts + static_cast<long long>(r) * n_tiles * sub;
-        for (int t = tb * sub + threadIdx.x; t < te * sub; t += kThreads) v += row[t];
+        const double* row = parts + static_cast<long long>(r) * n_tiles;
+        for (int t = tb + threadIdx.x; t < te; t += kThreads) v += row[t];
     }
     v = block_sum(v, sh);
     if (threadIdx.x == 0) out[static_cast<long long>(l) * out_stride] = v;
@@ -594,31 +570,31 @@ inline int check_launch() { return static_cast<int>(hipGetLastError()); }
 inline bool grid_fits(long long blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
 
 template <typename T, bool DIAG>
-int launch_gram_r(const Operands& ops, const LevelArgs& a, double* partials, hipStream_t st) {
-    const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups);
+int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, double* partials, hipStream_t st) {
+    const long long blocks = gt.n_tiles * static_cast<long long>(n_groups);
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const int nt = static_cast<int>(a.n_tiles);
-    switch (a.R) {
-        case 2: hipLaunchKernelGGL((gram_kernel<T, 2, DIAG>), grid, block, 0, st, ops, a.tiles, nt, partials); break;
-        case 4: hipLaunchKernelGGL((gram_kernel<T, 4, DIAG>), grid, block, 0, st, ops, a.tiles, nt, partials); break;
-        case 8: hipLaunchKernelGGL((gram_kernel<T, 8, DIAG>), grid, block, 0, st, ops, a.tiles, nt, partials); break;
+    const int nt = static_cast<int>(gt.n_tiles);
+    switch (R) {
+        case 2: hipLaunchKernelGGL((gram_kernel<T, 2, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
+        case 4: hipLaunchKernelGGL((gram_kernel<T, 4, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
+        case 8: hipLaunchKernelGGL((gram_kernel<T, 8, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
     return check_launch();
 }
 
 template <typename TI, typename TO>
-int launch_combine_r(const Operands& ops, const Outputs& outs, const LevelArgs& a, const double* weights,
-                     double* normparts, hipStream_t st) {
-    const long long blocks = a.n_tiles * static_cast<long long>(a.n_groups) * CombineShape<TI, TO>::SUB;
+int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
+                     int R, const double* weights, double* normparts, hipStream_t st) {
+    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups);
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const int nt = static_cast<int>(a.n_tiles);
+    const int nt = static_cast<int>(ct.n_tiles);
 #define ADASUM_COMBINE(RR)                                                                           \
-    hipLaunchKernelGGL((combine_kernel<TI, TO, RR>), grid, block, 0, st, ops, outs, a.tiles, nt,     \
-                       a.n_layers, weights, normparts)
-    switch (a.R) {
+    hipLaunchKernelGGL((combine_kernel<TI, TO, RR>), grid, block, 0, st, ops, outs, ct.tiles, nt,    \
+                       n_layers, weights, normparts)
+    switch (R) {
         case 1: ADASUM_COMBINE(1); break;
         case 2: ADASUM_COMBINE(2); break;
         case 4: ADASUM_COMBINE(4); break;
@@ -631,35 +607,30 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const LevelArgs& 
 
 }  // namespace
 
-int launch_gram(int dtype, bool diag, const Operands& ops, const LevelArgs& a, double* partials, void* stream) {
+int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
+                double* partials, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (a.n_tiles == 0 || a.n_groups == 0) return 0;
+    if (gt.n_tiles == 0 || n_groups == 0) return 0;
     if (dtype == ADASUM_BF16) {
-        return diag ? launch_gram_r<bf16_t, true>(ops, a, partials, st)
-                    : launch_gram_r<bf16_t, false>(ops, a, partials, st);
+        return diag ? launch_gram_r<bf16_t, true>(ops, gt, n_groups, R, partials, st)
+                    : launch_gram_r<bf16_t, false>(ops, gt, n_groups, R, partials, st);
     }
-    return diag ? launch_gram_r<float, true>(ops, a, partials, st)
-                : launch_gram_r<float, false>(ops, a, partials, st);
+    return diag ? launch_gram_r<float, true>(ops, gt, n_groups, R, partials, st)
+                : launch_gram_r<float, false>(ops, gt, n_groups, R, partials, st);
 }
 
-int combine_parts_per_tile(int dtype, int out_dtype) {
-    if (dtype == ADASUM_BF16)
-        return out_dtype == ADASUM_BF16 ? CombineShape<bf16_t, bf16_t>::SUB : CombineShape<bf16_t, float>::SUB;
-    return out_dtype == ADASUM_BF16 ? CombineShape<float, bf16_t>::SUB : CombineShape<float, float>::SUB;
-}
-
-int launch_gram_finish(bool diag, const LevelArgs& a, const double* partials, const double* normparts,
-                       int norm_sub, double* gram, void* stream) {
+int launch_gram_finish(bool diag, const TileSet& gt, const TileSet& nt, int n_layers, int n_groups, int R,
+                       const double* partials, const double* normparts, double* gram, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const long long blocks = static_cast<long long>(a.n_groups) * a.n_layers;
+    const long long blocks = static_cast<long long>(n_groups) * n_layers;
     if (blocks == 0) return 0;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const int nt = static_cast<int>(a.n_tiles);
+    const int ngt = static_cast<int>(gt.n_tiles), nnt = static_cast<int>(nt.n_tiles);
 #define ADASUM_FINISH(RR, DD)                                                                      \
     hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
-                       norm_sub, a.layer_tile_begin, nt, a.n_layers, gram)
-    switch (a.R) {
+                       gt.layer_begin, ngt, nt.layer_begin, nnt, n_layers, gram)
+    switch (R) {
         case 2: if (diag) ADASUM_FINISH(2, true); else ADASUM_FINISH(2, false); break;
         case 4: if (diag) ADASUM_FINISH(4, true); else ADASUM_FINISH(4, false); break;
         case 8: if (diag) ADASUM_FINISH(8, true); else ADASUM_FINISH(8, false); break;
@@ -685,24 +656,26 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order, double
     return check_launch();
 }
 
-int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const LevelArgs& a,
-                   const double* weights, double* normparts, void* stream) {
+int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                   int n_layers, int n_groups, int R, const double* weights, double* normparts, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (a.n_tiles == 0 || a.n_groups == 0) return 0;
+    if (ct.n_tiles == 0 || n_groups == 0) return 0;
     if (dtype == ADASUM_BF16) {
-        return out_dtype == ADASUM_BF16 ? launch_combine_r<bf16_t, bf16_t>(ops, out, a, weights, normparts, st)
-                                        : launch_combine_r<bf16_t, float>(ops, out, a, weights, normparts, st);
+        return out_dtype == ADASUM_BF16
+                   ? launch_combine_r<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st)
+                   : launch_combine_r<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
     }
-    return out_dtype == ADASUM_BF16 ? launch_combine_r<float, bf16_t>(ops, out, a, weights, normparts, st)
-                                    : launch_combine_r<float, float>(ops, out, a, weights, normparts, st);
+    return out_dtype == ADASUM_BF16
+               ? launch_combine_r<float, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st)
+               : launch_combine_r<float, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
 }
 
-int launch_layer_sums(const double* parts, int n_rows, int sub, const LevelArgs& a, double* layer_sum,
+int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers, double* layer_sum,
                       int out_stride, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (a.n_layers == 0) return 0;
-    hipLaunchKernelGGL(layer_sums_kernel, dim3(a.n_layers), dim3(kThreads), 0, st, parts, n_rows, sub,
-                       a.layer_tile_begin, static_cast<int>(a.n_tiles), layer_sum, out_stride);
+    if (n_layers == 0) return 0;
+    hipLaunchKernelGGL(layer_sums_kernel, dim3(n_layers), dim3(kThreads), 0, st, parts, n_rows,
+                       t.layer_begin, static_cast<int>(t.n_tiles), layer_sum, out_stride);
     return check_launch();
 }
 

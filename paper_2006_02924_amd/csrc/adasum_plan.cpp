@@ -6,6 +6,8 @@
 
 #include <algorithm>
 
+
+
 namespace adasum {
 
 int check_layer_table(const int64_t* layer_offsets, int n_layers) {
@@ -18,7 +20,7 @@ int check_layer_table(const int64_t* layer_offsets, int n_layers) {
     return ADASUM_OK;
 }
 
-void build_tiles(const int64_t* layer_offsets, int n_layers,
+void build_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
                  std::vector<adasum_tile>& tiles, std::vector<int32_t>& layer_tile_begin) {
     tiles.clear();
     layer_tile_begin.assign(static_cast<size_t>(n_layers) + 1, 0);
@@ -27,8 +29,8 @@ void build_tiles(const int64_t* layer_offsets, int n_layers,
         int64_t pos = layer_offsets[l];
         const int64_t end = layer_offsets[l + 1];
         while (pos < end) {
-            // next global multiple of kTile strictly above pos, clipped to the layer
-            int64_t stop = (pos / kTile + 1) * static_cast<int64_t>(kTile);
+            // next global multiple of the capacity strictly above pos, clipped to the layer
+            int64_t stop = (pos / capacity + 1) * capacity;
             if (stop > end) stop = end;
             adasum_tile t;
             t.start = pos;
@@ -56,10 +58,12 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     return ADASUM_OK;
 }
 
-Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, const std::vector<int>& radices) {
+Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t n_ctiles,
+                   const std::vector<int>& radices) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
+    lay.n_ctiles = n_ctiles;
     lay.n_layers = n_layers;
     lay.slot_elems = static_cast<int64_t>(align_up(static_cast<size_t>(N), 64));
     // nodes written by the first pass, unless that pass is already the root
@@ -82,7 +86,7 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, const std::v
     lay.off_partials = off;
     off = align_up(off + max_partials * sizeof(double), 256);
     lay.off_normparts = off;
-    off = align_up(off + max_nodes * static_cast<size_t>(n_tiles) * kMaxCombineParts * sizeof(double), 256);
+    off = align_up(off + max_nodes * static_cast<size_t>(n_ctiles) * sizeof(double), 256);
     lay.off_gram = off;
     off = align_up(off + max_gram * sizeof(double), 256);
     lay.off_weights = off;

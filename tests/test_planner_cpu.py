@@ -6,9 +6,12 @@ from paper_2006_02924_amd import binding as B
 from paper_2006_02924_amd import workloads as W
 
 
-def check_tiles(offsets):
-    cap = B.tile_capacity()
-    t = B.plan_tiles(offsets)
+def check_tiles(offsets, cap=None):
+    if cap is None:
+        for c in (1024, 2048):
+            check_tiles(offsets, c)
+    cap = cap or B.tile_capacity()
+    t = B.plan_tiles(offsets, cap)
     offsets = np.asarray(offsets, dtype=np.int64)
     N = int(offsets[-1])
     # cover [0, N) exactly, in order, without overlap
