@@ -66,8 +66,9 @@ typedef struct adasum_options {
     int32_t  out_dtype;        /* ADASUM_F32 | ADASUM_BF16; -1 = same as the input dtype */
     int32_t  radix;            /* how many binary tree levels one pass over the data fuses:
                                   2 = one level per pass (reduce pass + combine pass per level),
-                                  4 / 8 = two / three levels per pass (the pass computes the
-                                  group's Gram matrix, the tree's scalars follow from it);
+                                  4 / 8 / 16 = two / three / four levels per pass (the pass
+                                  computes the group's Gram matrix, the tree's scalars follow
+                                  from it);
                                   0 = library default.  The result is the same binary tree. */
     int32_t  order;            /* ADASUM_ORDER_TREE (default) | ADASUM_ORDER_LINEAR */
     int32_t  use_graph;        /* 1 = replay the level ladder as one hipGraph launch */
@@ -120,7 +121,7 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
  * operands, G[i][j] = x_i . x_j (the pair case R = 2 is the triple
  * [a.b, a.a, b.b]).
  *   x      HOST array of R DEVICE pointers (N elements of `dtype` each)
- *   R      2, 4 or 8
+ *   R      2, 4, 8 or 16
  *   gram   DEVICE, n_layers x R x R doubles, row-major per layer, symmetric
  */
 int adasum_group_gram(const void* const* x, int R,

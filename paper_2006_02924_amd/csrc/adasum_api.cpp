@@ -74,7 +74,7 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
         r.layer_stats = o->layer_stats;
     }
     if (r.out_dtype != ADASUM_F32 && r.out_dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
-    if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8) return ADASUM_ERR_UNSUPPORTED;
+    if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if (r.order == ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;   // scheduler: tree only
     if (r.workspace != nullptr && (reinterpret_cast<uintptr_t>(r.workspace) & 255u) != 0)
@@ -123,19 +123,38 @@ struct Plan {
     int K = 0;
     int radix = 0;
     std::vector<int64_t> offsets;
-    TileTable gram_tiles;        // capacity kTile
-    TileTable comb_tiles_f32;    // capacity combine_tile_capacity(ADASUM_F32)
-    TileTable comb_tiles_bf16;   // capacity combine_tile_capacity(ADASUM_BF16)
+    TileTable gram_tiles;                 // capacity kTile
+    std::map<int, TileTable> comb_tables; // by capacity, built on first use
     std::vector<int> radices;
     Layout lay;
     char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
 
-    const TileTable& comb_tiles(int dtype) const { return dtype == ADASUM_BF16 ? comb_tiles_bf16 : comb_tiles_f32; }
+    // The combine tile table for this input dtype and radix (device copy made on first use).
+    int comb_tiles(int dtype, int R, TileSet* out) {
+        const int cap = combine_tile_capacity(dtype, R);
+        auto it = comb_tables.find(cap);
+        if (it == comb_tables.end()) {
+            try {
+                TileTable t;
+                build_tiles(offsets.data(), static_cast<int>(offsets.size()) - 1, cap, t.tiles, t.layer_begin);
+                it = comb_tables.emplace(cap, std::move(t)).first;
+            } catch (const std::bad_alloc&) {
+                return ADASUM_ERR_OUT_OF_MEMORY;
+            }
+            int rc = it->second.upload();
+            if (rc != ADASUM_OK) {
+                it->second.release();
+                comb_tables.erase(it);
+                return rc;
+            }
+        }
+        *out = it->second.view();
+        return ADASUM_OK;
+    }
 
     ~Plan() {
         gram_tiles.release();
-        comb_tiles_f32.release();
-        comb_tiles_bf16.release();
+        for (auto& kv : comb_tables) kv.second.release();
         if (d_ws) (void)hipFree(d_ws);
     }
 };
@@ -162,20 +181,14 @@ int find_or_make_plan(int K, int radix, const int64_t* offsets, int n_layers, Pl
         p->radix = radix;
         p->offsets.assign(offsets, offsets + n_layers + 1);
         build_tiles(offsets, n_layers, kTile, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
-        build_tiles(offsets, n_layers, combine_tile_capacity(ADASUM_F32), p->comb_tiles_f32.tiles,
-                    p->comb_tiles_f32.layer_begin);
-        build_tiles(offsets, n_layers, combine_tile_capacity(ADASUM_BF16), p->comb_tiles_bf16.tiles,
-                    p->comb_tiles_bf16.layer_begin);
         int rc = build_levels(K, radix, p->radices);
         if (rc != ADASUM_OK) return rc;
         p->lay = make_layout(K, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
-                             static_cast<int64_t>(p->comb_tiles_f32.tiles.size()), p->radices);
+                             norm_entries_bound(K, offsets, n_layers, p->radices), p->radices);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
     int rc = p->gram_tiles.upload();
-    if (rc == ADASUM_OK) rc = p->comb_tiles_f32.upload();
-    if (rc == ADASUM_OK) rc = p->comb_tiles_bf16.upload();
     if (rc != ADASUM_OK) return rc;
     *out = p.get();
     g_plans.push_back(std::move(p));
@@ -293,7 +306,11 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         const int st_dtype = last ? o.out_dtype : ADASUM_F32;
         const int np = gram_entries(R, first);
         const bool want_norm = !last || o.layer_stats != nullptr;
-        const TileSet ct = p->comb_tiles(in_dtype).view();
+        TileSet ct;
+        {
+            const int rc = p->comb_tiles(in_dtype, R, &ct);
+            if (rc != ADASUM_OK) return rc;
+        }
 
         // groups per launch: the operand pointers travel by value in the kernel arguments
         const int batch = std::max(1, kMaxPack / R);
@@ -365,7 +382,11 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
     const Layout& lay = p->lay;
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
-    const TileSet ct = p->comb_tiles(dtype).view();
+    TileSet ct;
+    {
+        const int rc = p->comb_tiles(dtype, 1, &ct);
+        if (rc != ADASUM_OK) return rc;
+    }
     Operands ops;
     std::memset(&ops, 0, sizeof(ops));
     ops.pack[0] = grads[0];
@@ -448,12 +469,9 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
         std::vector<int> radices;
         rc = build_levels(K, o.radix, radices);
         if (rc != ADASUM_OK) return rc;
-        std::vector<adasum_tile> tiles, ctiles;
-        std::vector<int32_t> ltb;
-        build_tiles(layer_offsets, n_layers, kTile, tiles, ltb);
-        build_tiles(layer_offsets, n_layers, combine_tile_capacity(ADASUM_F32), ctiles, ltb);
-        const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers, static_cast<int64_t>(tiles.size()),
-                                       static_cast<int64_t>(ctiles.size()), radices);
+        const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers,
+                                       count_tiles(layer_offsets, n_layers, kTile),
+                                       norm_entries_bound(K, layer_offsets, n_layers, radices), radices);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -462,7 +480,7 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
 }
 
 static int step_common(const void* const* x, int R, const int64_t* layer_offsets, int n_layers, int dtype) {
-    if (R != 2 && R != 4 && R != 8) return ADASUM_ERR_UNSUPPORTED;
+    if (R != 2 && R != 4 && R != 8 && R != 16) return ADASUM_ERR_UNSUPPORTED;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
     if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
@@ -495,7 +513,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
 }
 
 int adasum_group_weights(const double* gram, int R, int n_layers, int order, double* weights, void* stream) {
-    if (R != 2 && R != 4 && R != 8) return ADASUM_ERR_UNSUPPORTED;
+    if (R != 2 && R != 4 && R != 8 && R != 16) return ADASUM_ERR_UNSUPPORTED;
     if (n_layers < 0) return ADASUM_ERR_INVALID_ARG;
     if (order != ADASUM_ORDER_TREE && order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if ((gram == nullptr || weights == nullptr) && n_layers > 0) return ADASUM_ERR_INVALID_ARG;
@@ -532,7 +550,9 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
     double* normparts = reinterpret_cast<double*>(ws + p->lay.off_normparts);
-    const TileSet ct = p->comb_tiles(dtype).view();
+    TileSet ct;
+    rc = p->comb_tiles(dtype, R, &ct);
+    if (rc != ADASUM_OK) return rc;
     Operands ops;
     std::memset(&ops, 0, sizeof(ops));
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
@@ -617,7 +637,7 @@ const char* adasum_strerror(int code) {
     switch (code) {
         case ADASUM_OK: return "ok";
         case ADASUM_ERR_INVALID_ARG: return "invalid argument";
-        case ADASUM_ERR_UNSUPPORTED: return "unsupported (K must be a power of two; dtype f32/bf16; radix 2/4/8)";
+        case ADASUM_ERR_UNSUPPORTED: return "unsupported (K must be a power of two; dtype f32/bf16; radix 2/4/8/16)";
         case ADASUM_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
         case ADASUM_ERR_OUT_OF_MEMORY: return "out of memory";
         case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";

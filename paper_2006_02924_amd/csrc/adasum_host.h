@@ -22,15 +22,19 @@ namespace adasum {
 #endif
 constexpr int kTile = ADASUM_TILE;
 constexpr int kThreads = ADASUM_THREADS;
-// A combine workgroup covers one 16-byte load per lane and operand: short-lived
-// workgroups that walk memory in launch order keep the mixed read/write stream
-// close to sequential.  Its tile capacity therefore depends on the input type.
-inline int combine_tile_capacity(int dtype) { return kThreads * (dtype == ADASUM_BF16 ? 8 : 4); }
+// A combine workgroup covers one 16-byte load per lane and operand and then
+// ends: short-lived workgroups that walk memory in launch order keep the mixed
+// read/write stream close to sequential.  Measured on MI355X, such a workgroup
+// streams best when it moves 16-20 KB in all, so wider groups get fewer lanes.
+constexpr int combine_threads(int R) { return R >= 16 ? 64 : (R >= 8 ? 128 : 256); }
+// Tile capacity of the combine pass: depends on the input type and the radix.
+inline int combine_tile_capacity(int dtype, int R) { return combine_threads(R) * (dtype == ADASUM_BF16 ? 8 : 4); }
+
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
-constexpr int kMaxRadix = 8;
+constexpr int kMaxRadix = 16;
 // Radix used when the caller asks for 0: the widest pass moves the fewest bytes.
-constexpr int kDefaultRadix = 8;
+constexpr int kDefaultRadix = 16;
 
 inline int elem_bytes(int dtype) { return dtype == ADASUM_BF16 ? 2 : 4; }
 inline bool is_pow2(long long v) { return v > 0 && (v & (v - 1)) == 0; }
@@ -61,7 +65,7 @@ struct Layout {
     int64_t slot_elems = 0;   // N rounded up so that fp32 slots stay 256-byte aligned
     int64_t n_slots = 0;      // fp32 intermediate tree nodes after the first pass
     int64_t n_tiles = 0;      // Gram tiles
-    int64_t n_ctiles = 0;     // combine tiles of the finest table (fp32 input)
+    int64_t norm_entries = 0; // doubles reserved for the combines' squared norms
     int     n_layers = 0;
     size_t  off_slots = 0;    // n_slots x slot_elems floats
     size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
@@ -71,8 +75,14 @@ struct Layout {
     size_t  off_leafnorm = 0; // doubles [layer]: sum over workers of the input squared norms
     size_t  total = 0;
 };
-Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t n_ctiles,
+// `norm_entries`: doubles needed for the squared norms the combines leave
+// (max over passes of nodes written x combine tiles of that pass).
+Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices);
+// Number of tiles build_tiles would produce.
+int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity);
+// Upper bound (over input dtypes) of make_layout's norm_entries for a schedule.
+int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices);
 
 // ---- kernel launchers (adasum_kernels.hip) -----------------------------------
 
@@ -109,7 +119,7 @@ int launch_gram_finish(bool diag, const TileSet& gt, const TileSet& nt, int n_la
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
 int launch_weights(const double* gram, int R, int64_t n_items, int order,
                    double* weights, void* stream);
-// `ct` must be the table of capacity combine_tile_capacity(dtype);
+// `ct` must be the table of capacity combine_tile_capacity(dtype, R);
 // normparts[group * ct.n_tiles + tile] (or null).
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out,
                    const TileSet& ct, int n_layers, int n_groups, int R,

@@ -433,18 +433,19 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, do
 
 // ---------------------------------------------------------------------------
 // Step 3: out = sum_r w_r x_r per element, squared norm of the result per tile.
-// One workgroup per combine tile: kThreads granules of 16 input bytes, i.e. one
+// One workgroup per combine tile: combine_threads(R) granules of 16 input bytes, i.e. one
 // 16-byte load per lane and operand, then the workgroup ends.  Short-lived
 // workgroups that walk memory in launch order keep the mixed read/write stream
 // close to sequential, worth 10-20 % of bandwidth over long-lived workgroups.
 // normparts[group * n_tiles + tile].  weights == nullptr: unit weights.
 // ---------------------------------------------------------------------------
 template <typename TI, typename TO, int R>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(combine_threads(R))
 combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
                int n_tiles, int n_layers, const double* __restrict__ weights,
                double* __restrict__ normparts) {
-    constexpr int G = 16 / (int)sizeof(TI);   // tile capacity is kThreads * G
+    constexpr int G = 16 / (int)sizeof(TI);   // tile capacity is THREADS * G
+    constexpr int THREADS = combine_threads(R);
     // Non-temporal stores pay off except where the output is half of the traffic
     // and every lane issues two of them (bf16 pair -> fp32): measured, 13.4 vs 16.4 ms.
     constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);
@@ -517,14 +518,14 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     }
 
     if (normparts != nullptr) {
-        __shared__ double sh[kThreads / 64];
+        __shared__ double sh[THREADS / 64];
         const float ws = wave_sum(nacc);
         if (lane == 0) sh[wave] = static_cast<double>(ws);
         __syncthreads();
         if (tid == 0) {
             double tot = sh[0];
 #pragma unroll
-            for (int k = 1; k < kThreads / 64; ++k) tot += sh[k];
+            for (int k = 1; k < THREADS / 64; ++k) tot += sh[k];
             if (nedge > 0) tot += enorm;
             normparts[static_cast<long long>(g) * n_tiles + tile_id] = tot;
         }
@@ -579,6 +580,7 @@ int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, d
         case 2: hipLaunchKernelGGL((gram_kernel<T, 2, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
         case 4: hipLaunchKernelGGL((gram_kernel<T, 4, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
         case 8: hipLaunchKernelGGL((gram_kernel<T, 8, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
+        case 16: hipLaunchKernelGGL((gram_kernel<T, 16, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
     return check_launch();
@@ -589,7 +591,7 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct
                      int R, const double* weights, double* normparts, hipStream_t st) {
     const long long blocks = ct.n_tiles * static_cast<long long>(n_groups);
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(combine_threads(R));
     const int nt = static_cast<int>(ct.n_tiles);
 #define ADASUM_COMBINE(RR)                                                                           \
     hipLaunchKernelGGL((combine_kernel<TI, TO, RR>), grid, block, 0, st, ops, outs, ct.tiles, nt,    \
@@ -599,6 +601,7 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct
         case 2: ADASUM_COMBINE(2); break;
         case 4: ADASUM_COMBINE(4); break;
         case 8: ADASUM_COMBINE(8); break;
+        case 16: ADASUM_COMBINE(16); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 #undef ADASUM_COMBINE
@@ -634,6 +637,7 @@ int launch_gram_finish(bool diag, const TileSet& gt, const TileSet& nt, int n_la
         case 2: if (diag) ADASUM_FINISH(2, true); else ADASUM_FINISH(2, false); break;
         case 4: if (diag) ADASUM_FINISH(4, true); else ADASUM_FINISH(4, false); break;
         case 8: if (diag) ADASUM_FINISH(8, true); else ADASUM_FINISH(8, false); break;
+        case 16: if (diag) ADASUM_FINISH(16, true); else ADASUM_FINISH(16, false); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 #undef ADASUM_FINISH
@@ -651,6 +655,7 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order, double
         case 2: hipLaunchKernelGGL((weights_kernel<2>), grid, block, 0, st, gram, n, order, weights); break;
         case 4: hipLaunchKernelGGL((weights_kernel<4>), grid, block, 0, st, gram, n, order, weights); break;
         case 8: hipLaunchKernelGGL((weights_kernel<8>), grid, block, 0, st, gram, n, order, weights); break;
+        case 16: hipLaunchKernelGGL((weights_kernel<16>), grid, block, 0, st, gram, n, order, weights); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
     return check_launch();

@@ -48,7 +48,7 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
     if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
     if (radix == 0) radix = kDefaultRadix;
-    if (radix != 2 && radix != 4 && radix != 8) return ADASUM_ERR_UNSUPPORTED;
+    if (radix != 2 && radix != 4 && radix != 8 && radix != 16) return ADASUM_ERR_UNSUPPORTED;
     int rest = K;
     while (rest > 1) {
         int r = std::min(rest, radix);
@@ -58,12 +58,35 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     return ADASUM_OK;
 }
 
-Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t n_ctiles,
+int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity) {
+    int64_t n = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int64_t lo = layer_offsets[l], hi = layer_offsets[l + 1];
+        if (hi > lo) n += (hi - 1) / capacity - lo / capacity + 1;
+    }
+    return n;
+}
+
+int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices) {
+    int64_t need = 1;
+    int groups = K;
+    for (size_t lv = 0; lv < radices.size(); ++lv) {
+        groups /= radices[lv];
+        // fp32 input gives the finest table of a pass
+        const int64_t t = count_tiles(layer_offsets, n_layers, combine_tile_capacity(ADASUM_F32, radices[lv]));
+        need = std::max<int64_t>(need, static_cast<int64_t>(groups) * t);
+    }
+    if (radices.empty())
+        need = std::max<int64_t>(need, count_tiles(layer_offsets, n_layers, combine_tile_capacity(ADASUM_F32, 1)));
+    return need;
+}
+
+Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
-    lay.n_ctiles = n_ctiles;
+    lay.norm_entries = norm_entries;
     lay.n_layers = n_layers;
     lay.slot_elems = static_cast<int64_t>(align_up(static_cast<size_t>(N), 64));
     // nodes written by the first pass, unless that pass is already the root
@@ -86,7 +109,7 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t n_ct
     lay.off_partials = off;
     off = align_up(off + max_partials * sizeof(double), 256);
     lay.off_normparts = off;
-    off = align_up(off + max_nodes * static_cast<size_t>(n_ctiles) * sizeof(double), 256);
+    off = align_up(off + static_cast<size_t>(norm_entries) * sizeof(double), 256);
     lay.off_gram = off;
     off = align_up(off + max_gram * sizeof(double), 256);
     lay.off_weights = off;

@@ -28,7 +28,7 @@ RAGGED = [0, 1, 2, 9, 9, 40, 41, 1064, 1064 + 16384, 1064 + 16384 + 33000, 60000
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("R", [2, 4, 8])
+@pytest.mark.parametrize("R", [2, 4, 8, 16])
 def test_group_gram_matches_dot_products(R, dtype):
     say(f"group_gram R={R} {dtype}")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=11)
@@ -50,7 +50,7 @@ def test_group_gram_matches_dot_products(R, dtype):
         np.testing.assert_allclose([got[-2][0, 1], got[-2][0, 0], got[-2][1, 1]], [d, n1, n2], rtol=2e-6)
 
 
-@pytest.mark.parametrize("R", [2, 4, 8])
+@pytest.mark.parametrize("R", [2, 4, 8, 16])
 def test_group_weights_reproduce_the_tree(R):
     say(f"group_weights R={R}")
     rng = np.random.default_rng(R)
@@ -90,7 +90,7 @@ def test_group_weights_reproduce_the_tree(R):
 
 @pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("R", [2, 4, 8])
+@pytest.mark.parametrize("R", [2, 4, 8, 16])
 def test_group_combine_matches_weighted_sum(R, dtype, out_dtype):
     say(f"group_combine R={R} {dtype}->{out_dtype}")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=12)
@@ -129,7 +129,7 @@ def test_group_combine_in_place_on_first_operand():
 # whole tree
 # ---------------------------------------------------------------------------
 
-@pytest.mark.parametrize("radix", [0, 2, 4, 8])
+@pytest.mark.parametrize("radix", [0, 2, 4, 8, 16])
 def test_config1(radix):
     say(f"config1 radix={radix}")
     w = W.config1(DEV)
@@ -140,10 +140,10 @@ def test_config1(radix):
     say(f"  max rel-L2 {err.max():.2e}")
 
 
-@pytest.mark.parametrize("radix", [2, 4, 8])
+@pytest.mark.parametrize("radix", [2, 4, 8, 16])
 @pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("K", [1, 2, 4, 8, 16, 32])
+@pytest.mark.parametrize("K", [1, 2, 4, 8, 16, 32, 64])
 def test_ragged_tables(K, dtype, out_dtype, radix):
     if K == 1 and radix != 2:
         pytest.skip("K=1 has no passes")
@@ -202,7 +202,7 @@ def test_layer_stats_orthogonality_metric():
     for i in range(K):
         grads.append(torch.cat([q[:, i].float() * (i + 1), base, rnd.grads[i]]).to(DEV))
     offs = [0, n, 2 * n, 2 * n + 3000]
-    for radix in (2, 8):
+    for radix in (2, 8, 16):
         stats = torch.zeros(3, 2, dtype=torch.float64, device=DEV)
         out = B.adasum_reduce(grads, offs, radix=radix, layer_stats=stats)
         torch.cuda.synchronize()
@@ -220,7 +220,7 @@ def test_config2_resnet50_full():
     say("config2 (K=8, fp32, ResNet-50 shapes, full size)")
     w = W.config2(DEV)
     ref = oracle_reduce(w.grads, w.layer_offsets)
-    for radix in (2, 8):
+    for radix in (2, 8, 16):
         out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix)
         torch.cuda.synchronize()
         err = assert_parity(out, ref, w.layer_offsets, what=f"config2 radix {radix}")
@@ -232,7 +232,7 @@ def test_config3_bert_fp32_scaled():
     sizes = W.scaled_down(W.bert_large_layer_sizes(), 16, floor=64)
     w = W.config3(DEV, sizes=sizes)
     ref = oracle_reduce(w.grads, w.layer_offsets)
-    for radix in (2, 4, 8):
+    for radix in (2, 4, 8, 16):
         out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix)
         torch.cuda.synchronize()
         err = assert_parity(out, ref, w.layer_offsets, what=f"config3 radix {radix}")
@@ -245,7 +245,7 @@ def test_config4_bert_bf16_scaled(out_dtype):
     sizes = W.scaled_down(W.bert_large_layer_sizes(), 32, floor=32)
     w = W.config4(DEV, sizes=sizes)
     ref = oracle_reduce(w.grads, w.layer_offsets)
-    for radix in (2, 4, 8):
+    for radix in (2, 4, 8, 16):
         out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix)
         torch.cuda.synchronize()
         err = assert_parity(out, ref, w.layer_offsets, what=f"config4 radix {radix}")
@@ -261,7 +261,7 @@ def test_config5_edge_cases_scaled():
     offs = w.layer_offsets
     ref = oracle_reduce(w.grads, offs)
     kinds = w.meta["kind"]
-    for radix in (2, 8):
+    for radix in (2, 8, 16):
         for out_dtype in (torch.bfloat16, torch.float32):
             out = B.adasum_reduce(w.grads, offs, out_dtype=out_dtype, radix=radix)
             torch.cuda.synchronize()

@@ -61,15 +61,18 @@ def test_tiles_bert_large():
 def test_levels():
     assert B.plan_levels(1) == []
     assert B.plan_levels(2) == [2]
-    assert B.plan_levels(64) == [8, 8]
+    assert B.plan_levels(64) == [16, 4]
     assert B.plan_levels(64, 2) == [2] * 6
     assert B.plan_levels(64, 8) == [8, 8]
     assert B.plan_levels(64, 4) == [4, 4, 4]
     assert B.plan_levels(128, 8) == [8, 8, 2]
     assert B.plan_levels(32, 8) == [8, 4]
     assert B.plan_levels(4, 8) == [4]
+    assert B.plan_levels(64, 16) == [16, 4]
+    assert B.plan_levels(128, 16) == [16, 8]
+    assert B.plan_levels(8, 16) == [8]
     for K in (2, 4, 8, 16, 32, 64, 128, 256):
-        for r in (2, 4, 8):
+        for r in (2, 4, 8, 16):
             assert int(np.prod(B.plan_levels(K, r))) == K
     with pytest.raises(B.AdasumError) as e:
         B.plan_levels(12)
