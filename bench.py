@@ -45,6 +45,7 @@ def parse_args():
                    choices=["config1", "config2", "config3", "config4", "config4_small", "copy"])
     p.add_argument("--radix", type=int, default=0, help="0 = library default")
     p.add_argument("--out-dtype", default="same", choices=["same", "f32", "bf16"])
+    p.add_argument("--graph", action="store_true", help="replay the level ladder as one hipGraph launch")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-profile", action="store_true",
                    help="do not bracket kernels with HIP events in the timed region")
@@ -139,7 +140,8 @@ def main():
     out = torch.empty(w.N, dtype=out_dtype, device=dev)
 
     def step():
-        B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=args.radix)
+        B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=args.radix,
+                        use_graph=args.graph)
 
     for _ in range(args.warmup):
         step()
@@ -186,7 +188,8 @@ def main():
         "config": {"workload": f"{args.workload}: K={w.K} workers, {w.n_layers} tensors, N={w.N} elements, "
                                f"stored {str(w.dtype).replace('torch.', '')}, output "
                                f"{str(out_dtype).replace('torch.', '')}",
-                   "passes": levels, "radix": args.radix, "input_GB": w.input_bytes / 1e9},
+                   "passes": levels, "radix": args.radix, "graph": bool(args.graph),
+                   "input_GB": w.input_bytes / 1e9},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -71,7 +71,9 @@ typedef struct adasum_options {
                                   from it);
                                   0 = library default.  The result is the same binary tree. */
     int32_t  order;            /* ADASUM_ORDER_TREE (default) | ADASUM_ORDER_LINEAR */
-    int32_t  use_graph;        /* 1 = replay the level ladder as one hipGraph launch */
+    int32_t  use_graph;        /* 1 = replay the level ladder as one hipGraph launch: captured
+                                  once per distinct set of buffers (grads, out, workspace,
+                                  layer_stats), cached in the plan, relaunched while they match */
     int32_t  reserved0;
     void*    workspace;        /* DEVICE, 256-byte aligned, or NULL = library-owned, cached per plan */
     size_t   workspace_bytes;  /* size of `workspace`; see adasum_workspace_bytes */

@@ -129,6 +129,15 @@ struct Plan {
     Layout lay;
     char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
 
+    // Captured level ladders, one per distinct set of buffers (see launch_as_graph).
+    struct GraphEntry {
+        std::vector<uintptr_t> key;
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+    };
+    std::vector<GraphEntry> graphs;
+    hipStream_t capture_stream = nullptr;
+
     // The combine tile table for this input dtype and radix (device copy made on first use).
     int comb_tiles(int dtype, int R, TileSet* out) {
         const int cap = combine_tile_capacity(dtype, R);
@@ -153,6 +162,11 @@ struct Plan {
     }
 
     ~Plan() {
+        for (auto& g : graphs) {
+            if (g.exec) (void)hipGraphExecDestroy(g.exec);
+            if (g.graph) (void)hipGraphDestroy(g.graph);
+        }
+        if (capture_stream) (void)hipStreamDestroy(capture_stream);
         gram_tiles.release();
         for (auto& kv : comb_tables) kv.second.release();
         if (d_ws) (void)hipFree(d_ws);
@@ -298,6 +312,13 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     int stride = 1;          // slot distance between consecutive alive nodes (passes >= 1)
     TileSet norm_tiles;      // the table the previous combine indexed its squared norms by
     const int n_levels = static_cast<int>(p->radices.size());
+    // Resolve (and on first use build and upload) every tile table before the first launch:
+    // nothing below may allocate, so the ladder can be captured into a graph.
+    std::vector<TileSet> comb_sets(n_levels);
+    for (int lv = 0; lv < n_levels; ++lv) {
+        const int rc = p->comb_tiles(lv == 0 ? dtype : ADASUM_F32, p->radices[lv], &comb_sets[lv]);
+        if (rc != ADASUM_OK) return rc;
+    }
     for (int lv = 0; lv < n_levels; ++lv) {
         const int R = p->radices[lv];
         const int groups = nodes / R;
@@ -306,11 +327,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         const int st_dtype = last ? o.out_dtype : ADASUM_F32;
         const int np = gram_entries(R, first);
         const bool want_norm = !last || o.layer_stats != nullptr;
-        TileSet ct;
-        {
-            const int rc = p->comb_tiles(in_dtype, R, &ct);
-            if (rc != ADASUM_OK) return rc;
-        }
+        const TileSet ct = comb_sets[lv];
 
         // groups per launch: the operand pointers travel by value in the kernel arguments
         const int batch = std::max(1, kMaxPack / R);
@@ -406,6 +423,78 @@ int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     return ADASUM_OK;
 }
 
+// Replays the whole ladder as one hipGraph launch.  The graph is captured once
+// per distinct set of buffers (kernel arguments are baked into its nodes) on a
+// private stream and cached in the plan; a call with other buffers captures
+// another one (at most kMaxGraphsPerPlan are kept, oldest dropped).
+constexpr size_t kMaxGraphsPerPlan = 8;
+
+int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o,
+                    void* stream) {
+    std::vector<uintptr_t> key;
+    key.reserve(static_cast<size_t>(p->K) + 6);
+    for (int k = 0; k < p->K; ++k) key.push_back(reinterpret_cast<uintptr_t>(grads[k]));
+    key.push_back(reinterpret_cast<uintptr_t>(out));
+    key.push_back(reinterpret_cast<uintptr_t>(ws));
+    key.push_back(reinterpret_cast<uintptr_t>(o.layer_stats));
+    key.push_back(static_cast<uintptr_t>(dtype));
+    key.push_back(static_cast<uintptr_t>(o.out_dtype));
+    key.push_back(static_cast<uintptr_t>(o.order));
+    for (auto& g : p->graphs) {
+        if (g.key == key) {
+            ADASUM_HIP(hipGraphLaunch(g.exec, static_cast<hipStream_t>(stream)));
+            return ADASUM_OK;
+        }
+    }
+    if (p->capture_stream == nullptr) {
+        ADASUM_HIP(hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking));
+    }
+    // everything that allocates happens before the capture starts
+    if (p->K == 1) {
+        TileSet ct;
+        const int rc = p->comb_tiles(dtype, 1, &ct);
+        if (rc != ADASUM_OK) return rc;
+    } else {
+        for (size_t lv = 0; lv < p->radices.size(); ++lv) {
+            TileSet ct;
+            const int rc = p->comb_tiles(lv == 0 ? dtype : ADASUM_F32, p->radices[lv], &ct);
+            if (rc != ADASUM_OK) return rc;
+        }
+    }
+    ADASUM_HIP(hipStreamBeginCapture(p->capture_stream, hipStreamCaptureModeThreadLocal));
+    const int rc = p->K == 1 ? run_copy(p, ws, grads, dtype, out, o, p->capture_stream)
+                             : run_tree(p, ws, grads, dtype, out, o, p->capture_stream);
+    hipGraph_t graph = nullptr;
+    const hipError_t end = hipStreamEndCapture(p->capture_stream, &graph);
+    if (rc != ADASUM_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (end != hipSuccess) {
+        g_last_hip_error = static_cast<int>(end);
+        return ADASUM_ERR_HIP;
+    }
+    hipGraphExec_t exec = nullptr;
+    const hipError_t inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (inst != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        g_last_hip_error = static_cast<int>(inst);
+        return inst == hipErrorOutOfMemory ? ADASUM_ERR_OUT_OF_MEMORY : ADASUM_ERR_HIP;
+    }
+    if (p->graphs.size() >= kMaxGraphsPerPlan) {
+        (void)hipGraphExecDestroy(p->graphs.front().exec);
+        (void)hipGraphDestroy(p->graphs.front().graph);
+        p->graphs.erase(p->graphs.begin());
+    }
+    Plan::GraphEntry e;
+    e.key = std::move(key);
+    e.graph = graph;
+    e.exec = exec;
+    p->graphs.push_back(std::move(e));
+    ADASUM_HIP(hipGraphLaunch(exec, static_cast<hipStream_t>(stream)));
+    return ADASUM_OK;
+}
+
 int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
                 void* out, const adasum_options* opts, void* stream) {
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
@@ -435,6 +524,7 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
+    if (o.use_graph && !g_profile) return launch_as_graph(p, ws, grads, dtype, out, o, stream);
     if (K == 1) return run_copy(p, ws, grads, dtype, out, o, stream);
     return run_tree(p, ws, grads, dtype, out, o, stream);
 }

@@ -279,3 +279,33 @@ def test_config5_edge_cases_scaled():
     for l, mode in w.meta["zero_modes"]:
         if mode == 0:
             assert np.all(got[offs[l]:offs[l + 1]] == 0.0)
+
+
+def test_graph_replay_matches_eager():
+    say("hipGraph replay vs eager launches")
+    sizes = W.scaled_down(W.resnet50_layer_sizes(), 16, floor=3)
+    for K, dtype, radix in ((8, torch.bfloat16, 0), (64, torch.float32, 16), (4, torch.float32, 2), (1, torch.bfloat16, 0)):
+        w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=31 + K)
+        stats_e = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+        stats_g = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+        out_e = torch.empty(w.N, dtype=dtype, device=DEV)
+        out_g = torch.empty(w.N, dtype=dtype, device=DEV)
+        for rep in range(4):
+            # eager work between replays: new values in the same buffers
+            for i, g in enumerate(w.grads):
+                g.mul_(1.0 + 0.25 * ((i + rep) % 3)).add_(0.01 * rep)
+            torch.cuda.synchronize()
+            B.adasum_reduce(w.grads, w.layer_offsets, out_e, radix=radix, layer_stats=stats_e)
+            B.adasum_reduce(w.grads, w.layer_offsets, out_g, radix=radix, layer_stats=stats_g, use_graph=True)
+            torch.cuda.synchronize()
+            assert torch.equal(out_e, out_g), (K, dtype, rep)
+            assert torch.equal(stats_e, stats_g), (K, dtype, rep)
+        # other buffers: a second graph is captured, the first one stays valid
+        other = [g.clone() for g in w.grads]
+        out_o = torch.empty_like(out_g)
+        B.adasum_reduce(other, w.layer_offsets, out_o, radix=radix, use_graph=True)
+        B.adasum_reduce(w.grads, w.layer_offsets, out_g, radix=radix, layer_stats=stats_g, use_graph=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out_o, out_e) and torch.equal(out_g, out_e)
+        ref = oracle_reduce(w.grads, w.layer_offsets)
+        assert_parity(out_g, ref, w.layer_offsets, what=f"graph K={K}")
