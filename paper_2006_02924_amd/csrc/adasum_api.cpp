@@ -90,15 +90,28 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
 struct TileTable {
     std::vector<adasum_tile> tiles;
     std::vector<int32_t> layer_begin;
+    std::vector<int32_t> first_in_gram;   // combine tables only
     adasum_tile* d_tiles = nullptr;
     int32_t* d_layer_begin = nullptr;
+    int32_t* d_first_in_gram = nullptr;
 
     TileSet view() const {
         TileSet t;
         t.tiles = d_tiles;
         t.layer_begin = d_layer_begin;
+        t.first_in_gram = d_first_in_gram;
         t.n_tiles = static_cast<int64_t>(tiles.size());
         return t;
+    }
+    // Both tables are sorted by start and a combine tile never straddles a Gram tile.
+    void index_against(const std::vector<adasum_tile>& gram_tiles) {
+        first_in_gram.assign(gram_tiles.size() + 1, 0);
+        size_t c = 0;
+        for (size_t t = 0; t < gram_tiles.size(); ++t) {
+            while (c < tiles.size() && tiles[c].start < gram_tiles[t].start) ++c;
+            first_in_gram[t] = static_cast<int32_t>(c);
+        }
+        first_in_gram[gram_tiles.size()] = static_cast<int32_t>(tiles.size());
     }
     int upload() {
         if (!tiles.empty()) {
@@ -108,13 +121,20 @@ struct TileTable {
         ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&d_layer_begin), layer_begin.size() * sizeof(int32_t)));
         ADASUM_HIP(hipMemcpy(d_layer_begin, layer_begin.data(), layer_begin.size() * sizeof(int32_t),
                              hipMemcpyHostToDevice));
+        if (!first_in_gram.empty()) {
+            ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&d_first_in_gram), first_in_gram.size() * sizeof(int32_t)));
+            ADASUM_HIP(hipMemcpy(d_first_in_gram, first_in_gram.data(), first_in_gram.size() * sizeof(int32_t),
+                                 hipMemcpyHostToDevice));
+        }
         return ADASUM_OK;
     }
     void release() {
         if (d_tiles) (void)hipFree(d_tiles);
         if (d_layer_begin) (void)hipFree(d_layer_begin);
+        if (d_first_in_gram) (void)hipFree(d_first_in_gram);
         d_tiles = nullptr;
         d_layer_begin = nullptr;
+        d_first_in_gram = nullptr;
     }
 };
 
@@ -146,6 +166,7 @@ struct Plan {
             try {
                 TileTable t;
                 build_tiles(offsets.data(), static_cast<int>(offsets.size()) - 1, cap, t.tiles, t.layer_begin);
+                t.index_against(gram_tiles.tiles);
                 it = comb_tables.emplace(cap, std::move(t)).first;
             } catch (const std::bad_alloc&) {
                 return ADASUM_ERR_OUT_OF_MEMORY;
@@ -303,6 +324,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     char* slots = ws + lay.off_slots;
     double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
+    double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
     double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
     double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
     const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
@@ -353,9 +375,13 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                                      stream));
         }
         // step 2: finish the sums, then the tree's scalars
+        if (!first) {
+            ADASUM_TIMED("norm_coarsen", 0.0, stream,
+                         launch_norm_coarsen(normparts, nodes, norm_tiles, gt, normcoarse, stream));
+        }
         kernel_name("gram_finish", 0, 0, R, first, namebuf, sizeof(namebuf));
         ADASUM_TIMED(namebuf, 0.0, stream,
-                     launch_gram_finish(first, gt, norm_tiles, L, groups, R, partials, normparts, gram, stream));
+                     launch_gram_finish(first, gt, L, groups, R, partials, normcoarse, gram, stream));
         if (first && o.layer_stats != nullptr) {
             ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, o.layer_stats + 1, 2, stream));
         }
@@ -390,7 +416,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         norm_tiles = ct;
     }
     if (o.layer_stats != nullptr) {
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, norm_tiles, L, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, norm_tiles, gt, normcoarse, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, L, o.layer_stats, 2, stream));
     }
     return ADASUM_OK;
 }
@@ -417,8 +444,11 @@ int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                  launch_combine(dtype, o.out_dtype, ops, outs, ct, lay.n_layers, 1, 1, nullptr,
                                 o.layer_stats ? normparts : nullptr, stream));
     if (o.layer_stats != nullptr) {
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, ct, lay.n_layers, o.layer_stats, 2, stream));
-        ADASUM_LAUNCH(launch_layer_sums(normparts, 1, ct, lay.n_layers, o.layer_stats + 1, 2, stream));
+        double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
+        const TileSet gt = p->gram_tiles.view();
+        ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, ct, gt, normcoarse, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, lay.n_layers, o.layer_stats, 2, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, lay.n_layers, o.layer_stats + 1, 2, stream));
     }
     return ADASUM_OK;
 }
@@ -598,7 +628,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     std::memset(&ops, 0, sizeof(ops));
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
     ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, stream));
-    ADASUM_LAUNCH(launch_gram_finish(true, gt, TileSet(), n_layers, 1, R, partials, nullptr, gram, stream));
+    ADASUM_LAUNCH(launch_gram_finish(true, gt, n_layers, 1, R, partials, nullptr, gram, stream));
     return ADASUM_OK;
 }
 
@@ -652,7 +682,12 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     outs.stride = 0;
     ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, ct, n_layers, 1, R, weights,
                                  sqnorm ? normparts : nullptr, stream));
-    if (sqnorm != nullptr) ADASUM_LAUNCH(launch_layer_sums(normparts, 1, ct, n_layers, sqnorm, 1, stream));
+    if (sqnorm != nullptr) {
+        double* normcoarse = reinterpret_cast<double*>(ws + p->lay.off_normcoarse);
+        const TileSet gt = p->gram_tiles.view();
+        ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, ct, gt, normcoarse, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, n_layers, sqnorm, 1, stream));
+    }
     return ADASUM_OK;
 }
 

@@ -70,6 +70,7 @@ struct Layout {
     size_t  off_slots = 0;    // n_slots x slot_elems floats
     size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
     size_t  off_normparts = 0;// doubles [node][combine tile]: squared norm of every node a combine wrote
+    size_t  off_normcoarse = 0;// doubles [node][Gram tile]: the same, summed per Gram tile
     size_t  off_gram = 0;     // doubles [group][layer][R*R] (finished Gram matrices)
     size_t  off_weights = 0;  // doubles [group][layer][R]
     size_t  off_leafnorm = 0; // doubles [layer]: sum over workers of the input squared norms
@@ -104,6 +105,9 @@ struct Outputs {
 struct TileSet {
     const adasum_tile* tiles = nullptr;      // device
     const int32_t* layer_begin = nullptr;    // device, n_layers + 1
+    // combine tables only: device, n_gram_tiles + 1; the tiles of this table
+    // that lie inside Gram tile t are first_in_gram[t] .. first_in_gram[t + 1]
+    const int32_t* first_in_gram = nullptr;
     int64_t n_tiles = 0;
 };
 
@@ -111,10 +115,14 @@ struct TileSet {
 // partials[(group * entries + entry) * gt.n_tiles + tile]
 int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
                 double* partials, void* stream);
-// Sums the per-tile partials (and, when !diag, the squared norms the previous
-// combine left per (node, tile of `nt`)) into full R x R Gram matrices
-// gram[group][layer][R*R].
-int launch_gram_finish(bool diag, const TileSet& gt, const TileSet& nt, int n_layers, int n_groups, int R,
+// coarse[node * gt.n_tiles + t] = sum of fine[node * ct.n_tiles + c] over the combine tiles c inside
+// Gram tile t.
+int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, const TileSet& gt, double* coarse,
+                        void* stream);
+// Sums the per-tile partials (and, when !diag, the coarsened squared norms
+// normparts[(group * R + i) * gt.n_tiles + tile] of the operand nodes) into full
+// R x R Gram matrices gram[group][layer][R*R].
+int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups, int R,
                        const double* partials, const double* normparts, double* gram, void* stream);
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
 int launch_weights(const double* gram, int R, int64_t n_items, int order,

@@ -351,42 +351,73 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
     return tot;
 }
 
+// The combine pass leaves one squared norm per (node, combine tile); combine
+// tiles are short, so a big layer has tens of thousands of them.  This kernel
+// sums them to one value per (node, Gram tile): first_in_gram[t] .. [t+1] are the
+// combine tiles inside Gram tile t.  One wave per (node, Gram tile).
+__global__ void __launch_bounds__(64)
+norm_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles,
+                    const int32_t* __restrict__ first_in_gram, int n_gram_tiles,
+                    double* __restrict__ coarse) {
+    const int t = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_gram_tiles));
+    const int node = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_gram_tiles));
+    const int b = first_in_gram[t], e = first_in_gram[t + 1];
+    const double* row = fine + static_cast<long long>(node) * n_fine_tiles;
+    double v = 0.0;
+    for (int i = b + static_cast<int>(threadIdx.x); i < e; i += 64) v += row[i];
+    v = wave_sum(v);
+    if (threadIdx.x == 0) coarse[static_cast<long long>(node) * n_gram_tiles + t] = v;
+}
+
+// Entry e of the Gram kernel's order -> (i, j).
+template <int R, bool DIAG>
+__device__ __forceinline__ void entry_to_ij(int e, int& i, int& j) {
+    i = 0;
+    int rowlen = DIAG ? R : R - 1;
+    while (e >= rowlen) {
+        e -= rowlen;
+        ++i;
+        --rowlen;
+    }
+    j = (DIAG ? i : i + 1) + e;
+}
+
+// One workgroup per (group, layer); its waves take the entries round-robin,
+// lanes stride over the layer's Gram tiles, a fixed-order wave reduction ends
+// each entry (no workgroup barrier).  When !DIAG the diagonal comes from the
+// coarsened squared norms normparts[(group * R + i) * n_tiles + tile].
 template <int R, bool DIAG>
 __global__ void __launch_bounds__(kThreads)
 gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts,
-                   const int32_t* __restrict__ layer_tile_begin, int n_tiles,
-                   const int32_t* __restrict__ norm_layer_begin, int n_norm_tiles, int n_layers,
+                   const int32_t* __restrict__ layer_tile_begin, int n_tiles, int n_layers,
                    double* __restrict__ gram) {
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
-    __shared__ double sh[kThreads / 64];
-    const int tid = threadIdx.x;
+    constexpr int NW = kThreads / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_layers));
     const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_layers));
     const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
     double* out = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
 
-    int e = 0;
-    for (int i = 0; i < R; ++i) {
-        for (int j = (DIAG ? i : i + 1); j < R; ++j) {
-            const double* row = partials + (static_cast<long long>(g) * NP + e) * n_tiles;
-            double v = 0.0;
-            for (int t = tb + tid; t < te; t += kThreads) v += row[t];
-            v = block_sum(v, sh);
-            if (tid == 0) {
-                out[i * R + j] = v;
-                out[j * R + i] = v;
-            }
-            ++e;
+    for (int e = wave; e < NP; e += NW) {
+        const double* row = partials + (static_cast<long long>(g) * NP + e) * n_tiles;
+        double v = 0.0;
+        for (int t = tb + lane; t < te; t += 64) v += row[t];
+        v = wave_sum(v);
+        if (lane == 0) {
+            int i, j;
+            entry_to_ij<R, DIAG>(e, i, j);
+            out[i * R + j] = v;
+            out[j * R + i] = v;
         }
     }
     if (!DIAG) {
-        const int nb = norm_layer_begin[l], ne = norm_layer_begin[l + 1];
-        for (int i = 0; i < R; ++i) {
-            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_norm_tiles;
+        for (int i = wave; i < R; i += NW) {
+            const double* row = normparts + (static_cast<long long>(g) * R + i) * n_tiles;
             double v = 0.0;
-            for (int t = nb + tid; t < ne; t += kThreads) v += row[t];
-            v = block_sum(v, sh);
-            if (tid == 0) out[i * R + i] = v;
+            for (int t = tb + lane; t < te; t += 64) v += row[t];
+            v = wave_sum(v);
+            if (lane == 0) out[i * R + i] = v;
         }
     }
 }
@@ -622,17 +653,28 @@ int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, in
                 : launch_gram_r<float, false>(ops, gt, n_groups, R, partials, st);
 }
 
-int launch_gram_finish(bool diag, const TileSet& gt, const TileSet& nt, int n_layers, int n_groups, int R,
+int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, const TileSet& gt, double* coarse,
+                        void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const long long blocks = static_cast<long long>(n_nodes) * gt.n_tiles;
+    if (blocks == 0) return 0;
+    if (!grid_fits(blocks) || ct.first_in_gram == nullptr) return static_cast<int>(hipErrorInvalidConfiguration);
+    hipLaunchKernelGGL(norm_coarsen_kernel, dim3(static_cast<unsigned>(blocks)), dim3(64), 0, st, fine,
+                       static_cast<int>(ct.n_tiles), ct.first_in_gram, static_cast<int>(gt.n_tiles), coarse);
+    return check_launch();
+}
+
+int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups, int R,
                        const double* partials, const double* normparts, double* gram, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const long long blocks = static_cast<long long>(n_groups) * n_layers;
     if (blocks == 0) return 0;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const int ngt = static_cast<int>(gt.n_tiles), nnt = static_cast<int>(nt.n_tiles);
+    const int ngt = static_cast<int>(gt.n_tiles);
 #define ADASUM_FINISH(RR, DD)                                                                      \
     hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
-                       gt.layer_begin, ngt, nt.layer_begin, nnt, n_layers, gram)
+                       gt.layer_begin, ngt, n_layers, gram)
     switch (R) {
         case 2: if (diag) ADASUM_FINISH(2, true); else ADASUM_FINISH(2, false); break;
         case 4: if (diag) ADASUM_FINISH(4, true); else ADASUM_FINISH(4, false); break;

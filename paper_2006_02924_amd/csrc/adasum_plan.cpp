@@ -110,6 +110,8 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
     off = align_up(off + max_partials * sizeof(double), 256);
     lay.off_normparts = off;
     off = align_up(off + static_cast<size_t>(norm_entries) * sizeof(double), 256);
+    lay.off_normcoarse = off;
+    off = align_up(off + max_nodes * static_cast<size_t>(n_tiles) * sizeof(double), 256);
     lay.off_gram = off;
     off = align_up(off + max_gram * sizeof(double), 256);
     lay.off_weights = off;
