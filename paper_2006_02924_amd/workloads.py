@@ -243,17 +243,19 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
             kind[l] = "orth_all"
             break
     offs = offsets_from_sizes(base)
-    N = offs[-1]
     dtype = torch.bfloat16
-    grads = [torch.empty(N, dtype=dtype, device=device) for _ in range(K)]
-    dg = _gen(device, 4)
+    for l, k in enumerate(kind):
+        if k == "parallel":
+            corr_l[l] = 0.999
+    # every layer first gets the plain correlated-Gaussian recipe; the special kinds overwrite theirs
+    grads = correlated_gaussian(base, K, dtype=dtype, device=device, seed=4, corr=corr_l, scale=scale_l).grads
+    dg = _gen(device, 4 + 1000)
     zero_seen = 0
     for l, n in enumerate(base):
-        if n == 0:
-            continue
         k = kind[l]
-        a = 0.999 if k == "parallel" else corr_l[l]
-        corr_l[l] = a
+        if n == 0 or k in ("gauss", "parallel"):
+            continue
+        a = corr_l[l]
         b = math.sqrt(max(0.0, 1.0 - a * a))
         sl = slice(offs[l], offs[l + 1])
         if k == "orth_all":
@@ -261,23 +263,19 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
             q, _ = torch.linalg.qr(m)
             for i in range(K):
                 grads[i][sl] = (q[:, i] * (scale_l[l] * math.sqrt(n))).to(dtype)
-            continue
-        c = torch.randn(n, generator=dg, device=device, dtype=torch.float32)
-        prev64 = None
-        for i in range(K):
-            ni = torch.randn(n, generator=dg, device=device, dtype=torch.float32)
-            g = (c * a + ni * b) * scale_l[l]
-            if k == "orth_pairs":
-                g64 = g.to(torch.float64)
+        elif k == "orth_pairs":
+            c = torch.randn(n, generator=dg, device=device, dtype=torch.float32)
+            prev64 = None
+            for i in range(K):
+                ni = torch.randn(n, generator=dg, device=device, dtype=torch.float32)
+                g64 = ((c * a + ni * b) * scale_l[l]).to(torch.float64)
                 if i % 2 == 0:
                     prev64 = g64
                 else:
-                    pn = torch.dot(prev64, prev64)
-                    if float(pn) > 0.0:
-                        g64 = g64 - (torch.dot(g64, prev64) / pn) * prev64
-                    g = g64
-            grads[i][sl] = g.to(dtype)
-        if k == "zero":
+                    pn = torch.dot(prev64, prev64).clamp_min(1e-300)
+                    g64 = g64 - (torch.dot(g64, prev64) / pn) * prev64
+                grads[i][sl] = g64.to(dtype)
+        elif k == "zero":
             mode = zero_seen % 3
             zero_seen += 1
             zero_modes.append((l, mode))
