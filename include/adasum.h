@@ -42,6 +42,8 @@ extern "C" {
 /* element storage types */
 #define ADASUM_F32  0   /* IEEE binary32 */
 #define ADASUM_BF16 1   /* bfloat16; stores round to nearest even */
+#define ADASUM_F16  2   /* IEEE binary16; stores round to nearest even (no loss scaling here:
+                           values must fit the format, as Section 4.4.1's dynamic scaling ensures) */
 
 /* error codes */
 #define ADASUM_OK                 0
@@ -63,7 +65,8 @@ extern "C" {
  */
 typedef struct adasum_options {
     uint32_t struct_bytes;     /* sizeof(adasum_options) as the caller compiled it */
-    int32_t  out_dtype;        /* ADASUM_F32 | ADASUM_BF16; -1 = same as the input dtype */
+    int32_t  out_dtype;        /* the input dtype or ADASUM_F32 (any storage type when the input
+                                  is fp32); -1 = same as the input dtype */
     int32_t  radix;            /* how many binary tree levels one pass over the data fuses:
                                   2 = one level per pass (reduce pass + combine pass per level),
                                   4 / 8 / 16 = two / three / four levels per pass (the pass
@@ -93,7 +96,7 @@ typedef struct adasum_options {
  *   layer_offsets  HOST, n_layers + 1 entries in element units, [0] = 0,
  *                  non-decreasing; layer l is [layer_offsets[l], layer_offsets[l+1]);
  *                  empty layers are allowed; N = 0 is a no-op
- *   dtype          ADASUM_F32 | ADASUM_BF16: storage type of grads AND of out
+ *   dtype          ADASUM_F32 | ADASUM_BF16 | ADASUM_F16: storage type of grads AND of out
  *   out            DEVICE, N elements of `dtype`; must not overlap any input
  *   stream         hipStream_t
  *

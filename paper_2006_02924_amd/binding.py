@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 # ADASUM_LIB overrides the library file (e.g. a build with other tuning knobs)
 LIB_PATH = os.environ.get("ADASUM_LIB") or os.path.join(HERE, "libadasum.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ORDER_TREE, ORDER_LINEAR = 0, 1
 
 OK = 0
@@ -131,12 +131,19 @@ def _dtype_code(t) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _code_of(torch_dtype) -> int:
+    import torch
+    return {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}[torch_dtype]
 
 
 def _torch_dtype(code: int):
     import torch
-    return torch.float32 if code == F32 else torch.bfloat16
+    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[code]
 
 
 def _stream(stream) -> C.c_void_p:
@@ -170,7 +177,7 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
     N = int(layer_offsets[-1])
     _check_inputs(grads, N)
     in_code = _dtype_code(grads[0])
-    out_code = in_code if out_dtype is None else (F32 if out_dtype == torch.float32 else BF16)
+    out_code = in_code if out_dtype is None else _code_of(out_dtype)
     if out is None:
         out = torch.empty(N, dtype=_torch_dtype(out_code), device=grads[0].device)
     elif _dtype_code(out) != out_code or out.numel() != N or not out.is_contiguous():
@@ -247,7 +254,7 @@ def adasum_group_combine(xs: Sequence, layer_offsets: Sequence[int], weights, *,
     N = int(layer_offsets[-1])
     _check_inputs(xs, N)
     in_code = _dtype_code(xs[0])
-    out_code = in_code if out_dtype is None else (F32 if out_dtype == torch.float32 else BF16)
+    out_code = in_code if out_dtype is None else _code_of(out_dtype)
     if weights.dtype != torch.float64 or weights.numel() != L * len(xs) or not weights.is_contiguous():
         raise ValueError("weights must be a contiguous float64 tensor of n_layers x R")
     if out is None:

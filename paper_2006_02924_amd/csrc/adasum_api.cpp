@@ -73,7 +73,7 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
         r.workspace_bytes = o->workspace_bytes;
         r.layer_stats = o->layer_stats;
     }
-    if (r.out_dtype != ADASUM_F32 && r.out_dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    if (!dtype_pair_ok(dtype, r.out_dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if (r.order == ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;   // scheduler: tree only
@@ -530,7 +530,7 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
-    if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
     Opts o;
     rc = read_opts(opts, dtype, o);
     if (rc != ADASUM_OK) return rc;
@@ -581,7 +581,7 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
     if (bytes == nullptr || K < 1) return ADASUM_ERR_INVALID_ARG;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
-    if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
     Opts o;
     rc = read_opts(opts, dtype, o);
     if (rc != ADASUM_OK && rc != ADASUM_ERR_WORKSPACE) return rc;
@@ -603,7 +603,7 @@ static int step_common(const void* const* x, int R, const int64_t* layer_offsets
     if (R != 2 && R != 4 && R != 8 && R != 16) return ADASUM_ERR_UNSUPPORTED;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
-    if (dtype != ADASUM_F32 && dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
     return check_operands(x, R, layer_offsets[n_layers], dtype);
 }
 
@@ -648,7 +648,7 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
                          const double* weights, void* out, int out_dtype, double* sqnorm, void* stream) {
     int rc = step_common(x, R, layer_offsets, n_layers, dtype);
     if (rc != ADASUM_OK) return rc;
-    if (out_dtype != ADASUM_F32 && out_dtype != ADASUM_BF16) return ADASUM_ERR_UNSUPPORTED;
+    if (!dtype_pair_ok(dtype, out_dtype)) return ADASUM_ERR_UNSUPPORTED;
     const int64_t N = layer_offsets[n_layers];
     if ((weights == nullptr && n_layers > 0) || (out == nullptr && N > 0)) return ADASUM_ERR_INVALID_ARG;
     if (!aligned16(out) || (reinterpret_cast<uintptr_t>(weights) & 7u) != 0 ||
@@ -762,7 +762,7 @@ const char* adasum_strerror(int code) {
     switch (code) {
         case ADASUM_OK: return "ok";
         case ADASUM_ERR_INVALID_ARG: return "invalid argument";
-        case ADASUM_ERR_UNSUPPORTED: return "unsupported (K must be a power of two; dtype f32/bf16; radix 2/4/8/16)";
+        case ADASUM_ERR_UNSUPPORTED: return "unsupported (K must be a power of two; dtype f32/bf16/f16, output the same type or f32; radix 2/4/8/16)";
         case ADASUM_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
         case ADASUM_ERR_OUT_OF_MEMORY: return "out of memory";
         case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";

@@ -28,7 +28,7 @@ constexpr int kThreads = ADASUM_THREADS;
 // streams best when it moves 16-20 KB in all, so wider groups get fewer lanes.
 constexpr int combine_threads(int R) { return R >= 16 ? 64 : (R >= 8 ? 128 : 256); }
 // Tile capacity of the combine pass: depends on the input type and the radix.
-inline int combine_tile_capacity(int dtype, int R) { return combine_threads(R) * (dtype == ADASUM_BF16 ? 8 : 4); }
+inline int combine_tile_capacity(int dtype, int R) { return combine_threads(R) * (dtype == ADASUM_F32 ? 4 : 8); }
 
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
@@ -36,7 +36,10 @@ constexpr int kMaxRadix = 16;
 // Radix used when the caller asks for 0: the widest pass moves the fewest bytes.
 constexpr int kDefaultRadix = 16;
 
-inline int elem_bytes(int dtype) { return dtype == ADASUM_BF16 ? 2 : 4; }
+inline int elem_bytes(int dtype) { return dtype == ADASUM_F32 ? 4 : 2; }
+inline bool known_dtype(int dtype) { return dtype == ADASUM_F32 || dtype == ADASUM_BF16 || dtype == ADASUM_F16; }
+// Output storage types a combine supports for an input type: the same type or fp32; any type from fp32.
+inline bool dtype_pair_ok(int in, int out) { return known_dtype(in) && known_dtype(out) && (in == out || in == ADASUM_F32 || out == ADASUM_F32); }
 inline bool is_pow2(long long v) { return v > 0 && (v & (v - 1)) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -20,6 +20,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 #include "adasum_host.h"
 
@@ -34,7 +35,11 @@
 #ifndef ADASUM_NT_STORE
 #define ADASUM_NT_STORE 1
 #endif
-// bf16 Gram entries through v_dot2c_f32_bf16 (1) or unpack + fp32 FMA (0)
+// bf16 Gram entries through v_dot2c_f32_bf16: 0 = never (unpack + fp32 FMA), 1 = only at
+// radix 16, where 136 entries per lane would otherwise be bound by the vector ALUs
+// (14.8 ms instead of 7.0 ms on the K=64 BERT-Large case), 2 = always.  The instruction
+// adds two exact bf16 products to the fp32 accumulator but, unlike an FMA, does not round
+// to nearest (measured: 1585 of 65536 probes differ from the FMA chain, all one ulp toward zero).
 #ifndef ADASUM_BF16_DOT2
 #define ADASUM_BF16_DOT2 1
 #endif
@@ -47,10 +52,13 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct bf16_t { unsigned short v; };
+struct f16_t { unsigned short v; };   // IEEE binary16
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 
 template <typename T> struct Traits;
 template <> struct Traits<float>  { static constexpr int VEC = 4; };
 template <> struct Traits<bf16_t> { static constexpr int VEC = 8; };
+template <> struct Traits<f16_t>  { static constexpr int VEC = 8; };
 
 // round to nearest even; NaN stays NaN (quiet), overflow rounds to infinity
 __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
@@ -121,6 +129,22 @@ __device__ __forceinline__ void unpack(const Granule<bf16_t, G>& r, float (&v)[G
     }
 }
 
+template <int G>
+__device__ __forceinline__ void unpack(const Granule<f16_t, G>& r, float (&v)[G]) {
+#pragma unroll
+    for (int i = 0; i < G / 2; ++i) {
+        const f16x2_t h = __builtin_bit_cast(f16x2_t, r.w[i]);
+        v[2 * i + 0] = static_cast<float>(h.x);
+        v[2 * i + 1] = static_cast<float>(h.y);
+    }
+}
+
+// fp32 -> binary16, round to nearest even (the conversion instruction's default mode)
+__device__ __forceinline__ unsigned int f32_to_f16_bits(float f) {
+    const _Float16 h = static_cast<_Float16>(f);
+    return static_cast<unsigned int>(__builtin_bit_cast(unsigned short, h));
+}
+
 template <bool NT, int NW>
 __device__ __forceinline__ void store_words(void* p, const unsigned int (&w)[NW]) {
     if constexpr (NW == 2) {
@@ -157,7 +181,21 @@ __device__ __forceinline__ void store_granule(bf16_t* p, const float (&v)[G]) {
     store_words<NT>(p, w);
 }
 
+template <bool NT, int G>
+__device__ __forceinline__ void store_granule(f16_t* p, const float (&v)[G]) {
+    unsigned int w[G / 2];
+#pragma unroll
+    for (int i = 0; i < G / 2; ++i) w[i] = f32_to_f16_bits(v[2 * i]) | (f32_to_f16_bits(v[2 * i + 1]) << 16);
+    store_words<NT>(p, w);
+}
+
 __device__ __forceinline__ float load_elem(const float* p) { return *p; }
+__device__ __forceinline__ float load_elem(const f16_t* p) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, p->v));
+}
+__device__ __forceinline__ void store_elem(f16_t* p, float v) {
+    p->v = static_cast<unsigned short>(f32_to_f16_bits(v));
+}
 __device__ __forceinline__ float load_elem(const bf16_t* p) {
     return __uint_as_float(static_cast<unsigned int>(p->v) << 16);
 }
@@ -236,19 +274,25 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     for (int e = 0; e < NP; ++e) acc[e] = 0.f;
 
     auto consume = [&](const Granule<T, G> (&raw)[R]) {
-        if constexpr (sizeof(T) == 2 && ADASUM_BF16_DOT2) {
-            // two bf16 products and the fp32 accumulate in one instruction, straight
-            // from the packed words (bf16 x bf16 is exact in fp32)
+        if constexpr (sizeof(T) == 2 && (ADASUM_BF16_DOT2 == 2 || (ADASUM_BF16_DOT2 == 1 && R >= 16))) {
+            // two 16-bit products and the fp32 accumulate in one instruction, straight
+            // from the packed words (bf16 x bf16 and f16 x f16 are exact in fp32)
             int e = 0;
 #pragma unroll
             for (int i = 0; i < R; ++i) {
 #pragma unroll
                 for (int j = (DIAG ? i : i + 1); j < R; ++j) {
 #pragma unroll
-                    for (int k = 0; k < Granule<T, G>::NW; ++k)
-                        acc[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw[i].w[k]),
-                                                                 __builtin_bit_cast(bf16x2_t, raw[j].w[k]),
-                                                                 acc[e], false);
+                    for (int k = 0; k < Granule<T, G>::NW; ++k) {
+                        if constexpr (std::is_same<T, bf16_t>::value) {
+                            acc[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw[i].w[k]),
+                                                                     __builtin_bit_cast(bf16x2_t, raw[j].w[k]),
+                                                                     acc[e], false);
+                        } else {
+                            acc[e] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, raw[i].w[k]),
+                                                            __builtin_bit_cast(f16x2_t, raw[j].w[k]), acc[e], false);
+                        }
+                    }
                     ++e;
                 }
             }
@@ -649,6 +693,10 @@ int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, in
         return diag ? launch_gram_r<bf16_t, true>(ops, gt, n_groups, R, partials, st)
                     : launch_gram_r<bf16_t, false>(ops, gt, n_groups, R, partials, st);
     }
+    if (dtype == ADASUM_F16) {
+        return diag ? launch_gram_r<f16_t, true>(ops, gt, n_groups, R, partials, st)
+                    : launch_gram_r<f16_t, false>(ops, gt, n_groups, R, partials, st);
+    }
     return diag ? launch_gram_r<float, true>(ops, gt, n_groups, R, partials, st)
                 : launch_gram_r<float, false>(ops, gt, n_groups, R, partials, st);
 }
@@ -707,14 +755,26 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
                    int n_layers, int n_groups, int R, const double* weights, double* normparts, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ct.n_tiles == 0 || n_groups == 0) return 0;
+    // supported pairs: T -> fp32, fp32 -> T, T -> T
     if (dtype == ADASUM_BF16) {
-        return out_dtype == ADASUM_BF16
-                   ? launch_combine_r<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st)
-                   : launch_combine_r<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        if (out_dtype == ADASUM_BF16)
+            return launch_combine_r<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        if (out_dtype == ADASUM_F32)
+            return launch_combine_r<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        return static_cast<int>(hipErrorInvalidValue);
     }
-    return out_dtype == ADASUM_BF16
-               ? launch_combine_r<float, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st)
-               : launch_combine_r<float, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+    if (dtype == ADASUM_F16) {
+        if (out_dtype == ADASUM_F16)
+            return launch_combine_r<f16_t, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        if (out_dtype == ADASUM_F32)
+            return launch_combine_r<f16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        return static_cast<int>(hipErrorInvalidValue);
+    }
+    if (out_dtype == ADASUM_BF16)
+        return launch_combine_r<float, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+    if (out_dtype == ADASUM_F16)
+        return launch_combine_r<float, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+    return launch_combine_r<float, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
 }
 
 int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers, double* layer_sum,
@@ -736,8 +796,8 @@ int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, dou
 }
 
 const char* kernel_name(const char* kind, int dtype, int out_dtype, int R, bool diag, char* buf, size_t n) {
-    const char* in = dtype == ADASUM_BF16 ? "bf16" : "f32";
-    const char* out = out_dtype == ADASUM_BF16 ? "bf16" : "f32";
+    const char* in = dtype == ADASUM_BF16 ? "bf16" : (dtype == ADASUM_F16 ? "f16" : "f32");
+    const char* out = out_dtype == ADASUM_BF16 ? "bf16" : (out_dtype == ADASUM_F16 ? "f16" : "f32");
     if (std::strcmp(kind, "gram") == 0) {
         std::snprintf(buf, n, "gram<%s,R=%d,%s>", in, R, diag ? "diag" : "offdiag");
     } else if (std::strcmp(kind, "combine") == 0) {

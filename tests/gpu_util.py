@@ -15,6 +15,11 @@ TOL_BF16 = 2e-3   # per-layer relative L2 error, bf16 output
 # each element against RNE(oracle) to within one ulp.
 TOL_BF16_TINY = 2.0 ** -8 * 1.001
 TINY_LAYER = 256
+# IEEE binary16 has three more significand bits than bf16: the same reasoning gives 2e-3 / 8
+# over many elements and 2^-11 for a few (values must stay in the normal range, which the
+# paper's dynamic loss scaling is there to ensure; the fp16 test inputs have scales >= 1e-2).
+TOL_F16 = 2.5e-4
+TOL_F16_TINY = 2.0 ** -11 * 1.001
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
@@ -37,16 +42,16 @@ def oracle_reduce(grads, layer_offsets, layers=None) -> np.ndarray:
 
 
 def tol_for(dtype: torch.dtype) -> float:
-    return TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
+    return {torch.bfloat16: TOL_BF16, torch.float16: TOL_F16}.get(dtype, TOL_F32)
 
 
 def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None, tol=None, what=""):
     tol = tol_for(out.dtype) if tol is None else tol
     offs = list(layer_offsets)
     tols = np.full(len(offs) - 1, tol)
-    if out.dtype == torch.bfloat16:
+    if out.dtype in (torch.bfloat16, torch.float16):
         sizes = np.diff(np.asarray(offs))
-        tols[sizes < TINY_LAYER] = max(tol, TOL_BF16_TINY)
+        tols[sizes < TINY_LAYER] = max(tol, TOL_BF16_TINY if out.dtype == torch.bfloat16 else TOL_F16_TINY)
     got = to_f64(out)
     if layers is None:
         err = O.rel_l2_per_layer(got, ref, offs)
@@ -63,19 +68,21 @@ def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None
 
 
 def assert_bf16_rounding(out_bf16: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None):
-    """Sharper than relative L2: every stored bf16 element is the oracle value
-    rounded once -- within half a bf16 ulp of it (relative 2^-8), plus the fp32
+    """Sharper than relative L2: every stored bf16 (or fp16) element is the oracle value
+    rounded once -- within half an ulp of it (relative 2^-8, or 2^-11 for fp16), plus the fp32
     noise of the computation, which is relative to the layer's magnitude (an
     element that nearly cancels is small against its own rounding noise)."""
     offs = list(layer_offsets)
     got = to_f64(out_bf16)
+    half_ulp = 2.0 ** -8 if out_bf16.dtype == torch.bfloat16 else 2.0 ** -11
+    quantum = 1e-45 if out_bf16.dtype == torch.bfloat16 else 2.0 ** -25   # half the subnormal spacing
     todo = range(len(offs) - 1) if layers is None else layers
     for l in todo:
         lo, hi = offs[l], offs[l + 1]
         if hi == lo:
             continue
         r = ref[lo:hi]
-        bound = 2.0 ** -8 * np.abs(r) + 2e-6 * np.abs(r).max() + 1e-45
+        bound = half_ulp * np.abs(r) + 2e-6 * np.abs(r).max() + quantum
         bad = np.abs(got[lo:hi] - r) > bound
         assert not bad.any(), (f"layer {l}: {int(bad.sum())} elements off by more than one rounding, "
                                f"first at {int(np.argmax(bad))}: got {got[lo:hi][bad][0]!r} want {r[bad][0]!r}")

@@ -76,7 +76,7 @@ def test_config4_full_size_sampled_layers(config4):
     a = outs[(0, torch.bfloat16)].float()
     b = outs[(2, torch.bfloat16)].float()
     differ = float((a != b).float().mean())
-    say(f"  radix 8 vs radix 2 bf16 outputs differ in {differ:.2e} of the elements")
+    say(f"  default radix vs radix 2 bf16 outputs differ in {differ:.2e} of the elements")
     assert differ < 1e-2
 
 

@@ -309,3 +309,52 @@ def test_graph_replay_matches_eager():
         assert torch.equal(out_o, out_e) and torch.equal(out_g, out_e)
         ref = oracle_reduce(w.grads, w.layer_offsets)
         assert_parity(out_g, ref, w.layer_offsets, what=f"graph K={K}")
+
+
+@pytest.mark.parametrize("radix", [2, 8, 16])
+@pytest.mark.parametrize("K", [1, 2, 16, 64])
+def test_fp16_storage(K, radix):
+    """IEEE binary16 gradients (the low-precision format of Section 4.4.1), fp16 and fp32 results."""
+    if K == 1 and radix != 2:
+        pytest.skip("K=1 has no passes")
+    say(f"fp16 K={K} radix={radix}")
+    sizes = np.diff(RAGGED).tolist()
+    scales = W.log_uniform_scales(len(sizes), 77, lo_exp=-2.0, hi_exp=0.0)
+    w = W.correlated_gaussian(sizes, K, dtype=torch.float16, device=DEV, seed=300 + K, scale=scales)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    for out_dtype in (torch.float16, torch.float32):
+        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix)
+        torch.cuda.synchronize()
+        assert out.dtype == out_dtype
+        assert_parity(out, ref, w.layer_offsets, what=f"fp16->{out_dtype}")
+        if out_dtype == torch.float16:
+            assert_bf16_rounding(out, ref, w.layer_offsets)
+    # fp32 gradients stored to fp16
+    w32 = W.correlated_gaussian(sizes, K, dtype=torch.float32, device=DEV, seed=300 + K, scale=scales)
+    out = B.adasum_reduce(w32.grads, w32.layer_offsets, out_dtype=torch.float16, radix=radix)
+    torch.cuda.synchronize()
+    ref32 = oracle_reduce(w32.grads, w32.layer_offsets)
+    assert_parity(out, ref32, w32.layer_offsets, what="f32->fp16")
+    assert_bf16_rounding(out, ref32, w32.layer_offsets)
+
+
+def test_unsupported_dtype_pairs():
+    g = [torch.zeros(64, dtype=torch.bfloat16, device=DEV) for _ in range(2)]
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(g, [0, 64], out_dtype=torch.float16)
+    assert e.value.code == B.ERR_UNSUPPORTED
+
+
+def test_fp16_step_entry_points():
+    say("fp16 group steps")
+    sizes = np.diff(RAGGED).tolist()
+    w = W.correlated_gaussian(sizes, 16, dtype=torch.float16, device=DEV, seed=41)
+    gram = B.adasum_group_gram(w.grads, w.layer_offsets)
+    torch.cuda.synchronize()
+    X = np.stack([to_f64(g) for g in w.grads])
+    got = gram.cpu().numpy()
+    for l in range(w.n_layers):
+        lo, hi = RAGGED[l], RAGGED[l + 1]
+        want = X[:, lo:hi] @ X[:, lo:hi].T
+        scale = np.sqrt(np.outer(np.diag(want), np.diag(want))) + 1e-300
+        assert np.max(np.abs(got[l] - want) / scale) < 2e-6, l
