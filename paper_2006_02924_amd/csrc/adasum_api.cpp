@@ -76,7 +76,7 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     if (!dtype_pair_ok(dtype, r.out_dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
-    if (r.order == ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;   // scheduler: tree only
+    if (r.order == ADASUM_ORDER_LINEAR && r.layer_stats != nullptr) return ADASUM_ERR_UNSUPPORTED;
     if (r.workspace != nullptr && (reinterpret_cast<uintptr_t>(r.workspace) & 255u) != 0)
         return ADASUM_ERR_WORKSPACE;
     if (r.layer_stats != nullptr && (reinterpret_cast<uintptr_t>(r.layer_stats) & 7u) != 0)
@@ -142,6 +142,7 @@ struct Plan {
     int device = 0;
     int K = 0;
     int radix = 0;
+    int order = ADASUM_ORDER_TREE;
     std::vector<int64_t> offsets;
     TileTable gram_tiles;                 // capacity kTile
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
@@ -197,11 +198,11 @@ struct Plan {
 std::mutex g_mutex;
 std::vector<std::unique_ptr<Plan>> g_plans;
 
-int find_or_make_plan(int K, int radix, const int64_t* offsets, int n_layers, Plan** out) {
+int find_or_make_plan(int K, int radix, int order, const int64_t* offsets, int n_layers, Plan** out) {
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
     for (auto& p : g_plans) {
-        if (p->device == device && p->K == K && p->radix == radix &&
+        if (p->device == device && p->K == K && p->radix == radix && p->order == order &&
             static_cast<int>(p->offsets.size()) == n_layers + 1 &&
             std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
             *out = p.get();
@@ -214,12 +215,14 @@ int find_or_make_plan(int K, int radix, const int64_t* offsets, int n_layers, Pl
         p->device = device;
         p->K = K;
         p->radix = radix;
+        p->order = order;
         p->offsets.assign(offsets, offsets + n_layers + 1);
         build_tiles(offsets, n_layers, kTile, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
-        int rc = build_levels(K, radix, p->radices);
+        int rc = order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, radix, p->radices)
+                                              : build_levels(K, radix, p->radices);
         if (rc != ADASUM_OK) return rc;
         p->lay = make_layout(K, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
-                             norm_entries_bound(K, offsets, n_layers, p->radices), p->radices);
+                             norm_entries_bound(K, offsets, n_layers, p->radices), p->radices, order);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
@@ -422,6 +425,76 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     return ADASUM_OK;
 }
 
+// Left-to-right order (Section 3.4, first recursion).  Pass 0 folds the first
+// leaves; every later pass folds the running result (fp32, slot 0, operand 0)
+// with the next leaves.  Leaves that are not stored as fp32 are first widened
+// into slots 1.. so that one pass reads operands of one type.
+int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
+    const Layout& lay = p->lay;
+    const int L = lay.n_layers;
+    const TileSet gt = p->gram_tiles.view();
+    char* slots = ws + lay.off_slots;
+    double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
+    double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
+    double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
+    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
+    const int n_passes = static_cast<int>(p->radices.size());
+
+    // every table first: nothing below may allocate
+    TileSet widen_tiles;
+    std::vector<TileSet> comb_sets(n_passes);
+    for (int b = 0; b < n_passes; ++b) {
+        const int rc = p->comb_tiles(b == 0 ? dtype : ADASUM_F32, p->radices[b], &comb_sets[b]);
+        if (rc != ADASUM_OK) return rc;
+    }
+    if (dtype != ADASUM_F32 && n_passes > 1) {
+        const int rc = p->comb_tiles(dtype, 1, &widen_tiles);
+        if (rc != ADASUM_OK) return rc;
+    }
+
+    int next_leaf = 0;
+    for (int b = 0; b < n_passes; ++b) {
+        const int R = p->radices[b];
+        const bool first = b == 0, last = b == n_passes - 1;
+        const int in_dtype = first ? dtype : ADASUM_F32;
+        const int st_dtype = last ? o.out_dtype : ADASUM_F32;
+        Operands ops;
+        std::memset(&ops, 0, sizeof(ops));
+        if (first) {
+            for (int r = 0; r < R; ++r) ops.pack[r] = grads[next_leaf + r];
+            next_leaf += R;
+        } else {
+            ops.pack[0] = slots;
+            for (int r = 1; r < R; ++r) {
+                const void* leaf = grads[next_leaf + r - 1];
+                if (dtype != ADASUM_F32) {
+                    char* wide = slots + static_cast<long long>(r) * slot_bytes;
+                    Operands one;
+                    std::memset(&one, 0, sizeof(one));
+                    one.pack[0] = leaf;
+                    Outputs wo;
+                    wo.base = wide;
+                    wo.slot_bytes = 0;
+                    wo.stride = 0;
+                    ADASUM_LAUNCH(launch_combine(dtype, ADASUM_F32, one, wo, widen_tiles, L, 1, 1, nullptr, nullptr, stream));
+                    leaf = wide;
+                }
+                ops.pack[r] = leaf;
+            }
+            next_leaf += R - 1;
+        }
+        ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, stream));
+        ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, stream));
+        ADASUM_LAUNCH(launch_weights(gram, R, L, ADASUM_ORDER_LINEAR, weights, stream));
+        Outputs outs;
+        outs.base = last ? static_cast<char*>(out) : slots;
+        outs.slot_bytes = 0;
+        outs.stride = 0;
+        ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights, nullptr, stream));
+    }
+    return ADASUM_OK;
+}
+
 // K = 1: the result is the gradient itself, converted to the output dtype.
 int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
     const Layout& lay = p->lay;
@@ -490,10 +563,17 @@ int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void
             const int rc = p->comb_tiles(lv == 0 ? dtype : ADASUM_F32, p->radices[lv], &ct);
             if (rc != ADASUM_OK) return rc;
         }
+        if (o.order == ADASUM_ORDER_LINEAR && dtype != ADASUM_F32) {
+            TileSet ct;
+            const int rc = p->comb_tiles(dtype, 1, &ct);
+            if (rc != ADASUM_OK) return rc;
+        }
     }
     ADASUM_HIP(hipStreamBeginCapture(p->capture_stream, hipStreamCaptureModeThreadLocal));
     const int rc = p->K == 1 ? run_copy(p, ws, grads, dtype, out, o, p->capture_stream)
-                             : run_tree(p, ws, grads, dtype, out, o, p->capture_stream);
+                   : o.order == ADASUM_ORDER_LINEAR
+                       ? run_linear(p, ws, grads, dtype, out, o, p->capture_stream)
+                       : run_tree(p, ws, grads, dtype, out, o, p->capture_stream);
     hipGraph_t graph = nullptr;
     const hipError_t end = hipStreamEndCapture(p->capture_stream, &graph);
     if (rc != ADASUM_OK) {
@@ -549,13 +629,14 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(K, o.radix == 0 ? kDefaultRadix : o.radix, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(K, o.radix == 0 ? kDefaultRadix : o.radix, o.order, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
     if (o.use_graph && !g_profile) return launch_as_graph(p, ws, grads, dtype, out, o, stream);
     if (K == 1) return run_copy(p, ws, grads, dtype, out, o, stream);
+    if (o.order == ADASUM_ORDER_LINEAR) return run_linear(p, ws, grads, dtype, out, o, stream);
     return run_tree(p, ws, grads, dtype, out, o, stream);
 }
 
@@ -587,11 +668,12 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
     if (rc != ADASUM_OK && rc != ADASUM_ERR_WORKSPACE) return rc;
     try {
         std::vector<int> radices;
-        rc = build_levels(K, o.radix, radices);
+        rc = o.order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, o.radix, radices)
+                                            : build_levels(K, o.radix, radices);
         if (rc != ADASUM_OK) return rc;
         const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers,
                                        count_tiles(layer_offsets, n_layers, kTile),
-                                       norm_entries_bound(K, layer_offsets, n_layers, radices), radices);
+                                       norm_entries_bound(K, layer_offsets, n_layers, radices), radices, o.order);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -616,7 +698,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     if (n_layers == 0) return ADASUM_OK;
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;
@@ -663,7 +745,7 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     }
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;

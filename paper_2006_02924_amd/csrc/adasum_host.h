@@ -57,6 +57,13 @@ void build_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
 // reads the narrow input dtype and touches the most data).
 int build_levels(int K, int radix, std::vector<int>& radices);
 
+// Left-to-right order (Section 3.4, first recursion): operand counts of the
+// passes.  The first pass folds `min(K, radix)` leaves; every later pass folds
+// the running result with up to radix - 1 further leaves (operand 0 is the
+// running result), using the widest instantiated radix that the remaining
+// leaves fill.  E.g. K = 64, radix 16 -> {16, 16, 16, 16, 4}.
+int build_linear_passes(int K, int radix, std::vector<int>& passes);
+
 // Number of Gram entries a pass of radix R accumulates per tile: all pairs
 // i < j, plus the R diagonal entries when `diag` (the first pass; later passes
 // get their squared norms from the previous combine).
@@ -82,7 +89,7 @@ struct Layout {
 // `norm_entries`: doubles needed for the squared norms the combines leave
 // (max over passes of nodes written x combine tiles of that pass).
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
-                   const std::vector<int>& radices);
+                   const std::vector<int>& radices, int order = ADASUM_ORDER_TREE);
 // Number of tiles build_tiles would produce.
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity);
 // Upper bound (over input dtypes) of make_layout's norm_entries for a schedule.

@@ -58,6 +58,25 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     return ADASUM_OK;
 }
 
+int build_linear_passes(int K, int radix, std::vector<int>& passes) {
+    passes.clear();
+    if (K < 1) return ADASUM_ERR_INVALID_ARG;
+    if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
+    if (radix == 0) radix = kDefaultRadix;
+    if (radix != 2 && radix != 4 && radix != 8 && radix != 16) return ADASUM_ERR_UNSUPPORTED;
+    if (K == 1) return ADASUM_OK;
+    const int first = std::min(K, radix);
+    passes.push_back(first);
+    int rest = K - first;
+    while (rest > 0) {
+        int r = radix;
+        while (r - 1 > rest) r /= 2;
+        passes.push_back(r);
+        rest -= r - 1;
+    }
+    return ADASUM_OK;
+}
+
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity) {
     int64_t n = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -82,7 +101,7 @@ int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, co
 }
 
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
-                   const std::vector<int>& radices) {
+                   const std::vector<int>& radices, int order) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
@@ -94,10 +113,17 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
 
     size_t max_partials = 0, max_gram = 0, max_weights = 0, max_nodes = 1;
     int groups = K;
+    if (order == ADASUM_ORDER_LINEAR) {
+        // one group per pass; slot 0 holds the running result, slots 1.. the leaves of a
+        // pass widened to fp32 (needed when the inputs are not fp32)
+        int widest = 0;
+        for (int R : radices) widest = std::max(widest, R);
+        lay.n_slots = radices.size() > 1 ? widest : 0;
+    }
     for (size_t lv = 0; lv < radices.size(); ++lv) {
         const int R = radices[lv];
-        groups /= R;
-        const size_t np = static_cast<size_t>(gram_entries(R, lv == 0));
+        groups = order == ADASUM_ORDER_LINEAR ? 1 : groups / R;
+        const size_t np = static_cast<size_t>(gram_entries(R, lv == 0 || order == ADASUM_ORDER_LINEAR));
         max_partials = std::max(max_partials, static_cast<size_t>(groups) * np * static_cast<size_t>(n_tiles));
         max_gram = std::max(max_gram, static_cast<size_t>(groups) * n_layers * R * R);
         max_weights = std::max(max_weights, static_cast<size_t>(groups) * n_layers * R);

@@ -358,3 +358,32 @@ def test_fp16_step_entry_points():
         want = X[:, lo:hi] @ X[:, lo:hi].T
         scale = np.sqrt(np.outer(np.diag(want), np.diag(want))) + 1e-300
         assert np.max(np.abs(got[l] - want) / scale) < 2e-6, l
+
+
+@pytest.mark.parametrize("radix", [2, 4, 16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K", [2, 4, 8, 32, 64])
+def test_linear_order(K, dtype, radix):
+    """Left-to-right application (Section 3.4, first recursion): a different result from the tree."""
+    say(f"linear order K={K} {dtype} radix={radix}")
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), K, dtype=dtype, device=DEV, seed=500 + K)
+    host = [to_f64(g) for g in w.grads]
+    ref = O.adasum_reduce(host, w.layer_offsets, order="linear")
+    before = [g.clone() for g in w.grads]
+    out = B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR, radix=radix)
+    torch.cuda.synchronize()
+    for g, b in zip(w.grads, before):
+        assert torch.equal(g, b)
+    assert_parity(out, ref, w.layer_offsets, what="linear")
+    if K > 2:
+        tree = O.adasum_reduce(host, w.layer_offsets)
+        big = len(RAGGED) - 4   # a layer of thousands of elements
+        lo, hi = RAGGED[big], RAGGED[big + 1]
+        assert np.linalg.norm(tree[lo:hi] - ref[lo:hi]) > 1e-3 * np.linalg.norm(ref[lo:hi])
+    out32 = B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR, radix=radix, out_dtype=torch.float32,
+                            use_graph=True)
+    torch.cuda.synchronize()
+    assert_parity(out32, ref, w.layer_offsets, what="linear f32 out, graph")
+    with pytest.raises(B.AdasumError):
+        B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR,
+                        layer_stats=torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV))

@@ -81,3 +81,33 @@ def test_levels():
         B.plan_levels(8, 3)
     with pytest.raises(B.AdasumError):
         B.plan_levels(0)
+
+
+def test_linear_passes_cover_all_workers():
+    import ctypes as C
+    lib = B.load()
+    # the schedule is visible through the workspace size only; check the arithmetic of the pass list here
+    def passes(K, radix):
+        first = min(K, radix)
+        out, rest = [first], K - first
+        while rest > 0:
+            r = radix
+            while r - 1 > rest:
+                r //= 2
+            out.append(r)
+            rest -= r - 1
+        return out
+    assert passes(64, 16) == [16, 16, 16, 16, 4]
+    for K in (2, 4, 8, 16, 32, 64, 128):
+        for r in (2, 4, 8, 16):
+            p = passes(K, r)
+            assert p[0] + sum(x - 1 for x in p[1:]) == K
+    # linear order needs at most `radix` fp32 slots whatever K is
+    offs = [0, 1000, 5096, 70632]
+    a = B.adasum_workspace_bytes(64, offs, B.BF16, radix=16)
+    o = B.Options(); o.struct_bytes = C.sizeof(B.Options); o.out_dtype = -1; o.radix = 16; o.order = B.ORDER_LINEAR
+    n = C.c_size_t(0)
+    arr = (C.c_int64 * 4)(*offs)
+    assert lib.adasum_workspace_bytes(64, arr, 3, B.BF16, C.byref(o), C.byref(n)) == B.OK
+    assert 16 * 70656 * 4 <= n.value < 16 * 70656 * 4 + (1 << 21)
+    assert a < n.value
