@@ -45,6 +45,9 @@ def parse_args():
     p.add_argument("--radix", type=int, default=0, help="0 = library default")
     p.add_argument("--out-dtype", default="same", choices=["same", "f32", "bf16"])
     p.add_argument("--graph", action="store_true", help="replay the level ladder as one hipGraph launch")
+    p.add_argument("--delta", action="store_true",
+                   help="time the Adasum-after-optimizer form: the K buffers are parameters after a local step, "
+                        "a starting-parameter buffer is subtracted on the fly and added back at the root")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-profile", action="store_true",
                    help="do not bracket kernels with HIP events in the timed region")
@@ -144,9 +147,13 @@ def main():
     out_dtype = {"same": w.dtype, "f32": torch.float32, "bf16": torch.bfloat16}[args.out_dtype]
     out = torch.empty(w.N, dtype=out_dtype, device=dev)
 
+    start = None
+    if args.delta:
+        start = (torch.randn(w.N, device=dev, dtype=torch.float32) * 0.02).to(w.dtype)
+
     def step():
         B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=args.radix,
-                        use_graph=args.graph)
+                        use_graph=args.graph, delta_start=start)
 
     for _ in range(args.warmup):
         step()
@@ -164,7 +171,7 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     value = w.input_bytes / (dt / args.steps) / 1e9
-    levels = B.plan_levels(w.K, args.radix)
+    levels = B.plan_levels(w.K, args.radix if (args.radix or not args.delta) else 8)
 
     roofline = None
     if prof:
@@ -193,7 +200,7 @@ def main():
         "config": {"workload": f"{args.workload}: K={w.K} workers, {w.n_layers} tensors, N={w.N} elements, "
                                f"stored {str(w.dtype).replace('torch.', '')}, output "
                                f"{str(out_dtype).replace('torch.', '')}",
-                   "passes": levels, "radix": args.radix, "graph": bool(args.graph),
+                   "passes": levels, "radix": args.radix, "graph": bool(args.graph), "delta_form": bool(args.delta),
                    "input_GB": w.input_bytes / 1e9},
         "roofline": roofline,
     }

@@ -84,6 +84,19 @@ typedef struct adasum_options {
                                   [l][0] = |Adasum(g_1..g_K)|^2 of layer l (of the fp32 value
                                   before the output store), [l][1] = sum_i |g_i|^2; their ratio
                                   is the orthogonality metric of Section 3.6 */
+    const void* delta_start;   /* DEVICE or NULL.  Section 4.1 (Adasum applied after the optimizer):
+                                  N elements of the input dtype, 16-byte aligned -- the model
+                                  parameters before the workers' local optimizer steps.  When set,
+                                  grads[k] holds worker k's parameters AFTER its local step; the
+                                  library reduces the effective gradients grads[k] - delta_start
+                                  (formed on the fly, never stored) and writes
+                                  out = delta_start + Adasum(...), the new parameters.
+                                  layer_stats then describe the effective gradients.  Needs
+                                  out_dtype == the input dtype and ADASUM_ORDER_TREE
+                                  (else ADASUM_ERR_UNSUPPORTED).  `out` may be the very same
+                                  buffer as delta_start (in-place parameter update); any other
+                                  overlap is ADASUM_ERR_ALIAS.  A struct_bytes that ends before
+                                  this field (the struct as it was without it) reads as NULL. */
 } adasum_options;
 
 /*

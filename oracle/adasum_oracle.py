@@ -18,6 +18,10 @@ What each function follows:
   the boundary bookkeeping of Section 4.4.3: each layer of the fused buffer is
   reduced on its own.
 * ``orthogonality``  -- the per-layer metric defined in Section 3.6.
+* ``adasum_after_optimizer`` -- Section 4.1: when the optimizer is stateful the
+  operator is applied to each worker's *effective gradient*, the parameters
+  after its local optimizer step minus the parameters before it; the combined
+  effective gradient is added to the parameters before the step.
 
 Dot products and squared norms are accumulated in double precision, as
 Section 4.4.1 prescribes; every intermediate tree node stays fp64 and nothing
@@ -126,6 +130,16 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], order: str = "t
             continue
         out[lo:hi] = combine([np.asarray(g)[lo:hi] for g in grads])
     return out
+
+
+def adasum_after_optimizer(start, currents: Sequence, layer_offsets: Sequence[int]) -> np.ndarray:
+    """New parameters of Section 4.1's scheme: every worker starts from ``start``,
+    takes its own optimizer step to ``currents[i]``; the effective gradients
+    ``currents[i] - start`` are combined per layer by the Adasum tree and the
+    result is added to ``start``."""
+    w0 = _as_f64(start)
+    deltas = [_as_f64(c) - w0 for c in currents]
+    return w0 + adasum_reduce(deltas, layer_offsets)
 
 
 def orthogonality(grads: Sequence, layer_offsets: Sequence[int]) -> np.ndarray:

@@ -50,6 +50,7 @@ class Options(C.Structure):
         ("workspace", C.c_void_p),
         ("workspace_bytes", C.c_size_t),
         ("layer_stats", C.c_void_p),
+        ("delta_start", C.c_void_p),
     ]
 
 
@@ -168,9 +169,12 @@ def _check_inputs(tensors, N):
 
 def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, out_dtype=None,
                   radix: int = 0, order: int = ORDER_TREE, layer_stats=None, workspace=None,
-                  use_graph: bool = False, stream=None):
+                  use_graph: bool = False, delta_start=None, stream=None):
     """Per-layer Adasum tree of ``grads`` (K device tensors of N elements).
-    Returns ``out`` (allocated here when None)."""
+    Returns ``out`` (allocated here when None).  With ``delta_start`` (a tensor
+    like one of ``grads``) the tensors in ``grads`` are parameters after a local
+    optimizer step, the tree runs on ``grads[k] - delta_start`` and the result
+    is ``delta_start + Adasum(...)``; ``out`` may then be ``delta_start`` itself."""
     import torch
     lib = load()
     offs, L = _offsets(layer_offsets)
@@ -184,7 +188,7 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
         raise ValueError("out has the wrong dtype, size or layout")
     ptrs = _ptr_array(grads)
     plain = (out_code == in_code and radix == 0 and order == ORDER_TREE and layer_stats is None
-             and workspace is None and not use_graph)
+             and workspace is None and not use_graph and delta_start is None)
     if plain:
         check(lib.adasum_reduce(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()), _stream(stream)))
         return out
@@ -201,19 +205,26 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
         if layer_stats.dtype != torch.float64 or layer_stats.numel() != 2 * L or not layer_stats.is_contiguous():
             raise ValueError("layer_stats must be a contiguous float64 tensor of n_layers x 2")
         o.layer_stats = layer_stats.data_ptr()
+    if delta_start is not None:
+        _check_inputs([delta_start], N)
+        if delta_start.dtype != grads[0].dtype or delta_start.device != grads[0].device:
+            raise ValueError("delta_start must have the dtype and device of grads")
+        o.delta_start = delta_start.data_ptr()
     check(lib.adasum_reduce_ex(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()),
                                C.byref(o), _stream(stream)))
     return out
 
 
 def adasum_workspace_bytes(K: int, layer_offsets: Sequence[int], dtype_code: int, *, radix: int = 0,
-                           out_dtype_code: int = -1) -> int:
+                           out_dtype_code: int = -1, delta: bool = False) -> int:
     lib = load()
     offs, L = _offsets(layer_offsets)
     o = Options()
     o.struct_bytes = C.sizeof(Options)
     o.out_dtype = out_dtype_code
     o.radix = radix
+    if delta:
+        o.delta_start = 0x100   # only "set or not" matters for the size
     n = C.c_size_t(0)
     check(lib.adasum_workspace_bytes(K, offs, L, dtype_code, C.byref(o), C.byref(n)))
     return int(n.value)

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <map>
@@ -53,7 +54,11 @@ struct Opts {
     void* workspace;
     size_t workspace_bytes;
     double* layer_stats;
+    const void* delta_start;
 };
+
+// adasum_options as it was before delta_start was appended: still accepted.
+constexpr uint32_t kOptionsBytesV1 = offsetof(adasum_options, delta_start);
 
 int read_opts(const adasum_options* o, int dtype, Opts& r) {
     r.out_dtype = dtype;
@@ -63,8 +68,10 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     r.workspace = nullptr;
     r.workspace_bytes = 0;
     r.layer_stats = nullptr;
+    r.delta_start = nullptr;
     if (o != nullptr) {
-        if (o->struct_bytes < sizeof(adasum_options)) return ADASUM_ERR_INVALID_ARG;
+        if (o->struct_bytes < kOptionsBytesV1) return ADASUM_ERR_INVALID_ARG;
+        if (o->struct_bytes >= sizeof(adasum_options)) r.delta_start = o->delta_start;
         if (o->out_dtype >= 0) r.out_dtype = o->out_dtype;
         r.radix = o->radix;
         r.order = o->order;
@@ -77,12 +84,20 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if (r.order == ADASUM_ORDER_LINEAR && r.layer_stats != nullptr) return ADASUM_ERR_UNSUPPORTED;
+    if (r.delta_start != nullptr) {
+        if (r.order != ADASUM_ORDER_TREE || r.out_dtype != dtype) return ADASUM_ERR_UNSUPPORTED;
+        if (!aligned16(r.delta_start)) return ADASUM_ERR_MISALIGNED;
+    }
     if (r.workspace != nullptr && (reinterpret_cast<uintptr_t>(r.workspace) & 255u) != 0)
         return ADASUM_ERR_WORKSPACE;
     if (r.layer_stats != nullptr && (reinterpret_cast<uintptr_t>(r.layer_stats) & 7u) != 0)
         return ADASUM_ERR_MISALIGNED;
     return ADASUM_OK;
 }
+
+// The delta form's Gram pass subtracts before it multiplies and so cannot use the packed
+// dot instructions; with 16 operands it runs out of registers, 8 is its fastest radix.
+int default_radix(const Opts& o) { return o.delta_start != nullptr ? 8 : kDefaultRadix; }
 
 // ---- plans -------------------------------------------------------------------
 
@@ -356,9 +371,13 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 
         // groups per launch: the operand pointers travel by value in the kernel arguments
         const int batch = std::max(1, kMaxPack / R);
-        const double gram_bytes_per_group = static_cast<double>(R) * N * elem_bytes(in_dtype);
+        // Section 4.1's delta form: the leaves are grads[k] - delta_start, the root adds delta_start back
+        const void* sub_in = first ? o.delta_start : nullptr;
+        const void* add_out = last ? o.delta_start : nullptr;
+        const double gram_bytes_per_group = static_cast<double>(R + (sub_in ? 1 : 0)) * N * elem_bytes(in_dtype);
         const double comb_bytes_per_group =
-            static_cast<double>(N) * (static_cast<double>(R) * elem_bytes(in_dtype) + elem_bytes(st_dtype));
+            static_cast<double>(N) * (static_cast<double>(R + (sub_in ? 1 : 0)) * elem_bytes(in_dtype) +
+                                      (add_out ? 2.0 : 1.0) * elem_bytes(st_dtype));
 
         auto fill_operands = [&](Operands& ops, int g0, int ng) {
             std::memset(&ops, 0, sizeof(ops));
@@ -375,7 +394,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
             kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
             ADASUM_TIMED(namebuf, gram_bytes_per_group * ng, stream,
                          launch_gram(in_dtype, first, ops, gt, ng, R, partials + static_cast<int64_t>(g0) * np * T,
-                                     stream));
+                                     sub_in, stream));
         }
         // step 2: finish the sums, then the tree's scalars
         if (!first) {
@@ -412,7 +431,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                          launch_combine(in_dtype, st_dtype, ops, outs, ct, L, ng, R,
                                         weights + static_cast<int64_t>(g0) * L * R,
                                         want_norm ? normparts + static_cast<int64_t>(g0) * ct.n_tiles : nullptr,
-                                        stream));
+                                        sub_in, add_out, stream));
         }
         stride = first ? 1 : R * stride;
         nodes = groups;
@@ -476,21 +495,23 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
                     wo.base = wide;
                     wo.slot_bytes = 0;
                     wo.stride = 0;
-                    ADASUM_LAUNCH(launch_combine(dtype, ADASUM_F32, one, wo, widen_tiles, L, 1, 1, nullptr, nullptr, stream));
+                    ADASUM_LAUNCH(launch_combine(dtype, ADASUM_F32, one, wo, widen_tiles, L, 1, 1, nullptr, nullptr, nullptr,
+                                                 nullptr, stream));
                     leaf = wide;
                 }
                 ops.pack[r] = leaf;
             }
             next_leaf += R - 1;
         }
-        ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, stream));
+        ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, nullptr, stream));
         ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, stream));
         ADASUM_LAUNCH(launch_weights(gram, R, L, ADASUM_ORDER_LINEAR, weights, stream));
         Outputs outs;
         outs.base = last ? static_cast<char*>(out) : slots;
         outs.slot_bytes = 0;
         outs.stride = 0;
-        ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights, nullptr, stream));
+        ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights, nullptr, nullptr,
+                                     nullptr, stream));
     }
     return ADASUM_OK;
 }
@@ -513,9 +534,12 @@ int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     outs.stride = 0;
     char namebuf[48];
     kernel_name("combine", dtype, o.out_dtype, 1, false, namebuf, sizeof(namebuf));
-    ADASUM_TIMED(namebuf, static_cast<double>(lay.N) * (elem_bytes(dtype) + elem_bytes(o.out_dtype)), stream,
+    // with delta_start the copy goes through the same arithmetic as any root: (x - start) + start
+    const double copy_bytes = static_cast<double>(lay.N) * ((o.delta_start ? 2.0 : 1.0) * elem_bytes(dtype) +
+                                                            (o.delta_start ? 2.0 : 1.0) * elem_bytes(o.out_dtype));
+    ADASUM_TIMED(namebuf, copy_bytes, stream,
                  launch_combine(dtype, o.out_dtype, ops, outs, ct, lay.n_layers, 1, 1, nullptr,
-                                o.layer_stats ? normparts : nullptr, stream));
+                                o.layer_stats ? normparts : nullptr, o.delta_start, o.delta_start, stream));
     if (o.layer_stats != nullptr) {
         double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
         const TileSet gt = p->gram_tiles.view();
@@ -540,6 +564,7 @@ int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void
     key.push_back(reinterpret_cast<uintptr_t>(out));
     key.push_back(reinterpret_cast<uintptr_t>(ws));
     key.push_back(reinterpret_cast<uintptr_t>(o.layer_stats));
+    key.push_back(reinterpret_cast<uintptr_t>(o.delta_start));
     key.push_back(static_cast<uintptr_t>(dtype));
     key.push_back(static_cast<uintptr_t>(o.out_dtype));
     key.push_back(static_cast<uintptr_t>(o.order));
@@ -626,10 +651,13 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     const size_t out_bytes = static_cast<size_t>(N) * elem_bytes(o.out_dtype);
     for (int k = 0; k < K; ++k)
         if (overlaps(grads[k], in_bytes, out, out_bytes)) return ADASUM_ERR_ALIAS;
+    // out may BE delta_start (every element is read by the lane that then writes it) but not straddle it
+    if (o.delta_start != nullptr && o.delta_start != out && overlaps(o.delta_start, in_bytes, out, out_bytes))
+        return ADASUM_ERR_ALIAS;
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(K, o.radix == 0 ? kDefaultRadix : o.radix, o.order, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);
@@ -668,8 +696,9 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
     if (rc != ADASUM_OK && rc != ADASUM_ERR_WORKSPACE) return rc;
     try {
         std::vector<int> radices;
-        rc = o.order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, o.radix, radices)
-                                            : build_levels(K, o.radix, radices);
+        const int radix = o.radix == 0 ? default_radix(o) : o.radix;
+        rc = o.order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, radix, radices)
+                                            : build_levels(K, radix, radices);
         if (rc != ADASUM_OK) return rc;
         const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers,
                                        count_tiles(layer_offsets, n_layers, kTile),
@@ -709,7 +738,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     Operands ops;
     std::memset(&ops, 0, sizeof(ops));
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
-    ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, stream));
+    ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, nullptr, stream));
     ADASUM_LAUNCH(launch_gram_finish(true, gt, n_layers, 1, R, partials, nullptr, gram, stream));
     return ADASUM_OK;
 }
@@ -763,7 +792,7 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     outs.slot_bytes = 0;
     outs.stride = 0;
     ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, ct, n_layers, 1, R, weights,
-                                 sqnorm ? normparts : nullptr, stream));
+                                 sqnorm ? normparts : nullptr, nullptr, nullptr, stream));
     if (sqnorm != nullptr) {
         double* normcoarse = reinterpret_cast<double*>(ws + p->lay.off_normcoarse);
         const TileSet gt = p->gram_tiles.view();

@@ -123,8 +123,9 @@ struct TileSet {
 
 // All launchers return a hipError_t as int (0 = success) and enqueue on `stream`.
 // partials[(group * entries + entry) * gt.n_tiles + tile]
+// delta_start (or null): operands are x_r - delta_start, same storage type as the operands; diag only.
 int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
-                double* partials, void* stream);
+                double* partials, const void* delta_start, void* stream);
 // coarse[node * gt.n_tiles + t] = sum of fine[node * ct.n_tiles + c] over the combine tiles c inside
 // Gram tile t.
 int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, const TileSet& gt, double* coarse,
@@ -141,7 +142,9 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order,
 // normparts[group * ct.n_tiles + tile] (or null).
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out,
                    const TileSet& ct, int n_layers, int n_groups, int R,
-                   const double* weights /* or null: unit weights */, double* normparts, void* stream);
+                   const double* weights /* or null: unit weights */, double* normparts,
+                   const void* sub_in /* type of the operands, or null */,
+                   const void* add_out /* type of the output, or null */, void* stream);
 // layer_sum[l * out_stride] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
 int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers,
                       double* layer_sum, int out_stride, void* stream);

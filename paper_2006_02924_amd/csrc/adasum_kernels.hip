@@ -248,10 +248,13 @@ __device__ __forceinline__ Split split_tile(const adasum_tile& t) {
 // Entry order: for i < R, for j from (DIAG ? i : i+1) to R-1.
 // partials[(group * NP + entry) * n_tiles + tile]
 // ---------------------------------------------------------------------------
-template <typename T, int R, bool DIAG>
+// DELTA: the operands are x_r - start (the "effective gradient" of Section 4.1:
+// parameters after the local step minus the parameters before it), formed on
+// the fly; `start` has the operands' type.
+template <typename T, int R, bool DIAG, bool DELTA>
 __global__ void __launch_bounds__(kThreads)
 gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_tiles,
-            double* __restrict__ partials) {
+            double* __restrict__ partials, const T* __restrict__ start) {
     constexpr int G = Traits<T>::VEC;
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
     constexpr int ITERS = kTile / G / kThreads;
@@ -273,8 +276,9 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
 #pragma unroll
     for (int e = 0; e < NP; ++e) acc[e] = 0.f;
 
-    auto consume = [&](const Granule<T, G> (&raw)[R]) {
-        if constexpr (sizeof(T) == 2 && (ADASUM_BF16_DOT2 == 2 || (ADASUM_BF16_DOT2 == 1 && R >= 16))) {
+    auto consume = [&](const Granule<T, G> (&raw)[R], long long idx) {
+        (void)idx;
+        if constexpr (!DELTA && sizeof(T) == 2 && (ADASUM_BF16_DOT2 == 2 || (ADASUM_BF16_DOT2 == 1 && R >= 16))) {
             // two 16-bit products and the fp32 accumulate in one instruction, straight
             // from the packed words (bf16 x bf16 and f16 x f16 are exact in fp32)
             int e = 0;
@@ -300,6 +304,16 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
             float v[R][G];
 #pragma unroll
             for (int r = 0; r < R; ++r) unpack(raw[r], v[r]);
+            if constexpr (DELTA) {
+                Granule<T, G> sraw;
+                load_raw(sraw, start + idx);
+                float sv[G];
+                unpack(sraw, sv);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int k = 0; k < G; ++k) v[r][k] -= sv[k];
+            }
             int e = 0;
 #pragma unroll
             for (int i = 0; i < R; ++i) {
@@ -323,7 +337,8 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
                 for (int r = 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) consume(raw[u]);
+            for (int u = 0; u < U; ++u)
+                consume(raw[u], s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G);
         }
     } else {
         for (int j = tid; j < s.ng; j += kThreads) {
@@ -331,7 +346,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
             const long long idx = s.bs + static_cast<long long>(j) * G;
 #pragma unroll
             for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
-            consume(raw);
+            consume(raw, idx);
         }
     }
     // Whole granules went through fp32 lanes.  The at most 2*(G-1) elements of a
@@ -343,20 +358,25 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     const int lane = tid & 63, wave = tid >> 6;
     const int nedge = s.nh + s.nt;
     if (nedge > 0 && wave == 0) {
-        float v[R];
+        double v[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) v[r] = 0.f;
+        for (int r = 0; r < R; ++r) v[r] = 0.0;
         if (lane < nedge) {
             const long long idx = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
 #pragma unroll
-            for (int r = 0; r < R; ++r) v[r] = load_elem(x[r] + idx);
+            for (int r = 0; r < R; ++r) v[r] = static_cast<double>(load_elem(x[r] + idx));
+            if constexpr (DELTA) {
+                const double sv = static_cast<double>(load_elem(start + idx));
+#pragma unroll
+                for (int r = 0; r < R; ++r) v[r] -= sv;
+            }
         }
         int e = 0;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
 #pragma unroll
             for (int j = (DIAG ? i : i + 1); j < R; ++j) {
-                const double p = wave_sum(static_cast<double>(v[i]) * static_cast<double>(v[j]));
+                const double p = wave_sum(v[i] * v[j]);
                 if (lane == 0) sh_edge[e] = p;
                 ++e;
             }
@@ -514,11 +534,11 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, do
 // close to sequential, worth 10-20 % of bandwidth over long-lived workgroups.
 // normparts[group * n_tiles + tile].  weights == nullptr: unit weights.
 // ---------------------------------------------------------------------------
-template <typename TI, typename TO, int R>
+template <typename TI, typename TO, int R, bool SUB>
 __global__ void __launch_bounds__(combine_threads(R))
 combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
                int n_tiles, int n_layers, const double* __restrict__ weights,
-               double* __restrict__ normparts) {
+               double* __restrict__ normparts, const TI* __restrict__ sub_in, const TO* add_out) {
     constexpr int G = 16 / (int)sizeof(TI);   // tile capacity is THREADS * G
     constexpr int THREADS = combine_threads(R);
     // Non-temporal stores pay off except where the output is half of the traffic
@@ -554,24 +574,41 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         w[r] = static_cast<float>(wd[r]);
     }
 
+    // Section 4.1's delta form: with SUB the operands are x_r - sub_in (the parameters
+    // before the local step); with add_out the stored result is add_out + z.  The
+    // squared norm is that of z either way.
     float nacc = 0.f;
     if (tid < s.ng) {
+        float sv[G];
+        if constexpr (SUB) {
+            Granule<TI, G> sraw;
+            load_raw(sraw, sub_in + idx);
+            unpack(sraw, sv);
+        }
         float z[G];
         {
             float v[G];
             unpack(raw[0], v);
 #pragma unroll
-            for (int k = 0; k < G; ++k) z[k] = w[0] * v[k];
+            for (int k = 0; k < G; ++k) z[k] = w[0] * (SUB ? v[k] - sv[k] : v[k]);
         }
 #pragma unroll
         for (int r = 1; r < R; ++r) {
             float v[G];
             unpack(raw[r], v);
 #pragma unroll
-            for (int k = 0; k < G; ++k) z[k] = __builtin_fmaf(w[r], v[k], z[k]);
+            for (int k = 0; k < G; ++k) z[k] = __builtin_fmaf(w[r], SUB ? v[k] - sv[k] : v[k], z[k]);
         }
 #pragma unroll
         for (int k = 0; k < G; ++k) nacc = __builtin_fmaf(z[k], z[k], nacc);
+        if (add_out != nullptr) {
+            Granule<TO, G> araw;
+            load_raw(araw, add_out + idx);
+            float av[G];
+            unpack(araw, av);
+#pragma unroll
+            for (int k = 0; k < G; ++k) z[k] += av[k];
+        }
         store_granule<NTS>(out + idx, z);
     }
 
@@ -582,12 +619,15 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     if (nedge > 0 && wave == 0) {
         if (lane < nedge) {
             const long long idx = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
-            double z = wd[0] * static_cast<double>(load_elem(x[0] + idx));
+            const double sd = SUB ? static_cast<double>(load_elem(sub_in + idx)) : 0.0;
+            double z = wd[0] * (static_cast<double>(load_elem(x[0] + idx)) - sd);
 #pragma unroll
-            for (int r = 1; r < R; ++r) z = __builtin_fma(wd[r], static_cast<double>(load_elem(x[r] + idx)), z);
+            for (int r = 1; r < R; ++r)
+                z = __builtin_fma(wd[r], static_cast<double>(load_elem(x[r] + idx)) - sd, z);
             const float zf = static_cast<float>(z);
-            store_elem(out + idx, zf);
             enorm = static_cast<double>(zf) * static_cast<double>(zf);
+            if (add_out != nullptr) z += static_cast<double>(load_elem(add_out + idx));
+            store_elem(out + idx, static_cast<float>(z));
         }
         if (normparts != nullptr) enorm = wave_sum(enorm);
     }
@@ -645,32 +685,63 @@ inline int check_launch() { return static_cast<int>(hipGetLastError()); }
 
 inline bool grid_fits(long long blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
 
-template <typename T, bool DIAG>
-int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, double* partials, hipStream_t st) {
+template <typename T, bool DIAG, bool DELTA>
+int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, double* partials, const void* start,
+                  hipStream_t st) {
     const long long blocks = gt.n_tiles * static_cast<long long>(n_groups);
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const int nt = static_cast<int>(gt.n_tiles);
+    const T* s0 = static_cast<const T*>(start);
+#define ADASUM_GRAM(RR)                                                                               \
+    hipLaunchKernelGGL((gram_kernel<T, RR, DIAG, DELTA>), grid, block, 0, st, ops, gt.tiles, nt, partials, s0)
     switch (R) {
-        case 2: hipLaunchKernelGGL((gram_kernel<T, 2, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
-        case 4: hipLaunchKernelGGL((gram_kernel<T, 4, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
-        case 8: hipLaunchKernelGGL((gram_kernel<T, 8, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
-        case 16: hipLaunchKernelGGL((gram_kernel<T, 16, DIAG>), grid, block, 0, st, ops, gt.tiles, nt, partials); break;
+        case 2: ADASUM_GRAM(2); break;
+        case 4: ADASUM_GRAM(4); break;
+        case 8: ADASUM_GRAM(8); break;
+        case 16: ADASUM_GRAM(16); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
+#undef ADASUM_GRAM
     return check_launch();
+}
+
+template <typename T>
+int launch_gram_t(bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R, double* partials,
+                  const void* start, hipStream_t st) {
+    if (start != nullptr) {
+        if (!diag) return static_cast<int>(hipErrorInvalidValue);   // the delta form exists for the leaves only
+        return launch_gram_r<T, true, true>(ops, gt, n_groups, R, partials, start, st);
+    }
+    return diag ? launch_gram_r<T, true, false>(ops, gt, n_groups, R, partials, nullptr, st)
+                : launch_gram_r<T, false, false>(ops, gt, n_groups, R, partials, nullptr, st);
 }
 
 template <typename TI, typename TO>
 int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
-                     int R, const double* weights, double* normparts, hipStream_t st) {
+                     int R, const double* weights, double* normparts, const void* sub_in, const void* add_out,
+                     hipStream_t st) {
     const long long blocks = ct.n_tiles * static_cast<long long>(n_groups);
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(combine_threads(R));
     const int nt = static_cast<int>(ct.n_tiles);
+#define ADASUM_COMBINE_AS(RR, SUB)                                                                   \
+    hipLaunchKernelGGL((combine_kernel<TI, TO, RR, SUB>), grid, block, 0, st, ops, outs, ct.tiles,  \
+                       nt, n_layers, weights, normparts, static_cast<const TI*>(sub_in),            \
+                       static_cast<const TO*>(add_out))
+    // the subtracting form exists where the delta form can use it: the first pass of several
+    // (fp32 nodes out) and a single pass (output of the input's type)
+    constexpr bool kSubOk = std::is_same<TO, float>::value || std::is_same<TI, TO>::value;
 #define ADASUM_COMBINE(RR)                                                                           \
-    hipLaunchKernelGGL((combine_kernel<TI, TO, RR>), grid, block, 0, st, ops, outs, ct.tiles, nt,    \
-                       n_layers, weights, normparts)
+    do {                                                                                             \
+        if (sub_in == nullptr) {                                                                     \
+            ADASUM_COMBINE_AS(RR, false);                                                            \
+        } else if constexpr (kSubOk) {                                                               \
+            ADASUM_COMBINE_AS(RR, true);                                                             \
+        } else {                                                                                     \
+            return static_cast<int>(hipErrorInvalidValue);                                           \
+        }                                                                                            \
+    } while (0)
     switch (R) {
         case 1: ADASUM_COMBINE(1); break;
         case 2: ADASUM_COMBINE(2); break;
@@ -679,6 +750,7 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct
         case 16: ADASUM_COMBINE(16); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
+#undef ADASUM_COMBINE_AS
 #undef ADASUM_COMBINE
     return check_launch();
 }
@@ -686,19 +758,12 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct
 }  // namespace
 
 int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
-                double* partials, void* stream) {
+                double* partials, const void* delta_start, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (gt.n_tiles == 0 || n_groups == 0) return 0;
-    if (dtype == ADASUM_BF16) {
-        return diag ? launch_gram_r<bf16_t, true>(ops, gt, n_groups, R, partials, st)
-                    : launch_gram_r<bf16_t, false>(ops, gt, n_groups, R, partials, st);
-    }
-    if (dtype == ADASUM_F16) {
-        return diag ? launch_gram_r<f16_t, true>(ops, gt, n_groups, R, partials, st)
-                    : launch_gram_r<f16_t, false>(ops, gt, n_groups, R, partials, st);
-    }
-    return diag ? launch_gram_r<float, true>(ops, gt, n_groups, R, partials, st)
-                : launch_gram_r<float, false>(ops, gt, n_groups, R, partials, st);
+    if (dtype == ADASUM_BF16) return launch_gram_t<bf16_t>(diag, ops, gt, n_groups, R, partials, delta_start, st);
+    if (dtype == ADASUM_F16) return launch_gram_t<f16_t>(diag, ops, gt, n_groups, R, partials, delta_start, st);
+    return launch_gram_t<float>(diag, ops, gt, n_groups, R, partials, delta_start, st);
 }
 
 int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, const TileSet& gt, double* coarse,
@@ -752,29 +817,30 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order, double
 }
 
 int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
-                   int n_layers, int n_groups, int R, const double* weights, double* normparts, void* stream) {
+                   int n_layers, int n_groups, int R, const double* weights, double* normparts,
+                   const void* sub_in, const void* add_out, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ct.n_tiles == 0 || n_groups == 0) return 0;
     // supported pairs: T -> fp32, fp32 -> T, T -> T
     if (dtype == ADASUM_BF16) {
         if (out_dtype == ADASUM_BF16)
-            return launch_combine_r<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+            return launch_combine_r<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
         if (out_dtype == ADASUM_F32)
-            return launch_combine_r<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+            return launch_combine_r<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
         return static_cast<int>(hipErrorInvalidValue);
     }
     if (dtype == ADASUM_F16) {
         if (out_dtype == ADASUM_F16)
-            return launch_combine_r<f16_t, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+            return launch_combine_r<f16_t, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
         if (out_dtype == ADASUM_F32)
-            return launch_combine_r<f16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+            return launch_combine_r<f16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
         return static_cast<int>(hipErrorInvalidValue);
     }
     if (out_dtype == ADASUM_BF16)
-        return launch_combine_r<float, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        return launch_combine_r<float, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
     if (out_dtype == ADASUM_F16)
-        return launch_combine_r<float, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
-    return launch_combine_r<float, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        return launch_combine_r<float, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
+    return launch_combine_r<float, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
 }
 
 int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers, double* layer_sum,

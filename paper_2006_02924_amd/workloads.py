@@ -165,6 +165,35 @@ def correlated_gaussian(sizes: Sequence[int], K: int, *, dtype=torch.float32,
                     {"corr": corr_l, "scale": scale_l, "kind": ["gauss"] * L})
 
 
+def after_local_step(sizes: Sequence[int], K: int, *, dtype=torch.float32, device="cpu", seed: int = 0,
+                     step: float = 0.1, corr=None, scale=None, name: str = "after_local_step") -> Workload:
+    """Inputs of the Adasum-after-optimizer form (Section 4.1): one starting
+    parameter buffer and K buffers of parameters after each worker's local step.
+
+    ``start = scale_l * N(0,1)`` (drawn after everything ``correlated_gaussian``
+    draws, from a generator seeded ``seed + 1``); worker k's local update is
+    ``-step * g_k`` with ``g_k`` the correlated Gaussian gradients of the same
+    seed, so ``current_k = start - step * g_k``, computed in fp32 and rounded
+    to ``dtype``.  ``start`` (also rounded to ``dtype``) is in ``meta["start"]``;
+    ``grads`` holds the K current-parameter buffers."""
+    w = correlated_gaussian(sizes, K, dtype=torch.float32, device=device, seed=seed, corr=corr, scale=scale,
+                            name=name)
+    reps = torch.tensor([int(x) for x in sizes], dtype=torch.int64)
+    per_elem = torch.repeat_interleave(torch.tensor(w.meta["scale"], dtype=torch.float32), reps).to(device)
+    start = torch.randn(w.N, generator=_gen(device, seed + 1), device=device, dtype=torch.float32) * per_elem
+    del per_elem
+    start = start.to(dtype)
+    wide = start.to(torch.float32)
+    current = []
+    for g in w.grads:
+        g.mul_(-step).add_(wide)
+        current.append(g.to(dtype) if dtype != torch.float32 else g)
+    meta = dict(w.meta)
+    meta["start"] = start
+    meta["step"] = step
+    return Workload(name, K, dtype, w.layer_offsets, current, meta)
+
+
 def log_uniform_scales(L: int, seed: int, lo_exp=-4.0, hi_exp=0.0) -> List[float]:
     """Per-layer magnitudes ``10^U(lo_exp, hi_exp)`` (layer-wise gradient spread)."""
     hg = _host_gen(seed + 7919)

@@ -89,6 +89,26 @@ def test_options_validation(lib):
     assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, bad) == B.ERR_INVALID_ARG
 
 
+def test_delta_options_validation(lib):
+    """Section 4.1's delta form: same dtype in and out, tree order, aligned, and
+    `out` either is `delta_start` or does not touch it."""
+    good = [0x1000, 0x2000]
+    offs = [0, 8]
+    assert _call_reduce(lib, good, 2, offs, B.BF16, 0x9000, _opts(delta_start=0x5000, out_dtype=B.F32)) \
+        == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(delta_start=0x5000, order=B.ORDER_LINEAR)) \
+        == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(delta_start=0x5004)) == B.ERR_MISALIGNED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(delta_start=0x9010)) == B.ERR_ALIAS
+    # a struct that ends before delta_start (the layout without the field) never reads it
+    old = _opts(delta_start=0x5004)
+    old.struct_bytes = B.Options.delta_start.offset
+    assert _call_reduce(lib, good, 2, [0], B.F32, 0x9000, old) == B.OK
+    # the delta form defaults to radix 8: K = 16 takes two passes and needs intermediate nodes
+    big = [0, 70632]
+    assert B.adasum_workspace_bytes(16, big, B.F32, delta=True) > B.adasum_workspace_bytes(16, big, B.F32) + 70632 * 4
+
+
 def test_step_entry_points_validate(lib):
     offs = (C.c_int64 * 3)(0, 10, 30)
     x = (C.c_void_p * 2)(0x1000, 0x2000)

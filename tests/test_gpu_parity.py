@@ -387,3 +387,85 @@ def test_linear_order(K, dtype, radix):
     with pytest.raises(B.AdasumError):
         B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR,
                         layer_stats=torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV))
+
+
+# ---------------------------------------------------------------------------
+# Adasum applied after the optimizer (Section 4.1): effective gradients formed on the fly
+# ---------------------------------------------------------------------------
+
+def _check_after_optimizer(out, start, currents, offs, what):
+    """`out` against the oracle's new parameters, and -- sharper -- the step it took,
+    out - start, against the oracle's combined effective gradient."""
+    w0 = to_f64(start)
+    ref = O.adasum_after_optimizer(w0, [to_f64(c) for c in currents], offs)
+    assert_parity(out, ref, offs, what=what)
+    if out.dtype != torch.float32:
+        assert_bf16_rounding(out, ref, offs)
+        return ref
+    got = to_f64(out)
+    for l in range(len(offs) - 1):
+        lo, hi = offs[l], offs[l + 1]
+        if hi == lo:
+            continue
+        step_ref = ref[lo:hi] - w0[lo:hi]
+        err = np.linalg.norm((got[lo:hi] - w0[lo:hi]) - step_ref)
+        # the combined step to the fp32 bar, plus one fp32 rounding of the stored sum
+        bound = TOL_F32 * np.linalg.norm(step_ref) + 2.0 ** -24 * np.linalg.norm(ref[lo:hi])
+        assert err <= bound, f"{what}: layer {l} step error {err:.3e} > {bound:.3e}"
+    return ref
+
+
+@pytest.mark.parametrize("radix", [0, 2, 4, 16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("K", [1, 2, 8, 64])
+def test_after_optimizer_delta_form(K, dtype, radix):
+    if K == 1 and radix != 0:
+        pytest.skip("K=1 has no passes")
+    say(f"delta form K={K} {dtype} radix={radix}")
+    sizes = np.diff(RAGGED).tolist()
+    scales = W.log_uniform_scales(len(sizes), 5, lo_exp=-2.0, hi_exp=0.0)
+    w = W.after_local_step(sizes, K, dtype=dtype, device=DEV, seed=400 + K, scale=scales, step=0.25)
+    start = w.meta["start"]
+    before = [g.clone() for g in w.grads] + [start.clone()]
+    out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, delta_start=start)
+    torch.cuda.synchronize()
+    for g, b in zip(w.grads + [start], before):
+        assert torch.equal(g, b), "inputs must not be modified"
+    _check_after_optimizer(out, start, w.grads, w.layer_offsets, f"delta K={K} {dtype} radix={radix}")
+
+
+def test_after_optimizer_in_place_stats_and_graph():
+    """`out` may be the starting parameters themselves; layer_stats describe the
+    effective gradients; a graph replay gives the eager bits."""
+    sizes = W.scaled_down(W.bert_large_layer_sizes(), 64, floor=1)
+    K = 16
+    w = W.after_local_step(sizes, K, dtype=torch.float32, device=DEV, seed=9, step=0.1)
+    start = w.meta["start"]
+    offs = w.layer_offsets
+    stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+    out = B.adasum_reduce(w.grads, offs, delta_start=start, layer_stats=stats)
+    torch.cuda.synchronize()
+    _check_after_optimizer(out, start, w.grads, offs, "delta bert/64")
+    w0 = to_f64(start)
+    deltas = [to_f64(c) - w0 for c in w.grads]
+    metric = O.orthogonality(deltas, offs)
+    s = stats.cpu().numpy()
+    np.testing.assert_allclose(s[:, 0] / s[:, 1], metric, rtol=2e-5)
+    np.testing.assert_allclose(s[:, 1], [sum(float(np.dot(d[a:b], d[a:b])) for d in deltas)
+                                         for a, b in zip(offs[:-1], offs[1:])], rtol=1e-6)
+    for _ in range(3):
+        again = B.adasum_reduce(w.grads, offs, delta_start=start, use_graph=True)
+        torch.cuda.synchronize()
+        assert torch.equal(again, out)
+    params = start.clone()
+    same = B.adasum_reduce(w.grads, offs, params, delta_start=params)
+    torch.cuda.synchronize()
+    assert same.data_ptr() == params.data_ptr()
+    assert torch.equal(params, out)
+    # refused: another output type, the left-to-right order
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(w.grads, offs, delta_start=start, out_dtype=torch.bfloat16)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(w.grads, offs, delta_start=start, order=B.ORDER_LINEAR)
+    assert e.value.code == B.ERR_UNSUPPORTED

@@ -253,6 +253,34 @@ def pin_low_precision_inputs_are_widened(O):
     assert d == float(n) and n1 == float(n) and n2 == float(n)
 
 
+def pin_after_optimizer(O):
+    # Section 4.1.  Hand-worked, K = 2, one layer: start (1,1); worker steps to (2,1) and (2,2), so the
+    # effective gradients are (1,0) and (1,1): d = 1, n1 = 1, n2 = 2, coefficients 1/2 and 3/4, combined
+    # (5/4, 3/4), new parameters (9/4, 7/4).  (The operator applied to the parameters themselves would
+    # give (2.05, 1.65).)
+    got = O.adasum_after_optimizer(np.array([1.0, 1.0]), [np.array([2.0, 1.0]), np.array([2.0, 2.0])], [0, 2])
+    np.testing.assert_allclose(got, [2.25, 1.75], rtol=1e-15)
+    rng = _rng(12)
+    start = rng.standard_normal(12)
+    # every worker took the same step: that step is taken (the operator is idempotent)
+    cur = start + 0.1 * rng.standard_normal(12)
+    np.testing.assert_allclose(O.adasum_after_optimizer(start, [cur] * 4, [0, 5, 12]), cur, rtol=1e-14)
+    # steps with disjoint supports are orthogonal: all of them are taken in full
+    curs = []
+    for k in range(4):
+        c = start.copy()
+        c[3 * k:3 * k + 3] += rng.standard_normal(3)
+        curs.append(c)
+    want = start + sum(c - start for c in curs)
+    np.testing.assert_allclose(O.adasum_after_optimizer(start, curs, [0, 12]), want, rtol=1e-14)
+    # per layer: a layer nobody moved keeps its parameters exactly
+    curs = [start.copy() for _ in range(2)]
+    curs[0][:5] += 1.0
+    got = O.adasum_after_optimizer(start, curs, [0, 5, 12])
+    np.testing.assert_array_equal(got[5:], start[5:])
+    np.testing.assert_allclose(got[:5], start[:5] + 1.0, rtol=1e-15)
+
+
 PINS = [
     pin_closed_form_two_vectors,
     pin_worked_tree_fixture,
@@ -268,6 +296,7 @@ PINS = [
     pin_zero_convention,
     pin_linear_order,
     pin_low_precision_inputs_are_widened,
+    pin_after_optimizer,
 ]
 
 
@@ -363,9 +392,28 @@ def _mut_linear_is_tree(m):
     m.adasum_linear = m.adasum_tree
 
 
+def _mut_delta_sign(m):
+    def f(start, currents, layer_offsets):
+        w0 = m._as_f64(start)
+        return w0 + m.adasum_reduce([w0 - m._as_f64(c) for c in currents], layer_offsets)
+    m.adasum_after_optimizer = f
+
+
+def _mut_delta_not_added_back(m):
+    def f(start, currents, layer_offsets):
+        w0 = m._as_f64(start)
+        return m.adasum_reduce([m._as_f64(c) - w0 for c in currents], layer_offsets)
+    m.adasum_after_optimizer = f
+
+
+def _mut_operator_on_parameters(m):
+    m.adasum_after_optimizer = lambda start, currents, layer_offsets: m.adasum_reduce(currents, layer_offsets)
+
+
 MUTANTS = [_mut_drop_two, _mut_swap_norms, _mut_plus_sign, _mut_norm_not_squared,
            _mut_tree_is_fold, _mut_uneven_split, _mut_whole_buffer,
-           _mut_no_zero_guard, _mut_fp32_accumulate, _mut_linear_is_tree]
+           _mut_no_zero_guard, _mut_fp32_accumulate, _mut_linear_is_tree,
+           _mut_delta_sign, _mut_delta_not_added_back, _mut_operator_on_parameters]
 
 
 @pytest.mark.parametrize("mutate", MUTANTS, ids=lambda f: f.__name__)
