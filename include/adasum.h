@@ -48,7 +48,7 @@ extern "C" {
 /* error codes */
 #define ADASUM_OK                 0
 #define ADASUM_ERR_INVALID_ARG   -1  /* null pointer, K < 1, n_layers < 0, bad layer table, bad option */
-#define ADASUM_ERR_UNSUPPORTED   -2  /* K not a power of two (Algorithm 1 requires one), unknown dtype/radix */
+#define ADASUM_ERR_UNSUPPORTED   -2  /* unknown dtype / radix / order, or a combination not offered */
 #define ADASUM_ERR_MISALIGNED    -3  /* a DEVICE pointer is not 16-byte aligned */
 #define ADASUM_ERR_OUT_OF_MEMORY -4  /* device or host allocation failed */
 #define ADASUM_ERR_HIP           -5  /* a HIP call failed; see adasum_last_hip_error() */
@@ -105,7 +105,10 @@ typedef struct adasum_options {
  *
  *   grads          HOST array of K DEVICE pointers; grads[k] is worker k's flat
  *                  fused buffer of N = layer_offsets[n_layers] elements of `dtype`
- *   K              number of workers; a power of two >= 1 (K = 1 copies)
+ *   K              number of workers, >= 1 (K = 1 copies).  Any count: the node over
+ *                  workers [lo, hi) splits at lo + (hi - lo) / 2, which is the paper's
+ *                  recursion g_[0,n/2) | g_[n/2,n] read literally (the left part takes
+ *                  floor(count / 2) workers) and the balanced tree for a power of two
  *   layer_offsets  HOST, n_layers + 1 entries in element units, [0] = 0,
  *                  non-decreasing; layer l is [layer_offsets[l], layer_offsets[l+1]);
  *                  empty layers are allowed; N = 0 is a no-op
@@ -193,10 +196,19 @@ int adasum_tile_capacity(void);
 int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
                       adasum_tile* tiles, int64_t cap, int64_t* n_tiles);
 
-/* Writes the radix of every pass for K workers (their product is K), e.g.
- * K = 64, radix 8 -> {8, 8}; K = 128 -> {8, 8, 2}.  *n_levels receives the
- * count; at most `cap` entries are written. */
+/* Writes the radix of every pass of the tree order for K workers, e.g. K = 64,
+ * radix 8 -> {8, 8}; K = 128 -> {8, 8, 2}.  Their product is K for a power of
+ * two, else the next power of two: the first pass's groups are then sub-trees
+ * with fewer leaves than its radix (see adasum_plan_groups), e.g. K = 12,
+ * radix 8 -> {8, 2} with two groups of 6.  *n_levels receives the count; at
+ * most `cap` entries are written. */
 int adasum_plan_levels(int K, int radix, int* radices, int cap, int* n_levels);
+
+/* The groups of the first pass of the tree order: group g reduces workers
+ * first_worker[g] .. first_worker[g+1]-1, a whole sub-tree of the recursion of
+ * Section 3.4 (split at lo + (hi - lo) / 2).  *n_groups receives the number of
+ * groups G; at most `cap` of the G + 1 boundaries are written. */
+int adasum_plan_groups(int K, int radix, int* first_worker, int cap, int* n_groups);
 
 /* ---- per-kernel timing (HIP events on the caller's stream) ---- */
 

@@ -34,9 +34,14 @@ Readings where the paper is silent:
   Adasum(0, 0) = 0.  The test is ``norm == 0`` exactly.  (The dot product with
   a zero vector is 0, so the other operand's coefficient is exactly 1 and any
   finite value would do for the zero one; the convention only removes 0/0.)
-* number of workers: Algorithm 1 requires a power of two; ``adasum_tree``
-  splits at ``(lo + hi) // 2`` for any K, but parity for K that is not a power
-  of two is unpinned (the HIP library rejects such K).
+* number of workers that is not a power of two: Algorithm 1 (the distributed
+  exchange) requires a power of two, the recursion of Section 3.4 does not.
+  It writes the two parts of g_[0,n] (n + 1 gradients) as [0, n/2) and
+  [n/2, n]; read literally, with n/2 a real number, the left part holds
+  ceil(n/2) = floor(K/2) of the K = n + 1 gradients.  ``adasum_tree`` splits
+  there (``K // 2``), at every node.  The written-out expansions for K = 3, 5,
+  6, 7 are pinned; that this reading is the authors' intent is not (their
+  implementation only runs on powers of two).
 * NaN/Inf inputs: propagated by IEEE arithmetic, unpinned.
 
 Everything else is pinned by ``tests/test_oracle_pins.py``.

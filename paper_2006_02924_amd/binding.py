@@ -27,7 +27,7 @@ ERR_OUT_OF_MEMORY, ERR_HIP, ERR_WORKSPACE, ERR_ALIAS = -4, -5, -6, -7
 EXPORTS = [
     "adasum_reduce", "adasum_reduce_ex", "adasum_workspace_bytes",
     "adasum_group_gram", "adasum_group_weights", "adasum_group_combine",
-    "adasum_tile_capacity", "adasum_plan_tiles", "adasum_plan_levels",
+    "adasum_tile_capacity", "adasum_plan_tiles", "adasum_plan_levels", "adasum_plan_groups",
     "adasum_profile_enable", "adasum_profile_collect",
     "adasum_strerror", "adasum_last_hip_error", "adasum_version", "adasum_shutdown",
 ]
@@ -303,6 +303,16 @@ def plan_levels(K: int, radix: int = 0) -> List[int]:
     n = C.c_int(0)
     check(lib.adasum_plan_levels(K, radix, buf, 64, C.byref(n)))
     return [int(buf[i]) for i in range(n.value)]
+
+
+def plan_groups(K: int, radix: int = 0) -> List[int]:
+    """Worker ranges of the first pass's groups: G + 1 boundaries."""
+    lib = load()
+    n = C.c_int(0)
+    check(lib.adasum_plan_groups(K, radix, None, 0, C.byref(n)))
+    buf = (C.c_int * (n.value + 1))()
+    check(lib.adasum_plan_groups(K, radix, buf, n.value + 1, C.byref(n)))
+    return [int(buf[i]) for i in range(n.value + 1)]
 
 
 # ---- per-kernel timing --------------------------------------------------------------

@@ -162,6 +162,8 @@ struct Plan {
     TileTable gram_tiles;                 // capacity kTile
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
     std::vector<int> radices;
+    std::vector<SmallLayer> small;        // layers reduced by the definition in fp64 (see kSmallLayer)
+    SmallLayer* d_small = nullptr;
     Layout lay;
     char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
 
@@ -206,6 +208,7 @@ struct Plan {
         if (capture_stream) (void)hipStreamDestroy(capture_stream);
         gram_tiles.release();
         for (auto& kv : comb_tables) kv.second.release();
+        if (d_small) (void)hipFree(d_small);
         if (d_ws) (void)hipFree(d_ws);
     }
 };
@@ -236,13 +239,22 @@ int find_or_make_plan(int K, int radix, int order, const int64_t* offsets, int n
         int rc = order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, radix, p->radices)
                                               : build_levels(K, radix, p->radices);
         if (rc != ADASUM_OK) return rc;
-        p->lay = make_layout(K, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
-                             norm_entries_bound(K, offsets, n_layers, p->radices), p->radices, order);
+        // the tree order lays its nodes out for the padded (power of two) leaf count
+        const int Kv = order == ADASUM_ORDER_LINEAR ? K : virtual_leaves(p->radices);
+        const int64_t small_elems = K > 1 ? find_small_layers(offsets, n_layers, p->small) : 0;
+        p->lay = make_layout(Kv, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
+                             norm_entries_bound(Kv, offsets, n_layers, p->radices), p->radices, order, K + 1,
+                             small_elems);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
     int rc = p->gram_tiles.upload();
     if (rc != ADASUM_OK) return rc;
+    if (!p->small.empty()) {
+        const size_t bytes = p->small.size() * sizeof(SmallLayer);
+        ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_small), bytes));
+        ADASUM_HIP(hipMemcpy(p->d_small, p->small.data(), bytes, hipMemcpyHostToDevice));
+    }
     *out = p.get();
     g_plans.push_back(std::move(p));
     return ADASUM_OK;
@@ -331,6 +343,37 @@ int check_operands(const void* const* ptrs, int count, int64_t N, int dtype) {
     return ADASUM_OK;
 }
 
+// ---- small layers, by the definition --------------------------------------------
+
+// Before anything is written: the small layers of every worker (minus delta_start) and of
+// delta_start itself go into the compact fp64 copy, kMaxPack workers per launch.
+int small_gather(Plan* p, char* ws, const void* const* grads, int dtype, const Opts& o, void* stream) {
+    if (p->small.empty()) return ADASUM_OK;
+    double* compact = reinterpret_cast<double*>(ws + p->lay.off_small);
+    const int n_small = static_cast<int>(p->small.size());
+    for (int k0 = 0; k0 < p->K; k0 += kMaxPack) {
+        const int n = std::min(kMaxPack, p->K - k0);
+        Operands ops;
+        std::memset(&ops, 0, sizeof(ops));
+        for (int j = 0; j < n; ++j) ops.pack[j] = grads[k0 + j];
+        ADASUM_TIMED("small_gather", 0.0, stream,
+                     launch_small_gather(dtype, ops, n, k0, p->d_small, n_small, p->lay.small_elems, o.delta_start,
+                                         k0 == 0 && o.delta_start != nullptr, p->K, compact, stream));
+    }
+    return ADASUM_OK;
+}
+
+// After the passes: the small layers again, pair by pair in fp64, over what they wrote.
+int small_reduce(Plan* p, char* ws, void* out, const Opts& o, void* stream) {
+    if (p->small.empty()) return ADASUM_OK;
+    const double* compact = reinterpret_cast<const double*>(ws + p->lay.off_small);
+    ADASUM_TIMED("small_layers", 0.0, stream,
+                 launch_small_reduce(o.out_dtype, compact, p->K, p->d_small, static_cast<int>(p->small.size()),
+                                     p->lay.small_elems, o.order, o.delta_start != nullptr, p->K, out,
+                                     o.layer_stats, stream));
+    return ADASUM_OK;
+}
+
 // ---- the level scheduler -------------------------------------------------------
 
 int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
@@ -348,7 +391,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
     char namebuf[48];
 
-    int nodes = p->K;        // tree nodes alive before this pass
+    int nodes = virtual_leaves(p->radices);   // tree nodes alive before this pass (leaves: padded count)
+    const int depth0 = first_depth(p->radices);   // the first pass's groups are the sub-trees of this depth
     int stride = 1;          // slot distance between consecutive alive nodes (passes >= 1)
     TileSet norm_tiles;      // the table the previous combine indexed its squared norms by
     const int n_levels = static_cast<int>(p->radices.size());
@@ -357,6 +401,10 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     std::vector<TileSet> comb_sets(n_levels);
     for (int lv = 0; lv < n_levels; ++lv) {
         const int rc = p->comb_tiles(lv == 0 ? dtype : ADASUM_F32, p->radices[lv], &comb_sets[lv]);
+        if (rc != ADASUM_OK) return rc;
+    }
+    {
+        const int rc = small_gather(p, ws, grads, dtype, o, stream);
         if (rc != ADASUM_OK) return rc;
     }
     for (int lv = 0; lv < n_levels; ++lv) {
@@ -374,16 +422,36 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         // Section 4.1's delta form: the leaves are grads[k] - delta_start, the root adds delta_start back
         const void* sub_in = first ? o.delta_start : nullptr;
         const void* add_out = last ? o.delta_start : nullptr;
-        const double gram_bytes_per_group = static_cast<double>(R + (sub_in ? 1 : 0)) * N * elem_bytes(in_dtype);
-        const double comb_bytes_per_group =
-            static_cast<double>(N) * (static_cast<double>(R + (sub_in ? 1 : 0)) * elem_bytes(in_dtype) +
-                                      (add_out ? 2.0 : 1.0) * elem_bytes(st_dtype));
+        // algorithmic bytes of a launch over `ng` groups with `leaves` distinct operands
+        auto gram_bytes = [&](int leaves, int ng) {
+            return static_cast<double>(leaves + (sub_in ? ng : 0)) * N * elem_bytes(in_dtype);
+        };
+        auto comb_bytes = [&](int leaves, int ng) {
+            return static_cast<double>(N) * (static_cast<double>(leaves + (sub_in ? ng : 0)) * elem_bytes(in_dtype) +
+                                             (add_out ? 2.0 : 1.0) * ng * elem_bytes(st_dtype));
+        };
 
+        // first pass: group g reads its sub-tree's leaves; a group with fewer than R leaves
+        // (K not a power of two) repeats its first leaf, which the weights kernel zeroes
         auto fill_operands = [&](Operands& ops, int g0, int ng) {
             std::memset(&ops, 0, sizeof(ops));
-            for (int i = 0; i < ng * R; ++i)
-                ops.pack[i] = first ? grads[g0 * R + i]
-                                    : slots + static_cast<long long>(g0 * R + i) * stride * slot_bytes;
+            if (first) {
+                for (int j = 0; j < ng; ++j) {
+                    int lo, hi;
+                    leaf_range(p->K, depth0, g0 + j, lo, hi);
+                    for (int i = 0; i < R; ++i) ops.pack[j * R + i] = grads[lo + i < hi ? lo + i : lo];
+                }
+            } else {
+                for (int i = 0; i < ng * R; ++i)
+                    ops.pack[i] = slots + static_cast<long long>(g0 * R + i) * stride * slot_bytes;
+            }
+        };
+        auto real_leaves = [&](int g0, int ng) {
+            if (!first) return ng * R;
+            int lo, hi, lo2, hi2;
+            leaf_range(p->K, depth0, g0, lo, hi);
+            leaf_range(p->K, depth0, g0 + ng - 1, lo2, hi2);
+            return hi2 - lo;
         };
 
         // step 1: partial Gram entries
@@ -392,7 +460,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
             Operands ops;
             fill_operands(ops, g0, ng);
             kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
-            ADASUM_TIMED(namebuf, gram_bytes_per_group * ng, stream,
+            ADASUM_TIMED(namebuf, gram_bytes(real_leaves(g0, ng), ng), stream,
                          launch_gram(in_dtype, first, ops, gt, ng, R, partials + static_cast<int64_t>(g0) * np * T,
                                      sub_in, stream));
         }
@@ -405,11 +473,12 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         ADASUM_TIMED(namebuf, 0.0, stream,
                      launch_gram_finish(first, gt, L, groups, R, partials, normcoarse, gram, stream));
         if (first && o.layer_stats != nullptr) {
-            ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, o.layer_stats + 1, 2, stream));
+            ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, p->K, depth0, o.layer_stats + 1, 2, stream));
         }
         kernel_name("weights", 0, 0, R, first, namebuf, sizeof(namebuf));
         ADASUM_TIMED(namebuf, 0.0, stream,
-                     launch_weights(gram, R, static_cast<int64_t>(groups) * L, o.order, weights, stream));
+                     launch_weights(gram, R, static_cast<int64_t>(groups) * L, o.order, L, first ? p->K : 0, depth0,
+                                    weights, stream));
         // step 3: apply
         for (int g0 = 0; g0 < groups; g0 += batch) {
             const int ng = std::min(batch, groups - g0);
@@ -427,7 +496,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                 outs.stride = ostride;
             }
             kernel_name("combine", in_dtype, st_dtype, R, false, namebuf, sizeof(namebuf));
-            ADASUM_TIMED(namebuf, comb_bytes_per_group * ng, stream,
+            ADASUM_TIMED(namebuf, comb_bytes(real_leaves(g0, ng), ng), stream,
                          launch_combine(in_dtype, st_dtype, ops, outs, ct, L, ng, R,
                                         weights + static_cast<int64_t>(g0) * L * R,
                                         want_norm ? normparts + static_cast<int64_t>(g0) * ct.n_tiles : nullptr,
@@ -441,7 +510,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, norm_tiles, gt, normcoarse, stream));
         ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, L, o.layer_stats, 2, stream));
     }
-    return ADASUM_OK;
+    return small_reduce(p, ws, out, o, stream);
 }
 
 // Left-to-right order (Section 3.4, first recursion).  Pass 0 folds the first
@@ -471,6 +540,10 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
         if (rc != ADASUM_OK) return rc;
     }
 
+    {
+        const int rc = small_gather(p, ws, grads, dtype, o, stream);
+        if (rc != ADASUM_OK) return rc;
+    }
     int next_leaf = 0;
     for (int b = 0; b < n_passes; ++b) {
         const int R = p->radices[b];
@@ -505,7 +578,7 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
         }
         ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, nullptr, stream));
         ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, stream));
-        ADASUM_LAUNCH(launch_weights(gram, R, L, ADASUM_ORDER_LINEAR, weights, stream));
+        ADASUM_LAUNCH(launch_weights(gram, R, L, ADASUM_ORDER_LINEAR, L, 0, 0, weights, stream));
         Outputs outs;
         outs.base = last ? static_cast<char*>(out) : slots;
         outs.slot_bytes = 0;
@@ -513,7 +586,7 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
         ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights, nullptr, nullptr,
                                      nullptr, stream));
     }
-    return ADASUM_OK;
+    return small_reduce(p, ws, out, o, stream);
 }
 
 // K = 1: the result is the gradient itself, converted to the output dtype.
@@ -639,7 +712,6 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     Opts o;
     rc = read_opts(opts, dtype, o);
     if (rc != ADASUM_OK) return rc;
-    if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
     if (K > (1 << 20)) return ADASUM_ERR_UNSUPPORTED;
     const int64_t N = layer_offsets[n_layers];
     rc = check_operands(grads, K, N, dtype);
@@ -700,9 +772,13 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
         rc = o.order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, radix, radices)
                                             : build_levels(K, radix, radices);
         if (rc != ADASUM_OK) return rc;
-        const Layout lay = make_layout(K, layer_offsets[n_layers], n_layers,
+        const int Kv = o.order == ADASUM_ORDER_LINEAR ? K : virtual_leaves(radices);
+        std::vector<SmallLayer> small;
+        const int64_t small_elems = K > 1 ? find_small_layers(layer_offsets, n_layers, small) : 0;
+        const Layout lay = make_layout(Kv, layer_offsets[n_layers], n_layers,
                                        count_tiles(layer_offsets, n_layers, kTile),
-                                       norm_entries_bound(K, layer_offsets, n_layers, radices), radices, o.order);
+                                       norm_entries_bound(Kv, layer_offsets, n_layers, radices), radices, o.order,
+                                       K + 1, small_elems);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -751,7 +827,7 @@ int adasum_group_weights(const double* gram, int R, int n_layers, int order, dou
     if ((reinterpret_cast<uintptr_t>(gram) & 7u) != 0 || (reinterpret_cast<uintptr_t>(weights) & 7u) != 0)
         return ADASUM_ERR_MISALIGNED;
     if (n_layers == 0) return ADASUM_OK;
-    ADASUM_LAUNCH(launch_weights(gram, R, n_layers, order, weights, stream));
+    ADASUM_LAUNCH(launch_weights(gram, R, n_layers, order, 1, 0, 0, weights, stream));
     return ADASUM_OK;
 }
 
@@ -831,6 +907,22 @@ int adasum_plan_levels(int K, int radix, int* radices, int cap, int* n_levels) {
     if (rc != ADASUM_OK) return rc;
     *n_levels = static_cast<int>(r.size());
     for (int i = 0; i < std::min<int>(cap, static_cast<int>(r.size())); ++i) radices[i] = r[i];
+    return ADASUM_OK;
+}
+
+int adasum_plan_groups(int K, int radix, int* first_worker, int cap, int* n_groups) {
+    if (n_groups == nullptr || cap < 0 || (first_worker == nullptr && cap > 0)) return ADASUM_ERR_INVALID_ARG;
+    std::vector<int> r;
+    int rc = build_levels(K, radix, r);
+    if (rc != ADASUM_OK) return rc;
+    const int depth = first_depth(r);
+    const int groups = 1 << depth;
+    *n_groups = groups;
+    for (int g = 0; g <= groups && g < cap; ++g) {
+        int lo = K, hi = K;
+        if (g < groups) leaf_range(K, depth, g, lo, hi);
+        first_worker[g] = lo;
+    }
     return ADASUM_OK;
 }
 

@@ -53,12 +53,43 @@ int check_layer_table(const int64_t* layer_offsets, int n_layers);
 void build_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
                  std::vector<adasum_tile>& tiles, std::vector<int32_t>& layer_tile_begin);
 
-// Radix of every pass; product equals K.  Largest radices first (the first pass
-// reads the narrow input dtype and touches the most data).
+// The halving tree of Section 3.4 over K leaves, for any K: the node over leaves [lo, hi)
+// splits at lo + (hi - lo) / 2, i.e. the left part takes floor(count / 2) leaves (for a
+// power of two, the balanced tree).  Returns the leaves of node g of depth `depth`
+// (g's bits from the most significant: 1 = right child).  Sizes at one depth differ by at
+// most one.  Host and device.
+constexpr void leaf_range(int K, int depth, int g, int& lo, int& hi) {
+    lo = 0;
+    hi = K;
+    for (int b = depth - 1; b >= 0; --b) {
+        const int mid = lo + (hi - lo) / 2;
+        if ((g >> b) & 1) lo = mid;
+        else hi = mid;
+    }
+}
+
+// Radix of every pass.  The first pass takes the sub-trees of depth `first_depth(radices)`
+// as its groups: at most radices[0] leaves each (fewer when K is not a power of two; a
+// short group is padded up to the radix with repeats of its first leaf, which get weight
+// 0).  Above them the tree is a balanced one over 2^depth nodes.  The product of the
+// radices is K for a power of two, else the next power of two.  Largest radices first
+// (the first pass reads the narrow input dtype and touches the most data).
 int build_levels(int K, int radix, std::vector<int>& radices);
+inline int virtual_leaves(const std::vector<int>& radices) {
+    int v = 1;
+    for (int r : radices) v *= r;
+    return v;
+}
+inline int first_depth(const std::vector<int>& radices) {
+    int groups = radices.empty() ? 1 : virtual_leaves(radices) / radices[0];
+    int d = 0;
+    while ((1 << d) < groups) ++d;
+    return d;
+}
 
 // Left-to-right order (Section 3.4, first recursion): operand counts of the
-// passes.  The first pass folds `min(K, radix)` leaves; every later pass folds
+// passes.  The first pass folds the largest power of two of leaves that is at most
+// min(K, radix); every later pass folds
 // the running result with up to radix - 1 further leaves (operand 0 is the
 // running result), using the widest instantiated radix that the remaining
 // leaves fill.  E.g. K = 64, radix 16 -> {16, 16, 16, 16, 4}.
@@ -68,6 +99,24 @@ int build_linear_passes(int K, int radix, std::vector<int>& passes);
 // i < j, plus the R diagonal entries when `diag` (the first pass; later passes
 // get their squared norms from the previous combine).
 inline int gram_entries(int R, bool diag) { return R * (R - 1) / 2 + (diag ? R : 0); }
+
+// Layers of at most kSmallLayer elements are reduced a second time by the definition
+// itself, pair by pair in fp64 over all K workers with no stored intermediate, and that
+// result replaces what the passes wrote.  Vectors of a few elements can nearly cancel at
+// a tree node (two scalars of opposite sign do so with probability ~eps); the relative
+// error of an fp32 node is amplified by 1/eps there, and the Gram route's scalars by its
+// square, so the passes alone cannot hold a relative bound on such layers.  From some ten
+// elements on the chance of a cancellation is negligible.
+constexpr int kSmallLayer = 16;
+struct SmallLayer {
+    int64_t start;   // first element in the fused buffer
+    int32_t len;     // 1 .. kSmallLayer
+    int32_t layer;
+    int32_t coff;    // first element in a row of the compact copy
+    int32_t pad;
+};
+// Small layers of a layer table; returns the elements they hold in total.
+int64_t find_small_layers(const int64_t* layer_offsets, int n_layers, std::vector<SmallLayer>& small);
 
 // Device workspace layout (byte offsets from a 256-byte aligned base).
 struct Layout {
@@ -84,12 +133,18 @@ struct Layout {
     size_t  off_gram = 0;     // doubles [group][layer][R*R] (finished Gram matrices)
     size_t  off_weights = 0;  // doubles [group][layer][R]
     size_t  off_leafnorm = 0; // doubles [layer]: sum over workers of the input squared norms
+    size_t  off_small = 0;    // doubles [K + 1][small_elems]: the small layers of every worker, widened
+                              // (row K: those of delta_start)
+    int64_t small_elems = 0;
     size_t  total = 0;
 };
 // `norm_entries`: doubles needed for the squared norms the combines leave
 // (max over passes of nodes written x combine tiles of that pass).
+// `K` is the padded leaf count in the tree order; `small_rows` x `small_elems` doubles are
+// reserved for the compact copy of the small layers.
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
-                   const std::vector<int>& radices, int order = ADASUM_ORDER_TREE);
+                   const std::vector<int>& radices, int order = ADASUM_ORDER_TREE, int64_t small_rows = 0,
+                   int64_t small_elems = 0);
 // Number of tiles build_tiles would produce.
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity);
 // Upper bound (over input dtypes) of make_layout's norm_entries for a schedule.
@@ -136,7 +191,10 @@ int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, cons
 int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups, int R,
                        const double* partials, const double* normparts, double* gram, void* stream);
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
-int launch_weights(const double* gram, int R, int64_t n_items, int order,
+// Item i is (group i / n_layers, layer i % n_layers).  K_leaves > 0: group g holds only the
+// leaves of node g of depth `depth` in the halving tree over K_leaves (leaf_range), in its
+// first operands; the rest are padding and get weight 0.  K_leaves = 0: every group is full.
+int launch_weights(const double* gram, int R, int64_t n_items, int order, int n_layers, int K_leaves, int depth,
                    double* weights, void* stream);
 // `ct` must be the table of capacity combine_tile_capacity(dtype, R);
 // normparts[group * ct.n_tiles + tile] (or null).
@@ -148,9 +206,23 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
 // layer_sum[l * out_stride] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
 int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers,
                       double* layer_sum, int out_stride, void* stream);
-// out[l * out_stride] = sum over groups of trace(gram[group][l]).
-int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers,
+// out[l * out_stride] = sum over groups of trace(gram[group][l]) (over each group's real
+// leaves: K_leaves and depth as in launch_weights).
+int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, int K_leaves, int depth,
                       double* out, int out_stride, void* stream);
+
+// Copies the small layers of `n_leaves` operands (ops.pack[0..n_leaves)), widened to fp64 and
+// minus `delta_start` when given, into rows leaf0.. of the compact copy; with `stash_start`
+// also delta_start's own small layers into row `start_row`.
+int launch_small_gather(int dtype, const Operands& ops, int n_leaves, int leaf0, const SmallLayer* small,
+                        int n_small, int64_t small_elems, const void* delta_start, bool stash_start,
+                        int start_row, double* compact, void* stream);
+// Reduces every small layer over the K rows of the compact copy by the definition (tree or
+// left-to-right), adds row `start_row` when add_start, stores to `out` (out_dtype) and, when
+// stats is given, writes stats[layer][0..1].
+int launch_small_reduce(int out_dtype, const double* compact, int K, const SmallLayer* small, int n_small,
+                        int64_t small_elems, int order, bool add_start, int start_row, void* out, double* stats,
+                        void* stream);
 
 const char* kernel_name(const char* kind, int dtype, int out_dtype, int R, bool diag, char* buf, size_t n);
 

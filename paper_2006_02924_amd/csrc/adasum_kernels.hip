@@ -511,17 +511,36 @@ __device__ __forceinline__ void merge_nodes(const double* G, double (&w)[R], int
 
 template <int R>
 __global__ void __launch_bounds__(64)
-weights_kernel(const double* __restrict__ gram, long long n_items, int order, double* __restrict__ weights) {
+weights_kernel(const double* __restrict__ gram, long long n_items, int order, int n_layers, int K_leaves,
+               int depth, double* __restrict__ weights) {
     const long long item = static_cast<long long>(blockIdx.x) * 64 + threadIdx.x;
     if (item >= n_items) return;
     const double* G = gram + item * (R * R);
+    // leaves this group really holds (its first r operands; the rest is padding)
+    int r = R;
+    if (K_leaves > 0) {
+        int lo, hi;
+        leaf_range(K_leaves, depth, static_cast<int>(item / n_layers), lo, hi);
+        r = hi - lo;
+    }
     double w[R];
-    for (int p = 0; p < R; ++p) w[p] = 1.0;
+    for (int p = 0; p < R; ++p) w[p] = p < r ? 1.0 : 0.0;
     if (order == ADASUM_ORDER_LINEAR) {
-        for (int k = 1; k < R; ++k) merge_nodes<R>(G, w, 0, k, k, k + 1);
+        for (int k = 1; k < r; ++k) merge_nodes<R>(G, w, 0, k, k, k + 1);
     } else {
-        for (int span = 1; span < R; span *= 2)
-            for (int j = 0; j < R; j += 2 * span) merge_nodes<R>(G, w, j, j + span, j + span, j + 2 * span);
+        // the halving tree over r leaves, deepest nodes first: children before parents
+        int levels = 0;
+        while ((1 << levels) < r) ++levels;
+        for (int d = levels - 1; d >= 0; --d) {
+            for (int j = 0; j < (1 << d); ++j) {
+                int lo, hi;
+                leaf_range(r, d, j, lo, hi);
+                if (hi - lo >= 2) {
+                    const int mid = lo + (hi - lo) / 2;
+                    merge_nodes<R>(G, w, lo, mid, mid, hi);
+                }
+            }
+        }
     }
     for (int p = 0; p < R; ++p) weights[item * R + p] = w[p];
 }
@@ -648,6 +667,107 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 }
 
 // ---------------------------------------------------------------------------
+// Small layers (at most kSmallLayer elements), by the definition itself: the
+// operator of Section 3 applied pair by pair over all K workers in fp64, in the
+// order of Section 3.4's recursion, nothing stored in between.
+// ---------------------------------------------------------------------------
+// compact[(leaf0 + j)][coff + e] = ops.pack[j][start + e] (- delta[start + e]); with
+// stash_start also compact[start_row][coff + e] = delta[start + e].
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+small_gather_kernel(const Operands ops, int n_leaves, int leaf0, const SmallLayer* __restrict__ small,
+                    long long small_elems, const T* __restrict__ delta, int stash_start, int start_row,
+                    double* __restrict__ compact) {
+    const SmallLayer s = small[blockIdx.x];
+    const int rows = n_leaves + (stash_start ? 1 : 0);
+    for (int i = threadIdx.x; i < rows * s.len; i += kThreads) {
+        const int j = i / s.len, e = i - j * s.len;
+        const long long idx = s.start + e;
+        if (j < n_leaves) {
+            double v = static_cast<double>(load_elem(static_cast<const T*>(ops.pack[j]) + idx));
+            if (delta != nullptr) v -= static_cast<double>(load_elem(delta + idx));
+            compact[static_cast<long long>(leaf0 + j) * small_elems + s.coff + e] = v;
+        } else {
+            compact[static_cast<long long>(start_row) * small_elems + s.coff + e] =
+                static_cast<double>(load_elem(delta + idx));
+        }
+    }
+}
+
+// One lane per element; lanes past the layer's length hold zeros.
+__device__ __forceinline__ double small_pair(double a, double b) {
+    const double d = wave_sum(a * b), n1 = wave_sum(a * a), n2 = wave_sum(b * b);
+    const double ca = n1 > 0.0 ? 1.0 - d / (2.0 * n1) : 1.0;
+    const double cb = n2 > 0.0 ? 1.0 - d / (2.0 * n2) : 1.0;
+    return ca * a + cb * b;
+}
+
+// Is [lo, hi) a node of the halving tree over K leaves?
+__device__ __forceinline__ bool is_tree_node(int K, int lo, int hi) {
+    int a = 0, b = K;
+    while (a != lo || b != hi) {
+        if (b - a < 2) return false;
+        const int mid = a + (b - a) / 2;
+        if (hi <= mid) b = mid;
+        else if (lo >= mid) a = mid;
+        else return false;
+    }
+    return true;
+}
+
+template <typename TO>
+__global__ void __launch_bounds__(64)
+small_reduce_kernel(const double* __restrict__ compact, int K, const SmallLayer* __restrict__ small,
+                    long long small_elems, int order, int add_start, int start_row, TO* out,
+                    double* __restrict__ stats) {
+    constexpr int kDepth = 34;   // a stack of complete sub-trees of distinct depths: at most log2(K) + 2
+    __shared__ double vstack[kDepth][64];
+    const SmallLayer s = small[blockIdx.x];
+    const int lane = threadIdx.x;
+    const bool live = lane < s.len;
+    const double* col = compact + s.coff + lane;
+    double leafsq = 0.0, r = 0.0;
+    if (order == ADASUM_ORDER_LINEAR) {
+        for (int k = 0; k < K; ++k) {
+            const double v = live ? col[static_cast<long long>(k) * small_elems] : 0.0;
+            leafsq += v * v;
+            r = k == 0 ? v : small_pair(r, v);
+        }
+    } else {
+        // leaves left to right; the two topmost sub-trees are merged as soon as together
+        // they form a node of the tree
+        int lo[kDepth], hi[kDepth];
+        int sp = 0;
+        for (int k = 0; k < K; ++k) {
+            const double v = live ? col[static_cast<long long>(k) * small_elems] : 0.0;
+            leafsq += v * v;
+            vstack[sp][lane] = v;
+            lo[sp] = k;
+            hi[sp] = k + 1;
+            ++sp;
+            while (sp >= 2 && is_tree_node(K, lo[sp - 2], hi[sp - 1])) {
+                const double b = vstack[sp - 1][lane], a = vstack[sp - 2][lane];
+                vstack[sp - 2][lane] = small_pair(a, b);
+                hi[sp - 2] = hi[sp - 1];
+                --sp;
+            }
+        }
+        r = vstack[0][lane];   // sp == 1: the root [0, K)
+    }
+    const double rsq = wave_sum(r * r);
+    leafsq = wave_sum(leafsq);
+    if (stats != nullptr && lane == 0) {
+        stats[2 * s.layer + 0] = rsq;
+        stats[2 * s.layer + 1] = leafsq;
+    }
+    if (live) {
+        double z = r;
+        if (add_start) z += compact[static_cast<long long>(start_row) * small_elems + s.coff + lane];
+        store_elem(out + s.start + lane, static_cast<float>(z));
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Per-layer statistics helpers (orthogonality metric of Section 3.6).
 // ---------------------------------------------------------------------------
 // out[l * out_stride] = sum over rows and the tiles of layer l of parts[row][tile]
@@ -667,16 +787,22 @@ layer_sums_kernel(const double* __restrict__ parts, int n_rows,
     if (threadIdx.x == 0) out[static_cast<long long>(l) * out_stride] = v;
 }
 
-// out[l * out_stride] = sum over groups of trace(gram[group][l])
+// out[l * out_stride] = sum over groups of trace(gram[group][l]) over each group's real leaves
 __global__ void __launch_bounds__(64)
-trace_sums_kernel(const double* __restrict__ gram, int R, int n_groups, int n_layers,
+trace_sums_kernel(const double* __restrict__ gram, int R, int n_groups, int n_layers, int K_leaves, int depth,
                   double* __restrict__ out, int out_stride) {
     const int l = blockIdx.x * 64 + threadIdx.x;
     if (l >= n_layers) return;
     double v = 0.0;
     for (int g = 0; g < n_groups; ++g) {
         const double* G = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
-        for (int i = 0; i < R; ++i) v += G[i * R + i];
+        int r = R;
+        if (K_leaves > 0) {
+            int lo, hi;
+            leaf_range(K_leaves, depth, g, lo, hi);
+            r = hi - lo;
+        }
+        for (int i = 0; i < r; ++i) v += G[i * R + i];
     }
     out[static_cast<long long>(l) * out_stride] = v;
 }
@@ -799,18 +925,20 @@ int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups,
     return check_launch();
 }
 
-int launch_weights(const double* gram, int R, int64_t n_items, int order, double* weights, void* stream) {
+int launch_weights(const double* gram, int R, int64_t n_items, int order, int n_layers, int K_leaves, int depth,
+                   double* weights, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_items == 0) return 0;
     const long long blocks = (n_items + 63) / 64;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(64);
     const long long n = n_items;
+    const int nl = n_layers > 0 ? n_layers : 1;
     switch (R) {
-        case 2: hipLaunchKernelGGL((weights_kernel<2>), grid, block, 0, st, gram, n, order, weights); break;
-        case 4: hipLaunchKernelGGL((weights_kernel<4>), grid, block, 0, st, gram, n, order, weights); break;
-        case 8: hipLaunchKernelGGL((weights_kernel<8>), grid, block, 0, st, gram, n, order, weights); break;
-        case 16: hipLaunchKernelGGL((weights_kernel<16>), grid, block, 0, st, gram, n, order, weights); break;
+        case 2: hipLaunchKernelGGL((weights_kernel<2>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
+        case 4: hipLaunchKernelGGL((weights_kernel<4>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
+        case 8: hipLaunchKernelGGL((weights_kernel<8>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
+        case 16: hipLaunchKernelGGL((weights_kernel<16>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
     return check_launch();
@@ -852,12 +980,49 @@ int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_l
     return check_launch();
 }
 
-int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, double* out, int out_stride,
-                      void* stream) {
+int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, int K_leaves, int depth, double* out,
+                      int out_stride, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_layers == 0) return 0;
     hipLaunchKernelGGL(trace_sums_kernel, dim3((n_layers + 63) / 64), dim3(64), 0, st, gram, R, n_groups,
-                       n_layers, out, out_stride);
+                       n_layers, K_leaves, depth, out, out_stride);
+    return check_launch();
+}
+
+int launch_small_gather(int dtype, const Operands& ops, int n_leaves, int leaf0, const SmallLayer* small,
+                        int n_small, int64_t small_elems, const void* delta_start, bool stash_start,
+                        int start_row, double* compact, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_small == 0 || n_leaves == 0) return 0;
+    if (n_leaves > kMaxPack || (stash_start && delta_start == nullptr)) return static_cast<int>(hipErrorInvalidValue);
+    const dim3 grid(static_cast<unsigned>(n_small)), block(kThreads);
+    const long long se = small_elems;
+    const int stash = stash_start ? 1 : 0;
+#define ADASUM_GATHER(T)                                                                              \
+    hipLaunchKernelGGL((small_gather_kernel<T>), grid, block, 0, st, ops, n_leaves, leaf0, small, se, \
+                       static_cast<const T*>(delta_start), stash, start_row, compact)
+    if (dtype == ADASUM_BF16) ADASUM_GATHER(bf16_t);
+    else if (dtype == ADASUM_F16) ADASUM_GATHER(f16_t);
+    else ADASUM_GATHER(float);
+#undef ADASUM_GATHER
+    return check_launch();
+}
+
+int launch_small_reduce(int out_dtype, const double* compact, int K, const SmallLayer* small, int n_small,
+                        int64_t small_elems, int order, bool add_start, int start_row, void* out, double* stats,
+                        void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_small == 0) return 0;
+    const dim3 grid(static_cast<unsigned>(n_small)), block(64);
+    const long long se = small_elems;
+    const int add = add_start ? 1 : 0;
+#define ADASUM_SMALL(T)                                                                                 \
+    hipLaunchKernelGGL((small_reduce_kernel<T>), grid, block, 0, st, compact, K, small, se, order, add, \
+                       start_row, static_cast<T*>(out), stats)
+    if (out_dtype == ADASUM_BF16) ADASUM_SMALL(bf16_t);
+    else if (out_dtype == ADASUM_F16) ADASUM_SMALL(f16_t);
+    else ADASUM_SMALL(float);
+#undef ADASUM_SMALL
     return check_launch();
 }
 

@@ -46,10 +46,17 @@ void build_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
 int build_levels(int K, int radix, std::vector<int>& radices) {
     radices.clear();
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
-    if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
     if (radix == 0) radix = kDefaultRadix;
     if (radix != 2 && radix != 4 && radix != 8 && radix != 16) return ADASUM_ERR_UNSUPPORTED;
-    int rest = K;
+    if (K == 1) return ADASUM_OK;
+    // the shallowest depth whose sub-trees have at most `radix` leaves
+    int depth = 0;
+    while ((K + (1 << depth) - 1) / (1 << depth) > radix) ++depth;
+    const int widest = (K + (1 << depth) - 1) / (1 << depth);
+    int first = 2;
+    while (first < widest) first *= 2;
+    radices.push_back(first);
+    int rest = 1 << depth;
     while (rest > 1) {
         int r = std::min(rest, radix);
         radices.push_back(r);
@@ -61,11 +68,11 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
 int build_linear_passes(int K, int radix, std::vector<int>& passes) {
     passes.clear();
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
-    if (!is_pow2(K)) return ADASUM_ERR_UNSUPPORTED;
     if (radix == 0) radix = kDefaultRadix;
     if (radix != 2 && radix != 4 && radix != 8 && radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (K == 1) return ADASUM_OK;
-    const int first = std::min(K, radix);
+    int first = radix;
+    while (first > K) first /= 2;
     passes.push_back(first);
     int rest = K - first;
     while (rest > 0) {
@@ -75,6 +82,24 @@ int build_linear_passes(int K, int radix, std::vector<int>& passes) {
         rest -= r - 1;
     }
     return ADASUM_OK;
+}
+
+int64_t find_small_layers(const int64_t* layer_offsets, int n_layers, std::vector<SmallLayer>& small) {
+    small.clear();
+    int64_t total = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int64_t len = layer_offsets[l + 1] - layer_offsets[l];
+        if (len < 1 || len > kSmallLayer) continue;
+        SmallLayer s;
+        s.start = layer_offsets[l];
+        s.len = static_cast<int32_t>(len);
+        s.layer = l;
+        s.coff = static_cast<int32_t>(total);
+        s.pad = 0;
+        small.push_back(s);
+        total += len;
+    }
+    return total;
 }
 
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity) {
@@ -101,7 +126,7 @@ int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, co
 }
 
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
-                   const std::vector<int>& radices, int order) {
+                   const std::vector<int>& radices, int order, int64_t small_rows, int64_t small_elems) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
@@ -144,6 +169,9 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
     off = align_up(off + max_weights * sizeof(double), 256);
     lay.off_leafnorm = off;
     off = align_up(off + static_cast<size_t>(n_layers) * sizeof(double), 256);
+    lay.off_small = off;
+    lay.small_elems = small_elems;
+    off = align_up(off + static_cast<size_t>(small_rows) * static_cast<size_t>(small_elems) * sizeof(double), 256);
     lay.total = off;
     return lay;
 }

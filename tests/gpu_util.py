@@ -22,22 +22,78 @@ TOL_F16 = 2.5e-4
 TOL_F16_TINY = 2.0 ** -11 * 1.001
 
 
+# The zero-norm convention (a zero-norm operand passes its sibling up) is discontinuous:
+# Adasum(u, v) -> v/2-ish as u -> 0 along a direction, but Adasum(0, v) = v.  A tree node that is
+# *exactly* zero in exact arithmetic although its children are not (possible for layers of a few
+# elements whose values sit on the coarse bf16 grid: about 2 % of 1-element layers at K = 48) is
+# therefore ill-posed: fp64 rounding noise decides, in the oracle as much as in the library,
+# whether the node is 0 or 1e-17, and the result differs by tens of percent.  Such layers have no
+# reference value.  They are detected on the oracle side only (from the inputs), reported, and
+# marked NaN in the reference; the comparison skips exactly those.
+ILL_POSED_MAX_SIZE = 16     # only layers this small are ever excused
+ILL_POSED_CANCEL = 1e-9     # |node| <= this x (|left| + |right|) with both children non-zero
+
+
+def _node_is_ill_posed(parts, order):
+    """Walks the oracle's own recursion over one layer and reports whether some node cancels."""
+    flagged = [False]
+
+    def combine(a, b):
+        r = O.adasum_pair(a, b)
+        na, nb, nr = np.linalg.norm(a), np.linalg.norm(b), np.linalg.norm(r)
+        if na > 0.0 and nb > 0.0 and nr <= ILL_POSED_CANCEL * (na + nb):
+            flagged[0] = True
+        return r
+
+    def tree(gs):
+        if len(gs) == 1:
+            return np.asarray(gs[0], dtype=np.float64)
+        mid = len(gs) // 2
+        return combine(tree(gs[:mid]), tree(gs[mid:]))
+
+    if order == "tree":
+        tree(parts)
+    else:
+        acc = np.asarray(parts[0], dtype=np.float64)
+        for g in parts[1:]:
+            acc = combine(acc, np.asarray(g, dtype=np.float64))
+    return flagged[0]
+
+
+def mark_ill_posed(ref, vectors64, offs, order="tree", layers=None):
+    """Sets ref to NaN on the small layers whose reduction hits the discontinuity."""
+    todo = range(len(offs) - 1) if layers is None else layers
+    for l in todo:
+        lo, hi = offs[l], offs[l + 1]
+        if 0 < hi - lo <= ILL_POSED_MAX_SIZE and _node_is_ill_posed([v[lo:hi] for v in vectors64], order):
+            print(f"  layer {l} (size {hi - lo}): a tree node cancels exactly; no reference value, skipped",
+                  flush=True)
+            ref[lo:hi] = np.nan
+    return ref
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Stored device values widened exactly to fp64 on the host."""
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
-def oracle_reduce(grads, layer_offsets, layers=None) -> np.ndarray:
+def oracle_reduce(grads, layer_offsets, layers=None, order="tree") -> np.ndarray:
     """fp64 oracle result for the whole buffer, or only for `layers` (other
     positions are left at 0)."""
     offs = list(layer_offsets)
     if layers is None:
-        return O.adasum_reduce([to_f64(g) for g in grads], offs)
+        f64 = [to_f64(g) for g in grads]
+        return mark_ill_posed(O.adasum_reduce(f64, offs, order=order), f64, offs, order)
     out = np.zeros(offs[-1], dtype=np.float64)
     for l in layers:
         lo, hi = offs[l], offs[l + 1]
         if hi > lo:
-            out[lo:hi] = O.adasum_tree([to_f64(g[lo:hi]) for g in grads])
+            parts = [to_f64(g[lo:hi]) for g in grads]
+            out[lo:hi] = O.adasum_tree(parts)
+            if hi - lo <= ILL_POSED_MAX_SIZE and _node_is_ill_posed(parts, "tree"):
+                print(f"  layer {l} (size {hi - lo}): a tree node cancels exactly; no reference value, skipped",
+                      flush=True)
+                out[lo:hi] = np.nan
     return out
 
 
@@ -53,6 +109,11 @@ def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None
         sizes = np.diff(np.asarray(offs))
         tols[sizes < TINY_LAYER] = max(tol, TOL_BF16_TINY if out.dtype == torch.bfloat16 else TOL_F16_TINY)
     got = to_f64(out)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    skip = np.isnan(ref)            # layers without a reference value (see mark_ill_posed)
+    if skip.any():
+        ref = np.where(skip, 0.0, ref)
+        got = np.where(skip, 0.0, got)
     if layers is None:
         err = O.rel_l2_per_layer(got, ref, offs)
     else:
@@ -61,7 +122,6 @@ def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None
             lo, hi = offs[l], offs[l + 1]
             err[l] = O.rel_l2_per_layer(got[lo:hi], ref[lo:hi], [0, hi - lo])[0]
     worst = int(np.argmax(err / tols))
-    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
     assert err[worst] <= tols[worst], (f"{what}: layer {worst} (size {offs[worst + 1] - offs[worst]}) "
                                        f"rel-L2 {err[worst]:.3e} > {tols[worst]:.1e}")
     return err
@@ -82,6 +142,8 @@ def assert_bf16_rounding(out_bf16: torch.Tensor, ref: np.ndarray, layer_offsets,
         if hi == lo:
             continue
         r = ref[lo:hi]
+        if np.isnan(r).all():
+            continue                # no reference value (see mark_ill_posed)
         bound = half_ulp * np.abs(r) + 2e-6 * np.abs(r).max() + quantum
         bad = np.abs(got[lo:hi] - r) > bound
         assert not bad.any(), (f"layer {l}: {int(bad.sum())} elements off by more than one rounding, "

@@ -60,8 +60,6 @@ def test_reduce_rejects_bad_arguments(lib):
     assert _call_reduce(lib, good, 4, [1, 10, 30], B.F32, 0x9000) == B.ERR_INVALID_ARG
     assert _call_reduce(lib, good, 4, [0, 30, 10], B.F32, 0x9000) == B.ERR_INVALID_ARG
     assert _call_reduce(lib, good, 4, offs, 7, 0x9000) == B.ERR_UNSUPPORTED
-    # Algorithm 1 requires a power-of-two number of workers
-    assert _call_reduce(lib, good[:3], 3, offs, B.F32, 0x9000) == B.ERR_UNSUPPORTED
     assert _call_reduce(lib, [0x1000, 0x2004, 0x3000, 0x4000], 4, offs, B.F32, 0x9000) == B.ERR_MISALIGNED
     assert _call_reduce(lib, good, 4, offs, B.F32, 0x9008) == B.ERR_MISALIGNED
     assert _call_reduce(lib, [0x1000, 0, 0x3000, 0x4000], 4, offs, B.F32, 0x9000) == B.ERR_INVALID_ARG
@@ -142,5 +140,8 @@ def test_workspace_bytes(lib):
     assert n4 < (1 << 20)
     n = C.c_size_t(0)
     o = (C.c_int64 * 4)(*offs)
-    assert lib.adasum_workspace_bytes(3, o, 3, B.F32, None, C.byref(n)) == B.ERR_UNSUPPORTED
+    # K = 3: two first-pass groups (1 and 2 workers) leave two fp32 nodes for the root pass
+    assert lib.adasum_workspace_bytes(3, o, 3, B.F32, None, C.byref(n)) == B.OK
+    assert n.value > 0
+    assert B.adasum_workspace_bytes(3, offs, B.F32, radix=2) >= 2 * 70656 * 4
     assert lib.adasum_workspace_bytes(4, o, 3, B.F32, None, None) == B.ERR_INVALID_ARG

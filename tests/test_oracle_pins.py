@@ -253,6 +253,23 @@ def pin_low_precision_inputs_are_widened(O):
     assert d == float(n) and n1 == float(n) and n2 == float(n)
 
 
+def pin_worker_counts_that_are_no_power_of_two(O):
+    # Section 3.4, second recursion, read literally: g_[0,n] -> g_[0,n/2) and g_[n/2,n], so of K = n + 1
+    # gradients the left part takes floor(K/2).  Written out by hand for K = 3, 5, 6, 7.
+    rng = _rng(13)
+    g = [rng.standard_normal(6) for _ in range(7)]
+    P = O.adasum_pair
+    np.testing.assert_allclose(O.adasum_tree(g[:3]), P(g[0], P(g[1], g[2])), rtol=1e-14)
+    np.testing.assert_allclose(O.adasum_tree(g[:5]), P(P(g[0], g[1]), P(g[2], P(g[3], g[4]))), rtol=1e-14)
+    np.testing.assert_allclose(O.adasum_tree(g[:6]), P(P(g[0], P(g[1], g[2])), P(g[3], P(g[4], g[5]))), rtol=1e-14)
+    np.testing.assert_allclose(O.adasum_tree(g[:7]),
+                               P(P(g[0], P(g[1], g[2])), P(P(g[3], g[4]), P(g[5], g[6]))), rtol=1e-14)
+    # properties that hold for any K: K copies give the copy, orthogonal inputs give the sum
+    np.testing.assert_allclose(O.adasum_tree([g[0]] * 5), g[0], rtol=1e-14)
+    e = np.eye(7)
+    np.testing.assert_array_equal(O.adasum_tree(list(e)), np.ones(7))
+
+
 def pin_after_optimizer(O):
     # Section 4.1.  Hand-worked, K = 2, one layer: start (1,1); worker steps to (2,1) and (2,2), so the
     # effective gradients are (1,0) and (1,1): d = 1, n1 = 1, n2 = 2, coefficients 1/2 and 3/4, combined
@@ -297,6 +314,7 @@ PINS = [
     pin_linear_order,
     pin_low_precision_inputs_are_widened,
     pin_after_optimizer,
+    pin_worker_counts_that_are_no_power_of_two,
 ]
 
 
@@ -352,6 +370,15 @@ def _mut_uneven_split(m):
         if len(gs) == 1:
             return np.asarray(gs[0], dtype=np.float64).copy()
         mid = 1 if len(gs) > 2 else len(gs) // 2
+        return m.adasum_pair(tree(gs[:mid]), tree(gs[mid:]))
+    m.adasum_tree = tree
+
+
+def _mut_left_takes_the_larger_part(m):
+    def tree(gs):
+        if len(gs) == 1:
+            return np.asarray(gs[0], dtype=np.float64).copy()
+        mid = (len(gs) + 1) // 2
         return m.adasum_pair(tree(gs[:mid]), tree(gs[mid:]))
     m.adasum_tree = tree
 
@@ -413,7 +440,8 @@ def _mut_operator_on_parameters(m):
 MUTANTS = [_mut_drop_two, _mut_swap_norms, _mut_plus_sign, _mut_norm_not_squared,
            _mut_tree_is_fold, _mut_uneven_split, _mut_whole_buffer,
            _mut_no_zero_guard, _mut_fp32_accumulate, _mut_linear_is_tree,
-           _mut_delta_sign, _mut_delta_not_added_back, _mut_operator_on_parameters]
+           _mut_delta_sign, _mut_delta_not_added_back, _mut_operator_on_parameters,
+           _mut_left_takes_the_larger_part]
 
 
 @pytest.mark.parametrize("mutate", MUTANTS, ids=lambda f: f.__name__)

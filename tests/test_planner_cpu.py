@@ -74,13 +74,49 @@ def test_levels():
     for K in (2, 4, 8, 16, 32, 64, 128, 256):
         for r in (2, 4, 8, 16):
             assert int(np.prod(B.plan_levels(K, r))) == K
-    with pytest.raises(B.AdasumError) as e:
-        B.plan_levels(12)
-    assert e.value.code == B.ERR_UNSUPPORTED
+    # any K: the first pass takes the sub-trees of the shallowest depth that fit the radix
+    assert B.plan_levels(12) == [16]
+    assert B.plan_levels(12, 8) == [8, 2]
+    assert B.plan_levels(3, 2) == [2, 2]
+    assert B.plan_levels(5, 2) == [2, 2, 2]
+    assert B.plan_levels(6, 4) == [4, 2]
+    assert B.plan_levels(33) == [16, 4]
+    assert B.plan_levels(100, 8) == [8, 8, 2]
     with pytest.raises(B.AdasumError):
         B.plan_levels(8, 3)
     with pytest.raises(B.AdasumError):
         B.plan_levels(0)
+
+
+def halving_tree(lo, hi, depth):
+    """Nodes of the given depth of the Section 3.4 recursion, the left part taking
+    floor(count / 2) workers: written as the recursion itself."""
+    if depth == 0:
+        return [(lo, hi)]
+    mid = lo + (hi - lo) // 2
+    return halving_tree(lo, mid, depth - 1) + halving_tree(mid, hi, depth - 1)
+
+
+def test_first_pass_groups_are_sub_trees():
+    for K in list(range(1, 70)) + [100, 127, 128, 129, 1000]:
+        for radix in (2, 4, 8, 16):
+            levels = B.plan_levels(K, radix)
+            bounds = B.plan_groups(K, radix)
+            G = len(bounds) - 1
+            if K == 1:
+                assert levels == [] and bounds == [0, 1]
+                continue
+            assert G * levels[0] == int(np.prod(levels))
+            depth = int(np.log2(G))
+            assert (1 << depth) == G
+            want = halving_tree(0, K, depth)
+            assert [(a, b) for a, b in zip(bounds[:-1], bounds[1:])] == want
+            sizes = np.diff(bounds)
+            assert sizes.min() >= 1 and sizes.max() <= levels[0] <= radix
+            assert sizes.max() > levels[0] // 2 or levels[0] == 2, (K, radix, sizes, levels)
+            # one level shallower would not fit the radix
+            if depth > 0:
+                assert max(b - a for a, b in halving_tree(0, K, depth - 1)) > radix
 
 
 def test_linear_passes_cover_all_workers():
@@ -88,7 +124,9 @@ def test_linear_passes_cover_all_workers():
     lib = B.load()
     # the schedule is visible through the workspace size only; check the arithmetic of the pass list here
     def passes(K, radix):
-        first = min(K, radix)
+        first = radix
+        while first > K:
+            first //= 2
         out, rest = [first], K - first
         while rest > 0:
             r = radix
@@ -98,7 +136,7 @@ def test_linear_passes_cover_all_workers():
             rest -= r - 1
         return out
     assert passes(64, 16) == [16, 16, 16, 16, 4]
-    for K in (2, 4, 8, 16, 32, 64, 128):
+    for K in (2, 3, 4, 5, 7, 8, 16, 21, 32, 64, 100, 128):
         for r in (2, 4, 8, 16):
             p = passes(K, r)
             assert p[0] + sum(x - 1 for x in p[1:]) == K
