@@ -44,6 +44,8 @@ def parse_args():
                    choices=["config1", "config2", "config3", "config4", "config4_small", "copy"])
     p.add_argument("--radix", type=int, default=0, help="0 = library default")
     p.add_argument("--out-dtype", default="same", choices=["same", "f32", "bf16"])
+    p.add_argument("--storage", default="same", choices=["same", "f16", "f64"],
+                   help="convert the generated gradients to this storage type before timing")
     p.add_argument("--graph", action="store_true", help="replay the level ladder as one hipGraph launch")
     p.add_argument("--delta", action="store_true",
                    help="time the Adasum-after-optimizer form: the K buffers are parameters after a local step, "
@@ -144,6 +146,12 @@ def main():
     print(f"[bench] {w.name}: K={w.K} N={w.N} layers={w.n_layers} dtype={w.dtype} "
           f"input={w.input_bytes / 1e9:.2f} GB generated in {time.perf_counter() - t0:.1f} s",
           file=sys.stderr, flush=True)
+    if args.storage != "same":
+        to = {"f16": torch.float16, "f64": torch.float64}[args.storage]
+        for i in range(w.K):
+            w.grads[i] = w.grads[i].to(to)
+        w.dtype = to
+        torch.cuda.synchronize()
     out_dtype = {"same": w.dtype, "f32": torch.float32, "bf16": torch.bfloat16}[args.out_dtype]
     out = torch.empty(w.N, dtype=out_dtype, device=dev)
 
@@ -171,7 +179,8 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     value = w.input_bytes / (dt / args.steps) / 1e9
-    levels = B.plan_levels(w.K, args.radix if (args.radix or not args.delta) else 8)
+    eight = args.delta or w.dtype == torch.float64     # these default to radix 8
+    levels = B.plan_levels(w.K, args.radix if (args.radix or not eight) else 8)
 
     roofline = None
     if prof:

@@ -44,6 +44,8 @@ extern "C" {
 #define ADASUM_BF16 1   /* bfloat16; stores round to nearest even */
 #define ADASUM_F16  2   /* IEEE binary16; stores round to nearest even (no loss scaling here:
                            values must fit the format, as Section 4.4.1's dynamic scaling ensures) */
+#define ADASUM_F64  3   /* IEEE binary64: reduced in fp64 throughout (lanes, tree nodes, output);
+                           only to an fp64 result, radix at most 8 (default 8) */
 
 /* error codes */
 #define ADASUM_OK                 0
@@ -112,7 +114,7 @@ typedef struct adasum_options {
  *   layer_offsets  HOST, n_layers + 1 entries in element units, [0] = 0,
  *                  non-decreasing; layer l is [layer_offsets[l], layer_offsets[l+1]);
  *                  empty layers are allowed; N = 0 is a no-op
- *   dtype          ADASUM_F32 | ADASUM_BF16 | ADASUM_F16: storage type of grads AND of out
+ *   dtype          ADASUM_F32 | ADASUM_BF16 | ADASUM_F16 | ADASUM_F64: storage type of grads AND of out
  *   out            DEVICE, N elements of `dtype`; must not overlap any input
  *   stream         hipStream_t
  *

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 # ADASUM_LIB overrides the library file (e.g. a build with other tuning knobs)
 LIB_PATH = os.environ.get("ADASUM_LIB") or os.path.join(HERE, "libadasum.so")
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, F64 = 0, 1, 2, 3
 ORDER_TREE, ORDER_LINEAR = 0, 1
 
 OK = 0
@@ -134,17 +134,19 @@ def _dtype_code(t) -> int:
         return BF16
     if t.dtype == torch.float16:
         return F16
+    if t.dtype == torch.float64:
+        return F64
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
 def _code_of(torch_dtype) -> int:
     import torch
-    return {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}[torch_dtype]
+    return {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16, torch.float64: F64}[torch_dtype]
 
 
 def _torch_dtype(code: int):
     import torch
-    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[code]
+    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16, F64: torch.float64}[code]
 
 
 def _stream(stream) -> C.c_void_p:

@@ -47,6 +47,7 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 }
 
 struct Opts {
+    int dtype;       // storage type of the inputs
     int out_dtype;
     int radix;
     int order;
@@ -61,6 +62,7 @@ struct Opts {
 constexpr uint32_t kOptionsBytesV1 = offsetof(adasum_options, delta_start);
 
 int read_opts(const adasum_options* o, int dtype, Opts& r) {
+    r.dtype = dtype;
     r.out_dtype = dtype;
     r.radix = 0;
     r.order = ADASUM_ORDER_TREE;
@@ -82,6 +84,7 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     }
     if (!dtype_pair_ok(dtype, r.out_dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
+    if (r.radix > max_radix(dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if (r.order == ADASUM_ORDER_LINEAR && r.layer_stats != nullptr) return ADASUM_ERR_UNSUPPORTED;
     if (r.delta_start != nullptr) {
@@ -97,7 +100,10 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
 
 // The delta form's Gram pass subtracts before it multiplies and so cannot use the packed
 // dot instructions; with 16 operands it runs out of registers, 8 is its fastest radix.
-int default_radix(const Opts& o) { return o.delta_start != nullptr ? 8 : kDefaultRadix; }
+// fp64 accumulators are twice as wide: 8 as well.
+int default_radix(const Opts& o) {
+    return (o.delta_start != nullptr || o.dtype == ADASUM_F64) ? 8 : kDefaultRadix;
+}
 
 // ---- plans -------------------------------------------------------------------
 
@@ -158,6 +164,7 @@ struct Plan {
     int K = 0;
     int radix = 0;
     int order = ADASUM_ORDER_TREE;
+    int node_type = ADASUM_F32;           // storage type of the intermediate nodes
     std::vector<int64_t> offsets;
     TileTable gram_tiles;                 // capacity kTile
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
@@ -216,11 +223,11 @@ struct Plan {
 std::mutex g_mutex;
 std::vector<std::unique_ptr<Plan>> g_plans;
 
-int find_or_make_plan(int K, int radix, int order, const int64_t* offsets, int n_layers, Plan** out) {
+int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers, Plan** out) {
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
     for (auto& p : g_plans) {
-        if (p->device == device && p->K == K && p->radix == radix && p->order == order &&
+        if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
             static_cast<int>(p->offsets.size()) == n_layers + 1 &&
             std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
             *out = p.get();
@@ -234,6 +241,7 @@ int find_or_make_plan(int K, int radix, int order, const int64_t* offsets, int n
         p->K = K;
         p->radix = radix;
         p->order = order;
+        p->node_type = node_type;
         p->offsets.assign(offsets, offsets + n_layers + 1);
         build_tiles(offsets, n_layers, kTile, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
         int rc = order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, radix, p->radices)
@@ -243,8 +251,8 @@ int find_or_make_plan(int K, int radix, int order, const int64_t* offsets, int n
         const int Kv = order == ADASUM_ORDER_LINEAR ? K : virtual_leaves(p->radices);
         const int64_t small_elems = K > 1 ? find_small_layers(offsets, n_layers, p->small) : 0;
         p->lay = make_layout(Kv, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
-                             norm_entries_bound(Kv, offsets, n_layers, p->radices), p->radices, order, K + 1,
-                             small_elems);
+                             norm_entries_bound(Kv, offsets, n_layers, p->radices, node_type), p->radices, order,
+                             K + 1, small_elems, node_type);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
@@ -388,7 +396,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
     double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
     double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
-    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
+    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * lay.node_bytes;
     char namebuf[48];
 
     int nodes = virtual_leaves(p->radices);   // tree nodes alive before this pass (leaves: padded count)
@@ -400,7 +408,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     // nothing below may allocate, so the ladder can be captured into a graph.
     std::vector<TileSet> comb_sets(n_levels);
     for (int lv = 0; lv < n_levels; ++lv) {
-        const int rc = p->comb_tiles(lv == 0 ? dtype : ADASUM_F32, p->radices[lv], &comb_sets[lv]);
+        const int rc = p->comb_tiles(lv == 0 ? dtype : node_dtype(dtype), p->radices[lv], &comb_sets[lv]);
         if (rc != ADASUM_OK) return rc;
     }
     {
@@ -411,8 +419,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         const int R = p->radices[lv];
         const int groups = nodes / R;
         const bool first = lv == 0, last = lv == n_levels - 1;
-        const int in_dtype = first ? dtype : ADASUM_F32;
-        const int st_dtype = last ? o.out_dtype : ADASUM_F32;
+        const int in_dtype = first ? dtype : node_dtype(dtype);
+        const int st_dtype = last ? o.out_dtype : node_dtype(dtype);
         const int np = gram_entries(R, first);
         const bool want_norm = !last || o.layer_stats != nullptr;
         const TileSet ct = comb_sets[lv];
@@ -525,17 +533,17 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
     double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
     double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
     double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
-    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * 4;
+    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * lay.node_bytes;
     const int n_passes = static_cast<int>(p->radices.size());
 
     // every table first: nothing below may allocate
     TileSet widen_tiles;
     std::vector<TileSet> comb_sets(n_passes);
     for (int b = 0; b < n_passes; ++b) {
-        const int rc = p->comb_tiles(b == 0 ? dtype : ADASUM_F32, p->radices[b], &comb_sets[b]);
+        const int rc = p->comb_tiles(b == 0 ? dtype : node_dtype(dtype), p->radices[b], &comb_sets[b]);
         if (rc != ADASUM_OK) return rc;
     }
-    if (dtype != ADASUM_F32 && n_passes > 1) {
+    if (dtype != node_dtype(dtype) && n_passes > 1) {
         const int rc = p->comb_tiles(dtype, 1, &widen_tiles);
         if (rc != ADASUM_OK) return rc;
     }
@@ -548,8 +556,8 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
     for (int b = 0; b < n_passes; ++b) {
         const int R = p->radices[b];
         const bool first = b == 0, last = b == n_passes - 1;
-        const int in_dtype = first ? dtype : ADASUM_F32;
-        const int st_dtype = last ? o.out_dtype : ADASUM_F32;
+        const int in_dtype = first ? dtype : node_dtype(dtype);
+        const int st_dtype = last ? o.out_dtype : node_dtype(dtype);
         Operands ops;
         std::memset(&ops, 0, sizeof(ops));
         if (first) {
@@ -559,7 +567,7 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
             ops.pack[0] = slots;
             for (int r = 1; r < R; ++r) {
                 const void* leaf = grads[next_leaf + r - 1];
-                if (dtype != ADASUM_F32) {
+                if (dtype != node_dtype(dtype)) {
                     char* wide = slots + static_cast<long long>(r) * slot_bytes;
                     Operands one;
                     std::memset(&one, 0, sizeof(one));
@@ -658,10 +666,10 @@ int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void
     } else {
         for (size_t lv = 0; lv < p->radices.size(); ++lv) {
             TileSet ct;
-            const int rc = p->comb_tiles(lv == 0 ? dtype : ADASUM_F32, p->radices[lv], &ct);
+            const int rc = p->comb_tiles(lv == 0 ? dtype : node_dtype(dtype), p->radices[lv], &ct);
             if (rc != ADASUM_OK) return rc;
         }
-        if (o.order == ADASUM_ORDER_LINEAR && dtype != ADASUM_F32) {
+        if (o.order == ADASUM_ORDER_LINEAR && dtype != node_dtype(dtype)) {
             TileSet ct;
             const int rc = p->comb_tiles(dtype, 1, &ct);
             if (rc != ADASUM_OK) return rc;
@@ -729,7 +737,8 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, node_dtype(dtype), layer_offsets,
+                           n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);
@@ -777,8 +786,8 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
         const int64_t small_elems = K > 1 ? find_small_layers(layer_offsets, n_layers, small) : 0;
         const Layout lay = make_layout(Kv, layer_offsets[n_layers], n_layers,
                                        count_tiles(layer_offsets, n_layers, kTile),
-                                       norm_entries_bound(Kv, layer_offsets, n_layers, radices), radices, o.order,
-                                       K + 1, small_elems);
+                                       norm_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype)),
+                                       radices, o.order, K + 1, small_elems, node_dtype(dtype));
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -790,7 +799,7 @@ static int step_common(const void* const* x, int R, const int64_t* layer_offsets
     if (R != 2 && R != 4 && R != 8 && R != 16) return ADASUM_ERR_UNSUPPORTED;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
-    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
+    if (!known_dtype(dtype) || R > max_radix(dtype)) return ADASUM_ERR_UNSUPPORTED;
     return check_operands(x, R, layer_offsets[n_layers], dtype);
 }
 
@@ -803,7 +812,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     if (n_layers == 0) return ADASUM_OK;
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, node_dtype(dtype), layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;
@@ -850,7 +859,7 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     }
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, node_dtype(dtype), layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;

@@ -28,7 +28,8 @@ constexpr int kThreads = ADASUM_THREADS;
 // streams best when it moves 16-20 KB in all, so wider groups get fewer lanes.
 constexpr int combine_threads(int R) { return R >= 16 ? 64 : (R >= 8 ? 128 : 256); }
 // Tile capacity of the combine pass: depends on the input type and the radix.
-inline int combine_tile_capacity(int dtype, int R) { return combine_threads(R) * (dtype == ADASUM_F32 ? 4 : 8); }
+inline int elem_bytes(int dtype) { return dtype == ADASUM_F64 ? 8 : dtype == ADASUM_F32 ? 4 : 2; }
+inline int combine_tile_capacity(int dtype, int R) { return combine_threads(R) * (16 / elem_bytes(dtype)); }
 
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
@@ -36,10 +37,17 @@ constexpr int kMaxRadix = 16;
 // Radix used when the caller asks for 0: the widest pass moves the fewest bytes.
 constexpr int kDefaultRadix = 16;
 
-inline int elem_bytes(int dtype) { return dtype == ADASUM_F32 ? 4 : 2; }
-inline bool known_dtype(int dtype) { return dtype == ADASUM_F32 || dtype == ADASUM_BF16 || dtype == ADASUM_F16; }
+inline bool known_dtype(int dtype) { return dtype == ADASUM_F32 || dtype == ADASUM_BF16 || dtype == ADASUM_F16 || dtype == ADASUM_F64; }
+// Storage type of the intermediate tree nodes for an input type.
+inline int node_dtype(int dtype) { return dtype == ADASUM_F64 ? ADASUM_F64 : ADASUM_F32; }
+// Widest radix a storage type is instantiated for.
+inline int max_radix(int dtype) { return dtype == ADASUM_F64 ? 8 : 16; }
 // Output storage types a combine supports for an input type: the same type or fp32; any type from fp32.
-inline bool dtype_pair_ok(int in, int out) { return known_dtype(in) && known_dtype(out) && (in == out || in == ADASUM_F32 || out == ADASUM_F32); }
+inline bool dtype_pair_ok(int in, int out) {
+    if (!known_dtype(in) || !known_dtype(out)) return false;
+    if (in == ADASUM_F64 || out == ADASUM_F64) return in == out;
+    return in == out || in == ADASUM_F32 || out == ADASUM_F32;
+}
 inline bool is_pow2(long long v) { return v > 0 && (v & (v - 1)) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -121,12 +129,13 @@ int64_t find_small_layers(const int64_t* layer_offsets, int n_layers, std::vecto
 // Device workspace layout (byte offsets from a 256-byte aligned base).
 struct Layout {
     int64_t N = 0;            // elements per gradient
-    int64_t slot_elems = 0;   // N rounded up so that fp32 slots stay 256-byte aligned
-    int64_t n_slots = 0;      // fp32 intermediate tree nodes after the first pass
+    int64_t slot_elems = 0;   // N rounded up so that slots stay 256-byte aligned
+    int64_t n_slots = 0;      // intermediate tree nodes after the first pass
+    int     node_bytes = 4;   // element size of a node: 4 (fp32), 8 for fp64 inputs
     int64_t n_tiles = 0;      // Gram tiles
     int64_t norm_entries = 0; // doubles reserved for the combines' squared norms
     int     n_layers = 0;
-    size_t  off_slots = 0;    // n_slots x slot_elems floats
+    size_t  off_slots = 0;    // n_slots x slot_elems x node_bytes
     size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
     size_t  off_normparts = 0;// doubles [node][combine tile]: squared norm of every node a combine wrote
     size_t  off_normcoarse = 0;// doubles [node][Gram tile]: the same, summed per Gram tile
@@ -144,11 +153,12 @@ struct Layout {
 // reserved for the compact copy of the small layers.
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices, int order = ADASUM_ORDER_TREE, int64_t small_rows = 0,
-                   int64_t small_elems = 0);
+                   int64_t small_elems = 0, int node_type = ADASUM_F32);
 // Number of tiles build_tiles would produce.
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity);
 // Upper bound (over input dtypes) of make_layout's norm_entries for a schedule.
-int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices);
+int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
+                           int node_type = ADASUM_F32);
 
 // ---- kernel launchers (adasum_kernels.hip) -----------------------------------
 

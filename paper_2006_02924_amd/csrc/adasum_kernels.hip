@@ -55,10 +55,16 @@ struct bf16_t { unsigned short v; };
 struct f16_t { unsigned short v; };   // IEEE binary16
 typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 
+// VEC: elements per 16-byte granule; acc_t: the type lanes compute in (fp64 storage is
+// reduced in fp64 throughout, everything else in fp32 lanes with fp64 above the wave)
 template <typename T> struct Traits;
-template <> struct Traits<float>  { static constexpr int VEC = 4; };
-template <> struct Traits<bf16_t> { static constexpr int VEC = 8; };
-template <> struct Traits<f16_t>  { static constexpr int VEC = 8; };
+template <> struct Traits<float>  { static constexpr int VEC = 4; typedef float acc_t; };
+template <> struct Traits<bf16_t> { static constexpr int VEC = 8; typedef float acc_t; };
+template <> struct Traits<f16_t>  { static constexpr int VEC = 8; typedef float acc_t; };
+template <> struct Traits<double> { static constexpr int VEC = 2; typedef double acc_t; };
+
+__device__ __forceinline__ float fma_t(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_t(double a, double b, double c) { return __builtin_fma(a, b, c); }
 
 // round to nearest even; NaN stays NaN (quiet), overflow rounds to infinity
 __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
@@ -139,6 +145,14 @@ __device__ __forceinline__ void unpack(const Granule<f16_t, G>& r, float (&v)[G]
     }
 }
 
+template <int G>
+__device__ __forceinline__ void unpack(const Granule<double, G>& r, double (&v)[G]) {
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+        v[i] = __longlong_as_double((static_cast<long long>(r.w[2 * i + 1]) << 32) |
+                                    static_cast<long long>(r.w[2 * i]));
+}
+
 // fp32 -> binary16, round to nearest even (the conversion instruction's default mode)
 __device__ __forceinline__ unsigned int f32_to_f16_bits(float f) {
     const _Float16 h = static_cast<_Float16>(f);
@@ -189,6 +203,20 @@ __device__ __forceinline__ void store_granule(f16_t* p, const float (&v)[G]) {
     store_words<NT>(p, w);
 }
 
+template <bool NT, int G>
+__device__ __forceinline__ void store_granule(double* p, const double (&v)[G]) {
+    unsigned int w[2 * G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        const long long b = __double_as_longlong(v[i]);
+        w[2 * i] = static_cast<unsigned int>(b);
+        w[2 * i + 1] = static_cast<unsigned int>(b >> 32);
+    }
+    store_words<NT>(p, w);
+}
+
+__device__ __forceinline__ double load_elem(const double* p) { return *p; }
+__device__ __forceinline__ void store_elem(double* p, double v) { *p = v; }
 __device__ __forceinline__ float load_elem(const float* p) { return *p; }
 __device__ __forceinline__ float load_elem(const f16_t* p) {
     return static_cast<float>(__builtin_bit_cast(_Float16, p->v));
@@ -256,6 +284,7 @@ __global__ void __launch_bounds__(kThreads)
 gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_tiles,
             double* __restrict__ partials, const T* __restrict__ start) {
     constexpr int G = Traits<T>::VEC;
+    typedef typename Traits<T>::acc_t acc_t;
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
     constexpr int ITERS = kTile / G / kThreads;
     constexpr int U0 = (R >= ADASUM_INFLIGHT) ? 1 : (ADASUM_INFLIGHT / R);   // granule-steps loaded ahead
@@ -272,9 +301,9 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
 #pragma unroll
     for (int r = 0; r < R; ++r) x[r] = static_cast<const T*>(operand_ptr<R>(ops, g, r));
 
-    float acc[NP];
+    acc_t acc[NP];
 #pragma unroll
-    for (int e = 0; e < NP; ++e) acc[e] = 0.f;
+    for (int e = 0; e < NP; ++e) acc[e] = 0;
 
     auto consume = [&](const Granule<T, G> (&raw)[R], long long idx) {
         (void)idx;
@@ -301,13 +330,13 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
                 }
             }
         } else {
-            float v[R][G];
+            acc_t v[R][G];
 #pragma unroll
             for (int r = 0; r < R; ++r) unpack(raw[r], v[r]);
             if constexpr (DELTA) {
                 Granule<T, G> sraw;
                 load_raw(sraw, start + idx);
-                float sv[G];
+                acc_t sv[G];
                 unpack(sraw, sv);
 #pragma unroll
                 for (int r = 0; r < R; ++r)
@@ -320,7 +349,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
 #pragma unroll
                 for (int j = (DIAG ? i : i + 1); j < R; ++j) {
 #pragma unroll
-                    for (int k = 0; k < G; ++k) acc[e] = __builtin_fmaf(v[i][k], v[j][k], acc[e]);
+                    for (int k = 0; k < G; ++k) acc[e] = fma_t(v[i][k], v[j][k], acc[e]);
                     ++e;
                 }
             }
@@ -384,7 +413,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     }
 #pragma unroll
     for (int e = 0; e < NP; ++e) {
-        const float w = wave_sum(acc[e]);
+        const acc_t w = wave_sum(acc[e]);
         if (lane == 0) sh[wave][e] = static_cast<double>(w);
     }
     __syncthreads();
@@ -527,6 +556,10 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, in
     for (int p = 0; p < R; ++p) w[p] = p < r ? 1.0 : 0.0;
     if (order == ADASUM_ORDER_LINEAR) {
         for (int k = 1; k < r; ++k) merge_nodes<R>(G, w, 0, k, k, k + 1);
+    } else if (r == R) {
+        // the balanced tree over all R leaves, level by level
+        for (int span = 1; span < R; span *= 2)
+            for (int j = 0; j < R; j += 2 * span) merge_nodes<R>(G, w, j, j + span, j + span, j + 2 * span);
     } else {
         // the halving tree over r leaves, deepest nodes first: children before parents
         int levels = 0;
@@ -560,6 +593,8 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
                double* __restrict__ normparts, const TI* __restrict__ sub_in, const TO* add_out) {
     constexpr int G = 16 / (int)sizeof(TI);   // tile capacity is THREADS * G
     constexpr int THREADS = combine_threads(R);
+    typedef typename Traits<TI>::acc_t acc_t;     // fp64 storage is combined in fp64
+    typedef typename Traits<TO>::acc_t out_acc_t; // what the stored value is rounded from
     // Non-temporal stores pay off except where the output is half of the traffic
     // and every lane issues two of them (bf16 pair -> fp32): measured, 13.4 vs 16.4 ms.
     constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);
@@ -586,44 +621,44 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     // fp64 weights as computed; the streaming body uses them rounded to fp32
     // (fetched after the operand loads are in flight)
     double wd[R];
-    float w[R];
+    acc_t w[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         wd[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0;
-        w[r] = static_cast<float>(wd[r]);
+        w[r] = static_cast<acc_t>(wd[r]);
     }
 
     // Section 4.1's delta form: with SUB the operands are x_r - sub_in (the parameters
     // before the local step); with add_out the stored result is add_out + z.  The
     // squared norm is that of z either way.
-    float nacc = 0.f;
+    acc_t nacc = 0;
     if (tid < s.ng) {
-        float sv[G];
+        acc_t sv[G];
         if constexpr (SUB) {
             Granule<TI, G> sraw;
             load_raw(sraw, sub_in + idx);
             unpack(sraw, sv);
         }
-        float z[G];
+        acc_t z[G];
         {
-            float v[G];
+            acc_t v[G];
             unpack(raw[0], v);
 #pragma unroll
             for (int k = 0; k < G; ++k) z[k] = w[0] * (SUB ? v[k] - sv[k] : v[k]);
         }
 #pragma unroll
         for (int r = 1; r < R; ++r) {
-            float v[G];
+            acc_t v[G];
             unpack(raw[r], v);
 #pragma unroll
-            for (int k = 0; k < G; ++k) z[k] = __builtin_fmaf(w[r], SUB ? v[k] - sv[k] : v[k], z[k]);
+            for (int k = 0; k < G; ++k) z[k] = fma_t(w[r], SUB ? v[k] - sv[k] : v[k], z[k]);
         }
 #pragma unroll
-        for (int k = 0; k < G; ++k) nacc = __builtin_fmaf(z[k], z[k], nacc);
+        for (int k = 0; k < G; ++k) nacc = fma_t(z[k], z[k], nacc);
         if (add_out != nullptr) {
             Granule<TO, G> araw;
             load_raw(araw, add_out + idx);
-            float av[G];
+            acc_t av[G];
             unpack(araw, av);
 #pragma unroll
             for (int k = 0; k < G; ++k) z[k] += av[k];
@@ -643,17 +678,17 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 #pragma unroll
             for (int r = 1; r < R; ++r)
                 z = __builtin_fma(wd[r], static_cast<double>(load_elem(x[r] + idx)) - sd, z);
-            const float zf = static_cast<float>(z);
-            enorm = static_cast<double>(zf) * static_cast<double>(zf);
+            const out_acc_t zs = static_cast<out_acc_t>(z);
+            enorm = static_cast<double>(zs) * static_cast<double>(zs);
             if (add_out != nullptr) z += static_cast<double>(load_elem(add_out + idx));
-            store_elem(out + idx, static_cast<float>(z));
+            store_elem(out + idx, static_cast<out_acc_t>(z));
         }
         if (normparts != nullptr) enorm = wave_sum(enorm);
     }
 
     if (normparts != nullptr) {
         __shared__ double sh[THREADS / 64];
-        const float ws = wave_sum(nacc);
+        const acc_t ws = wave_sum(nacc);
         if (lane == 0) sh[wave] = static_cast<double>(ws);
         __syncthreads();
         if (tid == 0) {
@@ -763,7 +798,7 @@ small_reduce_kernel(const double* __restrict__ compact, int K, const SmallLayer*
     if (live) {
         double z = r;
         if (add_start) z += compact[static_cast<long long>(start_row) * small_elems + s.coff + lane];
-        store_elem(out + s.start + lane, static_cast<float>(z));
+        store_elem(out + s.start + lane, static_cast<typename Traits<TO>::acc_t>(z));
     }
 }
 
@@ -825,7 +860,11 @@ int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, d
         case 2: ADASUM_GRAM(2); break;
         case 4: ADASUM_GRAM(4); break;
         case 8: ADASUM_GRAM(8); break;
-        case 16: ADASUM_GRAM(16); break;
+        case 16:
+            // 136 fp64 accumulators per lane do not fit the register file
+            if constexpr (std::is_same<T, double>::value) return static_cast<int>(hipErrorInvalidValue);
+            else ADASUM_GRAM(16);
+            break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 #undef ADASUM_GRAM
@@ -873,7 +912,10 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct
         case 2: ADASUM_COMBINE(2); break;
         case 4: ADASUM_COMBINE(4); break;
         case 8: ADASUM_COMBINE(8); break;
-        case 16: ADASUM_COMBINE(16); break;
+        case 16:
+            if constexpr (std::is_same<TI, double>::value) return static_cast<int>(hipErrorInvalidValue);
+            else ADASUM_COMBINE(16);
+            break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
 #undef ADASUM_COMBINE_AS
@@ -889,6 +931,7 @@ int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, in
     if (gt.n_tiles == 0 || n_groups == 0) return 0;
     if (dtype == ADASUM_BF16) return launch_gram_t<bf16_t>(diag, ops, gt, n_groups, R, partials, delta_start, st);
     if (dtype == ADASUM_F16) return launch_gram_t<f16_t>(diag, ops, gt, n_groups, R, partials, delta_start, st);
+    if (dtype == ADASUM_F64) return launch_gram_t<double>(diag, ops, gt, n_groups, R, partials, delta_start, st);
     return launch_gram_t<float>(diag, ops, gt, n_groups, R, partials, delta_start, st);
 }
 
@@ -949,7 +992,11 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
                    const void* sub_in, const void* add_out, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ct.n_tiles == 0 || n_groups == 0) return 0;
-    // supported pairs: T -> fp32, fp32 -> T, T -> T
+    // supported pairs: T -> fp32, fp32 -> T, T -> T; fp64 only with itself
+    if (dtype == ADASUM_F64 || out_dtype == ADASUM_F64) {
+        if (dtype != out_dtype) return static_cast<int>(hipErrorInvalidValue);
+        return launch_combine_r<double, double>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
+    }
     if (dtype == ADASUM_BF16) {
         if (out_dtype == ADASUM_BF16)
             return launch_combine_r<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, sub_in, add_out, st);
@@ -1003,6 +1050,7 @@ int launch_small_gather(int dtype, const Operands& ops, int n_leaves, int leaf0,
                        static_cast<const T*>(delta_start), stash, start_row, compact)
     if (dtype == ADASUM_BF16) ADASUM_GATHER(bf16_t);
     else if (dtype == ADASUM_F16) ADASUM_GATHER(f16_t);
+    else if (dtype == ADASUM_F64) ADASUM_GATHER(double);
     else ADASUM_GATHER(float);
 #undef ADASUM_GATHER
     return check_launch();
@@ -1021,14 +1069,18 @@ int launch_small_reduce(int out_dtype, const double* compact, int K, const Small
                        start_row, static_cast<T*>(out), stats)
     if (out_dtype == ADASUM_BF16) ADASUM_SMALL(bf16_t);
     else if (out_dtype == ADASUM_F16) ADASUM_SMALL(f16_t);
+    else if (out_dtype == ADASUM_F64) ADASUM_SMALL(double);
     else ADASUM_SMALL(float);
 #undef ADASUM_SMALL
     return check_launch();
 }
 
 const char* kernel_name(const char* kind, int dtype, int out_dtype, int R, bool diag, char* buf, size_t n) {
-    const char* in = dtype == ADASUM_BF16 ? "bf16" : (dtype == ADASUM_F16 ? "f16" : "f32");
-    const char* out = out_dtype == ADASUM_BF16 ? "bf16" : (out_dtype == ADASUM_F16 ? "f16" : "f32");
+    auto name = [](int d) {
+        return d == ADASUM_BF16 ? "bf16" : d == ADASUM_F16 ? "f16" : d == ADASUM_F64 ? "f64" : "f32";
+    };
+    const char* in = name(dtype);
+    const char* out = name(out_dtype);
     if (std::strcmp(kind, "gram") == 0) {
         std::snprintf(buf, n, "gram<%s,R=%d,%s>", in, R, diag ? "diag" : "offdiag");
     } else if (std::strcmp(kind, "combine") == 0) {

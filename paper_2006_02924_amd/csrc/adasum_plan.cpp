@@ -111,28 +111,31 @@ int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity
     return n;
 }
 
-int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices) {
+int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
+                           int node_type) {
     int64_t need = 1;
     int groups = K;
     for (size_t lv = 0; lv < radices.size(); ++lv) {
         groups /= radices[lv];
-        // fp32 input gives the finest table of a pass
-        const int64_t t = count_tiles(layer_offsets, n_layers, combine_tile_capacity(ADASUM_F32, radices[lv]));
+        // the widest storage type a pass may read gives its finest table
+        const int64_t t = count_tiles(layer_offsets, n_layers, combine_tile_capacity(node_type, radices[lv]));
         need = std::max<int64_t>(need, static_cast<int64_t>(groups) * t);
     }
     if (radices.empty())
-        need = std::max<int64_t>(need, count_tiles(layer_offsets, n_layers, combine_tile_capacity(ADASUM_F32, 1)));
+        need = std::max<int64_t>(need, count_tiles(layer_offsets, n_layers, combine_tile_capacity(node_type, 1)));
     return need;
 }
 
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
-                   const std::vector<int>& radices, int order, int64_t small_rows, int64_t small_elems) {
+                   const std::vector<int>& radices, int order, int64_t small_rows, int64_t small_elems,
+                   int node_type) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
     lay.norm_entries = norm_entries;
     lay.n_layers = n_layers;
     lay.slot_elems = static_cast<int64_t>(align_up(static_cast<size_t>(N), 64));
+    lay.node_bytes = elem_bytes(node_type);
     // nodes written by the first pass, unless that pass is already the root
     lay.n_slots = radices.size() > 1 ? K / radices[0] : 0;
 
@@ -156,7 +159,7 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
     }
     size_t off = 0;
     lay.off_slots = off;
-    off = align_up(off + static_cast<size_t>(lay.n_slots) * lay.slot_elems * sizeof(float), 256);
+    off = align_up(off + static_cast<size_t>(lay.n_slots) * lay.slot_elems * lay.node_bytes, 256);
     lay.off_partials = off;
     off = align_up(off + max_partials * sizeof(double), 256);
     lay.off_normparts = off;

@@ -19,6 +19,9 @@ TINY_LAYER = 256
 # over many elements and 2^-11 for a few (values must stay in the normal range, which the
 # paper's dynamic loss scaling is there to ensure; the fp16 test inputs have scales >= 1e-2).
 TOL_F16 = 2.5e-4
+# fp64 storage is reduced in fp64 throughout, like the oracle; the two differ in summation order
+# only: per-lane sums of 128-256 products, then fixed-order trees, each step 1.1e-16 relative.
+TOL_F64 = 1e-12
 TOL_F16_TINY = 2.0 ** -11 * 1.001
 
 
@@ -98,7 +101,7 @@ def oracle_reduce(grads, layer_offsets, layers=None, order="tree") -> np.ndarray
 
 
 def tol_for(dtype: torch.dtype) -> float:
-    return {torch.bfloat16: TOL_BF16, torch.float16: TOL_F16}.get(dtype, TOL_F32)
+    return {torch.bfloat16: TOL_BF16, torch.float16: TOL_F16, torch.float64: TOL_F64}.get(dtype, TOL_F32)
 
 
 def assert_parity(out: torch.Tensor, ref: np.ndarray, layer_offsets, layers=None, tol=None, what=""):

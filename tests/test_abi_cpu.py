@@ -87,6 +87,21 @@ def test_options_validation(lib):
     assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, bad) == B.ERR_INVALID_ARG
 
 
+def test_fp64_storage_limits(lib):
+    good = [0x1000, 0x2000]
+    offs = [0, 8]
+    assert _call_reduce(lib, good, 2, offs, B.F64, 0x9000, _opts(out_dtype=B.F32)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(out_dtype=B.F64)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 2, offs, B.F64, 0x9000, _opts(radix=16)) == B.ERR_UNSUPPORTED
+    # fp64 nodes are twice as wide as fp32 ones
+    big = [0, 70632]
+    assert B.adasum_workspace_bytes(64, big, B.F64, radix=8) > B.adasum_workspace_bytes(64, big, B.F32, radix=8) \
+        + 8 * 70632 * 4 - 4096
+    x = (C.c_void_p * 2)(0x1000, 0x2000)
+    o = (C.c_int64 * 2)(0, 8)
+    assert lib.adasum_group_combine(x, 2, o, 1, B.F64, 0xa000, 0x9000, B.F32, None, None) == B.ERR_UNSUPPORTED
+
+
 def test_delta_options_validation(lib):
     """Section 4.1's delta form: same dtype in and out, tree order, aligned, and
     `out` either is `delta_start` or does not touch it."""

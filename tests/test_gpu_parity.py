@@ -560,3 +560,69 @@ def test_small_layers_follow_the_definition_in_fp64(K, order):
             err = np.linalg.norm(got[lo:hi] - ref[lo:hi]) / np.linalg.norm(ref[lo:hi])
             # fp32 store (6e-8) plus fp64 noise amplified by the cancellations
             assert err <= (1e-6 if n <= 16 else TOL_F32), f"layer {l} (size {n}) radix {radix}: {err:.3e}"
+
+
+# ---------------------------------------------------------------------------
+# fp64 storage (the paper's dtype list: Section 4.4.1 names fp16, fp32 and fp64): reduced in fp64
+# ---------------------------------------------------------------------------
+
+def _fp64_workload(sizes, K, seed):
+    """The correlated-Gaussian recipe drawn in fp32 and widened, plus an fp64 perturbation so
+    that the values use the whole fp64 significand."""
+    w = W.correlated_gaussian(sizes, K, dtype=torch.float32, device=DEV, seed=seed)
+    g = torch.Generator(device=DEV).manual_seed(seed + 17)
+    grads = [x.double() * (1.0 + 1e-9 * torch.randn(w.N, generator=g, device=DEV, dtype=torch.float64))
+             for x in w.grads]
+    return W.Workload("fp64", K, torch.float64, w.layer_offsets, grads, w.meta)
+
+
+@pytest.mark.parametrize("radix", [0, 2, 4, 8])
+@pytest.mark.parametrize("K", [1, 2, 5, 16, 64])
+def test_fp64_storage(K, radix):
+    if K == 1 and radix != 0:
+        pytest.skip("K=1 has no passes")
+    say(f"fp64 K={K} radix={radix}")
+    w = _fp64_workload(np.diff(RAGGED).tolist(), K, 800 + K)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, layer_stats=stats)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.float64
+    err = assert_parity(out, ref, w.layer_offsets, what=f"fp64 K={K}")
+    say(f"  max rel-L2 {err.max():.2e}")
+    if K > 1:
+        lin = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, order=B.ORDER_LINEAR)
+        torch.cuda.synchronize()
+        assert_parity(lin, oracle_reduce(w.grads, w.layer_offsets, order="linear"), w.layer_offsets,
+                      what=f"fp64 linear K={K}")
+    metric = O.orthogonality([to_f64(g) for g in w.grads], w.layer_offsets)
+    s = stats.cpu().numpy()
+    ok = ~np.isnan(metric) & ~np.isnan([ref[a] if b > a else np.nan
+                                        for a, b in zip(w.layer_offsets[:-1], w.layer_offsets[1:])])
+    with np.errstate(invalid="ignore"):
+        got_metric = s[:, 0] / s[:, 1]
+    np.testing.assert_allclose(got_metric[ok], metric[ok], rtol=1e-9)
+
+
+def test_fp64_delta_form_and_limits():
+    sizes = np.diff(RAGGED).tolist()
+    d = W.after_local_step(sizes, 8, dtype=torch.float32, device=DEV, seed=41, step=0.25)
+    start = d.meta["start"].double()
+    cur = [c.double() for c in d.grads]
+    out = B.adasum_reduce(cur, d.layer_offsets, delta_start=start)
+    torch.cuda.synchronize()
+    w0 = to_f64(start)
+    cur64 = [to_f64(c) for c in cur]
+    ref = mark_ill_posed(O.adasum_after_optimizer(w0, cur64, d.layer_offsets), [c - w0 for c in cur64],
+                         list(d.layer_offsets))
+    assert_parity(out, ref, d.layer_offsets, what="fp64 delta")
+    # fp64 goes only to fp64, and at most 8 workers per pass
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(cur, d.layer_offsets, out_dtype=torch.float32)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(cur, d.layer_offsets, radix=16)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce([c.float() for c in cur], d.layer_offsets, out_dtype=torch.float64)
+    assert e.value.code == B.ERR_UNSUPPORTED
