@@ -29,9 +29,13 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see the
 # summaries under profiles/.  Keyed by (workload, kernel name).
 MEASURED_TRAFFIC_BYTES = {
-    ("config4", "combine<bf16,f32,R=16>"): 43.234e9 + 5.839e9,
+    ("config4", "combine<bf16,f32,R=16>"): 43.234e9 + 5.802e9,
     ("config4", "gram<bf16,R=16,diag>"): 42.901e9 + 0.099e9,
-    ("config4", "combine<bf16,f32,R=2>"): 43.574e9 + 43.066e9,
+    ("config4", "combine<bf16,f32,R=2>"): 43.571e9 + 43.066e9,
+    ("config3", "combine<f32,f32,R=16>"): 21.617e9 + 1.341e9,
+    ("config3", "gram<f32,R=16,diag>"): 21.450e9 + 0.025e9,
+    ("config2", "combine<f32,f32,R=8>"): 0.8243e9 + 0.1022e9,
+    ("config2", "gram<f32,R=8,diag>"): 0.8180e9 + 0.0006e9,
 }
 
 
@@ -41,7 +45,9 @@ def parse_args():
     p.add_argument("--steps", type=int, default=10)
     p.add_argument("--warmup", type=int, default=2)
     p.add_argument("--workload", default="config4",
-                   choices=["config1", "config2", "config3", "config4", "config4_small", "copy"])
+                   choices=["config1", "config2", "config3", "config4", "config5", "config4_small", "copy"])
+    p.add_argument("--workers", type=int, default=0, help="override the workload's number of workers K")
+    p.add_argument("--order", default="tree", choices=["tree", "linear"])
     p.add_argument("--radix", type=int, default=0, help="0 = library default")
     p.add_argument("--out-dtype", default="same", choices=["same", "f32", "bf16"])
     p.add_argument("--storage", default="same", choices=["same", "f16", "f64"],
@@ -56,16 +62,19 @@ def parse_args():
     return p.parse_args()
 
 
-def make_workload(name, device):
+def make_workload(name, device, workers=0):
     from paper_2006_02924_amd import workloads as W
+    kw = {"K": workers} if workers else {}
     if name == "config1":
         return W.config1(device)
     if name == "config2":
-        return W.config2(device)
+        return W.config2(device, **kw)
     if name == "config3":
-        return W.config3(device)
+        return W.config3(device, **kw)
     if name == "config4":
-        return W.config4(device)
+        return W.config4(device, **kw)
+    if name == "config5":
+        return W.config5(device, **kw)
     if name == "copy":
         # a plain copy of known size through the K = 1 path (reads N*4 bytes, writes N*4):
         # the yardstick that scales the FETCH_SIZE / WRITE_SIZE counters
@@ -141,7 +150,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     t0 = time.perf_counter()
-    w = make_workload(args.workload, dev)
+    w = make_workload(args.workload, dev, args.workers)
     torch.cuda.synchronize()
     print(f"[bench] {w.name}: K={w.K} N={w.N} layers={w.n_layers} dtype={w.dtype} "
           f"input={w.input_bytes / 1e9:.2f} GB generated in {time.perf_counter() - t0:.1f} s",
@@ -161,7 +170,8 @@ def main():
 
     def step():
         B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=args.radix,
-                        use_graph=args.graph, delta_start=start)
+                        use_graph=args.graph, delta_start=start,
+                        order=B.ORDER_LINEAR if args.order == "linear" else B.ORDER_TREE)
 
     for _ in range(args.warmup):
         step()
@@ -180,7 +190,7 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = w.input_bytes / (dt / args.steps) / 1e9
     eight = args.delta or w.dtype == torch.float64     # these default to radix 8
-    levels = B.plan_levels(w.K, args.radix if (args.radix or not eight) else 8)
+    levels = B.plan_levels(w.K, args.radix if (args.radix or not eight) else 8) if args.order == "tree" else None
 
     roofline = None
     if prof:
@@ -205,11 +215,12 @@ def main():
         "metric": "Adasum tree-reduce throughput: input GB/s and % of MI355X HBM peak",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f64" if w.dtype == torch.float64 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: K={w.K} workers, {w.n_layers} tensors, N={w.N} elements, "
                                f"stored {str(w.dtype).replace('torch.', '')}, output "
                                f"{str(out_dtype).replace('torch.', '')}",
                    "passes": levels, "radix": args.radix, "graph": bool(args.graph), "delta_form": bool(args.delta),
+                   "order": args.order,
                    "input_GB": w.input_bytes / 1e9},
         "roofline": roofline,
     }

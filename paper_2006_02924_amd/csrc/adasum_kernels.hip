@@ -756,39 +756,45 @@ small_reduce_kernel(const double* __restrict__ compact, int K, const SmallLayer*
                     long long small_elems, int order, int add_start, int start_row, TO* out,
                     double* __restrict__ stats) {
     constexpr int kDepth = 34;   // a stack of complete sub-trees of distinct depths: at most log2(K) + 2
+    constexpr int kAhead = 8;    // leaves fetched together (the fetches are what takes the time)
     __shared__ double vstack[kDepth][64];
+    __shared__ int slo[kDepth], shi[kDepth];   // the same in every lane
     const SmallLayer s = small[blockIdx.x];
     const int lane = threadIdx.x;
     const bool live = lane < s.len;
     const double* col = compact + s.coff + lane;
     double leafsq = 0.0, r = 0.0;
-    if (order == ADASUM_ORDER_LINEAR) {
-        for (int k = 0; k < K; ++k) {
-            const double v = live ? col[static_cast<long long>(k) * small_elems] : 0.0;
+    int sp = 0;
+    for (int k0 = 0; k0 < K; k0 += kAhead) {
+        double leaf[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+            leaf[u] = (live && k0 + u < K) ? col[static_cast<long long>(k0 + u) * small_elems] : 0.0;
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int k = k0 + u;
+            if (k >= K) break;
+            const double v = leaf[u];
             leafsq += v * v;
-            r = k == 0 ? v : small_pair(r, v);
-        }
-    } else {
-        // leaves left to right; the two topmost sub-trees are merged as soon as together
-        // they form a node of the tree
-        int lo[kDepth], hi[kDepth];
-        int sp = 0;
-        for (int k = 0; k < K; ++k) {
-            const double v = live ? col[static_cast<long long>(k) * small_elems] : 0.0;
-            leafsq += v * v;
+            if (order == ADASUM_ORDER_LINEAR) {
+                r = k == 0 ? v : small_pair(r, v);
+                continue;
+            }
+            // tree order: leaves left to right; the two topmost sub-trees are merged as soon as
+            // together they form a node of the tree
             vstack[sp][lane] = v;
-            lo[sp] = k;
-            hi[sp] = k + 1;
+            slo[sp] = k;
+            shi[sp] = k + 1;
             ++sp;
-            while (sp >= 2 && is_tree_node(K, lo[sp - 2], hi[sp - 1])) {
+            while (sp >= 2 && is_tree_node(K, slo[sp - 2], shi[sp - 1])) {
                 const double b = vstack[sp - 1][lane], a = vstack[sp - 2][lane];
                 vstack[sp - 2][lane] = small_pair(a, b);
-                hi[sp - 2] = hi[sp - 1];
+                shi[sp - 2] = shi[sp - 1];
                 --sp;
             }
         }
-        r = vstack[0][lane];   // sp == 1: the root [0, K)
     }
+    if (order != ADASUM_ORDER_LINEAR) r = vstack[0][lane];   // sp == 1: the root [0, K)
     const double rsq = wave_sum(r * r);
     leafsq = wave_sum(leafsq);
     if (stats != nullptr && lane == 0) {
