@@ -4,14 +4,19 @@
  * Operation (arXiv 2006.02924):
  *   - two-gradient operator, Section 1 / Section 3:
  *       Adasum(g1, g2) = (1 - g1.g2 / (2 |g1|^2)) g1 + (1 - g1.g2 / (2 |g2|^2)) g2
- *   - K gradients: recursive halving, Section 3.4 (second recursion) -- a
- *     balanced binary tree whose level-0 pairs are workers (2j, 2j+1);
+ *   - K gradients: recursive halving, Section 3.4 (second recursion) -- for a power
+ *     of two a balanced binary tree whose level-0 pairs are workers (2j, 2j+1); any
+ *     other K splits every node [lo, hi) at lo + (hi - lo) / 2;
  *   - the operator's scalars are taken per layer of the fused gradient buffer,
  *     Section 3.6 (last paragraph) and Section 4.4.3 (boundary bookkeeping);
  *   - dot products and squared norms: each lane accumulates a short run in fp32,
  *     a wave adds its lanes in fp32, everything above that (and the ragged
  *     head/tail elements of a layer) is summed in fp64; the operator's scalars
- *     are computed in fp64 (Section 4.4.1 asks for double accumulation).
+ *     are computed in fp64 (Section 4.4.1 asks for double accumulation).  fp64
+ *     inputs are reduced in fp64 throughout;
+ *   - layers of at most 16 elements are reduced by the definition itself, pair by
+ *     pair in fp64 over all K workers with nothing stored in between: vectors that
+ *     short can nearly cancel at a tree node, where stored fp32 nodes lose digits.
  * Reading where the paper is silent: an operand whose squared norm is exactly 0
  * gets coefficient 1, so Adasum(0, g) = g and Adasum(0, 0) = 0.
  *
@@ -67,8 +72,9 @@ extern "C" {
  */
 typedef struct adasum_options {
     uint32_t struct_bytes;     /* sizeof(adasum_options) as the caller compiled it */
-    int32_t  out_dtype;        /* the input dtype or ADASUM_F32 (any storage type when the input
-                                  is fp32); -1 = same as the input dtype */
+    int32_t  out_dtype;        /* the input dtype or ADASUM_F32 (any 16- or 32-bit storage type
+                                  when the input is fp32; fp64 goes with fp64 only);
+                                  -1 = same as the input dtype */
     int32_t  radix;            /* how many binary tree levels one pass over the data fuses:
                                   2 = one level per pass (reduce pass + combine pass per level),
                                   4 / 8 / 16 = two / three / four levels per pass (the pass
@@ -83,8 +89,8 @@ typedef struct adasum_options {
     void*    workspace;        /* DEVICE, 256-byte aligned, or NULL = library-owned, cached per plan */
     size_t   workspace_bytes;  /* size of `workspace`; see adasum_workspace_bytes */
     double*  layer_stats;      /* DEVICE or NULL: n_layers x 2 doubles written per call,
-                                  [l][0] = |Adasum(g_1..g_K)|^2 of layer l (of the fp32 value
-                                  before the output store), [l][1] = sum_i |g_i|^2; their ratio
+                                  [l][0] = |Adasum(g_1..g_K)|^2 of layer l (of the value before
+                                  it is rounded to the output type), [l][1] = sum_i |g_i|^2; their ratio
                                   is the orthogonality metric of Section 3.6 */
     const void* delta_start;   /* DEVICE or NULL.  Section 4.1 (Adasum applied after the optimizer):
                                   N elements of the input dtype, 16-byte aligned -- the model
@@ -118,9 +124,11 @@ typedef struct adasum_options {
  *   out            DEVICE, N elements of `dtype`; must not overlap any input
  *   stream         hipStream_t
  *
- * Intermediate tree nodes are kept in fp32 whatever the storage type; the only
- * rounding to bf16 is the final store.  Uses a library-owned workspace cached
- * per (K, dtype, layer table); the first call with a new shape allocates.
+ * Intermediate tree nodes are kept in fp32 for 16- and 32-bit storage types (fp64
+ * for fp64); the only rounding to bf16 / fp16 is the final store.  Uses a
+ * library-owned workspace cached with the plan for (K, radix, order, node type,
+ * layer table); the first call with a new shape allocates.  At most 64 plans are
+ * kept; making a 65th frees the least recently used one (and waits for the device).
  */
 int adasum_reduce(const void* const* grads, int K,
                   const int64_t* layer_offsets, int n_layers,
@@ -133,7 +141,9 @@ int adasum_reduce_ex(const void* const* grads, int K,
                      int dtype, void* out, const adasum_options* opts, void* stream);
 
 /* Bytes of DEVICE workspace adasum_reduce_ex needs for this problem (intermediate
- * fp32 tree nodes, per-tile partial sums, coefficient tables).  Host-only. */
+ * tree nodes, per-tile partial sums, coefficient tables, the compact copy of the
+ * small layers).  Depends on dtype, radix, order and on whether delta_start is set
+ * (any non-NULL value).  Host-only. */
 int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
                            int dtype, const adasum_options* opts, size_t* bytes);
 
@@ -186,7 +196,7 @@ typedef struct adasum_tile {
 } adasum_tile;
 
 /* Elements one workgroup of the Gram pass covers at most.  (The combine pass
- * uses finer tables of 256 x 4 or 256 x 8 elements: one 16-byte load per lane.) */
+ * uses finer tables: one 16-byte load per lane and operand, 64 to 256 lanes.) */
 int adasum_tile_capacity(void);
 
 /* Writes the tile table for a layer table: consecutive runs of at most

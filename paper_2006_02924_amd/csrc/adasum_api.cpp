@@ -221,19 +221,25 @@ struct Plan {
 };
 
 std::mutex g_mutex;
-std::vector<std::unique_ptr<Plan>> g_plans;
+std::vector<std::unique_ptr<Plan>> g_plans;   // least recently used first
+constexpr size_t kMaxPlans = 64;
 
 int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers, Plan** out) {
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
-    for (auto& p : g_plans) {
+    for (size_t i = 0; i < g_plans.size(); ++i) {
+        Plan* p = g_plans[i].get();
         if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
             static_cast<int>(p->offsets.size()) == n_layers + 1 &&
             std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
-            *out = p.get();
+            // most recently used last
+            std::rotate(g_plans.begin() + i, g_plans.begin() + i + 1, g_plans.end());
+            *out = p;
             return ADASUM_OK;
         }
     }
+    // a bounded cache: the least recently used plan goes (hipFree waits for work in flight)
+    while (g_plans.size() >= kMaxPlans) g_plans.erase(g_plans.begin());
     std::unique_ptr<Plan> p(new (std::nothrow) Plan());
     if (!p) return ADASUM_ERR_OUT_OF_MEMORY;
     try {

@@ -626,3 +626,20 @@ def test_fp64_delta_form_and_limits():
     with pytest.raises(B.AdasumError) as e:
         B.adasum_reduce([c.float() for c in cur], d.layer_offsets, out_dtype=torch.float64)
     assert e.value.code == B.ERR_UNSUPPORTED
+
+
+def test_plan_cache_is_bounded_and_evicts_safely():
+    """More distinct layer tables than the library keeps plans for: old plans are dropped
+    (their device memory freed) while results stay right, also for a table seen again."""
+    g = torch.Generator().manual_seed(5)
+    a = torch.randn(4000, generator=g).to(DEV)
+    b = torch.randn(4000, generator=g).to(DEV)
+    ref_of = {}
+    for rep in range(2):
+        for n in range(100, 100 + 80):
+            offs = [0, n, 2 * n + 7, 4000]
+            out = B.adasum_reduce([a, b], offs)
+            if n not in ref_of:
+                ref_of[n] = oracle_reduce([a, b], offs)
+            torch.cuda.synchronize()
+            assert_parity(out, ref_of[n], offs, what=f"table {n}")
