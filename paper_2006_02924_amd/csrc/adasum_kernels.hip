@@ -492,16 +492,34 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
     const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
     double* out = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
 
-    for (int e = wave; e < NP; e += NW) {
-        const double* row = partials + (static_cast<long long>(g) * NP + e) * n_tiles;
-        double v = 0.0;
-        for (int t = tb + lane; t < te; t += 64) v += row[t];
-        v = wave_sum(v);
-        if (lane == 0) {
-            int i, j;
-            entry_to_ij<R, DIAG>(e, i, j);
-            out[i * R + j] = v;
-            out[j * R + i] = v;
+    // kAhead entries per wave at a time, so that their loads are in flight together (a layer
+    // with hundreds of tiles is otherwise a chain of dependent fetches)
+    constexpr int kAhead = 8;
+    for (int e0 = wave; e0 < NP; e0 += NW * kAhead) {
+        double v[kAhead];
+        const double* row[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            v[u] = 0.0;
+            const int e = e0 + u * NW < NP ? e0 + u * NW : e0;   // past the end: a row that exists, result unused
+            row[u] = partials + (static_cast<long long>(g) * NP + e) * n_tiles;
+        }
+        for (int t = tb + lane; t < te; t += 64) {
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) v[u] += row[u][t];
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int e = e0 + u * NW;
+            if (e < NP) {
+                const double tot = wave_sum(v[u]);
+                if (lane == 0) {
+                    int i, j;
+                    entry_to_ij<R, DIAG>(e, i, j);
+                    out[i * R + j] = tot;
+                    out[j * R + i] = tot;
+                }
+            }
         }
     }
     if (!DIAG) {
