@@ -643,3 +643,27 @@ def test_plan_cache_is_bounded_and_evicts_safely():
                 ref_of[n] = oracle_reduce([a, b], offs)
             torch.cuda.synchronize()
             assert_parity(out, ref_of[n], offs, what=f"table {n}")
+
+
+@pytest.mark.parametrize("radix", [0, 2])
+@pytest.mark.parametrize("K", [129, 257, 1000, 1024])
+def test_many_workers(K, radix):
+    """More workers than one launch carries operand pointers for (128): batched launches, deep trees."""
+    say(f"many workers K={K} radix={radix} levels={B.plan_levels(K, radix)}")
+    sizes = [1, 40, 3000, 7, 20000]
+    w = W.correlated_gaussian(sizes, K, dtype=torch.float32, device=DEV, seed=1000 + K, corr=0.3)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, layer_stats=stats)
+    torch.cuda.synchronize()
+    err = assert_parity(out, ref, w.layer_offsets, what=f"K={K}")
+    say(f"  max rel-L2 {err.max():.2e}")
+    f64 = [to_f64(g) for g in w.grads]
+    s = stats.cpu().numpy()
+    offs = w.layer_offsets
+    for l in range(w.n_layers):
+        assert s[l, 1] == pytest.approx(sum(float(np.dot(g[offs[l]:offs[l + 1]], g[offs[l]:offs[l + 1]]))
+                                            for g in f64), rel=1e-6)
+    lin = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, order=B.ORDER_LINEAR)
+    torch.cuda.synchronize()
+    assert_parity(lin, oracle_reduce(w.grads, w.layer_offsets, order="linear"), w.layer_offsets, what=f"K={K} linear")
