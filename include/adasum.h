@@ -44,6 +44,9 @@
 extern "C" {
 #endif
 
+/* the library exports the entry points below and nothing else */
+#define ADASUM_API __attribute__((visibility("default")))
+
 /* element storage types */
 #define ADASUM_F32  0   /* IEEE binary32 */
 #define ADASUM_BF16 1   /* bfloat16; stores round to nearest even */
@@ -130,13 +133,13 @@ typedef struct adasum_options {
  * layer table); the first call with a new shape allocates.  At most 64 plans are
  * kept; making a 65th frees the least recently used one (and waits for the device).
  */
-int adasum_reduce(const void* const* grads, int K,
+ADASUM_API int adasum_reduce(const void* const* grads, int K,
                   const int64_t* layer_offsets, int n_layers,
                   int dtype, void* out, void* stream);
 
 /* Same operation with options (output dtype, radix, order, caller workspace,
  * per-layer statistics).  opts == NULL means all defaults. */
-int adasum_reduce_ex(const void* const* grads, int K,
+ADASUM_API int adasum_reduce_ex(const void* const* grads, int K,
                      const int64_t* layer_offsets, int n_layers,
                      int dtype, void* out, const adasum_options* opts, void* stream);
 
@@ -144,7 +147,7 @@ int adasum_reduce_ex(const void* const* grads, int K,
  * tree nodes, per-tile partial sums, coefficient tables, the compact copy of the
  * small layers).  Depends on dtype, radix, order and on whether delta_start is set
  * (any non-NULL value).  Host-only. */
-int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
+ADASUM_API int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
                            int dtype, const adasum_options* opts, size_t* bytes);
 
 /* ---- the steps of one tree level, exposed so that each can be checked alone ---- */
@@ -157,7 +160,7 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
  *   R      2, 4, 8 or 16
  *   gram   DEVICE, n_layers x R x R doubles, row-major per layer, symmetric
  */
-int adasum_group_gram(const void* const* x, int R,
+ADASUM_API int adasum_group_gram(const void* const* x, int R,
                       const int64_t* layer_offsets, int n_layers,
                       int dtype, double* gram, void* stream);
 
@@ -169,7 +172,7 @@ int adasum_group_gram(const void* const* x, int R,
  *   gram     DEVICE, n_layers x R x R doubles (as written by adasum_group_gram)
  *   weights  DEVICE, n_layers x R doubles
  */
-int adasum_group_weights(const double* gram, int R, int n_layers, int order,
+ADASUM_API int adasum_group_weights(const double* gram, int R, int n_layers, int order,
                          double* weights, void* stream);
 
 /*
@@ -182,7 +185,7 @@ int adasum_group_weights(const double* gram, int R, int n_layers, int order,
  *              when out_dtype == dtype, must not overlap any other operand
  *   sqnorm     DEVICE, n_layers doubles, or NULL
  */
-int adasum_group_combine(const void* const* x, int R,
+ADASUM_API int adasum_group_combine(const void* const* x, int R,
                          const int64_t* layer_offsets, int n_layers,
                          int dtype, const double* weights,
                          void* out, int out_dtype, double* sqnorm, void* stream);
@@ -197,7 +200,7 @@ typedef struct adasum_tile {
 
 /* Elements one workgroup of the Gram pass covers at most.  (The combine pass
  * uses finer tables: one 16-byte load per lane and operand, 64 to 256 lanes.) */
-int adasum_tile_capacity(void);
+ADASUM_API int adasum_tile_capacity(void);
 
 /* Writes the tile table for a layer table: consecutive runs of at most
  * `capacity` elements (0 = adasum_tile_capacity()) whose boundaries fall on
@@ -205,7 +208,7 @@ int adasum_tile_capacity(void);
  * crosses a layer.  *n_tiles receives the number of tiles; at most `cap` entries
  * are written to `tiles` (tiles may be NULL with cap = 0 to query the count).
  * Tiles are ordered by start; empty layers get no tile. */
-int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
+ADASUM_API int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity,
                       adasum_tile* tiles, int64_t cap, int64_t* n_tiles);
 
 /* Writes the radix of every pass of the tree order for K workers, e.g. K = 64,
@@ -214,13 +217,13 @@ int adasum_plan_tiles(const int64_t* layer_offsets, int n_layers, int64_t capaci
  * with fewer leaves than its radix (see adasum_plan_groups), e.g. K = 12,
  * radix 8 -> {8, 2} with two groups of 6.  *n_levels receives the count; at
  * most `cap` entries are written. */
-int adasum_plan_levels(int K, int radix, int* radices, int cap, int* n_levels);
+ADASUM_API int adasum_plan_levels(int K, int radix, int* radices, int cap, int* n_levels);
 
 /* The groups of the first pass of the tree order: group g reduces workers
  * first_worker[g] .. first_worker[g+1]-1, a whole sub-tree of the recursion of
  * Section 3.4 (split at lo + (hi - lo) / 2).  *n_groups receives the number of
  * groups G; at most `cap` of the G + 1 boundaries are written. */
-int adasum_plan_groups(int K, int radix, int* first_worker, int cap, int* n_groups);
+ADASUM_API int adasum_plan_groups(int K, int radix, int* first_worker, int cap, int* n_groups);
 
 /* ---- per-kernel timing (HIP events on the caller's stream) ---- */
 
@@ -234,18 +237,18 @@ typedef struct adasum_kernel_profile {
 
 /* on != 0: every kernel launched by adasum_reduce(_ex) is bracketed by a pair
  * of HIP events on its stream.  Off by default. */
-int adasum_profile_enable(int on);
+ADASUM_API int adasum_profile_enable(int on);
 /* Synchronises the recorded events, aggregates by kernel name, writes at most
  * `cap` entries, sets *n to the number of distinct kernels, and clears the log. */
-int adasum_profile_collect(adasum_kernel_profile* out, int cap, int* n);
+ADASUM_API int adasum_profile_collect(adasum_kernel_profile* out, int cap, int* n);
 
 /* ---- housekeeping ---- */
-const char* adasum_strerror(int code);
-int         adasum_last_hip_error(void);   /* hipError_t of the last failing HIP call in this thread */
-const char* adasum_version(void);
+ADASUM_API const char* adasum_strerror(int code);
+ADASUM_API int         adasum_last_hip_error(void);   /* hipError_t of the last failing HIP call in this thread */
+ADASUM_API const char* adasum_version(void);
 /* Frees every cached plan and library-owned workspace.  The caller must have
  * synchronised the streams it used. */
-int adasum_shutdown(void);
+ADASUM_API int adasum_shutdown(void);
 
 #ifdef __cplusplus
 }

@@ -30,7 +30,7 @@ def hipcc() -> str:
 
 
 def build_library(verbose: bool = True, extra_flags=(), out_path: str = LIB_PATH) -> str:
-    cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-command-line-argument",
+    cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden", "-Wall", "-Wno-unused-command-line-argument",
            *DEVICE_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra_flags]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", out_path]
