@@ -980,7 +980,7 @@ const char* adasum_strerror(int code) {
     switch (code) {
         case ADASUM_OK: return "ok";
         case ADASUM_ERR_INVALID_ARG: return "invalid argument";
-        case ADASUM_ERR_UNSUPPORTED: return "unsupported (K must be a power of two; dtype f32/bf16/f16, output the same type or f32; radix 2/4/8/16)";
+        case ADASUM_ERR_UNSUPPORTED: return "unsupported (dtype f32/bf16/f16/f64; output the input type or f32, f64 only with f64; radix 2/4/8/16, f64 up to 8; the delta form and layer_stats only in tree order)";
         case ADASUM_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
         case ADASUM_ERR_OUT_OF_MEMORY: return "out of memory";
         case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";
