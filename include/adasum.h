@@ -198,7 +198,8 @@ typedef struct adasum_tile {
     int32_t layer;
 } adasum_tile;
 
-/* Elements one workgroup of the Gram pass covers at most.  (The combine pass
+/* Elements one workgroup of the Gram pass covers at most (a layer table with fewer
+ * than 2048 such tiles is cut into tiles of 16384 instead).  (The combine pass
  * uses finer tables: one 16-byte load per lane and operand, 64 to 256 lanes.) */
 ADASUM_API int adasum_tile_capacity(void);
 

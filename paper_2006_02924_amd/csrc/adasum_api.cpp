@@ -109,6 +109,7 @@ int default_radix(const Opts& o) {
 
 // One tile table on the host and on the device.
 struct TileTable {
+    int capacity = 0;
     std::vector<adasum_tile> tiles;
     std::vector<int32_t> layer_begin;
     std::vector<int32_t> first_in_gram;   // combine tables only
@@ -122,6 +123,7 @@ struct TileTable {
         t.layer_begin = d_layer_begin;
         t.first_in_gram = d_first_in_gram;
         t.n_tiles = static_cast<int64_t>(tiles.size());
+        t.capacity = capacity;
         return t;
     }
     // Both tables are sorted by start and a combine tile never straddles a Gram tile.
@@ -190,6 +192,7 @@ struct Plan {
         if (it == comb_tables.end()) {
             try {
                 TileTable t;
+                t.capacity = cap;
                 build_tiles(offsets.data(), static_cast<int>(offsets.size()) - 1, cap, t.tiles, t.layer_begin);
                 t.index_against(gram_tiles.tiles);
                 it = comb_tables.emplace(cap, std::move(t)).first;
@@ -249,7 +252,8 @@ int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t*
         p->order = order;
         p->node_type = node_type;
         p->offsets.assign(offsets, offsets + n_layers + 1);
-        build_tiles(offsets, n_layers, kTile, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
+        p->gram_tiles.capacity = gram_tile_capacity(offsets, n_layers);
+        build_tiles(offsets, n_layers, p->gram_tiles.capacity, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
         int rc = order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, radix, p->radices)
                                               : build_levels(K, radix, p->radices);
         if (rc != ADASUM_OK) return rc;
@@ -483,16 +487,14 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
             ADASUM_TIMED("norm_coarsen", 0.0, stream,
                          launch_norm_coarsen(normparts, nodes, norm_tiles, gt, normcoarse, stream));
         }
+        // (the tree's weights come out of the same launch)
         kernel_name("gram_finish", 0, 0, R, first, namebuf, sizeof(namebuf));
         ADASUM_TIMED(namebuf, 0.0, stream,
-                     launch_gram_finish(first, gt, L, groups, R, partials, normcoarse, gram, stream));
+                     launch_gram_finish(first, gt, L, groups, R, partials, normcoarse, gram, weights, o.order,
+                                        first ? p->K : 0, depth0, stream));
         if (first && o.layer_stats != nullptr) {
             ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, p->K, depth0, o.layer_stats + 1, 2, stream));
         }
-        kernel_name("weights", 0, 0, R, first, namebuf, sizeof(namebuf));
-        ADASUM_TIMED(namebuf, 0.0, stream,
-                     launch_weights(gram, R, static_cast<int64_t>(groups) * L, o.order, L, first ? p->K : 0, depth0,
-                                    weights, stream));
         // step 3: apply
         for (int g0 = 0; g0 < groups; g0 += batch) {
             const int ng = std::min(batch, groups - g0);
@@ -591,8 +593,8 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
             next_leaf += R - 1;
         }
         ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, nullptr, stream));
-        ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, stream));
-        ADASUM_LAUNCH(launch_weights(gram, R, L, ADASUM_ORDER_LINEAR, L, 0, 0, weights, stream));
+        ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, weights, ADASUM_ORDER_LINEAR, 0, 0,
+                                         stream));
         Outputs outs;
         outs.base = last ? static_cast<char*>(out) : slots;
         outs.slot_bytes = 0;
@@ -791,7 +793,7 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
         std::vector<SmallLayer> small;
         const int64_t small_elems = K > 1 ? find_small_layers(layer_offsets, n_layers, small) : 0;
         const Layout lay = make_layout(Kv, layer_offsets[n_layers], n_layers,
-                                       count_tiles(layer_offsets, n_layers, kTile),
+                                       count_tiles(layer_offsets, n_layers, gram_tile_capacity(layer_offsets, n_layers)),
                                        norm_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype)),
                                        radices, o.order, K + 1, small_elems, node_dtype(dtype));
         *bytes = lay.total;
@@ -830,7 +832,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     std::memset(&ops, 0, sizeof(ops));
     for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
     ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, nullptr, stream));
-    ADASUM_LAUNCH(launch_gram_finish(true, gt, n_layers, 1, R, partials, nullptr, gram, stream));
+    ADASUM_LAUNCH(launch_gram_finish(true, gt, n_layers, 1, R, partials, nullptr, gram, nullptr, 0, 0, 0, stream));
     return ADASUM_OK;
 }
 

@@ -21,6 +21,10 @@ namespace adasum {
 #define ADASUM_THREADS 256
 #endif
 constexpr int kTile = ADASUM_TILE;
+// Small problems (fewer than kFewTiles long tiles: not even a few workgroups per compute
+// unit) are cut into shorter Gram tiles so that the pass still fills the chip evenly.
+constexpr int kTileSmall = 16384;
+constexpr int kFewTiles = 2048;
 constexpr int kThreads = ADASUM_THREADS;
 // A combine workgroup covers one 16-byte load per lane and operand and then
 // ends: short-lived workgroups that walk memory in launch order keep the mixed
@@ -156,6 +160,8 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
                    int64_t small_elems = 0, int node_type = ADASUM_F32);
 // Number of tiles build_tiles would produce.
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity);
+// Gram tile capacity for a layer table: kTile, or kTileSmall for a small problem.
+int gram_tile_capacity(const int64_t* layer_offsets, int n_layers);
 // Upper bound (over input dtypes) of make_layout's norm_entries for a schedule.
 int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
                            int node_type = ADASUM_F32);
@@ -184,6 +190,7 @@ struct TileSet {
     // that lie inside Gram tile t are first_in_gram[t] .. first_in_gram[t + 1]
     const int32_t* first_in_gram = nullptr;
     int64_t n_tiles = 0;
+    int capacity = 0;                        // elements a tile holds at most
 };
 
 // All launchers return a hipError_t as int (0 = success) and enqueue on `stream`.
@@ -199,7 +206,9 @@ int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, cons
 // normparts[(group * R + i) * gt.n_tiles + tile] of the operand nodes) into full
 // R x R Gram matrices gram[group][layer][R*R].
 int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups, int R,
-                       const double* partials, const double* normparts, double* gram, void* stream);
+                       const double* partials, const double* normparts, double* gram,
+                       double* weights /* or null: step 2b is not done here */, int order, int K_leaves, int depth,
+                       void* stream);
 // Gram matrices -> per-layer weights of the binary (or linear) tree over R leaves.
 // Item i is (group i / n_layers, layer i % n_layers).  K_leaves > 0: group g holds only the
 // leaves of node g of depth `depth` in the halving tree over K_leaves (leaf_range), in its

@@ -279,14 +279,14 @@ __device__ __forceinline__ Split split_tile(const adasum_tile& t) {
 // DELTA: the operands are x_r - start (the "effective gradient" of Section 4.1:
 // parameters after the local step minus the parameters before it), formed on
 // the fly; `start` has the operands' type.
-template <typename T, int R, bool DIAG, bool DELTA>
+template <typename T, int R, bool DIAG, bool DELTA, int TILE>
 __global__ void __launch_bounds__(kThreads)
 gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_tiles,
             double* __restrict__ partials, const T* __restrict__ start) {
     constexpr int G = Traits<T>::VEC;
     typedef typename Traits<T>::acc_t acc_t;
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
-    constexpr int ITERS = kTile / G / kThreads;
+    constexpr int ITERS = TILE / G / kThreads;
     constexpr int U0 = (R >= ADASUM_INFLIGHT) ? 1 : (ADASUM_INFLIGHT / R);   // granule-steps loaded ahead
     constexpr int U = U0 > ITERS ? ITERS : U0;
     static_assert(ITERS % U == 0, "unroll must divide the trip count");
@@ -356,7 +356,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
         }
     };
 
-    if (s.ng == kTile / G) {
+    if (s.ng == TILE / G) {
         for (int it0 = 0; it0 < ITERS; it0 += U) {
             Granule<T, G> raw[U][R];
 #pragma unroll
@@ -475,6 +475,57 @@ __device__ __forceinline__ void entry_to_ij(int e, int& i, int& j) {
     j = (DIAG ? i : i + 1) + e;
 }
 
+// The tree's weights from one Gram matrix, computed by one wave (64 lanes): every node of
+// the tree is a combination of its leaves, node = sum_p w_p x_p; for two sibling nodes A and
+// B the operator of Section 3 needs d = A.B = sum_{p in A, q in B} w_p w_q G_pq, n1 = |A|^2,
+// n2 = |B|^2 (quadratic forms whose terms are spread over the lanes and summed in a fixed
+// order) and scales A's weights by 1 - d/(2 n1), B's by 1 - d/(2 n2); a zero squared norm
+// gives coefficient 1.  G and w live in LDS; r leaves are real, the rest get weight 0.
+template <int R>
+__device__ __forceinline__ double wave_quadratic(const double* G, const double* w, int a0, int a1, int b0, int b1,
+                                                 int lane) {
+    const int nb = b1 - b0, n = (a1 - a0) * nb;
+    double v = 0.0;
+    for (int i = lane; i < n; i += 64) {
+        const int p = a0 + i / nb, q = b0 + i % nb;
+        v += w[p] * w[q] * G[p * R + q];
+    }
+    return wave_sum(v);
+}
+
+template <int R>
+__device__ __forceinline__ void wave_merge(const double* G, double* w, int a0, int a1, int b0, int b1, int lane) {
+    const double n1 = wave_quadratic<R>(G, w, a0, a1, a0, a1, lane);
+    const double n2 = wave_quadratic<R>(G, w, b0, b1, b0, b1, lane);
+    const double d = wave_quadratic<R>(G, w, a0, a1, b0, b1, lane);
+    const double ca = n1 > 0.0 ? 1.0 - d / (2.0 * n1) : 1.0;
+    const double cb = n2 > 0.0 ? 1.0 - d / (2.0 * n2) : 1.0;
+    if (lane >= a0 && lane < a1) w[lane] *= ca;
+    if (lane >= b0 && lane < b1) w[lane] *= cb;
+}
+
+template <int R>
+__device__ __forceinline__ void wave_tree_weights(const double* G, double* w, int r, int order, int lane) {
+    if (lane < R) w[lane] = lane < r ? 1.0 : 0.0;
+    if (order == ADASUM_ORDER_LINEAR) {
+        for (int k = 1; k < r; ++k) wave_merge<R>(G, w, 0, k, k, k + 1, lane);
+        return;
+    }
+    // the halving tree over r leaves, deepest nodes first: children before parents
+    int levels = 0;
+    while ((1 << levels) < r) ++levels;
+    for (int d = levels - 1; d >= 0; --d) {
+        for (int j = 0; j < (1 << d); ++j) {
+            int lo, hi;
+            leaf_range(r, d, j, lo, hi);
+            if (hi - lo >= 2) {
+                const int mid = lo + (hi - lo) / 2;
+                wave_merge<R>(G, w, lo, mid, mid, hi, lane);
+            }
+        }
+    }
+}
+
 // One workgroup per (group, layer); its waves take the entries round-robin,
 // lanes stride over the layer's Gram tiles, a fixed-order wave reduction ends
 // each entry (no workgroup barrier).  When !DIAG the diagonal comes from the
@@ -483,7 +534,7 @@ template <int R, bool DIAG>
 __global__ void __launch_bounds__(kThreads)
 gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts,
                    const int32_t* __restrict__ layer_tile_begin, int n_tiles, int n_layers,
-                   double* __restrict__ gram) {
+                   double* __restrict__ gram, double* __restrict__ weights, int order, int K_leaves, int depth) {
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
     constexpr int NW = kThreads / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -491,6 +542,8 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
     const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_layers));
     const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
     double* out = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
+    __shared__ double shG[R * R];
+    __shared__ double shW[R];
 
     // kAhead entries per wave at a time, so that their loads are in flight together (a layer
     // with hundreds of tiles is otherwise a chain of dependent fetches)
@@ -518,6 +571,8 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
                     entry_to_ij<R, DIAG>(e, i, j);
                     out[i * R + j] = tot;
                     out[j * R + i] = tot;
+                    shG[i * R + j] = tot;
+                    shG[j * R + i] = tot;
                 }
             }
         }
@@ -528,7 +583,24 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
             double v = 0.0;
             for (int t = tb + lane; t < te; t += 64) v += row[t];
             v = wave_sum(v);
-            if (lane == 0) out[i * R + i] = v;
+            if (lane == 0) {
+                out[i * R + i] = v;
+                shG[i * R + i] = v;
+            }
+        }
+    }
+    // Step 2b in the same launch: the weights of this (group, layer), by wave 0
+    if (weights != nullptr) {
+        __syncthreads();
+        if (wave == 0) {
+            int r = R;
+            if (K_leaves > 0) {
+                int lo, hi;
+                leaf_range(K_leaves, depth, g, lo, hi);
+                r = hi - lo;
+            }
+            wave_tree_weights<R>(shG, shW, r, order, lane);
+            if (lane < R) weights[(static_cast<long long>(g) * n_layers + l) * R + lane] = shW[lane];
         }
     }
 }
@@ -878,8 +950,17 @@ int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, d
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const int nt = static_cast<int>(gt.n_tiles);
     const T* s0 = static_cast<const T*>(start);
+    if (gt.capacity != kTile && gt.capacity != kTileSmall) return static_cast<int>(hipErrorInvalidValue);
+    const bool small = gt.capacity == kTileSmall;
 #define ADASUM_GRAM(RR)                                                                               \
-    hipLaunchKernelGGL((gram_kernel<T, RR, DIAG, DELTA>), grid, block, 0, st, ops, gt.tiles, nt, partials, s0)
+    do {                                                                                              \
+        if (small)                                                                                    \
+            hipLaunchKernelGGL((gram_kernel<T, RR, DIAG, DELTA, kTileSmall>), grid, block, 0, st, ops, \
+                               gt.tiles, nt, partials, s0);                                           \
+        else                                                                                          \
+            hipLaunchKernelGGL((gram_kernel<T, RR, DIAG, DELTA, kTile>), grid, block, 0, st, ops,     \
+                               gt.tiles, nt, partials, s0);                                           \
+    } while (0)
     switch (R) {
         case 2: ADASUM_GRAM(2); break;
         case 4: ADASUM_GRAM(4); break;
@@ -971,7 +1052,8 @@ int launch_norm_coarsen(const double* fine, int n_nodes, const TileSet& ct, cons
 }
 
 int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups, int R,
-                       const double* partials, const double* normparts, double* gram, void* stream) {
+                       const double* partials, const double* normparts, double* gram, double* weights, int order,
+                       int K_leaves, int depth, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const long long blocks = static_cast<long long>(n_groups) * n_layers;
     if (blocks == 0) return 0;
@@ -980,7 +1062,7 @@ int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups,
     const int ngt = static_cast<int>(gt.n_tiles);
 #define ADASUM_FINISH(RR, DD)                                                                      \
     hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
-                       gt.layer_begin, ngt, n_layers, gram)
+                       gt.layer_begin, ngt, n_layers, gram, weights, order, K_leaves, depth)
     switch (R) {
         case 2: if (diag) ADASUM_FINISH(2, true); else ADASUM_FINISH(2, false); break;
         case 4: if (diag) ADASUM_FINISH(4, true); else ADASUM_FINISH(4, false); break;

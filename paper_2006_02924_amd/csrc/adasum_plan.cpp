@@ -111,6 +111,10 @@ int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity
     return n;
 }
 
+int gram_tile_capacity(const int64_t* layer_offsets, int n_layers) {
+    return count_tiles(layer_offsets, n_layers, kTile) < kFewTiles ? kTileSmall : kTile;
+}
+
 int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
                            int node_type) {
     int64_t need = 1;
