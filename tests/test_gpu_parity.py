@@ -285,8 +285,14 @@ def test_config5_edge_cases_scaled():
 def test_graph_replay_matches_eager():
     say("hipGraph replay vs eager launches")
     sizes = W.scaled_down(W.resnet50_layer_sizes(), 16, floor=3)
-    for K, dtype, radix in ((8, torch.bfloat16, 0), (64, torch.float32, 16), (4, torch.float32, 2), (1, torch.bfloat16, 0)):
-        w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=31 + K)
+    # floor=3 leaves many layers of 3..16 elements: the small-layer kernels are part of the graph;
+    # K = 6 and 100 have short first-pass groups; fp64 uses its own node type
+    for K, dtype, radix in ((8, torch.bfloat16, 0), (64, torch.float32, 16), (4, torch.float32, 2), (1, torch.bfloat16, 0),
+                            (6, torch.bfloat16, 4), (100, torch.float16, 0), (16, torch.float64, 0)):
+        w = W.correlated_gaussian(sizes, K, dtype=torch.float32 if dtype == torch.float64 else dtype, device=DEV,
+                                  seed=31 + K)
+        if dtype == torch.float64:
+            w.grads = [g.double() for g in w.grads]
         stats_e = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
         stats_g = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
         out_e = torch.empty(w.N, dtype=dtype, device=DEV)
