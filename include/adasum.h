@@ -150,6 +150,33 @@ ADASUM_API int adasum_reduce_ex(const void* const* grads, int K,
 ADASUM_API int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
                            int dtype, const adasum_options* opts, size_t* bytes);
 
+/* ---- plans the caller owns ----
+ *
+ * adasum_reduce(_ex) look their plan up in a cache by shape on every call.  A caller
+ * that reduces the same shape again and again can hold the plan itself: tile tables
+ * on the current device, the pass schedule, captured graphs and (unless a workspace is
+ * given) the plan's own workspace, allocated on the first execute.
+ *
+ *   opts   as for adasum_reduce_ex; out_dtype, radix, order, use_graph and
+ *          workspace / workspace_bytes are fixed for the plan's lifetime;
+ *          layer_stats must be NULL here (it is an argument of execute);
+ *          delta_start != NULL (any 16-byte aligned value) plans for the delta form of
+ *          Section 4.1: every execute must then pass a delta_start, else none may
+ *   plan   receives the handle; destroy it with adasum_plan_destroy (waits for the
+ *          device).  adasum_shutdown does not touch it.
+ * Executes on one plan must be stream-ordered (they share its workspace).
+ */
+typedef struct adasum_plan adasum_plan;
+ADASUM_API int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                                  const adasum_options* opts, adasum_plan** plan);
+/* grads: HOST array of K DEVICE pointers; out, layer_stats (or NULL), delta_start (or
+ * NULL): DEVICE, as in adasum_reduce_ex.  Same checks, same errors. */
+ADASUM_API int adasum_plan_execute(adasum_plan* plan, const void* const* grads, void* out,
+                                   double* layer_stats, const void* delta_start, void* stream);
+/* Bytes of workspace the plan uses (what adasum_workspace_bytes reports for its shape). */
+ADASUM_API int adasum_plan_workspace_bytes(const adasum_plan* plan, size_t* bytes);
+ADASUM_API int adasum_plan_destroy(adasum_plan* plan);
+
 /* ---- the steps of one tree level, exposed so that each can be checked alone ---- */
 
 /*

@@ -26,6 +26,7 @@ ERR_OUT_OF_MEMORY, ERR_HIP, ERR_WORKSPACE, ERR_ALIAS = -4, -5, -6, -7
 
 EXPORTS = [
     "adasum_reduce", "adasum_reduce_ex", "adasum_workspace_bytes",
+    "adasum_plan_create", "adasum_plan_execute", "adasum_plan_workspace_bytes", "adasum_plan_destroy",
     "adasum_group_gram", "adasum_group_weights", "adasum_group_combine",
     "adasum_tile_capacity", "adasum_plan_tiles", "adasum_plan_levels", "adasum_plan_groups",
     "adasum_profile_enable", "adasum_profile_collect",
@@ -217,14 +218,83 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
     return out
 
 
+class Plan:
+    """A plan the caller owns (``adasum_plan_create`` .. ``adasum_plan_destroy``) for one
+    problem shape; ``execute`` reduces K tensors of that shape."""
+
+    def __init__(self, K: int, layer_offsets: Sequence[int], dtype, *, out_dtype=None, radix: int = 0,
+                 order: int = ORDER_TREE, use_graph: bool = False, workspace=None, delta: bool = False):
+        lib = load()
+        offs, L = _offsets(layer_offsets)
+        self.K, self.N = K, int(layer_offsets[-1])
+        self.in_code = _code_of(dtype)
+        self.out_code = self.in_code if out_dtype is None else _code_of(out_dtype)
+        self.delta = delta
+        self._workspace = workspace          # keep the tensor alive
+        o = Options()
+        o.struct_bytes = C.sizeof(Options)
+        o.out_dtype = self.out_code
+        o.radix = radix
+        o.order = order
+        o.use_graph = 1 if use_graph else 0
+        if workspace is not None:
+            o.workspace = workspace.data_ptr()
+            o.workspace_bytes = workspace.numel() * workspace.element_size()
+        if delta:
+            o.delta_start = 0x100            # "set": the pointer itself comes with every execute
+        self._h = C.c_void_p(None)
+        check(lib.adasum_plan_create(K, offs, L, self.in_code, C.byref(o), C.byref(self._h)))
+
+    def workspace_bytes(self) -> int:
+        n = C.c_size_t(0)
+        check(load().adasum_plan_workspace_bytes(self._h, C.byref(n)))
+        return int(n.value)
+
+    def execute(self, grads: Sequence, out=None, *, layer_stats=None, delta_start=None, stream=None):
+        import torch
+        if len(grads) != self.K:
+            raise ValueError("the plan was made for another number of workers")
+        _check_inputs(grads, self.N)
+        if _dtype_code(grads[0]) != self.in_code:
+            raise ValueError("the plan was made for another dtype")
+        if out is None:
+            out = torch.empty(self.N, dtype=_torch_dtype(self.out_code), device=grads[0].device)
+        elif _dtype_code(out) != self.out_code or out.numel() != self.N or not out.is_contiguous():
+            raise ValueError("out has the wrong dtype, size or layout")
+        stats_ptr = None
+        if layer_stats is not None:
+            if layer_stats.dtype != torch.float64 or not layer_stats.is_contiguous():
+                raise ValueError("layer_stats must be a contiguous float64 tensor of n_layers x 2")
+            stats_ptr = C.c_void_p(layer_stats.data_ptr())
+        start_ptr = None
+        if delta_start is not None:
+            _check_inputs([delta_start], self.N)
+            start_ptr = C.c_void_p(delta_start.data_ptr())
+        check(load().adasum_plan_execute(self._h, _ptr_array(grads), C.c_void_p(out.data_ptr()), stats_ptr,
+                                         start_ptr, _stream(stream)))
+        return out
+
+    def destroy(self) -> None:
+        if self._h:
+            check(load().adasum_plan_destroy(self._h))
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
 def adasum_workspace_bytes(K: int, layer_offsets: Sequence[int], dtype_code: int, *, radix: int = 0,
-                           out_dtype_code: int = -1, delta: bool = False) -> int:
+                           out_dtype_code: int = -1, delta: bool = False, order: int = ORDER_TREE) -> int:
     lib = load()
     offs, L = _offsets(layer_offsets)
     o = Options()
     o.struct_bytes = C.sizeof(Options)
     o.out_dtype = out_dtype_code
     o.radix = radix
+    o.order = order
     if delta:
         o.delta_start = 0x100   # only "set or not" matters for the size
     n = C.c_size_t(0)

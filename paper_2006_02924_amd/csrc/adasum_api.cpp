@@ -227,22 +227,11 @@ std::mutex g_mutex;
 std::vector<std::unique_ptr<Plan>> g_plans;   // least recently used first
 constexpr size_t kMaxPlans = 64;
 
-int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers, Plan** out) {
+// Builds a plan (host tables, their device copies; no workspace yet) on the current device.
+int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers,
+              std::unique_ptr<Plan>& out) {
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
-    for (size_t i = 0; i < g_plans.size(); ++i) {
-        Plan* p = g_plans[i].get();
-        if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
-            static_cast<int>(p->offsets.size()) == n_layers + 1 &&
-            std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
-            // most recently used last
-            std::rotate(g_plans.begin() + i, g_plans.begin() + i + 1, g_plans.end());
-            *out = p;
-            return ADASUM_OK;
-        }
-    }
-    // a bounded cache: the least recently used plan goes (hipFree waits for work in flight)
-    while (g_plans.size() >= kMaxPlans) g_plans.erase(g_plans.begin());
     std::unique_ptr<Plan> p(new (std::nothrow) Plan());
     if (!p) return ADASUM_ERR_OUT_OF_MEMORY;
     try {
@@ -273,6 +262,30 @@ int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t*
         ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_small), bytes));
         ADASUM_HIP(hipMemcpy(p->d_small, p->small.data(), bytes, hipMemcpyHostToDevice));
     }
+    out = std::move(p);
+    return ADASUM_OK;
+}
+
+// The library's own cache of plans, keyed by shape.
+int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers, Plan** out) {
+    int device = 0;
+    ADASUM_HIP(hipGetDevice(&device));
+    for (size_t i = 0; i < g_plans.size(); ++i) {
+        Plan* p = g_plans[i].get();
+        if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
+            static_cast<int>(p->offsets.size()) == n_layers + 1 &&
+            std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
+            // most recently used last
+            std::rotate(g_plans.begin() + i, g_plans.begin() + i + 1, g_plans.end());
+            *out = p;
+            return ADASUM_OK;
+        }
+    }
+    // a bounded cache: the least recently used plan goes (hipFree waits for work in flight)
+    while (g_plans.size() >= kMaxPlans) g_plans.erase(g_plans.begin());
+    std::unique_ptr<Plan> p;
+    const int rc = make_plan(K, radix, order, node_type, offsets, n_layers, p);
+    if (rc != ADASUM_OK) return rc;
     *out = p.get();
     g_plans.push_back(std::move(p));
     return ADASUM_OK;
@@ -719,18 +732,9 @@ int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void
     return ADASUM_OK;
 }
 
-int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
-                void* out, const adasum_options* opts, void* stream) {
-    if (K < 1) return ADASUM_ERR_INVALID_ARG;
-    int rc = check_layer_table(layer_offsets, n_layers);
-    if (rc != ADASUM_OK) return rc;
-    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
-    Opts o;
-    rc = read_opts(opts, dtype, o);
-    if (rc != ADASUM_OK) return rc;
-    if (K > (1 << 20)) return ADASUM_ERR_UNSUPPORTED;
-    const int64_t N = layer_offsets[n_layers];
-    rc = check_operands(grads, K, N, dtype);
+// Checks of one call's buffers against a problem shape (no device work).
+int check_call(const void* const* grads, int K, int64_t N, int dtype, void* out, const Opts& o) {
+    int rc = check_operands(grads, K, N, dtype);
     if (rc != ADASUM_OK) return rc;
     if (out == nullptr && N > 0) return ADASUM_ERR_INVALID_ARG;
     if (!aligned16(out)) return ADASUM_ERR_MISALIGNED;
@@ -742,19 +746,40 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     // out may BE delta_start (every element is read by the lane that then writes it) but not straddle it
     if (o.delta_start != nullptr && o.delta_start != out && overlaps(o.delta_start, in_bytes, out, out_bytes))
         return ADASUM_ERR_ALIAS;
+    return ADASUM_OK;
+}
+
+// Enqueues one reduction with a plan.  g_mutex held.
+int execute_plan(Plan* p, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
+    char* ws = nullptr;
+    const int rc = plan_workspace(p, o, &ws);
+    if (rc != ADASUM_OK) return rc;
+    if (o.use_graph && !g_profile) return launch_as_graph(p, ws, grads, dtype, out, o, stream);
+    if (p->K == 1) return run_copy(p, ws, grads, dtype, out, o, stream);
+    if (o.order == ADASUM_ORDER_LINEAR) return run_linear(p, ws, grads, dtype, out, o, stream);
+    return run_tree(p, ws, grads, dtype, out, o, stream);
+}
+
+int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                void* out, const adasum_options* opts, void* stream) {
+    if (K < 1) return ADASUM_ERR_INVALID_ARG;
+    int rc = check_layer_table(layer_offsets, n_layers);
+    if (rc != ADASUM_OK) return rc;
+    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
+    Opts o;
+    rc = read_opts(opts, dtype, o);
+    if (rc != ADASUM_OK) return rc;
+    if (K > (1 << 20)) return ADASUM_ERR_UNSUPPORTED;
+    const int64_t N = layer_offsets[n_layers];
+    rc = check_call(grads, K, N, dtype, out, o);
+    if (rc != ADASUM_OK || N == 0) return rc;
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
     rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, node_dtype(dtype), layer_offsets,
                            n_layers, &p);
     if (rc != ADASUM_OK) return rc;
-    char* ws = nullptr;
-    rc = plan_workspace(p, o, &ws);
-    if (rc != ADASUM_OK) return rc;
-    if (o.use_graph && !g_profile) return launch_as_graph(p, ws, grads, dtype, out, o, stream);
-    if (K == 1) return run_copy(p, ws, grads, dtype, out, o, stream);
-    if (o.order == ADASUM_ORDER_LINEAR) return run_linear(p, ws, grads, dtype, out, o, stream);
-    return run_tree(p, ws, grads, dtype, out, o, stream);
+    return execute_plan(p, grads, dtype, out, o, stream);
 }
 
 }  // namespace
@@ -762,7 +787,77 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
 
 using namespace adasum;
 
+// A plan the caller owns (adasum_plan_create): not part of the library's cache.
+struct adasum_plan {
+    std::unique_ptr<Plan> plan;   // null for an empty problem (N = 0)
+    int dtype = ADASUM_F32;
+    Opts opts{};                  // as fixed at creation; layer_stats / delta_start per execute
+    bool for_delta = false;
+};
+
 extern "C" {
+
+int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dtype, const adasum_options* opts,
+                       adasum_plan** plan) {
+    if (plan == nullptr || K < 1) return ADASUM_ERR_INVALID_ARG;
+    *plan = nullptr;
+    int rc = check_layer_table(layer_offsets, n_layers);
+    if (rc != ADASUM_OK) return rc;
+    if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
+    Opts o;
+    rc = read_opts(opts, dtype, o);
+    if (rc != ADASUM_OK) return rc;
+    if (K > (1 << 20)) return ADASUM_ERR_UNSUPPORTED;
+    if (o.layer_stats != nullptr) return ADASUM_ERR_INVALID_ARG;   // given per execute
+    std::unique_ptr<adasum_plan> h(new (std::nothrow) adasum_plan());
+    if (!h) return ADASUM_ERR_OUT_OF_MEMORY;
+    h->dtype = dtype;
+    h->for_delta = o.delta_start != nullptr;
+    h->opts = o;
+    h->opts.radix = o.radix == 0 ? default_radix(o) : o.radix;
+    h->opts.delta_start = nullptr;
+    if (layer_offsets[n_layers] > 0) {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), layer_offsets, n_layers, h->plan);
+        if (rc != ADASUM_OK) return rc;
+        if (o.workspace != nullptr && o.workspace_bytes < h->plan->lay.total) return ADASUM_ERR_WORKSPACE;
+    }
+    *plan = h.release();
+    return ADASUM_OK;
+}
+
+int adasum_plan_execute(adasum_plan* plan, const void* const* grads, void* out, double* layer_stats,
+                        const void* delta_start, void* stream) {
+    if (plan == nullptr) return ADASUM_ERR_INVALID_ARG;
+    Opts o = plan->opts;
+    o.layer_stats = layer_stats;
+    o.delta_start = delta_start;
+    if (layer_stats != nullptr) {
+        if ((reinterpret_cast<uintptr_t>(layer_stats) & 7u) != 0) return ADASUM_ERR_MISALIGNED;
+        if (o.order == ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
+    }
+    if ((delta_start != nullptr) != plan->for_delta) return ADASUM_ERR_INVALID_ARG;
+    if (delta_start != nullptr && !aligned16(delta_start)) return ADASUM_ERR_MISALIGNED;
+    if (!plan->plan) return ADASUM_OK;   // N = 0
+    Plan* p = plan->plan.get();
+    const int rc = check_call(grads, p->K, p->lay.N, plan->dtype, out, o);
+    if (rc != ADASUM_OK) return rc;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    return execute_plan(p, grads, plan->dtype, out, o, stream);
+}
+
+int adasum_plan_workspace_bytes(const adasum_plan* plan, size_t* bytes) {
+    if (plan == nullptr || bytes == nullptr) return ADASUM_ERR_INVALID_ARG;
+    *bytes = plan->plan ? plan->plan->lay.total : 0;
+    return ADASUM_OK;
+}
+
+int adasum_plan_destroy(adasum_plan* plan) {
+    if (plan == nullptr) return ADASUM_OK;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    delete plan;   // frees tables, graphs and the plan's own workspace (hipFree waits for work in flight)
+    return ADASUM_OK;
+}
 
 int adasum_reduce(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
                   void* out, void* stream) {

@@ -160,3 +160,27 @@ def test_workspace_bytes(lib):
     assert n.value > 0
     assert B.adasum_workspace_bytes(3, offs, B.F32, radix=2) >= 2 * 70656 * 4
     assert lib.adasum_workspace_bytes(4, o, 3, B.F32, None, None) == B.ERR_INVALID_ARG
+
+
+def test_plan_entry_points_validate(lib):
+    offs = (C.c_int64 * 3)(0, 10, 30)
+    h = C.c_void_p(None)
+    assert lib.adasum_plan_create(4, offs, 2, B.F32, None, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_plan_create(0, offs, 2, B.F32, None, C.byref(h)) == B.ERR_INVALID_ARG
+    assert lib.adasum_plan_create(4, offs, 2, 9, None, C.byref(h)) == B.ERR_UNSUPPORTED
+    assert lib.adasum_plan_create(4, offs, 2, B.F64, C.byref(_opts(radix=16)), C.byref(h)) == B.ERR_UNSUPPORTED
+    assert lib.adasum_plan_create(4, offs, 2, B.F32, C.byref(_opts(layer_stats=0x9000)), C.byref(h)) \
+        == B.ERR_INVALID_ARG
+    assert h.value is None
+    assert lib.adasum_plan_execute(None, None, None, None, None, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_plan_destroy(None) == B.OK
+    # an empty problem needs no device: the plan exists and executes as a no-op
+    empty = (C.c_int64 * 2)(0, 0)
+    assert lib.adasum_plan_create(2, empty, 1, B.BF16, None, C.byref(h)) == B.OK
+    n = C.c_size_t(7)
+    assert lib.adasum_plan_workspace_bytes(h, C.byref(n)) == B.OK and n.value == 0
+    x = (C.c_void_p * 2)(0, 0)
+    assert lib.adasum_plan_execute(h, x, None, None, None, None) == B.OK
+    # a plan made without the delta form refuses a delta_start, and the other way round
+    assert lib.adasum_plan_execute(h, x, None, None, 0x5000, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_plan_destroy(h) == B.OK

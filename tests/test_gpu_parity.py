@@ -673,3 +673,51 @@ def test_many_workers(K, radix):
     lin = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, order=B.ORDER_LINEAR)
     torch.cuda.synchronize()
     assert_parity(lin, oracle_reduce(w.grads, w.layer_offsets, order="linear"), w.layer_offsets, what=f"K={K} linear")
+
+
+def test_caller_owned_plans():
+    """adasum_plan_create / execute / destroy give the bits of adasum_reduce_ex, execute after
+    execute, with new values in the same buffers, the plan's own or a caller's workspace,
+    statistics per execute, the delta form, and graph replay."""
+    sizes = np.diff(RAGGED).tolist()
+    for K, dtype, radix, order in ((8, torch.bfloat16, 0, B.ORDER_TREE), (5, torch.float32, 4, B.ORDER_TREE),
+                                   (16, torch.float16, 0, B.ORDER_LINEAR), (64, torch.float64, 0, B.ORDER_TREE)):
+        say(f"plan K={K} {dtype} radix={radix} order={order}")
+        w = W.correlated_gaussian(sizes, K, dtype=torch.float32 if dtype == torch.float64 else dtype, device=DEV,
+                                  seed=40 + K)
+        if dtype == torch.float64:
+            w.grads = [g.double() for g in w.grads]
+        plan = B.Plan(K, w.layer_offsets, dtype, radix=radix, order=order)
+        assert plan.workspace_bytes() == B.adasum_workspace_bytes(K, w.layer_offsets, B._code_of(dtype), radix=radix,
+                                                                  order=order)
+        ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=DEV)
+        ws = ws[(-ws.data_ptr()) % 256:][:plan.workspace_bytes()]
+        plan_ws = B.Plan(K, w.layer_offsets, dtype, radix=radix, order=order, workspace=ws, use_graph=True)
+        for rep in range(3):
+            for i, g in enumerate(w.grads):
+                g.mul_(1.0 + 0.5 * ((i + rep) % 2))
+            want = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, order=order)
+            got = plan.execute(w.grads)
+            got_ws = plan_ws.execute(w.grads)
+            torch.cuda.synchronize()
+            assert torch.equal(got, want) and torch.equal(got_ws, want), (K, dtype, rep)
+        if order == B.ORDER_TREE:
+            stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+            stats_want = torch.zeros_like(stats)
+            B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, layer_stats=stats_want)
+            plan.execute(w.grads, layer_stats=stats)
+            torch.cuda.synchronize()
+            assert torch.equal(stats, stats_want)
+        with pytest.raises(B.AdasumError):
+            plan.execute(w.grads, delta_start=w.grads[0].clone())
+        plan.destroy()
+        plan_ws.destroy()
+    d = W.after_local_step(sizes, 8, dtype=torch.float32, device=DEV, seed=77, step=0.25)
+    plan = B.Plan(8, d.layer_offsets, torch.float32, delta=True)
+    want = B.adasum_reduce(d.grads, d.layer_offsets, delta_start=d.meta["start"])
+    got = plan.execute(d.grads, delta_start=d.meta["start"])
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    with pytest.raises(B.AdasumError):
+        plan.execute(d.grads)
+    plan.destroy()
