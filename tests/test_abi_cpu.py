@@ -184,3 +184,27 @@ def test_plan_entry_points_validate(lib):
     # a plan made without the delta form refuses a delta_start, and the other way round
     assert lib.adasum_plan_execute(h, x, None, None, 0x5000, None) == B.ERR_INVALID_ARG
     assert lib.adasum_plan_destroy(h) == B.OK
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/adasum.h compiles as C (gcc, C99, pedantic): no C++ or HIP types at the boundary."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "adasum.h"\n'
+        "int main(void) {\n"
+        "    adasum_options o = {0};\n"
+        "    adasum_plan* p = 0;\n"
+        "    o.struct_bytes = (uint32_t)sizeof o;\n"
+        "    return (adasum_plan_create(0, 0, 0, ADASUM_F32, &o, &p) == ADASUM_ERR_INVALID_ARG &&\n"
+        "            adasum_reduce(0, 0, 0, 0, ADASUM_BF16, 0, 0) == ADASUM_ERR_INVALID_ARG) ? 0 : 1;\n"
+        "}\n")
+    exe = tmp_path / "use_header"
+    libdir = os.path.join(ROOT, "paper_2006_02924_amd")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-ladasum", f"-Wl,-rpath,{libdir}"], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0
