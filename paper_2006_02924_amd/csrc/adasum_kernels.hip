@@ -606,35 +606,20 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
 }
 
 // ---------------------------------------------------------------------------
-// Step 2b: Gram matrix -> weights of the tree over R leaves.
-// Every node of the tree is a combination of its leaves, node = sum_p w_p x_p;
-// for two sibling nodes A and B the operator of Section 3 needs
-//   d = A.B = sum_{p in A, q in B} w_p w_q G_pq,  n1 = |A|^2,  n2 = |B|^2
-// and scales A's weights by 1 - d/(2 n1) and B's by 1 - d/(2 n2).  A zero
-// squared norm gives coefficient 1.  fp64 throughout.
+// Step 2b on its own (the step entry point): Gram matrices -> weights of the tree over R
+// leaves, one wave per (group, layer) item, the same routine the finish kernel runs.
 // ---------------------------------------------------------------------------
-template <int R>
-__device__ __forceinline__ void merge_nodes(const double* G, double (&w)[R], int a0, int a1, int b0, int b1) {
-    double d = 0.0, n1 = 0.0, n2 = 0.0;
-    for (int p = a0; p < a1; ++p)
-        for (int q = a0; q < a1; ++q) n1 += w[p] * w[q] * G[p * R + q];
-    for (int p = b0; p < b1; ++p)
-        for (int q = b0; q < b1; ++q) n2 += w[p] * w[q] * G[p * R + q];
-    for (int p = a0; p < a1; ++p)
-        for (int q = b0; q < b1; ++q) d += w[p] * w[q] * G[p * R + q];
-    const double ca = n1 > 0.0 ? 1.0 - d / (2.0 * n1) : 1.0;
-    const double cb = n2 > 0.0 ? 1.0 - d / (2.0 * n2) : 1.0;
-    for (int p = a0; p < a1; ++p) w[p] *= ca;
-    for (int q = b0; q < b1; ++q) w[q] *= cb;
-}
-
 template <int R>
 __global__ void __launch_bounds__(64)
 weights_kernel(const double* __restrict__ gram, long long n_items, int order, int n_layers, int K_leaves,
                int depth, double* __restrict__ weights) {
-    const long long item = static_cast<long long>(blockIdx.x) * 64 + threadIdx.x;
+    __shared__ double shG[R * R];
+    __shared__ double shW[R];
+    const long long item = blockIdx.x;
+    const int lane = threadIdx.x;
     if (item >= n_items) return;
-    const double* G = gram + item * (R * R);
+    for (int i = lane; i < R * R; i += 64) shG[i] = gram[item * (R * R) + i];
+    __builtin_amdgcn_wave_barrier();
     // leaves this group really holds (its first r operands; the rest is padding)
     int r = R;
     if (K_leaves > 0) {
@@ -642,30 +627,8 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, in
         leaf_range(K_leaves, depth, static_cast<int>(item / n_layers), lo, hi);
         r = hi - lo;
     }
-    double w[R];
-    for (int p = 0; p < R; ++p) w[p] = p < r ? 1.0 : 0.0;
-    if (order == ADASUM_ORDER_LINEAR) {
-        for (int k = 1; k < r; ++k) merge_nodes<R>(G, w, 0, k, k, k + 1);
-    } else if (r == R) {
-        // the balanced tree over all R leaves, level by level
-        for (int span = 1; span < R; span *= 2)
-            for (int j = 0; j < R; j += 2 * span) merge_nodes<R>(G, w, j, j + span, j + span, j + 2 * span);
-    } else {
-        // the halving tree over r leaves, deepest nodes first: children before parents
-        int levels = 0;
-        while ((1 << levels) < r) ++levels;
-        for (int d = levels - 1; d >= 0; --d) {
-            for (int j = 0; j < (1 << d); ++j) {
-                int lo, hi;
-                leaf_range(r, d, j, lo, hi);
-                if (hi - lo >= 2) {
-                    const int mid = lo + (hi - lo) / 2;
-                    merge_nodes<R>(G, w, lo, mid, mid, hi);
-                }
-            }
-        }
-    }
-    for (int p = 0; p < R; ++p) weights[item * R + p] = w[p];
+    wave_tree_weights<R>(shG, shW, r, order, lane);
+    if (lane < R) weights[item * R + lane] = shW[lane];
 }
 
 // ---------------------------------------------------------------------------
@@ -1078,7 +1041,7 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order, int n_
                    double* weights, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_items == 0) return 0;
-    const long long blocks = (n_items + 63) / 64;
+    const long long blocks = n_items;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
     const dim3 grid(static_cast<unsigned>(blocks)), block(64);
     const long long n = n_items;
