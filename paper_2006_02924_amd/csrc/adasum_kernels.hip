@@ -244,6 +244,32 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// Sums every one of N per-lane values over the 64 lanes of a wave with N + N/2 + ... shuffles
+// instead of 6 N: at the step with mask m a lane whose bit m is clear keeps the even-indexed
+// values and hands the odd-indexed ones to its partner (and the other way round), so each step
+// halves the number of values a lane carries.  On return lane l holds in v[i] the complete sum
+// of value number l + 64 i (values past N are padding).  Fixed order: bit-identical reruns.
+template <typename A, int N>
+__device__ __forceinline__ void wave_sum_scatter(A (&v)[N], int lane) {
+    static_assert(N >= 1, "");
+    int n = N;
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const bool upper = (lane & m) != 0;
+        const int half = (n + 1) / 2;
+#pragma unroll
+        for (int i = 0; i < (N + 1) / 2; ++i) {
+            if (i < half) {
+                const A a = v[2 * i];
+                const A b = (2 * i + 1 < n) ? v[2 * i + 1] : static_cast<A>(0);
+                const A keep = upper ? b : a, send = upper ? a : b;
+                v[i] = keep + __shfl_xor(send, m, 64);
+            }
+        }
+        n = half;
+    }
+}
+
 template <int R>
 __device__ __forceinline__ const void* operand_ptr(const Operands& ops, int g, int r) {
     return ops.pack[g * R + r];
@@ -411,10 +437,12 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
             }
         }
     }
+    // the wave's lanes added in the lanes' precision; lane l ends up with entries l, l + 64, ...
+    wave_sum_scatter(acc, lane);
 #pragma unroll
-    for (int e = 0; e < NP; ++e) {
-        const acc_t w = wave_sum(acc[e]);
-        if (lane == 0) sh[wave][e] = static_cast<double>(w);
+    for (int i = 0; i < (NP + 63) / 64; ++i) {
+        const int e = lane + 64 * i;
+        if (e < NP) sh[wave][e] = static_cast<double>(acc[i]);
     }
     __syncthreads();
     if (tid < NP) {
