@@ -2,10 +2,11 @@
 //
 // One pass over a group of R sibling tree nodes does what Algorithm 1 does for
 // a pair: "partial dot products" (gram_kernel), "finish dot products"
-// (gram_finish_kernel), the scalars of the Section 3 operator walked up the
-// binary tree of Section 3.4 over the group's R leaves (weights_kernel), and
+// (gram_finish_kernel, which also walks the scalars of the Section 3 operator up
+// the tree of Section 3.4 over the group's R leaves: wave_tree_weights), and
 // "apply Adasum" (combine_kernel), which also accumulates the squared norm of
-// what it writes so the next pass needs only the cross dot products.
+// what it writes so the next pass needs only the cross dot products.  Layers
+// of a few elements are redone by the definition in fp64 (small_*_kernel).
 //
 // The work is HBM-bound streaming: no matrix cores.  Every workgroup owns one
 // tile (consecutive elements inside one layer): a long one (kTile elements) in
@@ -13,9 +14,9 @@
 // be amortised, and a short one (one 16-byte load per lane and operand) in the
 // combine pass, where short-lived workgroups keep the mixed read/write stream
 // near sequential.  64-wide waves issue 16-byte non-temporal loads that cover
-// 1 KiB of one operand per instruction; partial sums go lane (fp32) -> wave
-// (fp32 shuffles) -> workgroup (fp64 via LDS) -> per-tile fp64 partial in
-// memory, summed later in a fixed order; no atomics anywhere.
+// 1 KiB of one operand per instruction; partial sums go lane (fp32; fp64 for
+// fp64 storage) -> wave (shuffles) -> workgroup (fp64 via LDS) -> per-tile fp64
+// partial in memory, summed later in a fixed order; no atomics anywhere.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
