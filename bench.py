@@ -56,6 +56,8 @@ def parse_args():
     p.add_argument("--delta", action="store_true",
                    help="time the Adasum-after-optimizer form: the K buffers are parameters after a local step, "
                         "a starting-parameter buffer is subtracted on the fly and added back at the root")
+    p.add_argument("--single-layer", action="store_true",
+                   help="treat the whole buffer as one layer (isolates the cost of the layer structure)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-profile", action="store_true",
                    help="do not bracket kernels with HIP events in the timed region")
@@ -155,6 +157,8 @@ def main():
     print(f"[bench] {w.name}: K={w.K} N={w.N} layers={w.n_layers} dtype={w.dtype} "
           f"input={w.input_bytes / 1e9:.2f} GB generated in {time.perf_counter() - t0:.1f} s",
           file=sys.stderr, flush=True)
+    if args.single_layer:
+        w.layer_offsets = [0, w.N]
     if args.storage != "same":
         to = {"f16": torch.float16, "f64": torch.float64}[args.storage]
         for i in range(w.K):

@@ -140,7 +140,7 @@ struct Layout {
     int64_t norm_entries = 0; // doubles reserved for the combines' squared norms
     int     n_layers = 0;
     size_t  off_slots = 0;    // n_slots x slot_elems x node_bytes
-    size_t  off_partials = 0; // doubles [group][entry][tile], sized for the widest pass
+    size_t  off_partials = 0; // doubles [group][tile][entry], sized for the widest pass
     size_t  off_normparts = 0;// doubles [node][combine tile]: squared norm of every node a combine wrote
     size_t  off_normcoarse = 0;// doubles [node][Gram tile]: the same, summed per Gram tile
     size_t  off_gram = 0;     // doubles [group][layer][R*R] (finished Gram matrices)
@@ -194,7 +194,7 @@ struct TileSet {
 };
 
 // All launchers return a hipError_t as int (0 = success) and enqueue on `stream`.
-// partials[(group * entries + entry) * gt.n_tiles + tile]
+// partials[(group * gt.n_tiles + tile) * entries + entry]
 // delta_start (or null): operands are x_r - delta_start, same storage type as the operands; diag only.
 int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
                 double* partials, const void* delta_start, void* stream);

@@ -301,7 +301,8 @@ __device__ __forceinline__ Split split_tile(const adasum_tile& t) {
 // ---------------------------------------------------------------------------
 // Step 1: per-tile partial Gram entries of R operands.
 // Entry order: for i < R, for j from (DIAG ? i : i+1) to R-1.
-// partials[(group * NP + entry) * n_tiles + tile]
+// partials[(group * n_tiles + tile) * NP + entry]: one workgroup's entries side by side (written
+// entry-major, 136 scattered 8-byte stores per workgroup cost the radix-16 pass 9 %)
 // ---------------------------------------------------------------------------
 // DELTA: the operands are x_r - start (the "effective gradient" of Section 4.1:
 // parameters after the local step minus the parameters before it), formed on
@@ -451,7 +452,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) tot += sh[w][tid];
         if (nedge > 0) tot += sh_edge[tid];
-        partials[(static_cast<long long>(g) * NP + tid) * n_tiles + tile_id] = tot;
+        partials[(static_cast<long long>(g) * n_tiles + tile_id) * NP + tid] = tot;
     }
 }
 
@@ -555,17 +556,20 @@ __device__ __forceinline__ void wave_tree_weights(const double* G, double* w, in
     }
 }
 
-// One workgroup per (group, layer); its waves take the entries round-robin,
-// lanes stride over the layer's Gram tiles, a fixed-order wave reduction ends
-// each entry (no workgroup barrier).  When !DIAG the diagonal comes from the
+// One workgroup per (group, layer).  When !DIAG the diagonal comes from the
 // coarsened squared norms normparts[(group * R + i) * n_tiles + tile].
+// Threads of a finish workgroup: enough rows of entries side by side to keep many loads in
+// flight (radix 16 has 136 entries per tile row).
+constexpr int finish_threads(int R) { return R >= 16 ? 1024 : kThreads; }
+
 template <int R, bool DIAG>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(finish_threads(R))
 gram_finish_kernel(const double* __restrict__ partials, const double* __restrict__ normparts,
                    const int32_t* __restrict__ layer_tile_begin, int n_tiles, int n_layers,
                    double* __restrict__ gram, double* __restrict__ weights, int order, int K_leaves, int depth) {
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
-    constexpr int NW = kThreads / 64;
+    constexpr int THREADS = finish_threads(R);
+    constexpr int NW = THREADS / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_layers));
     const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_layers));
@@ -574,37 +578,40 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
     __shared__ double shG[R * R];
     __shared__ double shW[R];
 
-    // kAhead entries per wave at a time, so that their loads are in flight together (a layer
-    // with hundreds of tiles is otherwise a chain of dependent fetches)
+    // partials[(group * n_tiles + tile) * NP + entry]: the layer's tiles form one contiguous run
+    // of NP-entry rows.  Thread (row, e) adds entry e of the tiles row, row + ROWS, ... (kAhead of
+    // them in flight together); consecutive threads read consecutive addresses.  The ROWS sums of
+    // an entry are then added in a fixed order.
+    constexpr int ROWS = THREADS / NP;   // tiles handled side by side (NP <= 136)
     constexpr int kAhead = 8;
-    for (int e0 = wave; e0 < NP; e0 += NW * kAhead) {
-        double v[kAhead];
-        const double* row[kAhead];
+    static_assert(ROWS >= 1, "more entries than threads");
+    __shared__ double shP[ROWS * NP];
+    {
+        const int row = static_cast<int>(threadIdx.x) / NP, e = static_cast<int>(threadIdx.x) % NP;
+        if (row < ROWS) {
+            double v = 0.0;
+            const double* base = partials + static_cast<long long>(g) * n_tiles * NP + e;
+            for (int t0 = tb + row; t0 < te; t0 += ROWS * kAhead) {
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            v[u] = 0.0;
-            const int e = e0 + u * NW < NP ? e0 + u * NW : e0;   // past the end: a row that exists, result unused
-            row[u] = partials + (static_cast<long long>(g) * NP + e) * n_tiles;
-        }
-        for (int t = tb + lane; t < te; t += 64) {
-#pragma unroll
-            for (int u = 0; u < kAhead; ++u) v[u] += row[u][t];
-        }
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const int e = e0 + u * NW;
-            if (e < NP) {
-                const double tot = wave_sum(v[u]);
-                if (lane == 0) {
-                    int i, j;
-                    entry_to_ij<R, DIAG>(e, i, j);
-                    out[i * R + j] = tot;
-                    out[j * R + i] = tot;
-                    shG[i * R + j] = tot;
-                    shG[j * R + i] = tot;
+                for (int u = 0; u < kAhead; ++u) {
+                    const int t = t0 + u * ROWS;
+                    if (t < te) v += base[static_cast<long long>(t) * NP];
                 }
             }
+            shP[row * NP + e] = v;
         }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < NP; e += THREADS) {
+        double tot = shP[e];
+#pragma unroll
+        for (int k = 1; k < ROWS; ++k) tot += shP[k * NP + e];
+        int i, j;
+        entry_to_ij<R, DIAG>(e, i, j);
+        out[i * R + j] = tot;
+        out[j * R + i] = tot;
+        shG[i * R + j] = tot;
+        shG[j * R + i] = tot;
     }
     if (!DIAG) {
         for (int i = wave; i < R; i += NW) {
@@ -1050,7 +1057,7 @@ int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups,
     const long long blocks = static_cast<long long>(n_groups) * n_layers;
     if (blocks == 0) return 0;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(finish_threads(R));
     const int ngt = static_cast<int>(gt.n_tiles);
 #define ADASUM_FINISH(RR, DD)                                                                      \
     hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
