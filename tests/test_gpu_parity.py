@@ -721,3 +721,37 @@ def test_caller_owned_plans():
     with pytest.raises(B.AdasumError):
         plan.execute(d.grads)
     plan.destroy()
+
+
+def test_two_host_threads_on_their_own_streams():
+    """Calls from two host threads (ctypes releases the GIL), each with its own shape -- hence its
+    own plan and workspace -- and its own stream: results stay right and deterministic."""
+    import threading
+    jobs = []
+    for K, seed in ((8, 1), (5, 2)):
+        w = W.correlated_gaussian(np.diff(RAGGED).tolist()[: 8 + K % 3], K, dtype=torch.bfloat16, device=DEV, seed=70 + seed)
+        jobs.append((w, oracle_reduce(w.grads, w.layer_offsets), torch.cuda.Stream(device=DEV)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(job):
+        w, ref, stream = job
+        try:
+            first = None
+            for _ in range(25):
+                out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=torch.float32, stream=stream)
+                stream.synchronize()
+                if first is None:
+                    first = out.clone()
+                    assert_parity(out, ref, w.layer_offsets, what=f"thread K={w.K}")
+                else:
+                    assert torch.equal(out, first)
+        except Exception as exc:   # surfaced in the main thread
+            errors.append(exc)
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
