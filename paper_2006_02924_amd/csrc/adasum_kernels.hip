@@ -818,25 +818,28 @@ small_gather_kernel(const Operands ops, int n_leaves, int leaf0, const SmallLaye
     }
 }
 
-// One lane per element; lanes past the layer's length hold zeros.
-__device__ __forceinline__ double small_pair(double a, double b) {
-    const double d = wave_sum(a * b), n1 = wave_sum(a * a), n2 = wave_sum(b * b);
+// One lane per element; lanes past the layer's length hold zeros.  A one-element layer needs no
+// sums over the lanes (lane 0 has the only products; the other lanes scale their zeros).
+__device__ __forceinline__ double small_pair(double a, double b, bool single) {
+    const double d = single ? a * b : wave_sum(a * b);
+    const double n1 = single ? a * a : wave_sum(a * a);
+    const double n2 = single ? b * b : wave_sum(b * b);
     const double ca = n1 > 0.0 ? 1.0 - d / (2.0 * n1) : 1.0;
     const double cb = n2 > 0.0 ? 1.0 - d / (2.0 * n2) : 1.0;
     return ca * a + cb * b;
 }
 
-// Is [lo, hi) a node of the halving tree over K leaves?
-__device__ __forceinline__ bool is_tree_node(int K, int lo, int hi) {
-    int a = 0, b = K;
-    while (a != lo || b != hi) {
-        if (b - a < 2) return false;
+// How many nodes of the halving tree over K leaves end with leaf k (k is their last leaf)?  Walking the
+// leaves left to right with a stack of finished sub-trees, that many merges of the two topmost follow
+// the push of leaf k.
+__device__ __forceinline__ int merges_after_leaf(int K, int k) {
+    int a = 0, b = K, count = 0;
+    while (b - a >= 2) {
+        if (b == k + 1) ++count;
         const int mid = a + (b - a) / 2;
-        if (hi <= mid) b = mid;
-        else if (lo >= mid) a = mid;
-        else return false;
+        if (k < mid) b = mid; else a = mid;
     }
-    return true;
+    return count;
 }
 
 template <typename TO>
@@ -847,43 +850,45 @@ small_reduce_kernel(const double* __restrict__ compact, int K, const SmallLayer*
     constexpr int kDepth = 34;   // a stack of complete sub-trees of distinct depths: at most log2(K) + 2
     constexpr int kAhead = 8;    // leaves fetched together (the fetches are what takes the time)
     __shared__ double vstack[kDepth][64];
-    __shared__ int slo[kDepth], shi[kDepth];   // the same in every lane
+    __shared__ int merges[64];   // per leaf of the current run of 64: merges that follow its push
     const SmallLayer s = small[blockIdx.x];
     const int lane = threadIdx.x;
     const bool live = lane < s.len;
+    const bool single = s.len == 1;
+    const bool linear = order == ADASUM_ORDER_LINEAR;
     const double* col = compact + s.coff + lane;
     double leafsq = 0.0, r = 0.0;
     int sp = 0;
     for (int k0 = 0; k0 < K; k0 += kAhead) {
+        if ((k0 & 63) == 0 && !linear) {
+            __syncthreads();
+            merges[lane] = k0 + lane < K ? merges_after_leaf(K, k0 + lane) : 0;
+            __syncthreads();
+        }
         double leaf[kAhead];
+        int todo[kAhead];
 #pragma unroll
-        for (int u = 0; u < kAhead; ++u)
+        for (int u = 0; u < kAhead; ++u) {
             leaf[u] = (live && k0 + u < K) ? col[static_cast<long long>(k0 + u) * small_elems] : 0.0;
+            todo[u] = linear ? 0 : merges[(k0 & 63) + u];
+        }
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             const int k = k0 + u;
             if (k >= K) break;
             const double v = leaf[u];
             leafsq += v * v;
-            if (order == ADASUM_ORDER_LINEAR) {
-                r = k == 0 ? v : small_pair(r, v);
+            if (linear) {
+                r = k == 0 ? v : small_pair(r, v, single);
                 continue;
             }
-            // tree order: leaves left to right; the two topmost sub-trees are merged as soon as
-            // together they form a node of the tree
-            vstack[sp][lane] = v;
-            slo[sp] = k;
-            shi[sp] = k + 1;
-            ++sp;
-            while (sp >= 2 && is_tree_node(K, slo[sp - 2], shi[sp - 1])) {
-                const double b = vstack[sp - 1][lane], a = vstack[sp - 2][lane];
-                vstack[sp - 2][lane] = small_pair(a, b);
-                shi[sp - 2] = shi[sp - 1];
-                --sp;
-            }
+            // tree order: the top of the stack stays in a register; each merge pops one sub-tree
+            if (k > 0) vstack[sp++][lane] = r;
+            r = v;
+            for (int m = 0; m < todo[u]; ++m) r = small_pair(vstack[--sp][lane], r, single);
         }
     }
-    if (order != ADASUM_ORDER_LINEAR) r = vstack[0][lane];   // sp == 1: the root [0, K)
+    // tree order: sp == 0 and r is the root [0, K)
     const double rsq = wave_sum(r * r);
     leafsq = wave_sum(leafsq);
     if (stats != nullptr && lane == 0) {
