@@ -127,3 +127,65 @@ def test_config5_full_size_edge_layers():
     del w
     B.shutdown()
     torch.cuda.empty_cache()
+
+
+def test_buffers_longer_than_2_31_elements():
+    """Element indices and byte offsets beyond 32 bits: K = 4 workers of 2^31 + 2^20 + 82 bf16
+    elements each (4.3 GB per buffer).  Checked against the oracle: the first layer, the layer
+    that straddles element 2^31, and every layer that starts beyond it; elsewhere the stored
+    values must be finite and the rerun identical."""
+    from oracle import adasum_oracle as O
+    from tests.gpu_util import TOL_BF16, TOL_BF16_TINY, TINY_LAYER
+
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60e9:
+        pytest.skip("needs ~60 GB of free HBM")
+    K = 4
+    sizes = [(1 << 26) + 5] + [1 << 26] * 31 + [1 << 20, 77]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    N = offs[-1]
+    assert N > (1 << 31) and offs[32] > (1 << 31) > offs[31]
+    gen = torch.Generator(device=DEV).manual_seed(77)
+    say(f"generating K={K} x N={N} bf16")
+    grads = []
+    common = None
+    for k in range(K + 1):
+        g = torch.empty(N, dtype=torch.bfloat16, device=DEV)
+        for l in range(len(sizes)):
+            g[offs[l]:offs[l + 1]].normal_(generator=gen)
+        if k == 0:
+            common = g
+        else:
+            g.mul_(0.8).add_(common, alpha=0.6)    # positively correlated workers
+            grads.append(g)
+    del common
+    torch.cuda.synchronize()
+    outs = {}
+    for out_dtype in (torch.bfloat16, torch.float32):
+        say(f"adasum_reduce -> {out_dtype}")
+        outs[out_dtype] = B.adasum_reduce(grads, offs, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+    again = B.adasum_reduce(grads, offs, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(again, outs[torch.bfloat16])
+    del again
+    layers = [0, 31, 32, 33]
+    for l in layers:
+        lo, hi = offs[l], offs[l + 1]
+        ref = O.adasum_tree([to_f64(g[lo:hi]) for g in grads])
+        for out_dtype, out in outs.items():
+            err = float(O.rel_l2_per_layer(to_f64(out[lo:hi]), ref, [0, hi - lo])[0])
+            tol = 1e-5 if out_dtype == torch.float32 else (TOL_BF16 if hi - lo >= TINY_LAYER else TOL_BF16_TINY)
+            say(f"  layer {l} [{lo}, {hi}) {out_dtype}: rel-L2 {err:.3e}")
+            assert err <= tol, (l, out_dtype, err)
+    for out in outs.values():
+        for l in range(len(sizes)):
+            assert bool(torch.isfinite(out[offs[l]:offs[l + 1]]).all()), l
+    # the fp32 and bf16 outputs are one rounding apart everywhere, also in the layers without an oracle value
+    for l in range(len(sizes)):
+        a = outs[torch.float32][offs[l]:offs[l + 1]]
+        b = outs[torch.bfloat16][offs[l]:offs[l + 1]].float()
+        assert bool(((a - b).abs() <= a.abs() * 2.0 ** -8 + 1e-30).all()), l
+    del grads, outs
+    B.shutdown()
+    torch.cuda.empty_cache()
