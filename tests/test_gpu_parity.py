@@ -174,6 +174,40 @@ def test_empty_and_degenerate_tables():
             assert_parity(out, oracle_reduce(g, offs), offs, what=str(offs))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K,radix", [(8, 0), (8, 2), (64, 0), (5, 0)])
+def test_nan_and_inf_stay_inside_their_layer(K, radix, dtype):
+    """IEEE propagation: a NaN or an infinity in one worker's layer makes that layer's result
+    NaN in every element (the scalars of the first node that sees it are NaN or Inf - Inf), in the
+    oracle and in the library alike; every other layer is reduced as if nothing had happened."""
+    say(f"non-finite inputs K={K} radix={radix} {dtype}")
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), K, dtype=dtype, device=DEV, seed=900 + K)
+    offs = list(w.layer_offsets)
+    poisoned = {2: (K - 1, 3, float("nan")),          # 7 elements: the small-layer path
+                6: (min(3, K - 1), 500, float("nan")),
+                7: (0, 16000, float("inf")),
+                8: (K // 2, 0, float("-inf"))}
+    for l, (k, e, v) in poisoned.items():
+        assert offs[l + 1] - offs[l] > e
+        w.grads[k][offs[l] + e] = v
+    with np.errstate(all="ignore"):
+        ref = O.adasum_reduce([to_f64(g) for g in w.grads], offs)
+    for out_dtype in (dtype, torch.float32):
+        out = B.adasum_reduce(w.grads, offs, out_dtype=out_dtype, radix=radix)
+        torch.cuda.synchronize()
+        got = to_f64(out)
+        tol = TOL_BF16 if out_dtype == torch.bfloat16 else TOL_F32
+        for l in range(len(offs) - 1):
+            lo, hi = offs[l], offs[l + 1]
+            if l in poisoned:
+                assert np.isnan(ref[lo:hi]).all(), l
+                assert np.isnan(got[lo:hi]).all(), (l, got[lo:hi][:8])
+            elif hi > lo:
+                assert np.isfinite(got[lo:hi]).all(), l
+                err = O.rel_l2_per_layer(got[lo:hi], ref[lo:hi], [0, hi - lo])[0]
+                assert err <= (tol if hi - lo >= 256 else max(tol, 2.0 ** -8 * 1.001 if out_dtype == torch.bfloat16 else tol)), (l, err)
+
+
 def test_deterministic_and_workspace_from_caller():
     say("determinism")
     sizes = W.scaled_down(W.resnet50_layer_sizes(), 16, floor=3)

@@ -298,6 +298,25 @@ def pin_after_optimizer(O):
     np.testing.assert_allclose(got[:5], start[:5] + 1.0, rtol=1e-15)
 
 
+def pin_non_finite_inputs(O):
+    """IEEE arithmetic on the Section 3 formula: one NaN or infinity in a layer of one worker makes
+    a scalar of the first node that sees it NaN (d or a norm is NaN, or Inf / Inf), so that node
+    and every ancestor is NaN in every element; other layers never see it (Section 3.6)."""
+    rng = np.random.default_rng(17)
+    for K in (2, 3, 8):
+        for bad in (np.nan, np.inf, -np.inf):
+            gs = [rng.standard_normal(14) for _ in range(K)]
+            gs[K // 2][9] = bad
+            clean = [g.copy() for g in gs]
+            clean[K // 2][9] = 0.25
+            with np.errstate(all="ignore"):
+                got = O.adasum_reduce(gs, [0, 6, 14])
+                lin = O.adasum_reduce(gs, [0, 6, 14], order="linear")
+            want = O.adasum_reduce(clean, [0, 6, 14])
+            assert np.isnan(got[6:]).all() and np.isnan(lin[6:]).all()
+            np.testing.assert_array_equal(got[:6], want[:6])
+
+
 PINS = [
     pin_closed_form_two_vectors,
     pin_worked_tree_fixture,
@@ -315,6 +334,7 @@ PINS = [
     pin_low_precision_inputs_are_widened,
     pin_after_optimizer,
     pin_worker_counts_that_are_no_power_of_two,
+    pin_non_finite_inputs,
 ]
 
 
