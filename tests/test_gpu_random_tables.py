@@ -1,0 +1,82 @@
+"""GPU parity on seeded random cases: worker count, storage and output type, radix,
+order, statistics and the layer table (empty, tiny, ragged, around the tile sizes,
+up to 200 000 elements) are all drawn per case; every layer is compared with the
+fp64 oracle to the bars of the other parity tests.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2006_02924_amd import binding as B
+from paper_2006_02924_amd import workloads as W
+from tests.gpu_util import assert_parity, oracle_reduce, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+CASES_PER_BLOCK = 10
+
+
+def draw_case(case):
+    rng = np.random.default_rng(10_000 + case)
+    K = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 11, 16, 17, 24, 32, 40]))
+    dtype = [torch.float32, torch.bfloat16, torch.float16, torch.float64][int(rng.integers(4))]
+    out_dtype = dtype
+    if dtype in (torch.bfloat16, torch.float16) and rng.random() < 0.5:
+        out_dtype = torch.float32
+    radix = int(rng.choice([0, 2, 4, 8, 16]))
+    if dtype == torch.float64 and radix == 16:
+        radix = 8                                    # fp64 passes take at most 8 workers
+    order = "tree" if rng.random() < 0.7 else "linear"
+    sizes = []
+    for _ in range(int(rng.integers(1, 12))):
+        kind = int(rng.integers(6))
+        if kind == 0:
+            sizes.append(0)
+        elif kind == 1:
+            sizes.append(int(rng.integers(1, 20)))
+        elif kind == 2:
+            sizes.append(int(rng.integers(20, 3000)))
+        elif kind == 3:
+            sizes.append(int(rng.choice([2048, 16384, 65536]) + rng.integers(-9, 10)))
+        elif kind == 4:
+            sizes.append(int(rng.integers(3000, 200000)))
+        else:
+            sizes.append(int(rng.choice([512, 1024, 4096, 8192])))
+    stats_on = bool(rng.random() < 0.5) and order == "tree"    # statistics exist in tree order only
+    return K, dtype, out_dtype, radix, order, sizes, stats_on
+
+
+@pytest.mark.parametrize("block", range(10))
+def test_random_cases(block):
+    for case in range(block * CASES_PER_BLOCK, (block + 1) * CASES_PER_BLOCK):
+        K, dtype, out_dtype, radix, order, sizes, stats_on = draw_case(case)
+        print(f"case {case}: K={K} {dtype}->{out_dtype} radix={radix} {order} stats={stats_on} sizes={sizes}",
+              flush=True)
+        w = W.correlated_gaussian(sizes, K, dtype=torch.float32 if dtype == torch.float64 else dtype,
+                                  device=DEV, seed=20_000 + case)
+        grads = w.grads
+        if dtype == torch.float64:
+            g = torch.Generator(device=DEV).manual_seed(case)
+            grads = [x.double() * (1.0 + 1e-3 * torch.randn(x.shape, generator=g, device=DEV, dtype=torch.float64))
+                     for x in grads]
+        offs = w.layer_offsets
+        ref = oracle_reduce(grads, offs, order=order)
+        stats = torch.zeros(len(sizes), 2, dtype=torch.float64, device=DEV) if stats_on else None
+        out = B.adasum_reduce(grads, offs, out_dtype=out_dtype, radix=radix,
+                              order=B.ORDER_TREE if order == "tree" else B.ORDER_LINEAR, layer_stats=stats)
+        torch.cuda.synchronize()
+        assert_parity(out, ref, offs, what=f"case {case}")
+        if not stats_on:
+            continue
+        f64 = [to_f64(x) for x in grads]
+        s = stats.cpu().numpy()
+        for l in range(len(sizes)):
+            lo, hi = offs[l], offs[l + 1]
+            if hi == lo:
+                continue
+            leaves = sum(float(np.dot(x[lo:hi], x[lo:hi])) for x in f64)
+            assert abs(s[l, 1] - leaves) <= 2e-6 * leaves, (case, l, s[l, 1], leaves)
+            if not np.isnan(ref[lo:hi]).any():
+                root = float(np.dot(ref[lo:hi], ref[lo:hi]))
+                tol = 1e-2 if out_dtype in (torch.bfloat16, torch.float16) else 1e-4
+                assert abs(s[l, 0] - root) <= tol * root + 1e-30, (case, l, s[l, 0], root)
