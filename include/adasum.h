@@ -94,7 +94,8 @@ typedef struct adasum_options {
     double*  layer_stats;      /* DEVICE or NULL: n_layers x 2 doubles written per call,
                                   [l][0] = |Adasum(g_1..g_K)|^2 of layer l (of the value before
                                   it is rounded to the output type), [l][1] = sum_i |g_i|^2; their ratio
-                                  is the orthogonality metric of Section 3.6 */
+                                  is the orthogonality metric of Section 3.6 (in either order: the
+                                  first entry is the norm of whatever `order` computes) */
     const void* delta_start;   /* DEVICE or NULL.  Section 4.1 (Adasum applied after the optimizer):
                                   N elements of the input dtype, 16-byte aligned -- the model
                                   parameters before the workers' local optimizer steps.  When set,

@@ -86,7 +86,6 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (r.radix > max_radix(dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
-    if (r.order == ADASUM_ORDER_LINEAR && r.layer_stats != nullptr) return ADASUM_ERR_UNSUPPORTED;
     if (r.delta_start != nullptr) {
         if (r.order != ADASUM_ORDER_TREE || r.out_dtype != dtype) return ADASUM_ERR_UNSUPPORTED;
         if (!aligned16(r.delta_start)) return ADASUM_ERR_MISALIGNED;
@@ -506,7 +505,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                      launch_gram_finish(first, gt, L, groups, R, partials, normcoarse, gram, weights, o.order,
                                         first ? p->K : 0, depth0, stream));
         if (first && o.layer_stats != nullptr) {
-            ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, p->K, depth0, o.layer_stats + 1, 2, stream));
+            ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, p->K, depth0, 0, false, o.layer_stats + 1, 2, stream));
         }
         // step 3: apply
         for (int g0 = 0; g0 < groups; g0 += batch) {
@@ -554,6 +553,8 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
     double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
     double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
     double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
+    double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
+    double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
     const long long slot_bytes = static_cast<long long>(lay.slot_elems) * lay.node_bytes;
     const int n_passes = static_cast<int>(p->radices.size());
 
@@ -608,12 +609,21 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
         ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, nullptr, stream));
         ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, weights, ADASUM_ORDER_LINEAR, 0, 0,
                                          stream));
+        // statistics: every leaf's squared norm is a diagonal entry of exactly one pass (entry 0 of a
+        // later pass is the running result)
+        if (o.layer_stats != nullptr) {
+            ADASUM_LAUNCH(launch_trace_sums(gram, R, 1, L, 0, 0, first ? 0 : 1, !first, o.layer_stats + 1, 2, stream));
+        }
         Outputs outs;
         outs.base = last ? static_cast<char*>(out) : slots;
         outs.slot_bytes = 0;
         outs.stride = 0;
-        ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights, nullptr, nullptr,
-                                     nullptr, stream));
+        ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights,
+                                     last && o.layer_stats != nullptr ? normparts : nullptr, nullptr, nullptr, stream));
+    }
+    if (o.layer_stats != nullptr && n_passes > 0) {
+        ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, comb_sets[n_passes - 1], gt, normcoarse, stream));
+        ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, L, o.layer_stats, 2, stream));
     }
     return small_reduce(p, ws, out, o, stream);
 }
@@ -834,7 +844,6 @@ int adasum_plan_execute(adasum_plan* plan, const void* const* grads, void* out, 
     o.delta_start = delta_start;
     if (layer_stats != nullptr) {
         if ((reinterpret_cast<uintptr_t>(layer_stats) & 7u) != 0) return ADASUM_ERR_MISALIGNED;
-        if (o.order == ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     }
     if ((delta_start != nullptr) != plan->for_delta) return ADASUM_ERR_INVALID_ARG;
     if (delta_start != nullptr && !aligned16(delta_start)) return ADASUM_ERR_MISALIGNED;
@@ -1077,7 +1086,7 @@ const char* adasum_strerror(int code) {
     switch (code) {
         case ADASUM_OK: return "ok";
         case ADASUM_ERR_INVALID_ARG: return "invalid argument";
-        case ADASUM_ERR_UNSUPPORTED: return "unsupported (dtype f32/bf16/f16/f64; output the input type or f32, f64 only with f64; radix 2/4/8/16, f64 up to 8; the delta form and layer_stats only in tree order)";
+        case ADASUM_ERR_UNSUPPORTED: return "unsupported (dtype f32/bf16/f16/f64; output the input type or f32, f64 only with f64; radix 2/4/8/16, f64 up to 8; the delta form only in tree order)";
         case ADASUM_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
         case ADASUM_ERR_OUT_OF_MEMORY: return "out of memory";
         case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";

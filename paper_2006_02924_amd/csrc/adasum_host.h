@@ -225,10 +225,11 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
 // layer_sum[l * out_stride] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
 int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers,
                       double* layer_sum, int out_stride, void* stream);
-// out[l * out_stride] = sum over groups of trace(gram[group][l]) (over each group's real
-// leaves: K_leaves and depth as in launch_weights).
+// out[l * out_stride] = sum over groups of the diagonal entries first_entry.. of gram[group][l]
+// (over each group's real leaves: K_leaves and depth as in launch_weights); `accumulate` adds to
+// what out holds instead of replacing it.
 int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, int K_leaves, int depth,
-                      double* out, int out_stride, void* stream);
+                      int first_entry, bool accumulate, double* out, int out_stride, void* stream);
 
 // Copies the small layers of `n_leaves` operands (ops.pack[0..n_leaves)), widened to fp64 and
 // minus `delta_start` when given, into rows leaf0.. of the compact copy; with `stash_start`

@@ -922,13 +922,14 @@ layer_sums_kernel(const double* __restrict__ parts, int n_rows,
     if (threadIdx.x == 0) out[static_cast<long long>(l) * out_stride] = v;
 }
 
-// out[l * out_stride] = sum over groups of trace(gram[group][l]) over each group's real leaves
+// out[l * out_stride] (+)= sum over groups of the diagonal entries first_entry.. of gram[group][l], over
+// each group's real leaves
 __global__ void __launch_bounds__(64)
 trace_sums_kernel(const double* __restrict__ gram, int R, int n_groups, int n_layers, int K_leaves, int depth,
-                  double* __restrict__ out, int out_stride) {
+                  int first_entry, int accumulate, double* __restrict__ out, int out_stride) {
     const int l = blockIdx.x * 64 + threadIdx.x;
     if (l >= n_layers) return;
-    double v = 0.0;
+    double v = accumulate ? out[static_cast<long long>(l) * out_stride] : 0.0;
     for (int g = 0; g < n_groups; ++g) {
         const double* G = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
         int r = R;
@@ -937,7 +938,7 @@ trace_sums_kernel(const double* __restrict__ gram, int R, int n_groups, int n_la
             leaf_range(K_leaves, depth, g, lo, hi);
             r = hi - lo;
         }
-        for (int i = 0; i < r; ++i) v += G[i * R + i];
+        for (int i = first_entry; i < r; ++i) v += G[i * R + i];
     }
     out[static_cast<long long>(l) * out_stride] = v;
 }
@@ -1137,12 +1138,12 @@ int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_l
     return check_launch();
 }
 
-int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, int K_leaves, int depth, double* out,
-                      int out_stride, void* stream) {
+int launch_trace_sums(const double* gram, int R, int n_groups, int n_layers, int K_leaves, int depth,
+                      int first_entry, bool accumulate, double* out, int out_stride, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_layers == 0) return 0;
     hipLaunchKernelGGL(trace_sums_kernel, dim3((n_layers + 63) / 64), dim3(64), 0, st, gram, R, n_groups,
-                       n_layers, K_leaves, depth, out, out_stride);
+                       n_layers, K_leaves, depth, first_entry, accumulate ? 1 : 0, out, out_stride);
     return check_launch();
 }
 

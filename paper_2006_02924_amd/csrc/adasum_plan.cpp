@@ -123,7 +123,8 @@ int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, co
         groups /= radices[lv];
         // the widest storage type a pass may read gives its finest table
         const int64_t t = count_tiles(layer_offsets, n_layers, combine_tile_capacity(node_type, radices[lv]));
-        need = std::max<int64_t>(need, static_cast<int64_t>(groups) * t);
+        // (the left-to-right order has one group per pass)
+        need = std::max<int64_t>(need, static_cast<int64_t>(std::max(groups, 1)) * t);
     }
     if (radices.empty())
         need = std::max<int64_t>(need, count_tiles(layer_offsets, n_layers, combine_tile_capacity(node_type, 1)));

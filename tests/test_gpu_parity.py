@@ -426,9 +426,22 @@ def test_linear_order(K, dtype, radix):
                             use_graph=True)
     torch.cuda.synchronize()
     assert_parity(out32, ref, w.layer_offsets, what="linear f32 out, graph")
-    with pytest.raises(B.AdasumError):
-        B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR,
-                        layer_stats=torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV))
+    # the statistics of Section 3.6 in this order: the fold's squared norm and every leaf's, once
+    stats = torch.full((w.n_layers, 2), -1.0, dtype=torch.float64, device=DEV)
+    again = B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR, radix=radix, layer_stats=stats)
+    torch.cuda.synchronize()
+    assert torch.equal(again, out)
+    s = stats.cpu().numpy()
+    offs = w.layer_offsets
+    for l in range(w.n_layers):
+        lo, hi = offs[l], offs[l + 1]
+        if hi == lo:
+            continue
+        leaves = sum(float(np.dot(g[lo:hi], g[lo:hi])) for g in host)
+        assert s[l, 1] == pytest.approx(leaves, rel=2e-6)
+        if not np.isnan(ref[lo:hi]).any():
+            assert s[l, 0] == pytest.approx(float(np.dot(ref[lo:hi], ref[lo:hi])), rel=1e-2 if dtype != torch.float32 else 1e-4,
+                                            abs=1e-30)
 
 
 # ---------------------------------------------------------------------------

@@ -42,7 +42,7 @@ def draw_case(case):
             sizes.append(int(rng.integers(3000, 200000)))
         else:
             sizes.append(int(rng.choice([512, 1024, 4096, 8192])))
-    stats_on = bool(rng.random() < 0.5) and order == "tree"    # statistics exist in tree order only
+    stats_on = bool(rng.random() < 0.5)
     return K, dtype, out_dtype, radix, order, sizes, stats_on
 
 
