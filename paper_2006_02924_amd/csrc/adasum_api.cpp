@@ -542,9 +542,9 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 }
 
 // Left-to-right order (Section 3.4, first recursion).  Pass 0 folds the first
-// leaves; every later pass folds the running result (fp32, slot 0, operand 0)
-// with the next leaves.  Leaves that are not stored as fp32 are first widened
-// into slots 1.. so that one pass reads operands of one type.
+// leaves; every later pass folds the running result (a node: fp32 or fp64, slot 0,
+// operand 0, updated in place) with the next leaves, which are read in their own
+// storage type.
 int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
     const Layout& lay = p->lay;
     const int L = lay.n_layers;
@@ -555,18 +555,13 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
     double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);
     double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
-    const long long slot_bytes = static_cast<long long>(lay.slot_elems) * lay.node_bytes;
     const int n_passes = static_cast<int>(p->radices.size());
+    const bool mixed = dtype != node_dtype(dtype);   // 16-bit leaves next to an fp32 running result
 
     // every table first: nothing below may allocate
-    TileSet widen_tiles;
     std::vector<TileSet> comb_sets(n_passes);
     for (int b = 0; b < n_passes; ++b) {
-        const int rc = p->comb_tiles(b == 0 ? dtype : node_dtype(dtype), p->radices[b], &comb_sets[b]);
-        if (rc != ADASUM_OK) return rc;
-    }
-    if (dtype != node_dtype(dtype) && n_passes > 1) {
-        const int rc = p->comb_tiles(dtype, 1, &widen_tiles);
+        const int rc = p->comb_tiles(dtype, p->radices[b], &comb_sets[b]);
         if (rc != ADASUM_OK) return rc;
     }
 
@@ -578,7 +573,6 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
     for (int b = 0; b < n_passes; ++b) {
         const int R = p->radices[b];
         const bool first = b == 0, last = b == n_passes - 1;
-        const int in_dtype = first ? dtype : node_dtype(dtype);
         const int st_dtype = last ? o.out_dtype : node_dtype(dtype);
         Operands ops;
         std::memset(&ops, 0, sizeof(ops));
@@ -587,28 +581,26 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
             next_leaf += R;
         } else {
             ops.pack[0] = slots;
-            for (int r = 1; r < R; ++r) {
-                const void* leaf = grads[next_leaf + r - 1];
-                if (dtype != node_dtype(dtype)) {
-                    char* wide = slots + static_cast<long long>(r) * slot_bytes;
-                    Operands one;
-                    std::memset(&one, 0, sizeof(one));
-                    one.pack[0] = leaf;
-                    Outputs wo;
-                    wo.base = wide;
-                    wo.slot_bytes = 0;
-                    wo.stride = 0;
-                    ADASUM_LAUNCH(launch_combine(dtype, ADASUM_F32, one, wo, widen_tiles, L, 1, 1, nullptr, nullptr, nullptr,
-                                                 nullptr, stream));
-                    leaf = wide;
-                }
-                ops.pack[r] = leaf;
-            }
+            for (int r = 1; r < R; ++r) ops.pack[r] = grads[next_leaf + r - 1];
             next_leaf += R - 1;
         }
-        ADASUM_LAUNCH(launch_gram(in_dtype, true, ops, gt, 1, R, partials, nullptr, stream));
-        ADASUM_LAUNCH(launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, weights, ADASUM_ORDER_LINEAR, 0, 0,
-                                         stream));
+        const bool head32 = mixed && !first;
+        // algorithmic bytes: R operands read, operand 0 of a later pass as a node
+        const double read_bytes = static_cast<double>(lay.N) *
+                                  ((first ? R : R - 1) * elem_bytes(dtype) + (first ? 0 : lay.node_bytes));
+        char namebuf[64], base[48];
+        kernel_name("gram", dtype, 0, R, true, base, sizeof(base));
+        std::snprintf(namebuf, sizeof(namebuf), "%s%s", base, head32 ? "+f32 head" : "");
+        if (head32) {
+            ADASUM_TIMED(namebuf, read_bytes, stream, launch_gram_head32(dtype, ops, gt, R, partials, stream));
+        } else {
+            ADASUM_TIMED(namebuf, read_bytes, stream,
+                         launch_gram(dtype, true, ops, gt, 1, R, partials, nullptr, stream));
+        }
+        kernel_name("gram_finish", 0, 0, R, true, namebuf, sizeof(namebuf));
+        ADASUM_TIMED(namebuf, 0.0, stream,
+                     launch_gram_finish(true, gt, L, 1, R, partials, nullptr, gram, weights, ADASUM_ORDER_LINEAR, 0, 0,
+                                        stream));
         // statistics: every leaf's squared norm is a diagonal entry of exactly one pass (entry 0 of a
         // later pass is the running result)
         if (o.layer_stats != nullptr) {
@@ -618,8 +610,18 @@ int run_linear(Plan* p, char* ws, const void* const* grads, int dtype, void* out
         outs.base = last ? static_cast<char*>(out) : slots;
         outs.slot_bytes = 0;
         outs.stride = 0;
-        ADASUM_LAUNCH(launch_combine(in_dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights,
-                                     last && o.layer_stats != nullptr ? normparts : nullptr, nullptr, nullptr, stream));
+        double* np = last && o.layer_stats != nullptr ? normparts : nullptr;
+        const double comb_bytes = read_bytes + static_cast<double>(lay.N) * elem_bytes(st_dtype);
+        kernel_name("combine", dtype, st_dtype, R, false, base, sizeof(base));
+        std::snprintf(namebuf, sizeof(namebuf), "%s%s", base, head32 ? "+f32 head" : "");
+        if (head32) {
+            ADASUM_TIMED(namebuf, comb_bytes, stream,
+                         launch_combine_head32(dtype, st_dtype, ops, outs, comb_sets[b], L, R, weights, np, stream));
+        } else {
+            ADASUM_TIMED(namebuf, comb_bytes, stream,
+                         launch_combine(dtype, st_dtype, ops, outs, comb_sets[b], L, 1, R, weights, np, nullptr,
+                                        nullptr, stream));
+        }
     }
     if (o.layer_stats != nullptr && n_passes > 0) {
         ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, comb_sets[n_passes - 1], gt, normcoarse, stream));
@@ -697,12 +699,9 @@ int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void
     } else {
         for (size_t lv = 0; lv < p->radices.size(); ++lv) {
             TileSet ct;
-            const int rc = p->comb_tiles(lv == 0 ? dtype : node_dtype(dtype), p->radices[lv], &ct);
-            if (rc != ADASUM_OK) return rc;
-        }
-        if (o.order == ADASUM_ORDER_LINEAR && dtype != node_dtype(dtype)) {
-            TileSet ct;
-            const int rc = p->comb_tiles(dtype, 1, &ct);
+            // (the left-to-right order reads leaves, in their storage type, in every pass)
+            const bool leaves = lv == 0 || o.order == ADASUM_ORDER_LINEAR;
+            const int rc = p->comb_tiles(leaves ? dtype : node_dtype(dtype), p->radices[lv], &ct);
             if (rc != ADASUM_OK) return rc;
         }
     }

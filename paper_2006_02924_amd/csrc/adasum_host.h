@@ -222,6 +222,12 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
                    const double* weights /* or null: unit weights */, double* normparts,
                    const void* sub_in /* type of the operands, or null */,
                    const void* add_out /* type of the output, or null */, void* stream);
+// Steps 1 and 3 for one group whose operand 0 is stored as fp32 while operands 1..R-1 are
+// 16-bit (`dtype`): the running result of the left-to-right order folded with the next leaves.
+// Always the full Gram matrix (diagonal included); tiles as for `dtype`.
+int launch_gram_head32(int dtype, const Operands& ops, const TileSet& gt, int R, double* partials, void* stream);
+int launch_combine_head32(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                          int n_layers, int R, const double* weights, double* normparts, void* stream);
 // layer_sum[l * out_stride] = sum over `n_rows` rows and the tiles of layer l of parts[row][tile].
 int launch_layer_sums(const double* parts, int n_rows, const TileSet& t, int n_layers,
                       double* layer_sum, int out_stride, void* stream);

@@ -307,10 +307,13 @@ __device__ __forceinline__ Split split_tile(const adasum_tile& t) {
 // DELTA: the operands are x_r - start (the "effective gradient" of Section 4.1:
 // parameters after the local step minus the parameters before it), formed on
 // the fly; `start` has the operands' type.
-template <typename T, int R, bool DIAG, bool DELTA, int TILE>
+// HEAD32: operand 0 is stored as fp32 while the others are 16-bit (the running result of the
+// left-to-right order folded with the next leaves).
+template <typename T, int R, bool DIAG, bool DELTA, int TILE, bool HEAD32 = false>
 __global__ void __launch_bounds__(kThreads)
 gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_tiles,
             double* __restrict__ partials, const T* __restrict__ start) {
+    static_assert(!HEAD32 || (sizeof(T) == 2 && DIAG && !DELTA), "fp32 head: 16-bit leaves, full Gram matrix");
     constexpr int G = Traits<T>::VEC;
     typedef typename Traits<T>::acc_t acc_t;
     constexpr int NP = R * (R - 1) / 2 + (DIAG ? R : 0);
@@ -328,14 +331,60 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     const T* x[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) x[r] = static_cast<const T*>(operand_ptr<R>(ops, g, r));
+    const float* x0 = static_cast<const float*>(operand_ptr<R>(ops, g, 0));   // used with HEAD32 only
 
     acc_t acc[NP];
 #pragma unroll
     for (int e = 0; e < NP; ++e) acc[e] = 0;
 
-    auto consume = [&](const Granule<T, G> (&raw)[R], long long idx) {
+    constexpr bool kDot2 = !DELTA && sizeof(T) == 2 && (ADASUM_BF16_DOT2 == 2 || (ADASUM_BF16_DOT2 == 1 && R >= 16));
+    auto dot2 = [&](const Granule<T, G>& a, const Granule<T, G>& b, acc_t& sum) {
+#pragma unroll
+        for (int k = 0; k < Granule<T, G>::NW; ++k) {
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w[k]),
+                                                      __builtin_bit_cast(bf16x2_t, b.w[k]), sum, false);
+            } else if constexpr (std::is_same<T, f16_t>::value) {
+                sum = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, a.w[k]), __builtin_bit_cast(f16x2_t, b.w[k]),
+                                             sum, false);
+            }
+        }
+    };
+    // raw[0] is not loaded with HEAD32: `head` holds operand 0 instead
+    auto consume = [&](const Granule<T, G> (&raw)[R], const Granule<float, G>& head, long long idx) {
         (void)idx;
-        if constexpr (!DELTA && sizeof(T) == 2 && (ADASUM_BF16_DOT2 == 2 || (ADASUM_BF16_DOT2 == 1 && R >= 16))) {
+        (void)head;
+        if constexpr (HEAD32) {
+            // row 0 (the fp32 operand against everything) in fp32 FMAs; the 16-bit rows as usual
+            float v0[G];
+            unpack(head, v0);
+#pragma unroll
+            for (int k = 0; k < G; ++k) acc[0] = fma_t(v0[k], v0[k], acc[0]);
+#pragma unroll
+            for (int j = 1; j < R; ++j) {
+                float vj[G];
+                unpack(raw[j], vj);
+#pragma unroll
+                for (int k = 0; k < G; ++k) acc[j] = fma_t(v0[k], vj[k], acc[j]);
+            }
+            int e = R;
+#pragma unroll
+            for (int i = 1; i < R; ++i) {
+#pragma unroll
+                for (int j = i; j < R; ++j) {
+                    if constexpr (kDot2) {
+                        dot2(raw[i], raw[j], acc[e]);
+                    } else {
+                        float vi[G], vj[G];
+                        unpack(raw[i], vi);
+                        unpack(raw[j], vj);
+#pragma unroll
+                        for (int k = 0; k < G; ++k) acc[e] = fma_t(vi[k], vj[k], acc[e]);
+                    }
+                    ++e;
+                }
+            }
+        } else if constexpr (kDot2) {
             // two 16-bit products and the fp32 accumulate in one instruction, straight
             // from the packed words (bf16 x bf16 and f16 x f16 are exact in fp32)
             int e = 0;
@@ -343,17 +392,7 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
             for (int i = 0; i < R; ++i) {
 #pragma unroll
                 for (int j = (DIAG ? i : i + 1); j < R; ++j) {
-#pragma unroll
-                    for (int k = 0; k < Granule<T, G>::NW; ++k) {
-                        if constexpr (std::is_same<T, bf16_t>::value) {
-                            acc[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, raw[i].w[k]),
-                                                                     __builtin_bit_cast(bf16x2_t, raw[j].w[k]),
-                                                                     acc[e], false);
-                        } else {
-                            acc[e] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, raw[i].w[k]),
-                                                            __builtin_bit_cast(f16x2_t, raw[j].w[k]), acc[e], false);
-                        }
-                    }
+                    dot2(raw[i], raw[j], acc[e]);
                     ++e;
                 }
             }
@@ -387,23 +426,27 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
     if (s.ng == TILE / G) {
         for (int it0 = 0; it0 < ITERS; it0 += U) {
             Granule<T, G> raw[U][R];
+            Granule<float, G> head[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const long long idx = s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G;
+                if constexpr (HEAD32) load_raw(head[u], x0 + idx);
 #pragma unroll
-                for (int r = 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
+                for (int r = HEAD32 ? 1 : 0; r < R; ++r) load_raw(raw[u][r], x[r] + idx);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                consume(raw[u], s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G);
+                consume(raw[u], head[u], s.bs + (static_cast<long long>(it0 + u) * kThreads + tid) * G);
         }
     } else {
         for (int j = tid; j < s.ng; j += kThreads) {
             Granule<T, G> raw[R];
+            Granule<float, G> head;
             const long long idx = s.bs + static_cast<long long>(j) * G;
+            if constexpr (HEAD32) load_raw(head, x0 + idx);
 #pragma unroll
-            for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
-            consume(raw, idx);
+            for (int r = HEAD32 ? 1 : 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+            consume(raw, head, idx);
         }
     }
     // Whole granules went through fp32 lanes.  The at most 2*(G-1) elements of a
@@ -421,7 +464,8 @@ gram_kernel(const Operands ops, const adasum_tile* __restrict__ tiles, int n_til
         if (lane < nedge) {
             const long long idx = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
 #pragma unroll
-            for (int r = 0; r < R; ++r) v[r] = static_cast<double>(load_elem(x[r] + idx));
+            for (int r = HEAD32 ? 1 : 0; r < R; ++r) v[r] = static_cast<double>(load_elem(x[r] + idx));
+            if constexpr (HEAD32) v[0] = static_cast<double>(x0[idx]);
             if constexpr (DELTA) {
                 const double sv = static_cast<double>(load_elem(start + idx));
 #pragma unroll
@@ -675,11 +719,13 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, in
 // close to sequential, worth 10-20 % of bandwidth over long-lived workgroups.
 // normparts[group * n_tiles + tile].  weights == nullptr: unit weights.
 // ---------------------------------------------------------------------------
-template <typename TI, typename TO, int R, bool SUB>
+// HEAD32: operand 0 is stored as fp32 while the others are 16-bit (left-to-right order).
+template <typename TI, typename TO, int R, bool SUB, bool HEAD32 = false>
 __global__ void __launch_bounds__(combine_threads(R))
 combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles,
                int n_tiles, int n_layers, const double* __restrict__ weights,
                double* __restrict__ normparts, const TI* __restrict__ sub_in, const TO* add_out) {
+    static_assert(!HEAD32 || (sizeof(TI) == 2 && !SUB), "fp32 head: 16-bit leaves, no delta form");
     constexpr int G = 16 / (int)sizeof(TI);   // tile capacity is THREADS * G
     constexpr int THREADS = combine_threads(R);
     typedef typename Traits<TI>::acc_t acc_t;     // fp64 storage is combined in fp64
@@ -698,13 +744,16 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     const TI* x[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
+    const float* x0 = static_cast<const float*>(operand_ptr<R>(ops, g, 0));   // used with HEAD32 only
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
 
     const long long idx = s.bs + static_cast<long long>(tid) * G;
     Granule<TI, G> raw[R];
+    Granule<float, G> head;
     if (tid < s.ng) {
+        if constexpr (HEAD32) load_raw(head, x0 + idx);
 #pragma unroll
-        for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+        for (int r = HEAD32 ? 1 : 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
     }
 
     // fp64 weights as computed; the streaming body uses them rounded to fp32
@@ -731,7 +780,8 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         acc_t z[G];
         {
             acc_t v[G];
-            unpack(raw[0], v);
+            if constexpr (HEAD32) unpack(head, v);
+            else unpack(raw[0], v);
 #pragma unroll
             for (int k = 0; k < G; ++k) z[k] = w[0] * (SUB ? v[k] - sv[k] : v[k]);
         }
@@ -763,7 +813,10 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         if (lane < nedge) {
             const long long idx = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
             const double sd = SUB ? static_cast<double>(load_elem(sub_in + idx)) : 0.0;
-            double z = wd[0] * (static_cast<double>(load_elem(x[0] + idx)) - sd);
+            double first;
+            if constexpr (HEAD32) first = static_cast<double>(x0[idx]);
+            else first = static_cast<double>(load_elem(x[0] + idx));
+            double z = wd[0] * (first - sd);
 #pragma unroll
             for (int r = 1; r < R; ++r)
                 z = __builtin_fma(wd[r], static_cast<double>(load_elem(x[r] + idx)) - sd, z);
@@ -1033,7 +1086,79 @@ int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct
     return check_launch();
 }
 
+// Operand 0 stored as fp32, operands 1.. as T (16-bit): one group, the full Gram matrix.
+template <typename T>
+int launch_gram_head32_t(const Operands& ops, const TileSet& gt, int R, double* partials, hipStream_t st) {
+    if (!grid_fits(gt.n_tiles)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(gt.n_tiles)), block(kThreads);
+    const int nt = static_cast<int>(gt.n_tiles);
+    if (gt.capacity != kTile && gt.capacity != kTileSmall) return static_cast<int>(hipErrorInvalidValue);
+    const bool small = gt.capacity == kTileSmall;
+#define ADASUM_GRAM_HEAD32(RR)                                                                              \
+    do {                                                                                                    \
+        if (small)                                                                                          \
+            hipLaunchKernelGGL((gram_kernel<T, RR, true, false, kTileSmall, true>), grid, block, 0, st, ops, \
+                               gt.tiles, nt, partials, static_cast<const T*>(nullptr));                     \
+        else                                                                                                \
+            hipLaunchKernelGGL((gram_kernel<T, RR, true, false, kTile, true>), grid, block, 0, st, ops,     \
+                               gt.tiles, nt, partials, static_cast<const T*>(nullptr));                     \
+    } while (0)
+    switch (R) {
+        case 2: ADASUM_GRAM_HEAD32(2); break;
+        case 4: ADASUM_GRAM_HEAD32(4); break;
+        case 8: ADASUM_GRAM_HEAD32(8); break;
+        case 16: ADASUM_GRAM_HEAD32(16); break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+#undef ADASUM_GRAM_HEAD32
+    return check_launch();
+}
+
+template <typename TI, typename TO>
+int launch_combine_head32_r(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int R,
+                            const double* weights, double* normparts, hipStream_t st) {
+    if (!grid_fits(ct.n_tiles)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(ct.n_tiles)), block(combine_threads(R));
+    const int nt = static_cast<int>(ct.n_tiles);
+#define ADASUM_COMBINE_HEAD32(RR)                                                                           \
+    hipLaunchKernelGGL((combine_kernel<TI, TO, RR, false, true>), grid, block, 0, st, ops, outs, ct.tiles,  \
+                       nt, n_layers, weights, normparts, static_cast<const TI*>(nullptr),                   \
+                       static_cast<const TO*>(nullptr))
+    switch (R) {
+        case 2: ADASUM_COMBINE_HEAD32(2); break;
+        case 4: ADASUM_COMBINE_HEAD32(4); break;
+        case 8: ADASUM_COMBINE_HEAD32(8); break;
+        case 16: ADASUM_COMBINE_HEAD32(16); break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+#undef ADASUM_COMBINE_HEAD32
+    return check_launch();
+}
+
 }  // namespace
+
+int launch_gram_head32(int dtype, const Operands& ops, const TileSet& gt, int R, double* partials, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (gt.n_tiles == 0) return 0;
+    if (dtype == ADASUM_BF16) return launch_gram_head32_t<bf16_t>(ops, gt, R, partials, st);
+    if (dtype == ADASUM_F16) return launch_gram_head32_t<f16_t>(ops, gt, R, partials, st);
+    return static_cast<int>(hipErrorInvalidValue);
+}
+
+int launch_combine_head32(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                          int n_layers, int R, const double* weights, double* normparts, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (ct.n_tiles == 0) return 0;
+    if (dtype == ADASUM_BF16 && out_dtype == ADASUM_BF16)
+        return launch_combine_head32_r<bf16_t, bf16_t>(ops, out, ct, n_layers, R, weights, normparts, st);
+    if (dtype == ADASUM_BF16 && out_dtype == ADASUM_F32)
+        return launch_combine_head32_r<bf16_t, float>(ops, out, ct, n_layers, R, weights, normparts, st);
+    if (dtype == ADASUM_F16 && out_dtype == ADASUM_F16)
+        return launch_combine_head32_r<f16_t, f16_t>(ops, out, ct, n_layers, R, weights, normparts, st);
+    if (dtype == ADASUM_F16 && out_dtype == ADASUM_F32)
+        return launch_combine_head32_r<f16_t, float>(ops, out, ct, n_layers, R, weights, normparts, st);
+    return static_cast<int>(hipErrorInvalidValue);
+}
 
 int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
                 double* partials, const void* delta_start, void* stream) {

@@ -147,11 +147,8 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
     size_t max_partials = 0, max_gram = 0, max_weights = 0, max_nodes = 1;
     int groups = K;
     if (order == ADASUM_ORDER_LINEAR) {
-        // one group per pass; slot 0 holds the running result, slots 1.. the leaves of a
-        // pass widened to fp32 (needed when the inputs are not fp32)
-        int widest = 0;
-        for (int R : radices) widest = std::max(widest, R);
-        lay.n_slots = radices.size() > 1 ? widest : 0;
+        // one group per pass; slot 0 holds the running result
+        lay.n_slots = radices.size() > 1 ? 1 : 0;
     }
     for (size_t lv = 0; lv < radices.size(); ++lv) {
         const int R = radices[lv];
