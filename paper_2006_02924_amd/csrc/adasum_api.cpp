@@ -335,19 +335,40 @@ struct Timed {
         int rc = take_event(&rec.start);
         if (rc != ADASUM_OK) return rc;
         rc = take_event(&rec.stop);
-        if (rc != ADASUM_OK) return rc;
+        if (rc != ADASUM_OK) {
+            g_event_pool.push_back(rec.start);
+            return rc;
+        }
         rec.name = name;
         rec.bytes = bytes;
-        ADASUM_HIP(hipEventRecord(rec.start, st));
+        const hipError_t e = hipEventRecord(rec.start, st);
+        if (e != hipSuccess) {
+            give_back();
+            g_last_hip_error = static_cast<int>(e);
+            return ADASUM_ERR_HIP;
+        }
         active = true;
         return ADASUM_OK;
     }
     int end() {
         if (!active) return ADASUM_OK;
-        ADASUM_HIP(hipEventRecord(rec.stop, st));
-        g_records.push_back(rec);
         active = false;
+        const hipError_t e = hipEventRecord(rec.stop, st);
+        if (e != hipSuccess) {
+            give_back();
+            g_last_hip_error = static_cast<int>(e);
+            return ADASUM_ERR_HIP;
+        }
+        g_records.push_back(rec);
         return ADASUM_OK;
+    }
+    // a launch that failed leaves no record: its events go back to the pool
+    void give_back() {
+        g_event_pool.push_back(rec.start);
+        g_event_pool.push_back(rec.stop);
+    }
+    ~Timed() {
+        if (active) give_back();
     }
 };
 
