@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see the
 # summaries under profiles/.  Keyed by (workload, kernel name).
 MEASURED_TRAFFIC_BYTES = {
-    ("config4", "combine<bf16,f32,R=16>"): 43.234e9 + 5.793e9,
+    ("config4", "combine<bf16,f32,R=16>"): 43.234e9 + 5.795e9,
     ("config4", "gram<bf16,R=16,diag>"): 42.898e9 + 0.024e9,
     ("config4", "combine<bf16,f32,R=2>"): 43.571e9 + 43.066e9,
     ("config3", "combine<f32,f32,R=16>"): 21.617e9 + 1.341e9,
