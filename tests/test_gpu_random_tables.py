@@ -80,3 +80,22 @@ def test_random_cases(block):
                 root = float(np.dot(ref[lo:hi], ref[lo:hi]))
                 tol = 1e-2 if out_dtype in (torch.bfloat16, torch.float16) else 1e-4
                 assert abs(s[l, 0] - root) <= tol * root + 1e-30, (case, l, s[l, 0], root)
+
+
+@pytest.mark.parametrize("K,dtype", [(8, torch.float32), (24, torch.bfloat16)])
+def test_many_tiny_layers(K, dtype):
+    """A table of 20 000 layers of 0 to 40 elements (biases, scales, scalars): most go through
+    the small-layer path, the rest through one-tile Gram and combine launches."""
+    rng = np.random.default_rng(5 + K)
+    sizes = rng.integers(0, 41, size=20_000).tolist()
+    print(f"many tiny layers: K={K} {dtype} N={sum(sizes)}", flush=True)
+    w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=30_000 + K)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    stats = torch.zeros(len(sizes), 2, dtype=torch.float64, device=DEV)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=torch.float32, layer_stats=stats)
+    torch.cuda.synchronize()
+    assert_parity(out, ref, w.layer_offsets, what="many tiny layers")
+    s = stats.cpu().numpy()
+    empty = np.asarray(sizes) == 0
+    assert np.all(s[empty] == 0.0)
+    assert np.all(s[~empty, 1] > 0.0)
