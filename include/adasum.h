@@ -156,7 +156,10 @@ ADASUM_API int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n
  * adasum_reduce(_ex) look their plan up in a cache by shape on every call.  A caller
  * that reduces the same shape again and again can hold the plan itself: tile tables
  * on the current device, the pass schedule, captured graphs and (unless a workspace is
- * given) the plan's own workspace, allocated on the first execute.
+ * given) the plan's own workspace.  All of it is allocated by adasum_plan_create:
+ * adasum_plan_execute with use_graph = 0 and profiling off only launches kernels
+ * (no allocation, no copy, no synchronisation), so it may be issued on a stream the
+ * caller is capturing into a hipGraph of its own.
  *
  *   opts   as for adasum_reduce_ex; out_dtype, radix, order, use_graph and
  *          workspace / workspace_bytes are fixed for the plan's lifetime;

@@ -685,6 +685,23 @@ int run_copy(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     return ADASUM_OK;
 }
 
+// Builds and uploads every combine tile table a reduction with this plan reads, so that the
+// launch ladder itself allocates nothing.
+int prebuild_tables(Plan* p, int dtype, int order) {
+    if (p->K == 1) {
+        TileSet ct;
+        return p->comb_tiles(dtype, 1, &ct);
+    }
+    for (size_t lv = 0; lv < p->radices.size(); ++lv) {
+        TileSet ct;
+        // (the left-to-right order reads leaves, in their storage type, in every pass)
+        const bool leaves = lv == 0 || order == ADASUM_ORDER_LINEAR;
+        const int rc = p->comb_tiles(leaves ? dtype : node_dtype(dtype), p->radices[lv], &ct);
+        if (rc != ADASUM_OK) return rc;
+    }
+    return ADASUM_OK;
+}
+
 // Replays the whole ladder as one hipGraph launch.  The graph is captured once
 // per distinct set of buffers (kernel arguments are baked into its nodes) on a
 // private stream and cached in the plan; a call with other buffers captures
@@ -713,18 +730,9 @@ int launch_as_graph(Plan* p, char* ws, const void* const* grads, int dtype, void
         ADASUM_HIP(hipStreamCreateWithFlags(&p->capture_stream, hipStreamNonBlocking));
     }
     // everything that allocates happens before the capture starts
-    if (p->K == 1) {
-        TileSet ct;
-        const int rc = p->comb_tiles(dtype, 1, &ct);
+    {
+        const int rc = prebuild_tables(p, dtype, o.order);
         if (rc != ADASUM_OK) return rc;
-    } else {
-        for (size_t lv = 0; lv < p->radices.size(); ++lv) {
-            TileSet ct;
-            // (the left-to-right order reads leaves, in their storage type, in every pass)
-            const bool leaves = lv == 0 || o.order == ADASUM_ORDER_LINEAR;
-            const int rc = p->comb_tiles(leaves ? dtype : node_dtype(dtype), p->radices[lv], &ct);
-            if (rc != ADASUM_OK) return rc;
-        }
     }
     ADASUM_HIP(hipStreamBeginCapture(p->capture_stream, hipStreamCaptureModeThreadLocal));
     const int rc = p->K == 1 ? run_copy(p, ws, grads, dtype, out, o, p->capture_stream)
@@ -851,6 +859,12 @@ int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dt
         rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), layer_offsets, n_layers, h->plan);
         if (rc != ADASUM_OK) return rc;
         if (o.workspace != nullptr && o.workspace_bytes < h->plan->lay.total) return ADASUM_ERR_WORKSPACE;
+        // everything execute needs exists from here on: it allocates nothing
+        rc = prebuild_tables(h->plan.get(), dtype, o.order);
+        if (rc != ADASUM_OK) return rc;
+        char* ws = nullptr;
+        rc = plan_workspace(h->plan.get(), h->opts, &ws);
+        if (rc != ADASUM_OK) return rc;
     }
     *plan = h.release();
     return ADASUM_OK;

@@ -770,6 +770,40 @@ def test_caller_owned_plans():
     plan.destroy()
 
 
+@pytest.mark.parametrize("K,dtype,order", [(64, torch.bfloat16, B.ORDER_TREE), (6, torch.float32, B.ORDER_TREE),
+                                            (20, torch.bfloat16, B.ORDER_LINEAR)])
+def test_plan_execute_inside_the_callers_graph(K, dtype, order):
+    """adasum_plan_execute only launches kernels (tables and workspace exist since plan creation), so
+    a caller can record it into a graph of its own; every replay, with new values in the same
+    buffers and eager work in between, gives the bits of an eager call."""
+    say(f"execute under the caller's capture: K={K} {dtype} order={order}")
+    sizes = np.diff(RAGGED).tolist()
+    w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=60 + K)
+    plan = B.Plan(K, w.layer_offsets, dtype, order=order)
+    out = torch.zeros(w.N, dtype=dtype, device=DEV)
+    stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        plan.execute(w.grads, out, layer_stats=stats)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for i, g in enumerate(w.grads):
+            g.mul_(1.0 + 0.25 * ((i + rep) % 3))
+        want_stats = torch.zeros_like(stats)
+        want = B.adasum_reduce(w.grads, w.layer_offsets, order=order, layer_stats=want_stats)
+        out.zero_()
+        stats.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), (K, dtype, rep)
+        assert torch.equal(stats, want_stats), (K, dtype, rep)
+    del graph
+    plan.destroy()
+
+
 def test_two_host_threads_on_their_own_streams():
     """Calls from two host threads (ctypes releases the GIL), each with its own shape -- hence its
     own plan and workspace -- and its own stream: results stay right and deterministic."""
