@@ -99,3 +99,49 @@ def test_many_tiny_layers(K, dtype):
     empty = np.asarray(sizes) == 0
     assert np.all(s[empty] == 0.0)
     assert np.all(s[~empty, 1] > 0.0)
+
+
+def _guarded(nbytes, align, fill=0xA5, guard=4096):
+    """A uint8 view of `nbytes` bytes, `align`-aligned, with `guard` bytes of a known pattern on
+    both sides.  Returns (whole buffer, view, offset of the view)."""
+    whole = torch.full((nbytes + 2 * guard + align,), fill, dtype=torch.uint8, device=DEV)
+    off = guard + (-(whole.data_ptr() + guard)) % align
+    return whole, whole[off:off + nbytes], off
+
+
+def _guards_intact(whole, off, nbytes, fill=0xA5):
+    return bool((whole[:off] == fill).all()) and bool((whole[off + nbytes:] == fill).all())
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_nothing_is_written_outside_out_and_workspace(block):
+    """The result and a caller-provided workspace sit between guard bands; no byte of either band
+    changes, the inputs keep their bits, and the result is the one computed without guards."""
+    for case in range(200 + block * 10, 200 + (block + 1) * 10):
+        K, dtype, out_dtype, radix, order, sizes, stats_on = draw_case(case)
+        print(f"guarded case {case}: K={K} {dtype}->{out_dtype} radix={radix} {order} stats={stats_on} sizes={sizes}",
+              flush=True)
+        w = W.correlated_gaussian(sizes, K, dtype=torch.float32 if dtype == torch.float64 else dtype,
+                                  device=DEV, seed=40_000 + case)
+        grads = [g.double() for g in w.grads] if dtype == torch.float64 else w.grads
+        offs = w.layer_offsets
+        code = B.ORDER_TREE if order == "tree" else B.ORDER_LINEAR
+        want = B.adasum_reduce(grads, offs, out_dtype=out_dtype, radix=radix, order=code)
+        before = [g.clone() for g in grads]
+        esize = torch.empty(0, dtype=out_dtype).element_size()
+        out_whole, out_bytes, out_off = _guarded(w.N * esize, 16)
+        out = out_bytes.view(out_dtype)
+        need = B.adasum_workspace_bytes(K, offs, B._code_of(dtype), radix=radix, out_dtype_code=B._code_of(out_dtype),
+                                        order=code)
+        ws_whole, ws, ws_off = _guarded(need, 256)
+        stats_whole, stats_bytes, stats_off = _guarded(len(sizes) * 16, 8)
+        stats = stats_bytes.view(torch.float64).view(len(sizes), 2) if stats_on else None
+        got = B.adasum_reduce(grads, offs, out, out_dtype=out_dtype, radix=radix, order=code, workspace=ws,
+                              layer_stats=stats)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), case
+        assert _guards_intact(out_whole, out_off, w.N * esize), f"case {case}: wrote outside out"
+        assert _guards_intact(ws_whole, ws_off, need), f"case {case}: wrote outside the workspace"
+        assert _guards_intact(stats_whole, stats_off, len(sizes) * 16), f"case {case}: wrote outside layer_stats"
+        for g, b in zip(grads, before):
+            assert torch.equal(g, b), f"case {case}: an input changed"
