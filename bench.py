@@ -36,6 +36,9 @@ MEASURED_TRAFFIC_BYTES = {
     ("config3", "gram<f32,R=16,diag>"): 21.450e9 + 0.025e9,
     ("config2", "combine<f32,f32,R=8>"): 0.8243e9 + 0.1022e9,
     ("config2", "gram<f32,R=8,diag>"): 0.8180e9 + 0.0006e9,
+    # counters taken at K = 128 on config 4's generator (config 5 adds 16 one-element tensors to it)
+    ("config5", "combine<bf16,f32,R=16>"): 86.468e9 + 11.586e9,
+    ("config5", "gram<bf16,R=16,diag>"): 85.796e9 + 0.048e9,
 }
 
 
