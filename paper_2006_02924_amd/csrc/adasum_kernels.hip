@@ -627,7 +627,7 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
     // them in flight together); consecutive threads read consecutive addresses.  The ROWS sums of
     // an entry are then added in a fixed order.
     constexpr int ROWS = THREADS / NP;   // tiles handled side by side (NP <= 136)
-    constexpr int kAhead = 8;
+    constexpr int kAhead = 16;   // loads in flight per thread (one workgroup sums all tiles of a layer)
     static_assert(ROWS >= 1, "more entries than threads");
     __shared__ double shP[ROWS * NP];
     {
@@ -636,11 +636,16 @@ gram_finish_kernel(const double* __restrict__ partials, const double* __restrict
             double v = 0.0;
             const double* base = partials + static_cast<long long>(g) * n_tiles * NP + e;
             for (int t0 = tb + row; t0 < te; t0 += ROWS * kAhead) {
+                // branch-free so that the loads of a round are issued together: a tile past the
+                // end re-reads the layer's last tile and its value is dropped
+                double x[kAhead];
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
                     const int t = t0 + u * ROWS;
-                    if (t < te) v += base[static_cast<long long>(t) * NP];
+                    x[u] = base[static_cast<long long>(t < te ? t : te - 1) * NP];
                 }
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) v += (t0 + u * ROWS < te) ? x[u] : 0.0;
             }
             shP[row * NP + e] = v;
         }
