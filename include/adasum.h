@@ -64,6 +64,7 @@ extern "C" {
 #define ADASUM_ERR_HIP           -5  /* a HIP call failed; see adasum_last_hip_error() */
 #define ADASUM_ERR_WORKSPACE     -6  /* caller-provided workspace too small or misaligned */
 #define ADASUM_ERR_ALIAS         -7  /* `out` overlaps an input buffer */
+#define ADASUM_ERR_TOO_LARGE     -8  /* adasum_reduce_noalloc: the problem needs more than the static scratch */
 
 /* tree order (Section 3.4 gives both recursions; they give different results) */
 #define ADASUM_ORDER_TREE   0   /* recursive halving -- the one the paper uses in practice */
@@ -180,6 +181,33 @@ ADASUM_API int adasum_plan_execute(adasum_plan* plan, const void* const* grads, 
 /* Bytes of workspace the plan uses (what adasum_workspace_bytes reports for its shape). */
 ADASUM_API int adasum_plan_workspace_bytes(const adasum_plan* plan, size_t* bytes);
 ADASUM_API int adasum_plan_destroy(adasum_plan* plan);
+
+/* ---- for callers that cannot allocate ----
+ *
+ * Code under HIP graph capture, tight serving loops and harnesses that forbid device
+ * allocation cannot use the entry points above on a new shape (their first call with a
+ * shape allocates tile tables and a workspace with hipMalloc).  adasum_reduce_noalloc is
+ * adasum_reduce_ex for them: same arguments, same kernels, same result bit for bit, but it
+ * calls no hipMalloc / hipFree / hipMemcpy and no other allocating or synchronising routine.
+ * The layer table travels to the device in kernel arguments, the tile tables are built there,
+ * and tables plus workspace live in one static device array of
+ * ADASUM_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until the process
+ * ends.  Per-kernel timing (adasum_profile_enable) does not cover it.
+ *
+ *   opts   as for adasum_reduce_ex, except workspace must be NULL and use_graph 0
+ *          (ADASUM_ERR_INVALID_ARG otherwise); NULL = all defaults
+ * Limit: tables + workspace of the problem (about adasum_workspace_bytes() plus 16 bytes per
+ * 512 elements) must fit the array, else ADASUM_ERR_TOO_LARGE and nothing is enqueued.  That
+ * holds for e.g. ResNet-50 (25.6 M elements) at K <= 16, or 3 M elements at K = 64.
+ * Every call on one GPU uses the same array and finds the previous call's contents there:
+ * each call rebuilds all it reads (nothing needs to start at zero), and two calls that
+ * overlap in time on one GPU -- on different streams without an ordering between them -- race.
+ * Calls on one stream, or ordered by events, are safe.
+ */
+#define ADASUM_NOALLOC_SCRATCH_BYTES (64u << 20)
+ADASUM_API int adasum_reduce_noalloc(const void* const* grads, int K,
+                          const int64_t* layer_offsets, int n_layers,
+                          int dtype, void* out, const adasum_options* opts, void* stream);
 
 /* ---- the steps of one tree level, exposed so that each can be checked alone ---- */
 

@@ -22,10 +22,11 @@ ORDER_TREE, ORDER_LINEAR = 0, 1
 
 OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_MISALIGNED = -1, -2, -3
-ERR_OUT_OF_MEMORY, ERR_HIP, ERR_WORKSPACE, ERR_ALIAS = -4, -5, -6, -7
+ERR_OUT_OF_MEMORY, ERR_HIP, ERR_WORKSPACE, ERR_ALIAS, ERR_TOO_LARGE = -4, -5, -6, -7, -8
+NOALLOC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
-    "adasum_reduce", "adasum_reduce_ex", "adasum_workspace_bytes",
+    "adasum_reduce", "adasum_reduce_ex", "adasum_reduce_noalloc", "adasum_workspace_bytes",
     "adasum_plan_create", "adasum_plan_execute", "adasum_plan_workspace_bytes", "adasum_plan_destroy",
     "adasum_group_gram", "adasum_group_weights", "adasum_group_combine",
     "adasum_tile_capacity", "adasum_plan_tiles", "adasum_plan_levels", "adasum_plan_groups",
@@ -82,6 +83,7 @@ def load() -> C.CDLL:
     lib.adasum_reduce.argtypes = [pp, C.c_int, i64p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     lib.adasum_reduce_ex.argtypes = [pp, C.c_int, i64p, C.c_int, C.c_int, C.c_void_p,
                                      C.POINTER(Options), C.c_void_p]
+    lib.adasum_reduce_noalloc.argtypes = lib.adasum_reduce_ex.argtypes
     lib.adasum_workspace_bytes.argtypes = [C.c_int, i64p, C.c_int, C.c_int, C.POINTER(Options),
                                            C.POINTER(C.c_size_t)]
     lib.adasum_group_gram.argtypes = [pp, C.c_int, i64p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -172,14 +174,18 @@ def _check_inputs(tensors, N):
 
 def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, out_dtype=None,
                   radix: int = 0, order: int = ORDER_TREE, layer_stats=None, workspace=None,
-                  use_graph: bool = False, delta_start=None, stream=None):
+                  use_graph: bool = False, delta_start=None, stream=None, noalloc: bool = False):
     """Per-layer Adasum tree of ``grads`` (K device tensors of N elements).
     Returns ``out`` (allocated here when None).  With ``delta_start`` (a tensor
     like one of ``grads``) the tensors in ``grads`` are parameters after a local
     optimizer step, the tree runs on ``grads[k] - delta_start`` and the result
-    is ``delta_start + Adasum(...)``; ``out`` may then be ``delta_start`` itself."""
+    is ``delta_start + Adasum(...)``; ``out`` may then be ``delta_start`` itself.
+    ``noalloc`` calls ``adasum_reduce_noalloc`` (tables and workspace in the library's
+    static scratch; ``out`` must then be given, so that nothing here allocates either)."""
     import torch
     lib = load()
+    if noalloc and out is None:
+        raise ValueError("noalloc: pass `out` (this call must not allocate)")
     offs, L = _offsets(layer_offsets)
     N = int(layer_offsets[-1])
     _check_inputs(grads, N)
@@ -191,7 +197,7 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
         raise ValueError("out has the wrong dtype, size or layout")
     ptrs = _ptr_array(grads)
     plain = (out_code == in_code and radix == 0 and order == ORDER_TREE and layer_stats is None
-             and workspace is None and not use_graph and delta_start is None)
+             and workspace is None and not use_graph and delta_start is None and not noalloc)
     if plain:
         check(lib.adasum_reduce(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()), _stream(stream)))
         return out
@@ -213,8 +219,8 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
         if delta_start.dtype != grads[0].dtype or delta_start.device != grads[0].device:
             raise ValueError("delta_start must have the dtype and device of grads")
         o.delta_start = delta_start.data_ptr()
-    check(lib.adasum_reduce_ex(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()),
-                               C.byref(o), _stream(stream)))
+    fn = lib.adasum_reduce_noalloc if noalloc else lib.adasum_reduce_ex
+    check(fn(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()), C.byref(o), _stream(stream)))
     return out
 
 

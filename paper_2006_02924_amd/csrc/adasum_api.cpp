@@ -115,13 +115,16 @@ struct TileTable {
     adasum_tile* d_tiles = nullptr;
     int32_t* d_layer_begin = nullptr;
     int32_t* d_first_in_gram = nullptr;
+    // >= 0: the device tables are borrowed (built on the device inside someone else's memory,
+    // no host copy, never freed here) and hold this many tiles
+    int64_t n_borrowed = -1;
 
     TileSet view() const {
         TileSet t;
         t.tiles = d_tiles;
         t.layer_begin = d_layer_begin;
         t.first_in_gram = d_first_in_gram;
-        t.n_tiles = static_cast<int64_t>(tiles.size());
+        t.n_tiles = n_borrowed >= 0 ? n_borrowed : static_cast<int64_t>(tiles.size());
         t.capacity = capacity;
         return t;
     }
@@ -151,6 +154,7 @@ struct TileTable {
         return ADASUM_OK;
     }
     void release() {
+        if (n_borrowed >= 0) return;
         if (d_tiles) (void)hipFree(d_tiles);
         if (d_layer_begin) (void)hipFree(d_layer_begin);
         if (d_first_in_gram) (void)hipFree(d_first_in_gram);
@@ -171,9 +175,11 @@ struct Plan {
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
     std::vector<int> radices;
     std::vector<SmallLayer> small;        // layers reduced by the definition in fp64 (see kSmallLayer)
+    int n_small = 0;                      // entries of d_small
     SmallLayer* d_small = nullptr;
     Layout lay;
     char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
+    bool borrowed = false;  // every device pointer lives in memory this plan does not own
 
     // Captured level ladders, one per distinct set of buffers (see launch_as_graph).
     struct GraphEntry {
@@ -189,6 +195,7 @@ struct Plan {
         const int cap = combine_tile_capacity(dtype, R);
         auto it = comb_tables.find(cap);
         if (it == comb_tables.end()) {
+            if (borrowed) return ADASUM_ERR_INVALID_ARG;   // such a plan comes with all its tables
             try {
                 TileTable t;
                 t.capacity = cap;
@@ -217,6 +224,7 @@ struct Plan {
         if (capture_stream) (void)hipStreamDestroy(capture_stream);
         gram_tiles.release();
         for (auto& kv : comb_tables) kv.second.release();
+        if (borrowed) return;
         if (d_small) (void)hipFree(d_small);
         if (d_ws) (void)hipFree(d_ws);
     }
@@ -261,6 +269,7 @@ int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets
         ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_small), bytes));
         ADASUM_HIP(hipMemcpy(p->d_small, p->small.data(), bytes, hipMemcpyHostToDevice));
     }
+    p->n_small = static_cast<int>(p->small.size());
     out = std::move(p);
     return ADASUM_OK;
 }
@@ -311,6 +320,7 @@ struct ProfRecord {
     double bytes;
 };
 bool g_profile = false;
+thread_local bool t_no_profile = false;   // set while adasum_reduce_noalloc enqueues: events are allocations
 std::vector<ProfRecord> g_records;
 std::vector<hipEvent_t> g_event_pool;
 
@@ -331,7 +341,7 @@ struct Timed {
     hipStream_t st;
     int begin(const char* name, double bytes, void* stream) {
         st = static_cast<hipStream_t>(stream);
-        if (!g_profile) return ADASUM_OK;
+        if (!g_profile || t_no_profile) return ADASUM_OK;
         int rc = take_event(&rec.start);
         if (rc != ADASUM_OK) return rc;
         rc = take_event(&rec.stop);
@@ -399,9 +409,9 @@ int check_operands(const void* const* ptrs, int count, int64_t N, int dtype) {
 // Before anything is written: the small layers of every worker (minus delta_start) and of
 // delta_start itself go into the compact fp64 copy, kMaxPack workers per launch.
 int small_gather(Plan* p, char* ws, const void* const* grads, int dtype, const Opts& o, void* stream) {
-    if (p->small.empty()) return ADASUM_OK;
+    if (p->n_small == 0) return ADASUM_OK;
     double* compact = reinterpret_cast<double*>(ws + p->lay.off_small);
-    const int n_small = static_cast<int>(p->small.size());
+    const int n_small = p->n_small;
     for (int k0 = 0; k0 < p->K; k0 += kMaxPack) {
         const int n = std::min(kMaxPack, p->K - k0);
         Operands ops;
@@ -416,10 +426,10 @@ int small_gather(Plan* p, char* ws, const void* const* grads, int dtype, const O
 
 // After the passes: the small layers again, pair by pair in fp64, over what they wrote.
 int small_reduce(Plan* p, char* ws, void* out, const Opts& o, void* stream) {
-    if (p->small.empty()) return ADASUM_OK;
+    if (p->n_small == 0) return ADASUM_OK;
     const double* compact = reinterpret_cast<const double*>(ws + p->lay.off_small);
     ADASUM_TIMED("small_layers", 0.0, stream,
-                 launch_small_reduce(o.out_dtype, compact, p->K, p->d_small, static_cast<int>(p->small.size()),
+                 launch_small_reduce(o.out_dtype, compact, p->K, p->d_small, p->n_small,
                                      p->lay.small_elems, o.order, o.delta_start != nullptr, p->K, out,
                                      o.layer_stats, stream));
     return ADASUM_OK;
@@ -798,18 +808,26 @@ int execute_plan(Plan* p, const void* const* grads, int dtype, void* out, const 
     return run_tree(p, ws, grads, dtype, out, o, stream);
 }
 
-int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
-                void* out, const adasum_options* opts, void* stream) {
+// The argument checks every reduce entry point starts with (no device work).  N receives the
+// number of elements per gradient.
+int check_reduce_args(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                      void* out, const adasum_options* opts, Opts& o, int64_t& N) {
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
     if (!known_dtype(dtype)) return ADASUM_ERR_UNSUPPORTED;
-    Opts o;
     rc = read_opts(opts, dtype, o);
     if (rc != ADASUM_OK) return rc;
     if (K > (1 << 20)) return ADASUM_ERR_UNSUPPORTED;
-    const int64_t N = layer_offsets[n_layers];
-    rc = check_call(grads, K, N, dtype, out, o);
+    N = layer_offsets[n_layers];
+    return check_call(grads, K, N, dtype, out, o);
+}
+
+int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                void* out, const adasum_options* opts, void* stream) {
+    Opts o;
+    int64_t N = 0;
+    int rc = check_reduce_args(grads, K, layer_offsets, n_layers, dtype, out, opts, o, N);
     if (rc != ADASUM_OK || N == 0) return rc;
 
     std::lock_guard<std::mutex> lock(g_mutex);
@@ -818,6 +836,146 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
                            n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     return execute_plan(p, grads, dtype, out, o, stream);
+}
+
+// ---- the same reduction without any allocation -----------------------------------
+
+// Hands out consecutive pieces of a region, each at the next multiple of `align` bytes.
+struct Carver {
+    size_t off = 0;
+    size_t take(size_t bytes, size_t align = 256) {
+        off = align_up(off, align);
+        const size_t at = off;
+        off += bytes;
+        return at;
+    }
+};
+
+// adasum_reduce_ex with tile tables and workspace inside the library's static device array:
+// the layer table goes to the device in kernel arguments, the tables are built there, and the
+// scheduler then runs on a plan that only borrows that memory.
+int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                        void* out, const adasum_options* opts, void* stream) {
+    Opts o;
+    int64_t N = 0;
+    int rc = check_reduce_args(grads, K, layer_offsets, n_layers, dtype, out, opts, o, N);
+    if (rc != ADASUM_OK) return rc;
+    if (o.workspace != nullptr || o.use_graph) return ADASUM_ERR_INVALID_ARG;
+    if (N == 0) return ADASUM_OK;
+
+    const int L = n_layers;
+    const int node_type = node_dtype(dtype);
+    Plan plan;   // host-side description only; its device pointers point into the static array
+    plan.borrowed = true;
+    plan.K = K;
+    plan.radix = o.radix == 0 ? default_radix(o) : o.radix;
+    plan.order = o.order;
+    plan.node_type = node_type;
+    struct CombTable {
+        int cap;
+        int64_t n;
+        size_t off_tiles, off_begin, off_index;
+    };
+    std::vector<CombTable> combs;
+    Carver carve;
+    size_t off_offsets = 0, off_gram_tiles = 0, off_gram_begin = 0, off_small = 0, off_ws = 0;
+    int gcap = 0;
+    int64_t n_gram = 0;
+    try {
+        rc = o.order == ADASUM_ORDER_LINEAR ? build_linear_passes(K, plan.radix, plan.radices)
+                                            : build_levels(K, plan.radix, plan.radices);
+        if (rc != ADASUM_OK) return rc;
+        const int Kv = o.order == ADASUM_ORDER_LINEAR ? K : virtual_leaves(plan.radices);
+        int64_t small_elems = 0;
+        if (K > 1) {
+            for (int l = 0; l < L; ++l) {
+                const int64_t len = layer_offsets[l + 1] - layer_offsets[l];
+                if (len >= 1 && len <= kSmallLayer) {
+                    ++plan.n_small;
+                    small_elems += len;
+                }
+            }
+        }
+        gcap = gram_tile_capacity(layer_offsets, L);
+        n_gram = count_tiles(layer_offsets, L, gcap);
+        plan.lay = make_layout(Kv, N, L, n_gram, norm_entries_bound(Kv, layer_offsets, L, plan.radices, node_type),
+                               plan.radices, o.order, K + 1, small_elems, node_type);
+        // the combine tables this reduction reads: one per distinct tile capacity
+        std::vector<int> caps;
+        if (K == 1) caps.push_back(combine_tile_capacity(dtype, 1));
+        for (size_t lv = 0; lv < plan.radices.size(); ++lv) {
+            const bool leaves = lv == 0 || o.order == ADASUM_ORDER_LINEAR;
+            caps.push_back(combine_tile_capacity(leaves ? dtype : node_type, plan.radices[lv]));
+        }
+        off_offsets = carve.take(sizeof(int64_t) * (static_cast<size_t>(L) + 1));
+        off_gram_tiles = carve.take(sizeof(adasum_tile) * static_cast<size_t>(n_gram));
+        off_gram_begin = carve.take(sizeof(int32_t) * (static_cast<size_t>(L) + 1));
+        for (int cap : caps) {
+            bool seen = false;
+            for (const CombTable& c : combs) seen = seen || c.cap == cap;
+            if (seen) continue;
+            if (cap < 1 || gcap % cap != 0) return ADASUM_ERR_INVALID_ARG;   // (never: powers of two below the Gram tile)
+            CombTable c;
+            c.cap = cap;
+            c.n = count_tiles(layer_offsets, L, cap);
+            c.off_tiles = carve.take(sizeof(adasum_tile) * static_cast<size_t>(c.n));
+            c.off_begin = carve.take(sizeof(int32_t) * (static_cast<size_t>(L) + 1));
+            c.off_index = carve.take(sizeof(int32_t) * (static_cast<size_t>(n_gram) + 1));
+            combs.push_back(c);
+        }
+        off_small = carve.take(sizeof(SmallLayer) * static_cast<size_t>(plan.n_small));
+        off_ws = carve.take(plan.lay.total);
+    } catch (const std::bad_alloc&) {
+        return ADASUM_ERR_OUT_OF_MEMORY;
+    }
+    if (carve.off > ADASUM_NOALLOC_SCRATCH_BYTES) return ADASUM_ERR_TOO_LARGE;
+
+    char* base = nullptr;
+    size_t have = 0;
+    ADASUM_LAUNCH(static_scratch(&base, &have));
+    if (carve.off > have) return ADASUM_ERR_TOO_LARGE;
+    ADASUM_HIP(hipGetDevice(&plan.device));
+
+    int64_t* d_offsets = reinterpret_cast<int64_t*>(base + off_offsets);
+    ADASUM_LAUNCH(launch_put_offsets(layer_offsets, L, d_offsets, stream));
+    plan.gram_tiles.capacity = gcap;
+    plan.gram_tiles.n_borrowed = n_gram;
+    plan.gram_tiles.d_tiles = reinterpret_cast<adasum_tile*>(base + off_gram_tiles);
+    plan.gram_tiles.d_layer_begin = reinterpret_cast<int32_t*>(base + off_gram_begin);
+    ADASUM_LAUNCH(launch_build_tiles(d_offsets, L, gcap, n_gram, plan.gram_tiles.d_tiles,
+                                     plan.gram_tiles.d_layer_begin, stream));
+    try {
+        for (const CombTable& c : combs) {
+            TileTable t;
+            t.capacity = c.cap;
+            t.n_borrowed = c.n;
+            t.d_tiles = reinterpret_cast<adasum_tile*>(base + c.off_tiles);
+            t.d_layer_begin = reinterpret_cast<int32_t*>(base + c.off_begin);
+            t.d_first_in_gram = reinterpret_cast<int32_t*>(base + c.off_index);
+            ADASUM_LAUNCH(launch_build_tiles(d_offsets, L, c.cap, c.n, t.d_tiles, t.d_layer_begin, stream));
+            ADASUM_LAUNCH(launch_index_tiles(d_offsets, plan.gram_tiles.d_tiles, n_gram, c.cap, t.d_layer_begin, c.n,
+                                             t.d_first_in_gram, stream));
+            plan.comb_tables.emplace(c.cap, std::move(t));
+        }
+    } catch (const std::bad_alloc&) {
+        return ADASUM_ERR_OUT_OF_MEMORY;
+    }
+    plan.d_small = reinterpret_cast<SmallLayer*>(base + off_small);
+    ADASUM_LAUNCH(launch_build_small(d_offsets, L, plan.n_small, plan.d_small, stream));
+
+    // per-kernel timing would create events: not here
+    struct NoProfile {
+        NoProfile() { t_no_profile = true; }
+        ~NoProfile() { t_no_profile = false; }
+    } quiet;
+    char* ws = base + off_ws;
+    try {
+        if (K == 1) return run_copy(&plan, ws, grads, dtype, out, o, stream);
+        if (o.order == ADASUM_ORDER_LINEAR) return run_linear(&plan, ws, grads, dtype, out, o, stream);
+        return run_tree(&plan, ws, grads, dtype, out, o, stream);
+    } catch (const std::bad_alloc&) {
+        return ADASUM_ERR_OUT_OF_MEMORY;
+    }
 }
 
 }  // namespace
@@ -910,6 +1068,11 @@ int adasum_reduce(const void* const* grads, int K, const int64_t* layer_offsets,
 int adasum_reduce_ex(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
                      void* out, const adasum_options* opts, void* stream) {
     return reduce_impl(grads, K, layer_offsets, n_layers, dtype, out, opts, stream);
+}
+
+int adasum_reduce_noalloc(const void* const* grads, int K, const int64_t* layer_offsets, int n_layers, int dtype,
+                          void* out, const adasum_options* opts, void* stream) {
+    return reduce_noalloc_impl(grads, K, layer_offsets, n_layers, dtype, out, opts, stream);
 }
 
 int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, int dtype,
@@ -1126,6 +1289,7 @@ const char* adasum_strerror(int code) {
         case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";
         case ADASUM_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
         case ADASUM_ERR_ALIAS: return "output overlaps an input";
+        case ADASUM_ERR_TOO_LARGE: return "adasum_reduce_noalloc: tile tables and workspace of this problem exceed the static scratch (ADASUM_NOALLOC_SCRATCH_BYTES); use adasum_reduce_ex or a plan";
         default: return "unknown error";
     }
 }

@@ -12,7 +12,7 @@
 namespace adasum {
 
 // Elements one Gram workgroup covers at most (a long tile amortises the
-// workgroup's start-up and its 36-value reduction).  A multiple of every
+// workgroup's start-up and its reduction of up to 136 values).  A multiple of every
 // granule (4 fp32 or 8 bf16 elements per 16-byte access) times the workgroup size.
 #ifndef ADASUM_TILE
 #define ADASUM_TILE 65536
@@ -251,5 +251,24 @@ int launch_small_reduce(int out_dtype, const double* compact, int K, const Small
                         void* stream);
 
 const char* kernel_name(const char* kind, int dtype, int out_dtype, int R, bool diag, char* buf, size_t n);
+
+// ---- set-up without allocation (adasum_reduce_noalloc) ---------------------------
+
+// Device address and size of the library's static scratch array on the current device
+// (looked up once per device).  Returns a hipError_t as int.
+int static_scratch(char** base, size_t* bytes);
+// Copies a host layer table (n_layers + 1 entries) to `d_offsets` through kernel arguments,
+// a few hundred entries per launch: no copy engine, no staging buffer.
+int launch_put_offsets(const int64_t* layer_offsets, int n_layers, int64_t* d_offsets, void* stream);
+// The device-side twin of build_tiles: writes the tile table of `capacity` elements for the
+// layer table at d_offsets.  `n_tiles` must be count_tiles(...) for the same table.
+int launch_build_tiles(const int64_t* d_offsets, int n_layers, int64_t capacity, int64_t n_tiles,
+                       adasum_tile* d_tiles, int32_t* d_layer_begin, void* stream);
+// first_in_gram[t] = first tile of the combine table (capacity `ccap`, a divisor of the Gram
+// tiles' capacity) inside Gram tile t; first_in_gram[n_gram] = n_comb.
+int launch_index_tiles(const int64_t* d_offsets, const adasum_tile* d_gram_tiles, int64_t n_gram, int64_t ccap,
+                       const int32_t* d_comb_layer_begin, int64_t n_comb, int32_t* d_first_in_gram, void* stream);
+// The device-side twin of find_small_layers; `n_small` must be what that returns in `small`.
+int launch_build_small(const int64_t* d_offsets, int n_layers, int n_small, SmallLayer* d_small, void* stream);
 
 }  // namespace adasum

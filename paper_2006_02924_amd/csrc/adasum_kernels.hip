@@ -19,8 +19,10 @@
 // partial in memory, summed later in a fixed order; no atomics anywhere.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "adasum_host.h"
@@ -44,6 +46,11 @@
 #ifndef ADASUM_BF16_DOT2
 #define ADASUM_BF16_DOT2 1
 #endif
+
+// Scratch memory of the entry point that allocates nothing (adasum_reduce_noalloc): tile
+// tables and workspace of one reduction.  One copy per GPU, held until the process ends; its
+// device address comes from hipGetSymbolAddress (static_scratch below), never from this name.
+static __device__ __align__(256) unsigned char scratch[ADASUM_NOALLOC_SCRATCH_BYTES];
 
 namespace adasum {
 namespace {
@@ -1001,6 +1008,144 @@ trace_sums_kernel(const double* __restrict__ gram, int R, int n_groups, int n_la
     out[static_cast<long long>(l) * out_stride] = v;
 }
 
+// ---------------------------------------------------------------------------
+// Set-up without allocation: the layer table arrives in kernel arguments and the
+// tile tables are built on the device (the twins of build_tiles / index_against /
+// find_small_layers on the host).
+// ---------------------------------------------------------------------------
+constexpr int kOffsetsPerLaunch = 384;
+struct OffsetChunk {
+    long long v[kOffsetsPerLaunch];
+};
+
+__global__ void __launch_bounds__(kOffsetsPerLaunch)
+put_offsets_kernel(const OffsetChunk c, int n, long long* __restrict__ dst) {
+    const int i = threadIdx.x;
+    if (i < n) dst[i] = c.v[i];
+}
+
+constexpr int kScanThreads = 1024;
+
+// Exclusive prefix sums of one value per thread over a workgroup of kScanThreads; returns the
+// sum of the values of the threads before this one, *total gets the sum over all threads.
+__device__ __forceinline__ long long block_exclusive_scan(long long v, long long* sh, long long* total) {
+    const int tid = threadIdx.x;
+    __syncthreads();   // sh may still be read from a previous scan
+    sh[tid] = v;
+    __syncthreads();
+    for (int d = 1; d < kScanThreads; d <<= 1) {
+        const long long add = tid >= d ? sh[tid - d] : 0;
+        __syncthreads();
+        sh[tid] += add;
+        __syncthreads();
+    }
+    *total = sh[kScanThreads - 1];
+    return sh[tid] - v;
+}
+
+__device__ __forceinline__ long long tiles_of_layer(long long lo, long long hi, long long cap) {
+    return hi > lo ? (hi - 1) / cap - lo / cap + 1 : 0;
+}
+
+// layer_begin[l] = tiles of the layers before l; layer_begin[n_layers] = all tiles.  One workgroup:
+// every thread takes a run of consecutive layers.
+__global__ void __launch_bounds__(kScanThreads)
+tile_scan_kernel(const long long* __restrict__ offs, int n_layers, long long cap, int32_t* __restrict__ layer_begin) {
+    __shared__ long long sh[kScanThreads];
+    const int tid = threadIdx.x;
+    const int per = (n_layers + kScanThreads - 1) / kScanThreads;
+    const long long first = static_cast<long long>(tid) * per;
+    const int l0 = first < n_layers ? static_cast<int>(first) : n_layers;
+    const int l1 = first + per < n_layers ? static_cast<int>(first + per) : n_layers;
+    long long mine = 0;
+    for (int l = l0; l < l1; ++l) mine += tiles_of_layer(offs[l], offs[l + 1], cap);
+    long long total;
+    long long run = block_exclusive_scan(mine, sh, &total);
+    for (int l = l0; l < l1; ++l) {
+        layer_begin[l] = static_cast<int32_t>(run);
+        run += tiles_of_layer(offs[l], offs[l + 1], cap);
+    }
+    if (tid == 0) layer_begin[n_layers] = static_cast<int32_t>(total);
+}
+
+// Tile t of the table: its layer is the last one whose first tile is at or before t; inside the
+// layer the boundaries are the global multiples of the capacity.
+__global__ void __launch_bounds__(kThreads)
+tile_fill_kernel(const long long* __restrict__ offs, int n_layers, long long cap,
+                 const int32_t* __restrict__ layer_begin, int n_tiles, adasum_tile* __restrict__ tiles) {
+    const int t = static_cast<int>(blockIdx.x) * kThreads + static_cast<int>(threadIdx.x);
+    if (t >= n_tiles) return;
+    int lo = 0, hi = n_layers - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) / 2;
+        if (layer_begin[mid] <= t) lo = mid;
+        else hi = mid - 1;
+    }
+    const long long a = offs[lo], b = offs[lo + 1];
+    const long long j = t - layer_begin[lo];
+    const long long s = j == 0 ? a : (a / cap + j) * cap;
+    const long long stop = (a / cap + j + 1) * cap;
+    adasum_tile r;
+    r.start = s;
+    r.len = static_cast<int32_t>((stop < b ? stop : b) - s);
+    r.layer = lo;
+    tiles[t] = r;
+}
+
+// A Gram tile starts at its layer's first element or at a global multiple of the Gram capacity,
+// which the combine capacity divides: the combine tile that starts there is found by counting.
+__global__ void __launch_bounds__(kThreads)
+tile_index_kernel(const long long* __restrict__ offs, const adasum_tile* __restrict__ gram_tiles, int n_gram,
+                  long long ccap, const int32_t* __restrict__ comb_layer_begin, int n_comb,
+                  int32_t* __restrict__ first_in_gram) {
+    const int t = static_cast<int>(blockIdx.x) * kThreads + static_cast<int>(threadIdx.x);
+    if (t > n_gram) return;
+    if (t == n_gram) {
+        first_in_gram[t] = n_comb;
+        return;
+    }
+    const adasum_tile g = gram_tiles[t];
+    const long long a = offs[g.layer];
+    first_in_gram[t] = comb_layer_begin[g.layer] + static_cast<int32_t>(g.start / ccap - a / ccap);
+}
+
+// The table of the layers of 1 .. kSmallLayer elements, in layer order, with each one's place in
+// a row of the compact copy.  One workgroup, as tile_scan_kernel.
+__global__ void __launch_bounds__(kScanThreads)
+small_table_kernel(const long long* __restrict__ offs, int n_layers, SmallLayer* __restrict__ small) {
+    __shared__ long long sh[kScanThreads];
+    const int tid = threadIdx.x;
+    const int per = (n_layers + kScanThreads - 1) / kScanThreads;
+    const long long first = static_cast<long long>(tid) * per;
+    const int l0 = first < n_layers ? static_cast<int>(first) : n_layers;
+    const int l1 = first + per < n_layers ? static_cast<int>(first + per) : n_layers;
+    long long count = 0, elems = 0;
+    for (int l = l0; l < l1; ++l) {
+        const long long len = offs[l + 1] - offs[l];
+        if (len >= 1 && len <= kSmallLayer) {
+            ++count;
+            elems += len;
+        }
+    }
+    long long total;
+    long long idx = block_exclusive_scan(count, sh, &total);
+    long long coff = block_exclusive_scan(elems, sh, &total);
+    for (int l = l0; l < l1; ++l) {
+        const long long len = offs[l + 1] - offs[l];
+        if (len >= 1 && len <= kSmallLayer) {
+            SmallLayer s;
+            s.start = offs[l];
+            s.len = static_cast<int32_t>(len);
+            s.layer = l;
+            s.coff = static_cast<int32_t>(coff);
+            s.pad = 0;
+            small[idx] = s;
+            ++idx;
+            coff += len;
+        }
+    }
+}
+
 inline int check_launch() { return static_cast<int>(hipGetLastError()); }
 
 inline bool grid_fits(long long blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
@@ -1313,6 +1458,80 @@ int launch_small_reduce(int out_dtype, const double* compact, int K, const Small
     else if (out_dtype == ADASUM_F64) ADASUM_SMALL(double);
     else ADASUM_SMALL(float);
 #undef ADASUM_SMALL
+    return check_launch();
+}
+
+int static_scratch(char** base, size_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static char* ptrs[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        // every GPU holds its own copy of the array at its own address
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return static_cast<int>(e);
+        if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 255u) != 0) return static_cast<int>(hipErrorInvalidSymbol);
+        ptrs[dev] = static_cast<char*>(p);
+    }
+    *base = ptrs[dev];
+    *bytes = sizeof(scratch);
+    return 0;
+}
+
+int launch_put_offsets(const int64_t* layer_offsets, int n_layers, int64_t* d_offsets, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n = static_cast<int64_t>(n_layers) + 1;
+    for (int64_t i0 = 0; i0 < n; i0 += kOffsetsPerLaunch) {
+        const int m = static_cast<int>(std::min<int64_t>(kOffsetsPerLaunch, n - i0));
+        OffsetChunk c;
+        for (int i = 0; i < kOffsetsPerLaunch; ++i) c.v[i] = i < m ? layer_offsets[i0 + i] : 0;
+        hipLaunchKernelGGL(put_offsets_kernel, dim3(1), dim3(kOffsetsPerLaunch), 0, st, c, m,
+                           reinterpret_cast<long long*>(d_offsets) + i0);
+        const int rc = check_launch();
+        if (rc != 0) return rc;
+    }
+    return 0;
+}
+
+int launch_build_tiles(const int64_t* d_offsets, int n_layers, int64_t capacity, int64_t n_tiles,
+                       adasum_tile* d_tiles, int32_t* d_layer_begin, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_layers < 1 || capacity < 1 || n_tiles < 0 || n_tiles > 0x7fffffffLL)
+        return static_cast<int>(hipErrorInvalidValue);
+    const long long* offs = reinterpret_cast<const long long*>(d_offsets);
+    hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, offs, n_layers,
+                       static_cast<long long>(capacity), d_layer_begin);
+    int rc = check_launch();
+    if (rc != 0 || n_tiles == 0) return rc;
+    const unsigned blocks = static_cast<unsigned>((n_tiles + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(tile_fill_kernel, dim3(blocks), dim3(kThreads), 0, st, offs, n_layers,
+                       static_cast<long long>(capacity), d_layer_begin, static_cast<int>(n_tiles), d_tiles);
+    return check_launch();
+}
+
+int launch_index_tiles(const int64_t* d_offsets, const adasum_tile* d_gram_tiles, int64_t n_gram, int64_t ccap,
+                       const int32_t* d_comb_layer_begin, int64_t n_comb, int32_t* d_first_in_gram, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_gram < 0 || n_gram >= 0x7fffffffLL || n_comb < 0 || n_comb > 0x7fffffffLL || ccap < 1)
+        return static_cast<int>(hipErrorInvalidValue);
+    const unsigned blocks = static_cast<unsigned>((n_gram + 1 + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(tile_index_kernel, dim3(blocks), dim3(kThreads), 0, st,
+                       reinterpret_cast<const long long*>(d_offsets), d_gram_tiles, static_cast<int>(n_gram),
+                       static_cast<long long>(ccap), d_comb_layer_begin, static_cast<int>(n_comb), d_first_in_gram);
+    return check_launch();
+}
+
+int launch_build_small(const int64_t* d_offsets, int n_layers, int n_small, SmallLayer* d_small, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_small == 0) return 0;
+    if (n_layers < 1) return static_cast<int>(hipErrorInvalidValue);
+    hipLaunchKernelGGL(small_table_kernel, dim3(1), dim3(kScanThreads), 0, st,
+                       reinterpret_cast<const long long*>(d_offsets), n_layers, d_small);
     return check_launch();
 }
 

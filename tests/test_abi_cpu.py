@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_strerror(lib):
     assert b"libadasum" in lib.adasum_version()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert lib.adasum_strerror(code)
     assert lib.adasum_strerror(-99) == b"unknown error"
 
@@ -66,6 +66,32 @@ def test_reduce_rejects_bad_arguments(lib):
     assert _call_reduce(lib, good, 4, offs, B.F32, None) == B.ERR_INVALID_ARG
     # out overlapping worker 1's buffer (30 fp32 = 120 bytes from 0x2000)
     assert _call_reduce(lib, good, 4, offs, B.F32, 0x2040) == B.ERR_ALIAS
+
+
+def test_noalloc_entry_point_validates_before_any_device_work(lib):
+    """adasum_reduce_noalloc: the checks of adasum_reduce_ex, no caller workspace or graph replay,
+    and a problem whose tables and workspace exceed the static array is refused up front."""
+    def call(ptrs, K, offs, dtype, out, opts=None):
+        arr = (C.c_void_p * len(ptrs))(*ptrs)
+        o = (C.c_int64 * len(offs))(*offs)
+        return lib.adasum_reduce_noalloc(arr, K, o, len(offs) - 1, dtype, out, C.byref(opts) if opts else None, None)
+
+    good = [0x100000 * (i + 1) for i in range(64)]
+    out = 0x90000000
+    assert call(good[:2], 2, [0], B.BF16, out) == B.OK                      # empty problem
+    assert call(good[:2], 0, [0, 8], B.BF16, out) == B.ERR_INVALID_ARG
+    assert call(good[:2], 2, [0, 8], 9, out) == B.ERR_UNSUPPORTED
+    assert call(good[:2], 2, [0, 8], B.F32, out + 4) == B.ERR_MISALIGNED
+    assert call(good[:2], 2, [0, 8], B.F32, good[1] + 16) == B.ERR_ALIAS
+    assert call(good[:2], 2, [0, 8], B.F32, out, _opts(use_graph=1)) == B.ERR_INVALID_ARG
+    assert call(good[:2], 2, [0, 8], B.F32, out, _opts(workspace=0x10000, workspace_bytes=1 << 30)) \
+        == B.ERR_INVALID_ARG
+    # K = 64 over 4.2 M elements needs four fp32 nodes = 67 MB: more than the 64 MiB array
+    assert call(good, 64, [0, 4_200_000], B.BF16, out) == B.ERR_TOO_LARGE
+    assert B.adasum_workspace_bytes(64, [0, 4_200_000], B.BF16) > B.NOALLOC_SCRATCH_BYTES
+    assert b"static scratch" in lib.adasum_strerror(B.ERR_TOO_LARGE)
+    header = open(os.path.join(ROOT, "include", "adasum.h")).read()
+    assert re.search(r"#define\s+ADASUM_NOALLOC_SCRATCH_BYTES\s+\(64u << 20\)", header)
 
 
 def test_empty_problem_is_a_no_op(lib):
