@@ -28,9 +28,16 @@
  *     16-byte aligned.  The caller owns every buffer it passes; inputs are never
  *     modified; host arrays are copied during the call and may be freed at return.
  *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
- *     default stream) and the call returns without synchronising.  Calls that
- *     share a plan (same K, dtypes, radix and layer table) must be issued on one
- *     stream or be externally ordered: they share the plan's workspace.
+ *     default stream) and the call returns without synchronising.
+ *   - thread-safe.  Calls with the same K, dtypes, radix, order, delta form and
+ *     layer table share one cached plan and its workspace; the library orders
+ *     them on the device: a call issued on another stream than the previous call
+ *     with that plan first waits for it (an event wait, no host blocking).  So
+ *     the same model shape may be reduced from several host threads and streams
+ *     at once and every result is right, but those calls run one after another;
+ *     callers that want them to overlap hold one plan each (adasum_plan_create).
+ *     No ordering is inserted on a stream that is being captured into a graph:
+ *     what a caller captures, it orders.
  *   - results are deterministic: identical inputs give bit-identical outputs
  *     (no atomics anywhere on the path).
  */
@@ -169,7 +176,9 @@ ADASUM_API int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n
  *          Section 4.1: every execute must then pass a delta_start, else none may
  *   plan   receives the handle; destroy it with adasum_plan_destroy (waits for the
  *          device).  adasum_shutdown does not touch it.
- * Executes on one plan must be stream-ordered (they share its workspace).
+ * Executes on one plan share its workspace and are ordered like the calls above (a
+ * different stream than the previous execute waits for it; none while capturing).
+ * Executes on different plans take no common lock and may overlap.
  */
 typedef struct adasum_plan adasum_plan;
 ADASUM_API int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dtype,

@@ -193,8 +193,9 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
     out_code = in_code if out_dtype is None else _code_of(out_dtype)
     if out is None:
         out = torch.empty(N, dtype=_torch_dtype(out_code), device=grads[0].device)
-    elif _dtype_code(out) != out_code or out.numel() != N or not out.is_contiguous():
-        raise ValueError("out has the wrong dtype, size or layout")
+    elif (_dtype_code(out) != out_code or out.numel() != N or not out.is_contiguous()
+          or out.device != grads[0].device):
+        raise ValueError("out has the wrong dtype, size, layout or device")
     ptrs = _ptr_array(grads)
     plain = (out_code == in_code and radix == 0 and order == ORDER_TREE and layer_stats is None
              and workspace is None and not use_graph and delta_start is None and not noalloc)
@@ -211,8 +212,9 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
     if layer_stats is not None:
-        if layer_stats.dtype != torch.float64 or layer_stats.numel() != 2 * L or not layer_stats.is_contiguous():
-            raise ValueError("layer_stats must be a contiguous float64 tensor of n_layers x 2")
+        if (layer_stats.dtype != torch.float64 or layer_stats.numel() != 2 * L or not layer_stats.is_contiguous()
+                or layer_stats.device != grads[0].device):
+            raise ValueError("layer_stats must be a contiguous float64 tensor of n_layers x 2 on the device of grads")
         o.layer_stats = layer_stats.data_ptr()
     if delta_start is not None:
         _check_inputs([delta_start], N)
@@ -232,7 +234,7 @@ class Plan:
                  order: int = ORDER_TREE, use_graph: bool = False, workspace=None, delta: bool = False):
         lib = load()
         offs, L = _offsets(layer_offsets)
-        self.K, self.N = K, int(layer_offsets[-1])
+        self.K, self.N, self.n_layers = K, int(layer_offsets[-1]), L
         self.in_code = _code_of(dtype)
         self.out_code = self.in_code if out_dtype is None else _code_of(out_dtype)
         self.delta = delta
@@ -267,14 +269,21 @@ class Plan:
             out = torch.empty(self.N, dtype=_torch_dtype(self.out_code), device=grads[0].device)
         elif _dtype_code(out) != self.out_code or out.numel() != self.N or not out.is_contiguous():
             raise ValueError("out has the wrong dtype, size or layout")
+        if out.device != grads[0].device:
+            raise ValueError("out must be on the device of grads")
         stats_ptr = None
         if layer_stats is not None:
-            if layer_stats.dtype != torch.float64 or not layer_stats.is_contiguous():
-                raise ValueError("layer_stats must be a contiguous float64 tensor of n_layers x 2")
+            # the kernels write n_layers x 2 doubles: a shorter buffer would be overrun on the device
+            if (layer_stats.dtype != torch.float64 or not layer_stats.is_contiguous()
+                    or layer_stats.numel() != 2 * self.n_layers or layer_stats.device != grads[0].device):
+                raise ValueError("layer_stats must be a contiguous float64 tensor of n_layers x 2 on the device "
+                                 "of grads")
             stats_ptr = C.c_void_p(layer_stats.data_ptr())
         start_ptr = None
         if delta_start is not None:
             _check_inputs([delta_start], self.N)
+            if delta_start.dtype != grads[0].dtype or delta_start.device != grads[0].device:
+                raise ValueError("delta_start must have the dtype and device of grads")
             start_ptr = C.c_void_p(delta_start.data_ptr())
         check(load().adasum_plan_execute(self._h, _ptr_array(grads), C.c_void_p(out.data_ptr()), stats_ptr,
                                          start_ptr, _stream(stream)))

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstddef>
 #include <cstdio>
 #include <cstring>
@@ -170,6 +171,9 @@ struct Plan {
     int radix = 0;
     int order = ADASUM_ORDER_TREE;
     int node_type = ADASUM_F32;           // storage type of the intermediate nodes
+    // cache key of library-owned plans beyond the shape: calls that differ in any of these get
+    // plans (and workspaces) of their own
+    int in_dtype = -1, out_dtype = -1, delta = 0;
     std::vector<int64_t> offsets;
     TileTable gram_tiles;                 // capacity kTile
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
@@ -180,6 +184,14 @@ struct Plan {
     Layout lay;
     char* d_ws = nullptr;   // library-owned workspace (lazily allocated)
     bool borrowed = false;  // every device pointer lives in memory this plan does not own
+
+    // Calls on one plan share its workspace.  Each eager call leaves `done` on its stream; a call
+    // that arrives on another stream first waits for it, so calls from several streams are
+    // serialised on the device instead of racing.  `mu` serialises the host side.
+    std::mutex mu;
+    hipEvent_t done = nullptr;
+    hipStream_t last_stream = nullptr;
+    bool has_last = false;
 
     // Captured level ladders, one per distinct set of buffers (see launch_as_graph).
     struct GraphEntry {
@@ -222,6 +234,7 @@ struct Plan {
             if (g.graph) (void)hipGraphDestroy(g.graph);
         }
         if (capture_stream) (void)hipStreamDestroy(capture_stream);
+        if (done) (void)hipEventDestroy(done);
         gram_tiles.release();
         for (auto& kv : comb_tables) kv.second.release();
         if (borrowed) return;
@@ -270,17 +283,23 @@ int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets
         ADASUM_HIP(hipMemcpy(p->d_small, p->small.data(), bytes, hipMemcpyHostToDevice));
     }
     p->n_small = static_cast<int>(p->small.size());
+    ADASUM_HIP(hipEventCreateWithFlags(&p->done, hipEventDisableTiming));
     out = std::move(p);
     return ADASUM_OK;
 }
 
 // The library's own cache of plans, keyed by shape.
-int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers, Plan** out) {
+// `order` is a tree order or kStepPlans (the step entry points keep plans of their own).
+constexpr int kStepPlans = 100;
+int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, bool delta, const int64_t* offsets,
+                      int n_layers, Plan** out) {
+    const int node_type = node_dtype(in_dtype);
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
     for (size_t i = 0; i < g_plans.size(); ++i) {
         Plan* p = g_plans[i].get();
         if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
+            p->in_dtype == in_dtype && p->out_dtype == out_dtype && p->delta == (delta ? 1 : 0) &&
             static_cast<int>(p->offsets.size()) == n_layers + 1 &&
             std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
             // most recently used last
@@ -292,8 +311,12 @@ int find_or_make_plan(int K, int radix, int order, int node_type, const int64_t*
     // a bounded cache: the least recently used plan goes (hipFree waits for work in flight)
     while (g_plans.size() >= kMaxPlans) g_plans.erase(g_plans.begin());
     std::unique_ptr<Plan> p;
-    const int rc = make_plan(K, radix, order, node_type, offsets, n_layers, p);
+    const int rc = make_plan(K, radix, order == kStepPlans ? ADASUM_ORDER_TREE : order, node_type, offsets, n_layers, p);
     if (rc != ADASUM_OK) return rc;
+    p->order = order;
+    p->in_dtype = in_dtype;
+    p->out_dtype = out_dtype;
+    p->delta = delta ? 1 : 0;
     *out = p.get();
     g_plans.push_back(std::move(p));
     return ADASUM_OK;
@@ -319,12 +342,14 @@ struct ProfRecord {
     hipEvent_t start, stop;
     double bytes;
 };
-bool g_profile = false;
+std::atomic<bool> g_profile{false};
+std::mutex g_prof_mutex;   // guards g_records and g_event_pool
 thread_local bool t_no_profile = false;   // set while adasum_reduce_noalloc enqueues: events are allocations
 std::vector<ProfRecord> g_records;
 std::vector<hipEvent_t> g_event_pool;
 
 int take_event(hipEvent_t* e) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (!g_event_pool.empty()) {
         *e = g_event_pool.back();
         g_event_pool.pop_back();
@@ -346,6 +371,7 @@ struct Timed {
         if (rc != ADASUM_OK) return rc;
         rc = take_event(&rec.stop);
         if (rc != ADASUM_OK) {
+            std::lock_guard<std::mutex> lock(g_prof_mutex);
             g_event_pool.push_back(rec.start);
             return rc;
         }
@@ -369,11 +395,13 @@ struct Timed {
             g_last_hip_error = static_cast<int>(e);
             return ADASUM_ERR_HIP;
         }
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
         g_records.push_back(rec);
         return ADASUM_OK;
     }
     // a launch that failed leaves no record: its events go back to the pool
     void give_back() {
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
         g_event_pool.push_back(rec.start);
         g_event_pool.push_back(rec.stop);
     }
@@ -797,15 +825,50 @@ int check_call(const void* const* grads, int K, int64_t N, int dtype, void* out,
     return ADASUM_OK;
 }
 
-// Enqueues one reduction with a plan.  g_mutex held.
+// Device-side ordering of the calls that share a plan's workspace.  begin: a call that arrives
+// on another stream than the previous one first waits for that call's event.  end: leaves the
+// event on this call's stream.  A stream that is being captured into a caller's graph gets
+// neither (the caller orders what it captures).  The caller holds the plan's lock or g_mutex.
+int begin_on_stream(Plan* p, void* stream, bool* eager) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    *eager = false;
+    if (p->done == nullptr) return ADASUM_OK;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    ADASUM_HIP(hipStreamIsCapturing(st, &cs));
+    if (cs != hipStreamCaptureStatusNone) return ADASUM_OK;
+    *eager = true;
+    if (p->has_last && p->last_stream != st) ADASUM_HIP(hipStreamWaitEvent(st, p->done, 0));
+    return ADASUM_OK;
+}
+
+int end_on_stream(Plan* p, void* stream, bool eager, int rc) {
+    if (!eager) return rc;
+    // also after a failed enqueue: the launches before the failure may be in flight
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = hipEventRecord(p->done, st);
+    if (e == hipSuccess) {
+        p->last_stream = st;
+        p->has_last = true;
+    } else if (rc == ADASUM_OK) {
+        g_last_hip_error = static_cast<int>(e);
+        rc = ADASUM_ERR_HIP;
+    }
+    return rc;
+}
+
+// Enqueues one reduction with a plan.  The caller holds the plan's lock or g_mutex.
 int execute_plan(Plan* p, const void* const* grads, int dtype, void* out, const Opts& o, void* stream) {
     char* ws = nullptr;
-    const int rc = plan_workspace(p, o, &ws);
+    int rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
-    if (o.use_graph && !g_profile) return launch_as_graph(p, ws, grads, dtype, out, o, stream);
-    if (p->K == 1) return run_copy(p, ws, grads, dtype, out, o, stream);
-    if (o.order == ADASUM_ORDER_LINEAR) return run_linear(p, ws, grads, dtype, out, o, stream);
-    return run_tree(p, ws, grads, dtype, out, o, stream);
+    bool eager = false;
+    rc = begin_on_stream(p, stream, &eager);
+    if (rc != ADASUM_OK) return rc;
+    if (o.use_graph && !g_profile) rc = launch_as_graph(p, ws, grads, dtype, out, o, stream);
+    else if (p->K == 1) rc = run_copy(p, ws, grads, dtype, out, o, stream);
+    else if (o.order == ADASUM_ORDER_LINEAR) rc = run_linear(p, ws, grads, dtype, out, o, stream);
+    else rc = run_tree(p, ws, grads, dtype, out, o, stream);
+    return end_on_stream(p, stream, eager, rc);
 }
 
 // The argument checks every reduce entry point starts with (no device work).  N receives the
@@ -832,8 +895,8 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, node_dtype(dtype), layer_offsets,
-                           n_layers, &p);
+    rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, dtype, o.out_dtype,
+                           o.delta_start != nullptr, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     return execute_plan(p, grads, dtype, out, o, stream);
 }
@@ -1013,7 +1076,6 @@ int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dt
     h->opts.radix = o.radix == 0 ? default_radix(o) : o.radix;
     h->opts.delta_start = nullptr;
     if (layer_offsets[n_layers] > 0) {
-        std::lock_guard<std::mutex> lock(g_mutex);
         rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), layer_offsets, n_layers, h->plan);
         if (rc != ADASUM_OK) return rc;
         if (o.workspace != nullptr && o.workspace_bytes < h->plan->lay.total) return ADASUM_ERR_WORKSPACE;
@@ -1043,7 +1105,8 @@ int adasum_plan_execute(adasum_plan* plan, const void* const* grads, void* out, 
     Plan* p = plan->plan.get();
     const int rc = check_call(grads, p->K, p->lay.N, plan->dtype, out, o);
     if (rc != ADASUM_OK) return rc;
-    std::lock_guard<std::mutex> lock(g_mutex);
+    // the plan's own lock: plans of different callers enqueue side by side
+    std::lock_guard<std::mutex> lock(p->mu);
     return execute_plan(p, grads, plan->dtype, out, o, stream);
 }
 
@@ -1055,7 +1118,6 @@ int adasum_plan_workspace_bytes(const adasum_plan* plan, size_t* bytes) {
 
 int adasum_plan_destroy(adasum_plan* plan) {
     if (plan == nullptr) return ADASUM_OK;
-    std::lock_guard<std::mutex> lock(g_mutex);
     delete plan;   // frees tables, graphs and the plan's own workspace (hipFree waits for work in flight)
     return ADASUM_OK;
 }
@@ -1121,20 +1183,26 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     if (n_layers == 0) return ADASUM_OK;
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, node_dtype(dtype), layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
-    double* partials = reinterpret_cast<double*>(ws + p->lay.off_partials);
-    const TileSet gt = p->gram_tiles.view();
-    Operands ops;
-    std::memset(&ops, 0, sizeof(ops));
-    for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
-    ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, nullptr, stream));
-    ADASUM_LAUNCH(launch_gram_finish(true, gt, n_layers, 1, R, partials, nullptr, gram, nullptr, 0, 0, 0, stream));
-    return ADASUM_OK;
+    bool eager = false;
+    rc = begin_on_stream(p, stream, &eager);
+    if (rc != ADASUM_OK) return rc;
+    auto enqueue = [&]() -> int {
+        double* partials = reinterpret_cast<double*>(ws + p->lay.off_partials);
+        const TileSet gt = p->gram_tiles.view();
+        Operands ops;
+        std::memset(&ops, 0, sizeof(ops));
+        for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
+        ADASUM_LAUNCH(launch_gram(dtype, true, ops, gt, 1, R, partials, nullptr, stream));
+        ADASUM_LAUNCH(launch_gram_finish(true, gt, n_layers, 1, R, partials, nullptr, gram, nullptr, 0, 0, 0, stream));
+        return ADASUM_OK;
+    };
+    return end_on_stream(p, stream, eager, enqueue());
 }
 
 int adasum_group_weights(const double* gram, int R, int n_layers, int order, double* weights, void* stream) {
@@ -1168,32 +1236,38 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     }
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, ADASUM_ORDER_TREE, node_dtype(dtype), layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;
     rc = plan_workspace(p, o, &ws);
     if (rc != ADASUM_OK) return rc;
-    double* normparts = reinterpret_cast<double*>(ws + p->lay.off_normparts);
     TileSet ct;
     rc = p->comb_tiles(dtype, R, &ct);
     if (rc != ADASUM_OK) return rc;
-    Operands ops;
-    std::memset(&ops, 0, sizeof(ops));
-    for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
-    Outputs outs;
-    outs.base = static_cast<char*>(out);
-    outs.slot_bytes = 0;
-    outs.stride = 0;
-    ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, ct, n_layers, 1, R, weights,
-                                 sqnorm ? normparts : nullptr, nullptr, nullptr, stream));
-    if (sqnorm != nullptr) {
-        double* normcoarse = reinterpret_cast<double*>(ws + p->lay.off_normcoarse);
-        const TileSet gt = p->gram_tiles.view();
-        ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, ct, gt, normcoarse, stream));
-        ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, n_layers, sqnorm, 1, stream));
-    }
-    return ADASUM_OK;
+    bool eager = false;
+    rc = begin_on_stream(p, stream, &eager);
+    if (rc != ADASUM_OK) return rc;
+    auto enqueue = [&]() -> int {
+        double* normparts = reinterpret_cast<double*>(ws + p->lay.off_normparts);
+        Operands ops;
+        std::memset(&ops, 0, sizeof(ops));
+        for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
+        Outputs outs;
+        outs.base = static_cast<char*>(out);
+        outs.slot_bytes = 0;
+        outs.stride = 0;
+        ADASUM_LAUNCH(launch_combine(dtype, out_dtype, ops, outs, ct, n_layers, 1, R, weights,
+                                     sqnorm ? normparts : nullptr, nullptr, nullptr, stream));
+        if (sqnorm != nullptr) {
+            double* normcoarse = reinterpret_cast<double*>(ws + p->lay.off_normcoarse);
+            const TileSet gt = p->gram_tiles.view();
+            ADASUM_LAUNCH(launch_norm_coarsen(normparts, 1, ct, gt, normcoarse, stream));
+            ADASUM_LAUNCH(launch_layer_sums(normcoarse, 1, gt, n_layers, sqnorm, 1, stream));
+        }
+        return ADASUM_OK;
+    };
+    return end_on_stream(p, stream, eager, enqueue());
 }
 
 int adasum_tile_capacity(void) { return kTile; }
@@ -1245,14 +1319,13 @@ int adasum_plan_groups(int K, int radix, int* first_worker, int cap, int* n_grou
 }
 
 int adasum_profile_enable(int on) {
-    std::lock_guard<std::mutex> lock(g_mutex);
     g_profile = on != 0;
     return ADASUM_OK;
 }
 
 int adasum_profile_collect(adasum_kernel_profile* out, int cap, int* n) {
     if (n == nullptr || cap < 0 || (out == nullptr && cap > 0)) return ADASUM_ERR_INVALID_ARG;
-    std::lock_guard<std::mutex> lock(g_mutex);
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     std::vector<adasum_kernel_profile> agg;
     for (auto& r : g_records) {
         ADASUM_HIP(hipEventSynchronize(r.stop));
@@ -1301,6 +1374,7 @@ const char* adasum_version(void) { return "libadasum 0.1.0 (gfx950)"; }
 int adasum_shutdown(void) {
     std::lock_guard<std::mutex> lock(g_mutex);
     g_plans.clear();
+    std::lock_guard<std::mutex> prof_lock(g_prof_mutex);
     for (auto& r : g_records) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);

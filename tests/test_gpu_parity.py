@@ -836,3 +836,88 @@ def test_two_host_threads_on_their_own_streams():
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+def test_same_shape_from_several_streams_and_threads():
+    """The common case: several host threads reduce the SAME model shape, each on its own stream
+    with its own values.  They share one cached plan and its workspace; the library orders
+    their launches on the device (a call on another stream than the previous one waits for
+    it), so every result is right -- against the oracle and bit-identical on every repeat.
+    One thread also switches between bf16 and fp32 results and the delta form on the same
+    table (plans of their own)."""
+    import threading
+    sizes = [3, 40000, 1, 70000, 16384 * 3 + 5]
+    K = 16
+    jobs = []
+    for seed in (1, 2, 3):
+        w = W.correlated_gaussian(sizes, K, dtype=torch.bfloat16, device=DEV, seed=90 + seed)
+        jobs.append((w, oracle_reduce(w.grads, w.layer_offsets), torch.cuda.Stream(device=DEV)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i, job):
+        w, ref, stream = job
+        try:
+            first = {}
+            # output buffers made up front: a buffer torch frees while a side stream still writes
+            # it could be handed to another thread
+            bufs = {od: torch.empty(w.N, dtype=od, device=DEV) for od in (torch.float32, torch.bfloat16)}
+            torch.cuda.synchronize()
+            for rep in range(40):
+                od = torch.float32 if (i == 0 and rep % 2) else torch.bfloat16
+                # no synchronisation between the calls of a thread: launches of the threads interleave
+                out = B.adasum_reduce(w.grads, w.layer_offsets, bufs[od], out_dtype=od, stream=stream)
+                if rep % 8 == 7 or rep < 2:
+                    stream.synchronize()
+                    if od not in first:
+                        first[od] = out.clone()
+                        assert_parity(out, ref, w.layer_offsets, what=f"thread {i} {od}")
+                    else:
+                        assert torch.equal(out, first[od]), (i, rep)
+            stream.synchronize()
+        except Exception as exc:   # surfaced in the main thread
+            errors.append(exc)
+
+    threads = [threading.Thread(target=work, args=(i, j)) for i, j in enumerate(jobs)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    # one host thread, two streams, same plan, no host synchronisation in between
+    (w0, ref0, s0), (w1, ref1, s1) = jobs[0], jobs[1]
+    outs = [torch.empty(w0.N, dtype=torch.bfloat16, device=DEV) for _ in range(6)]
+    torch.cuda.synchronize()
+    for rep in range(6):
+        w, s = (w0, s0) if rep % 2 == 0 else (w1, s1)
+        B.adasum_reduce(w.grads, w.layer_offsets, outs[rep], stream=s)
+    torch.cuda.synchronize()
+    for rep, out in enumerate(outs):
+        assert_parity(out, ref0 if rep % 2 == 0 else ref1, w0.layer_offsets, what=f"alternating streams, call {rep}")
+
+
+def test_binding_rejects_buffers_the_kernels_would_overrun():
+    """A caller-owned plan's execute checks what the library itself cannot see from a pointer:
+    a layer_stats tensor shorter than n_layers x 2 doubles (the statistics kernels would write
+    past it), one on the host, and a delta_start of another dtype."""
+    sizes = [100, 5000, 7]
+    w = W.correlated_gaussian(sizes, 4, dtype=torch.bfloat16, device=DEV, seed=3)
+    plan = B.Plan(4, w.layer_offsets, torch.bfloat16)
+    short = torch.zeros(2 * len(sizes) - 2, dtype=torch.float64, device=DEV)
+    with pytest.raises(ValueError):
+        plan.execute(w.grads, layer_stats=short)
+    with pytest.raises(ValueError):
+        plan.execute(w.grads, layer_stats=torch.zeros(len(sizes), 2, dtype=torch.float64))
+    with pytest.raises(ValueError):
+        plan.execute(w.grads, layer_stats=torch.zeros(len(sizes), 2, dtype=torch.float32, device=DEV))
+    ok = torch.zeros(len(sizes), 2, dtype=torch.float64, device=DEV)
+    out = plan.execute(w.grads, layer_stats=ok)
+    torch.cuda.synchronize()
+    assert bool((ok[:, 1] > 0).all()) and bool(torch.isfinite(out.float()).all())
+    plan.destroy()
+    dplan = B.Plan(4, w.layer_offsets, torch.bfloat16, delta=True)
+    with pytest.raises(ValueError):
+        dplan.execute(w.grads, delta_start=torch.zeros(w.N, dtype=torch.float32, device=DEV))
+    dplan.destroy()
+    with pytest.raises(ValueError):
+        B.adasum_reduce(w.grads, w.layer_offsets, layer_stats=torch.zeros(len(sizes), 2, dtype=torch.float64))
