@@ -92,11 +92,24 @@ def oracle_reduce(grads, layer_offsets, layers=None, order="tree") -> np.ndarray
         lo, hi = offs[l], offs[l + 1]
         if hi > lo:
             parts = [to_f64(g[lo:hi]) for g in grads]
-            out[lo:hi] = O.adasum_tree(parts)
-            if hi - lo <= ILL_POSED_MAX_SIZE and _node_is_ill_posed(parts, "tree"):
+            out[lo:hi] = O.adasum_tree(parts) if order == "tree" else O.adasum_linear(parts)
+            if hi - lo <= ILL_POSED_MAX_SIZE and _node_is_ill_posed(parts, order):
                 print(f"  layer {l} (size {hi - lo}): a tree node cancels exactly; no reference value, skipped",
                       flush=True)
                 out[lo:hi] = np.nan
+    return out
+
+
+def oracle_after_optimizer(start, currents, layer_offsets, layers) -> np.ndarray:
+    """Section 4.1's new parameters, start + Adasum(current_k - start), from the oracle on
+    `layers` only (other positions are left at 0)."""
+    offs = list(layer_offsets)
+    out = np.zeros(offs[-1], dtype=np.float64)
+    for l in layers:
+        lo, hi = offs[l], offs[l + 1]
+        if hi > lo:
+            out[lo:hi] = O.adasum_after_optimizer(to_f64(start[lo:hi]), [to_f64(c[lo:hi]) for c in currents],
+                                                  [0, hi - lo])
     return out
 
 

@@ -9,7 +9,7 @@ import torch
 
 from paper_2006_02924_amd import binding as B
 from paper_2006_02924_amd import workloads as W
-from tests.gpu_util import assert_bf16_rounding, assert_parity, oracle_reduce, to_f64
+from tests.gpu_util import (assert_bf16_rounding, assert_parity, oracle_after_optimizer, oracle_reduce, to_f64)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -78,6 +78,168 @@ def test_config4_full_size_sampled_layers(config4):
     differ = float((a != b).float().mean())
     say(f"  default radix vs radix 2 bf16 outputs differ in {differ:.2e} of the elements")
     assert differ < 1e-2
+    B.shutdown()   # the cached plans' workspaces (43 GB at radix 2) go back before the next test
+
+
+def test_config4_full_size_left_to_right_order(config4):
+    """The left-to-right order (Section 3.4, first recursion) at full size: the kernels that take
+    the running fp32 result next to fifteen bf16 leaves, on long Gram tiles."""
+    w = config4
+    layers = sampled_layers(w)
+    say(f"oracle (left-to-right) on layers {layers}")
+    ref = oracle_reduce(w.grads, w.layer_offsets, layers=layers, order="linear")
+    say("oracle done")
+    for out_dtype in (torch.bfloat16, torch.float32):
+        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, order=B.ORDER_LINEAR)
+        torch.cuda.synchronize()
+        err = assert_parity(out, ref, w.layer_offsets, layers=layers, what=f"config4 left-to-right {out_dtype}")
+        say(f"  {out_dtype}: max rel-L2 on sampled layers {err.max():.3e}")
+        if out_dtype == torch.bfloat16:
+            assert_bf16_rounding(out, ref, w.layer_offsets, layers=layers)
+        assert bool(torch.isfinite(out).all())
+        again = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, order=B.ORDER_LINEAR)
+        torch.cuda.synchronize()
+        assert torch.equal(again, out)
+        del out, again
+    B.shutdown()
+
+
+def test_config4_full_size_after_optimizer_form(config4):
+    """Section 4.1's delta form at full size.  Starting parameters start = s_l N(0,1) per layer;
+    worker k's parameters after its local step are start - 0.25 g_k (g_k: config 4's gradients),
+    rounded to bf16.  The library subtracts start on the fly and adds it back at the root, also
+    in place on the starting parameters."""
+    w = config4
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80e9:
+        pytest.skip("needs ~80 GB of free HBM beside config 4")
+    layers = sampled_layers(w)
+    offs = w.layer_offsets
+    gen = torch.Generator(device=DEV).manual_seed(404)
+    reps = torch.tensor(np.diff(np.asarray(offs)), dtype=torch.int64)
+    scale = torch.repeat_interleave(torch.tensor(w.meta["scale"], dtype=torch.float32), reps).to(DEV)
+    start32 = torch.randn(w.N, generator=gen, device=DEV, dtype=torch.float32) * scale
+    del scale
+    start = start32.to(torch.bfloat16)
+    start32 = start.float()
+    currents = [(start32 - 0.25 * g.float()).to(torch.bfloat16) for g in w.grads]
+    del start32
+    torch.cuda.synchronize()
+    say(f"oracle (after-optimizer form) on layers {layers}")
+    ref = oracle_after_optimizer(start, currents, offs, layers)
+    say("oracle done")
+    out = B.adasum_reduce(currents, offs, delta_start=start)
+    torch.cuda.synchronize()
+    err = assert_parity(out, ref, offs, layers=layers, what="config4 delta form")
+    say(f"  max rel-L2 of the new parameters on sampled layers {err.max():.3e}")
+    assert_bf16_rounding(out, ref, offs, layers=layers)
+    assert bool(torch.isfinite(out).all())
+    param = start.clone()
+    same = B.adasum_reduce(currents, offs, param, delta_start=param)
+    torch.cuda.synchronize()
+    assert same.data_ptr() == param.data_ptr() and torch.equal(param, out)
+    del currents, out, param, start
+    B.shutdown()
+    torch.cuda.empty_cache()
+
+
+def test_config3_full_size_sampled_layers():
+    """K = 16 workers, fp32, BERT-Large shapes (21.4 GB of input): one radix-16 pass on long Gram
+    tiles, fp32 and bf16 results, against the oracle on one layer per size class, the
+    31 M-element embedding, the first and the last layer."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60e9:
+        pytest.skip("needs ~60 GB of free HBM")
+    say("generating config 3 at full size")
+    w = W.config3(DEV)
+    torch.cuda.synchronize()
+    layers = sampled_layers(w)
+    say(f"oracle on layers {layers}")
+    ref = oracle_reduce(w.grads, w.layer_offsets, layers=layers)
+    say("oracle done")
+    stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
+    for radix, out_dtype in ((0, torch.float32), (0, torch.bfloat16), (2, torch.float32)):
+        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix,
+                              layer_stats=stats if (radix == 0 and out_dtype == torch.float32) else None)
+        torch.cuda.synchronize()
+        err = assert_parity(out, ref, w.layer_offsets, layers=layers, what=f"config3 radix {radix} {out_dtype}")
+        say(f"  radix {radix} {out_dtype}: max rel-L2 on sampled layers {err.max():.3e}")
+        if out_dtype == torch.bfloat16:
+            assert_bf16_rounding(out, ref, w.layer_offsets, layers=layers)
+        assert bool(torch.isfinite(out).all())
+        if radix == 0 and out_dtype == torch.float32:
+            again = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype)
+            torch.cuda.synchronize()
+            assert torch.equal(again, out)
+            del again
+        del out
+    s = stats.cpu().numpy()
+    metric = s[:, 0] / s[:, 1]
+    assert np.all(metric <= 1.0 + 1e-5) and np.all(metric > 0.0), (metric.min(), metric.max())
+    lin = B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR)
+    torch.cuda.synchronize()
+    small = [l for l in layers if w.layer_offsets[l + 1] - w.layer_offsets[l] <= (1 << 22)]
+    assert_parity(lin, oracle_reduce(w.grads, w.layer_offsets, layers=small, order="linear"), w.layer_offsets,
+                  layers=small, what="config3 left-to-right")
+    del w, lin
+    B.shutdown()
+    torch.cuda.empty_cache()
+
+
+# Layers of 2^26 elements: more than 2048 long Gram tiles in all, which is what makes the planner
+# choose them (a smaller table is cut into short tiles and runs other kernel instantiations).
+LONG_TILE_SIZES = [7, 1 << 26, 4096, (1 << 26) + 3, 1 << 20, 1000]
+
+
+@pytest.mark.parametrize("storage", ["fp16", "fp64"])
+def test_other_storage_types_on_long_tiles(storage):
+    """IEEE binary16 (K = 32: a radix-16 pass into fp32 nodes, then a pair pass) and fp64
+    (K = 16: radix 8, then a pair pass, fp64 throughout) on a table big enough for the long
+    Gram tiles that the timed runs use.  Checked against the oracle on every layer but one of
+    the two 67 M-element ones; that one must be finite and repeat bit for bit."""
+    from tests.gpu_util import TOL_F64
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60e9:
+        pytest.skip("needs ~60 GB of free HBM")
+    sizes = LONG_TILE_SIZES
+    assert sum(s // B.tile_capacity() for s in sizes) >= 2048
+    if storage == "fp16":
+        K = 32
+        scales = W.log_uniform_scales(len(sizes), 78, lo_exp=-2.0, hi_exp=0.0)
+        w = W.correlated_gaussian(sizes, K, dtype=torch.float16, device=DEV, seed=901, scale=scales)
+        outs = (torch.float16, torch.float32)
+    else:
+        K = 16
+        w = W.correlated_gaussian(sizes, K, dtype=torch.float32, device=DEV, seed=902)
+        w.grads = [g.double() for g in w.grads]
+        w.dtype = torch.float64
+        outs = (torch.float64,)
+    torch.cuda.synchronize()
+    layers = [0, 1, 2, 4, 5]
+    say(f"{storage}: K={K}, N={w.N}; oracle on layers {layers}")
+    ref = oracle_reduce(w.grads, w.layer_offsets, layers=layers)
+    say("oracle done")
+    for out_dtype in outs:
+        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        err = assert_parity(out, ref, w.layer_offsets, layers=layers, what=f"{storage} -> {out_dtype}",
+                            tol=TOL_F64 if storage == "fp64" else None)
+        say(f"  {out_dtype}: max rel-L2 {err.max():.3e}")
+        if out_dtype == torch.float16:
+            assert_bf16_rounding(out, ref, w.layer_offsets, layers=layers)
+        assert bool(torch.isfinite(out).all())
+        again = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert torch.equal(again, out)
+        del out, again
+    small = [0, 2, 4, 5]
+    lin = B.adasum_reduce(w.grads, w.layer_offsets, order=B.ORDER_LINEAR)
+    torch.cuda.synchronize()
+    assert_parity(lin, oracle_reduce(w.grads, w.layer_offsets, layers=small, order="linear"), w.layer_offsets,
+                  layers=small, what=f"{storage} left-to-right", tol=TOL_F64 if storage == "fp64" else None)
+    del w, lin
+    B.shutdown()
+    torch.cuda.empty_cache()
 
 
 def test_config5_full_size_edge_layers():
