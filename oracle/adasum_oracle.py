@@ -42,7 +42,13 @@ Readings where the paper is silent:
   there (``K // 2``), at every node.  The written-out expansions for K = 3, 5,
   6, 7 are pinned; that this reading is the authors' intent is not (their
   implementation only runs on powers of two).
-* NaN/Inf inputs: propagated by IEEE arithmetic, unpinned.
+* NaN/Inf inputs: propagated by IEEE arithmetic (a non-finite value poisons its
+  own layer and no other; pinned).
+
+``rel_l2_per_layer`` is the comparison metric of the parity tests, not part of
+the method; it is pinned by hand values and planted slips like the rest.
+Sums of products go through ``numpy.dot`` (a library routine in fp64, whose
+summation order differs from a plain loop by rounding only).
 
 Everything else is pinned by ``tests/test_oracle_pins.py``.
 """

@@ -239,11 +239,16 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
         zero", "one worker of a leaf pair zero" and "a whole quarter subtree
         zero";
       * ``orth_all``  (one layer of >= K elements): all K workers mutually
-        orthogonal (QR of a Gaussian matrix in fp64, then rounded);
+        orthogonal (Gram-Schmidt, applied twice, on a Gaussian matrix in fp64,
+        then rounded);
       * ``gauss``     everything else.
     ``n_scalar_layers`` one-element tensors are inserted at seeded positions;
     they make every later boundary odd, so no later layer starts on a 16-byte
     boundary.
+
+    Only element-wise kernels and plain sums are used on the device (no BLAS or
+    solver library call), so the generator also runs under a counter-collecting
+    profiler.
     """
     base = list(bert_large_layer_sizes() if sizes is None else sizes)
     hg = _host_gen(4)
@@ -288,8 +293,7 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
         b = math.sqrt(max(0.0, 1.0 - a * a))
         sl = slice(offs[l], offs[l + 1])
         if k == "orth_all":
-            m = torch.randn(n, K, generator=dg, device=device, dtype=torch.float64)
-            q, _ = torch.linalg.qr(m)
+            q = _orthonormal_columns(torch.randn(n, K, generator=dg, device=device, dtype=torch.float64))
             for i in range(K):
                 grads[i][sl] = (q[:, i] * (scale_l[l] * math.sqrt(n))).to(dtype)
         elif k == "orth_pairs":
@@ -301,8 +305,8 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
                 if i % 2 == 0:
                     prev64 = g64
                 else:
-                    pn = torch.dot(prev64, prev64).clamp_min(1e-300)
-                    g64 = g64 - (torch.dot(g64, prev64) / pn) * prev64
+                    pn = (prev64 * prev64).sum().clamp_min(1e-300)
+                    g64 = g64 - ((g64 * prev64).sum() / pn) * prev64
                 grads[i][sl] = g64.to(dtype)
         elif k == "zero":
             mode = zero_seen % 3
@@ -320,6 +324,20 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
     return Workload("config5", K, dtype, offs, grads,
                     {"corr": corr_l, "scale": scale_l, "kind": kind,
                      "zero_modes": zero_modes})
+
+
+def _orthonormal_columns(m: torch.Tensor) -> torch.Tensor:
+    """Columns of ``m`` (n x k, fp64, n >= k) made orthonormal by classical Gram-Schmidt
+    applied twice per column, with element-wise products and sums only."""
+    q = m.clone()
+    for i in range(q.shape[1]):
+        v = q[:, i].clone()
+        for _ in range(2):
+            if i > 0:
+                coef = (q[:, :i] * v[:, None]).sum(0)
+                v = v - (q[:, :i] * coef[None, :]).sum(1)
+        q[:, i] = v / (v * v).sum().sqrt()
+    return q
 
 
 def scaled_down(sizes: Sequence[int], factor: int, floor: int = 1) -> List[int]:

@@ -317,6 +317,39 @@ def pin_non_finite_inputs(O):
             np.testing.assert_array_equal(got[:6], want[:6])
 
 
+def pin_comparison_metric(O):
+    """rel_l2_per_layer: per layer |test - ref|_2 / |ref|_2.  Hand values: against ref (3, 4)
+    (norm 5) the test (4, 6) is off by (1, 2), norm sqrt 5: the score is sqrt(5)/5; against
+    ref (3, 0) the test (3, 4) scores 4/3.  Each layer is scored on its own norm; a zero
+    reference scores 0 for a zero output and +inf otherwise; an empty layer scores 0; the roles
+    of test and ref are not interchangeable; fp32 inputs are widened."""
+    got = O.rel_l2_per_layer([4.0, 6.0], [3.0, 4.0], [0, 2])
+    assert got.shape == (1,) and got[0] == pytest.approx(np.sqrt(5.0) / 5.0, rel=1e-15)
+    assert O.rel_l2_per_layer([3.0, 4.0], [3.0, 0.0], [0, 2])[0] == pytest.approx(4.0 / 3.0, rel=1e-15)
+    # two layers of very different scale, an empty one between them: 0 and exactly 1
+    ref = np.array([1000.0, 0.0, 1e-3, 0.0])
+    test = np.array([1000.0, 0.0, 2e-3, 0.0])
+    np.testing.assert_allclose(O.rel_l2_per_layer(test, ref, [0, 2, 2, 4]), [0.0, 0.0, 1.0], rtol=1e-15)
+    # zero reference
+    z = O.rel_l2_per_layer([0.0, 0.0, 0.0, 1e-30], [0.0, 0.0, 0.0, 0.0], [0, 2, 4])
+    assert z[0] == 0.0 and np.isinf(z[1])
+    # exact agreement scores exactly 0; sign flips of both leave the score alone
+    r = _rng(3).standard_normal(50)
+    assert np.all(O.rel_l2_per_layer(r, r, [0, 20, 50]) == 0.0)
+    t = r + 1e-3 * _rng(4).standard_normal(50)
+    np.testing.assert_allclose(O.rel_l2_per_layer(-t, -r, [0, 20, 50]), O.rel_l2_per_layer(t, r, [0, 20, 50]),
+                               rtol=1e-15)
+    # homogeneous of degree 0; scaled error scales the score
+    np.testing.assert_allclose(O.rel_l2_per_layer(7.0 * t, 7.0 * r, [0, 50]), O.rel_l2_per_layer(t, r, [0, 50]),
+                               rtol=1e-13)
+    np.testing.assert_allclose(O.rel_l2_per_layer(r + 2.0 * (t - r), r, [0, 50]),
+                               2.0 * O.rel_l2_per_layer(t, r, [0, 50]), rtol=1e-12)
+    # low-precision inputs are widened, not compared in their own precision
+    t32 = np.array([1.0, 1.0 + 2.0 ** -20], dtype=np.float32)
+    r64 = np.array([1.0, 1.0])
+    assert O.rel_l2_per_layer(t32, r64, [0, 2])[0] == pytest.approx(2.0 ** -20 / np.sqrt(2.0), rel=1e-12)
+
+
 PINS = [
     pin_closed_form_two_vectors,
     pin_worked_tree_fixture,
@@ -335,6 +368,7 @@ PINS = [
     pin_after_optimizer,
     pin_worker_counts_that_are_no_power_of_two,
     pin_non_finite_inputs,
+    pin_comparison_metric,
 ]
 
 
@@ -457,11 +491,47 @@ def _mut_operator_on_parameters(m):
     m.adasum_after_optimizer = lambda start, currents, layer_offsets: m.adasum_reduce(currents, layer_offsets)
 
 
+def _metric_mutant(score):
+    """rel_l2_per_layer with the per-layer score replaced by score(test_layer, ref_layer, test, ref)."""
+    def install(m):
+        def f(test, ref, layer_offsets):
+            t, r = m._as_f64(test), m._as_f64(ref)
+            offs = [int(o) for o in layer_offsets]
+            res = np.zeros(len(offs) - 1)
+            for l in range(len(offs) - 1):
+                lo, hi = offs[l], offs[l + 1]
+                if hi > lo:
+                    with np.errstate(all="ignore"):
+                        res[l] = score(t[lo:hi], r[lo:hi], t, r)
+            return res
+        m.rel_l2_per_layer = f
+    return install
+
+
+def _named(name, fn):
+    fn.__name__ = name
+    return fn
+
+
+_norm = np.linalg.norm
+METRIC_MUTANTS = [
+    _named("_mut_metric_squared", _metric_mutant(lambda t, r, T, R: _norm(t - r) ** 2 / _norm(r) ** 2)),
+    _named("_mut_metric_denominator_not_rooted", _metric_mutant(lambda t, r, T, R: _norm(t - r) / np.dot(r, r))),
+    _named("_mut_metric_whole_buffer_norm", _metric_mutant(lambda t, r, T, R: _norm(t - r) / _norm(R))),
+    _named("_mut_metric_max_norm", _metric_mutant(lambda t, r, T, R: np.abs(t - r).max() / np.abs(r).max())),
+    _named("_mut_metric_l1_norm", _metric_mutant(lambda t, r, T, R: np.abs(t - r).sum() / np.abs(r).sum())),
+    _named("_mut_metric_relative_to_test", _metric_mutant(lambda t, r, T, R: _norm(t - r) / _norm(t))),
+    _named("_mut_metric_zero_reference_passes",
+           _metric_mutant(lambda t, r, T, R: 0.0 if _norm(r) == 0.0 else _norm(t - r) / _norm(r))),
+    _named("_mut_metric_mean_square", _metric_mutant(lambda t, r, T, R: _norm(t - r) / _norm(r) / np.sqrt(len(r)))),
+]
+
+
 MUTANTS = [_mut_drop_two, _mut_swap_norms, _mut_plus_sign, _mut_norm_not_squared,
            _mut_tree_is_fold, _mut_uneven_split, _mut_whole_buffer,
            _mut_no_zero_guard, _mut_fp32_accumulate, _mut_linear_is_tree,
            _mut_delta_sign, _mut_delta_not_added_back, _mut_operator_on_parameters,
-           _mut_left_takes_the_larger_part]
+           _mut_left_takes_the_larger_part] + METRIC_MUTANTS
 
 
 @pytest.mark.parametrize("mutate", MUTANTS, ids=lambda f: f.__name__)
