@@ -3,19 +3,23 @@
 
 One "step" = one whole ``adasum_reduce`` (every tree level: Gram pass, finish,
 weights, combine pass) over K synthetic worker gradients already resident in
-HBM.  Default workload: K = 64 workers, BERT-Large-shaped (391 tensors,
+HBM.  Headline workload: K = 64 workers, BERT-Large-shaped (391 tensors,
 335 141 888 elements), gradients stored bf16, bf16 result -- the configuration
-the headline metric is quoted on.
+the metric is quoted on.
 
 Prints ONE JSON line: whole-job input GB/s (K*N*2 bytes / step time), the
 roofline of the dominant kernel (algorithmic bytes / HIP-event duration against
-the 8 TB/s HBM peak) and the CPU oracle timed on a bounded sample.
+the 8 TB/s HBM peak), the CPU oracle timed on a bounded sample (one thread and
+all cores) and -- in the default run -- the same measurements for the other four
+synthetic configurations and for the one-pair-per-level schedule (radix 2).
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,22 +28,27 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.md")
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); see the
-# summaries under profiles/.  Keyed by (workload, kernel name).
-MEASURED_TRAFFIC_BYTES = {
-    ("config4", "combine<bf16,f32,R=16>"): 43.234e9 + 5.795e9,
-    ("config4", "gram<bf16,R=16,diag>"): 42.898e9 + 0.024e9,
-    ("config4", "combine<bf16,f32,R=2>"): 43.571e9 + 43.066e9,
-    ("config3", "combine<f32,f32,R=16>"): 21.617e9 + 1.341e9,
-    ("config3", "gram<f32,R=16,diag>"): 21.450e9 + 0.025e9,
-    ("config2", "combine<f32,f32,R=8>"): 0.8243e9 + 0.1022e9,
-    ("config2", "gram<f32,R=8,diag>"): 0.8180e9 + 0.0006e9,
-    # counters taken at K = 128 on config 4's generator (config 5 adds 16 one-element tensors to it)
-    ("config5", "combine<bf16,f32,R=16>"): 86.468e9 + 11.586e9,
-    ("config5", "gram<bf16,R=16,diag>"): 85.796e9 + 0.048e9,
-}
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` on `workload` from the tracked counter summary
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size).
+    Rows of the table: | workload | kernel | read bytes | written bytes | commit |."""
+    try:
+        text = open(TRAFFIC_TABLE).read()
+    except OSError:
+        return None
+    for line in text.splitlines():
+        cells = [c.strip().strip("`") for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 5 and cells[0] == workload and cells[1] == kernel:
+            try:
+                return {"bytes": float(cells[2]) + float(cells[3]), "read_bytes": float(cells[2]),
+                        "written_bytes": float(cells[3]), "measured_at_commit": cells[4],
+                        "source": "profiles/hbm_traffic_table.md"}
+            except ValueError:
+                return None
+    return None
 
 
 def parse_args():
@@ -64,6 +73,9 @@ def parse_args():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-profile", action="store_true",
                    help="do not bracket kernels with HIP events in the timed region")
+    p.add_argument("--headline-only", action="store_true",
+                   help="only the workload named by --workload: skip the other configurations "
+                        "(they run by default when nothing but --steps / --warmup is given)")
     return p.parse_args()
 
 
@@ -98,11 +110,28 @@ def make_workload(name, device, workers=0):
     raise ValueError(name)
 
 
-def cpu_baseline(w, budget_elems=13_500_000):
+def pair_per_level_bytes(K, N, in_bytes, out_bytes):
+    """Bytes of the schedule that follows the paper's structure literally on one GPU: one pair per
+    tree level, two passes over both operands per level (dot products and norms, then the
+    scaled sum), fp32 tree nodes, the root stored in the output type.  K a power of two."""
+    total, level, pairs = 0, 0, K // 2
+    while pairs >= 1:
+        s = in_bytes if level == 0 else 4
+        so = out_bytes if pairs == 1 else 4
+        total += pairs * N * (4 * s + so)
+        pairs //= 2
+        level += 1
+    return float(total)
+
+
+def cpu_baseline(w, budget_elems=40_000_000):
     """The fp64 NumPy oracle, as it stands, on a bounded sample: the first layers
     of the same workload (all K workers) up to about `budget_elems` elements per
-    worker, skipping any single layer larger than the budget."""
-    import numpy as np
+    worker, skipping any single layer larger than a third of the budget.  Timed twice:
+    on one thread, and as a plain parallel-for over the sample's layers on all host cores
+    this process may use (NumPy's own threading pinned to one thread per worker)."""
+    from concurrent.futures import ThreadPoolExecutor
+
     from oracle import adasum_oracle as O
     try:
         from threadpoolctl import threadpool_limits
@@ -112,7 +141,7 @@ def cpu_baseline(w, budget_elems=13_500_000):
     layers, total = [], 0
     for l in range(w.n_layers):
         n = offs[l + 1] - offs[l]
-        if n == 0 or n > budget_elems:
+        if n == 0 or n > budget_elems // 3:
             continue
         if total + n > budget_elems:
             break
@@ -120,23 +149,133 @@ def cpu_baseline(w, budget_elems=13_500_000):
         total += n
     host = [[g[offs[l]:offs[l + 1]].cpu() for g in w.grads] for l in layers]
 
-    def run():
+    def one_layer(per_layer):
+        return O.adasum_tree([t.double().numpy() for t in per_layer])
+
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:  # pragma: no cover
+        usable = os.cpu_count() or 1
+    env_cap = os.environ.get("OMP_NUM_THREADS")
+    threads = max(1, min(usable, int(env_cap)) if env_cap and env_cap.isdigit() else usable)
+    in_bytes = total * w.K * w.grads[0].element_size()
+
+    class _Unlimited:
+        def __enter__(self):
+            return self
+
+        def __exit__(self, *a):
+            return False
+
+    limit1 = (lambda: threadpool_limits(limits=1)) if threadpool_limits is not None else _Unlimited
+    with limit1():
         t0 = time.perf_counter()
         for per_layer in host:
-            O.adasum_tree([t.double().numpy() for t in per_layer])
-        return time.perf_counter() - t0
+            one_layer(per_layer)
+        t1 = time.perf_counter() - t0
+        order = sorted(range(len(host)), key=lambda i: -host[i][0].numel())
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(lambda i: one_layer(host[i]), order))
+        tn = time.perf_counter() - t0
+    sample = (f"layers {layers[0]}..{layers[-1]} of {w.name} except those over {budget_elems // 3} elements "
+              f"({total} elements x K={w.K} workers, {in_bytes / 1e9:.2f} GB of input), fp64 NumPy, input widening "
+              f"included: {t1:.1f} s on 1 thread, {tn:.1f} s on {threads} threads")
+    return {"value": in_bytes / tn / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle", "sample": sample,
+            "single_thread": {"value": in_bytes / t1 / 1e9, "unit": "GB/s", "cores": 1, "seconds": t1},
+            "seconds": tn, "host_cpus": os.cpu_count()}
 
-    if threadpool_limits is not None:
-        with threadpool_limits(limits=1):
-            dt = run()
-        cores = 1
-    else:
-        dt = run()
-        cores = os.cpu_count() or 1
-    in_bytes = total * w.K * w.grads[0].element_size()
-    return {"value": in_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"layers {layers[0]}..{layers[-1]} of {w.name} ({total} elements x K={w.K} workers, "
-                      f"{in_bytes / 1e9:.2f} GB of input) in {dt:.1f} s, fp64 NumPy, input widening included"}
+
+def timed_steps(B, w, out, *, out_dtype, radix, order, graph, start, steps, warmup, profile):
+    """`warmup` untimed steps, then exactly `steps` timed ones between device synchronisations.
+    Returns (seconds for the timed steps, per-kernel HIP-event records or [])."""
+    import torch
+
+    def step():
+        B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=radix,
+                        use_graph=graph, delta_start=start,
+                        order=B.ORDER_LINEAR if order == "linear" else B.ORDER_TREE)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    B.profile_collect()
+    B.profile_enable(profile)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    B.profile_enable(False)
+    return dt, B.profile_collect()
+
+
+def kernel_summary(prof, steps, ms_per_step, workload, verbose_tag=None):
+    """Dominant kernel (most GPU time) against the HBM roofline, from HIP-event records."""
+    if not prof:
+        return None
+    if verbose_tag is not None:
+        for k in prof:
+            print(f"[bench] {verbose_tag}{k['name']:32s} launches={k['launches']:5d} "
+                  f"avg={k['total_ms'] / k['launches']:9.4f} ms "
+                  f"alg={k['bytes'] / max(k['total_ms'], 1e-9) / 1e6:8.1f} GB/s", file=sys.stderr, flush=True)
+    dom = max(prof, key=lambda k: k["total_ms"])
+    per_launch_bytes = dom["bytes"] / dom["launches"]
+    avg_ms = dom["total_ms"] / dom["launches"]
+    achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
+    total_bytes = sum(k["bytes"] for k in prof) / steps
+    total_ms = sum(k["total_ms"] for k in prof) / steps
+    return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "kernel": dom["name"], "kernel_avg_ms": avg_ms, "kernel_bytes_per_launch": per_launch_bytes,
+            "kernel_share_of_step": dom["total_ms"] / steps / ms_per_step,
+            "all_kernels_algorithmic_GBps": total_bytes / (total_ms * 1e-3) / 1e9,
+            "all_kernels_ms_per_step": total_ms,
+            "schedule_bytes": total_bytes}
+
+
+def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None):
+    """One more configuration, default options: the step time from an event-free loop, the kernel
+    breakdown from a second, event-bracketed loop of the same steps."""
+    import torch
+    dev = "cuda:0"
+    own = w is None
+    t0 = time.perf_counter()
+    if own:
+        w = make_workload(name, dev)
+        torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t0
+    out = torch.empty(w.N, dtype=w.dtype, device=dev)
+    kw = dict(out_dtype=w.dtype, radix=radix, order="tree", graph=False, start=None)
+    dt, _ = timed_steps(B, w, out, steps=steps, warmup=warmup, profile=False, **kw)
+    ms = dt / steps * 1e3
+    dtp, prof = timed_steps(B, w, out, steps=steps, warmup=0, profile=True, **kw)
+    roof = kernel_summary(prof, steps, dtp / steps * 1e3, name, verbose_tag=f"{name}{' radix ' + str(radix) if radix else ''}: ")
+    es = w.grads[0].element_size()
+    row = {"workload": f"{name}: K={w.K}, {w.n_layers} tensors, N={w.N}, stored and output "
+                       f"{str(w.dtype).replace('torch.', '')}",
+           "passes": B.plan_levels(w.K, radix), "steps": steps, "warmup": warmup,
+           "ms_per_step": ms, "input_GBps": w.input_bytes / (ms * 1e-3) / 1e9, "input_GB": w.input_bytes / 1e9,
+           "generated_in_s": gen_s}
+    if roof is not None:
+        row.update({"schedule_bytes": roof["schedule_bytes"],
+                    "algorithmic_GBps": roof["schedule_bytes"] / (ms * 1e-3) / 1e9,
+                    "step_frac_of_hbm_peak": roof["schedule_bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "dominant_kernel": roof["kernel"], "dominant_kernel_avg_ms": roof["kernel_avg_ms"],
+                    "dominant_kernel_GBps": roof["achieved"], "dominant_kernel_frac": roof["frac"],
+                    "ms_per_step_with_events": dtp / steps * 1e3})
+        t = measured_traffic(name if not radix else f"{name}_radix{radix}", roof["kernel"])
+        row["dominant_kernel_traffic"] = t["bytes"] if t else None
+    if w.K & (w.K - 1) == 0 and w.K > 1:
+        row["pair_per_level_bytes"] = pair_per_level_bytes(w.K, w.N, es, es)
+    del out
+    if own:
+        del w
+    B.shutdown()
+    gc.collect()
+    torch.cuda.empty_cache()
+    return row
 
 
 def main():
@@ -154,6 +293,10 @@ def main():
     B.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    plain = (args.workload == "config4" and not args.workers and args.order == "tree" and args.radix == 0
+             and args.out_dtype == "same" and args.storage == "same" and not args.graph and not args.delta
+             and not args.single_layer and not args.no_profile)
+    with_others = plain and not args.headline_only
     t0 = time.perf_counter()
     w = make_workload(args.workload, dev, args.workers)
     torch.cuda.synchronize()
@@ -175,48 +318,29 @@ def main():
     if args.delta:
         start = (torch.randn(w.N, device=dev, dtype=torch.float32) * 0.02).to(w.dtype)
 
-    def step():
-        B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=args.radix,
-                        use_graph=args.graph, delta_start=start,
-                        order=B.ORDER_LINEAR if args.order == "linear" else B.ORDER_TREE)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    B.profile_collect()
-    B.profile_enable(not args.no_profile)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    B.profile_enable(False)
-    prof = B.profile_collect()
+    dt, prof = timed_steps(B, w, out, out_dtype=out_dtype, radix=args.radix, order=args.order, graph=args.graph,
+                           start=start, steps=args.steps, warmup=args.warmup, profile=not args.no_profile)
 
     ms_per_step = dt / args.steps * 1e3
     value = w.input_bytes / (dt / args.steps) / 1e9
     eight = args.delta or w.dtype == torch.float64     # these default to radix 8
     levels = B.plan_levels(w.K, args.radix if (args.radix or not eight) else 8) if args.order == "tree" else None
 
-    roofline = None
-    if prof:
-        for k in prof:
-            print(f"[bench] {k['name']:32s} launches={k['launches']:5d} avg={k['total_ms'] / k['launches']:9.4f} ms "
-                  f"alg={k['bytes'] / max(k['total_ms'], 1e-9) / 1e6:8.1f} GB/s", file=sys.stderr, flush=True)
-        dom = max(prof, key=lambda k: k["total_ms"])
-        per_launch_bytes = dom["bytes"] / dom["launches"]
-        avg_ms = dom["total_ms"] / dom["launches"]
-        achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
-        total_bytes = sum(k["bytes"] for k in prof) / args.steps
-        total_ms = sum(k["total_ms"] for k in prof) / args.steps
-        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom["name"])),
-                    "kernel": dom["name"], "kernel_avg_ms": avg_ms, "kernel_bytes_per_launch": per_launch_bytes,
-                    "kernel_share_of_step": dom["total_ms"] / args.steps / ms_per_step,
-                    "all_kernels_algorithmic_GBps": total_bytes / (total_ms * 1e-3) / 1e9,
-                    "all_kernels_bytes_per_step": total_bytes}
+    roofline = kernel_summary(prof, args.steps, ms_per_step, args.workload, verbose_tag="")
+    if roofline is not None:
+        key = args.workload if not args.radix else f"{args.workload}_radix{args.radix}"
+        t = measured_traffic(key, roofline["kernel"]) if (args.order == "tree" and not args.delta) else None
+        if t is not None:
+            roofline["traffic"] = t["bytes"]
+            roofline["traffic_detail"] = t
+        # the whole step against the same peak, on the bytes this schedule moves ...
+        roofline["step_algorithmic_GBps"] = roofline["schedule_bytes"] / (ms_per_step * 1e-3) / 1e9
+        roofline["step_frac"] = roofline["step_algorithmic_GBps"] / HBM_PEAK_GBS
+        # ... which are fewer than those of one pair per level and two passes per level
+        if w.K > 1 and w.K & (w.K - 1) == 0 and args.order == "tree" and not args.delta:
+            ppl = pair_per_level_bytes(w.K, w.N, w.grads[0].element_size(), out.element_size())
+            roofline["pair_per_level_bytes"] = ppl
+            roofline["schedule_over_pair_per_level"] = roofline["schedule_bytes"] / ppl
 
     line = {
         "metric": "Adasum tree-reduce throughput: input GB/s and % of MI355X HBM peak",
@@ -232,7 +356,38 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
         line["cpu_baseline"] = cpu_baseline(w)
+        print(f"[bench] cpu baseline in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    if with_others:
+        others = []
+        del out
+        B.shutdown()
+        torch.cuda.empty_cache()
+        # the one-pair-per-level schedule on the headline workload, then the other four configurations
+        # (the headline workload is dropped before the first of them is generated)
+        todo = [("config4", 2, 10, 2), ("config1", 0, 200, 20), ("config2", 0, 50, 5), ("config3", 0, 20, 3),
+                ("config5", 0, 10, 2)]
+        for name, radix, steps, warmup in todo:
+            reuse = w if radix else None
+            if reuse is None and w is not None:
+                w = None
+                gc.collect()
+                torch.cuda.empty_cache()
+            try:
+                t0 = time.perf_counter()
+                row = run_other(B, name, radix=radix, steps=steps, warmup=warmup, w=reuse)
+                print(f"[bench] {name}{' radix 2' if radix else ''}: {row['ms_per_step']:.4f} ms/step, "
+                      f"{row['input_GBps']:.0f} GB/s of input ({time.perf_counter() - t0:.1f} s in all)",
+                      file=sys.stderr, flush=True)
+            except Exception as exc:  # keep the headline line whatever happens here
+                row = {"workload": name, "error": f"{type(exc).__name__}: {exc}"}
+            del reuse
+            if radix:
+                row["radix"] = radix
+            others.append(row)
+        line["other_configs"] = others
     print(json.dumps(line), flush=True)
 
 
