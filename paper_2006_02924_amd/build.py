@@ -15,6 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libadasum.so")
+# a measuring tool (the memory system's ceiling for the combine pass's access pattern)
+CEILING_PATH = os.path.join(HERE, "pattern_ceiling")
 
 SOURCES = ["adasum_kernels.hip", "adasum_api.cpp", "adasum_plan.cpp"]
 
@@ -40,7 +42,18 @@ def build_library(verbose: bool = True, extra_flags=(), out_path: str = LIB_PATH
     return out_path
 
 
+def build_pattern_ceiling(verbose: bool = True, out_path: str = CEILING_PATH) -> str:
+    cmd = [hipcc(), "-O3", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument", *DEVICE_FLAGS,
+           os.path.join(CSRC, "pattern_ceiling.hip"), "-o", out_path]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return out_path
+
+
 if __name__ == "__main__":
     build_library()
+    build_pattern_ceiling()
     print(LIB_PATH)
+    print(CEILING_PATH)
     sys.exit(0)

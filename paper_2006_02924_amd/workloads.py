@@ -246,9 +246,9 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
     they make every later boundary odd, so no later layer starts on a 16-byte
     boundary.
 
-    Only element-wise kernels and plain sums are used on the device (no BLAS or
-    solver library call), so the generator also runs under a counter-collecting
-    profiler.
+    Only element-wise kernels and short row sums are used on the device (no BLAS
+    or solver library call, no reduction that spans workgroups), so the generator
+    also runs under a counter-collecting profiler.
     """
     base = list(bert_large_layer_sizes() if sizes is None else sizes)
     hg = _host_gen(4)
@@ -305,8 +305,8 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
                 if i % 2 == 0:
                     prev64 = g64
                 else:
-                    pn = (prev64 * prev64).sum().clamp_min(1e-300)
-                    g64 = g64 - ((g64 * prev64).sum() / pn) * prev64
+                    pn = _sum_last(prev64 * prev64).clamp_min(1e-300)
+                    g64 = g64 - (_sum_last(g64 * prev64) / pn) * prev64
                 grads[i][sl] = g64.to(dtype)
         elif k == "zero":
             mode = zero_seen % 3
@@ -326,18 +326,30 @@ def config5(device="cpu", K: int = 128, sizes=None, n_scalar_layers: int = 16) -
                      "zero_modes": zero_modes})
 
 
+def _sum_last(x: torch.Tensor) -> torch.Tensor:
+    """Sum over the last dimension in stages of at most 1024 terms per output, so that no
+    single reduction is split over several workgroups."""
+    c = 1024
+    while x.shape[-1] > c:
+        pad = (-x.shape[-1]) % c
+        if pad:
+            x = torch.nn.functional.pad(x, (0, pad))
+        x = x.reshape(*x.shape[:-1], -1, c).sum(-1)
+    return x.sum(-1)
+
+
 def _orthonormal_columns(m: torch.Tensor) -> torch.Tensor:
     """Columns of ``m`` (n x k, fp64, n >= k) made orthonormal by classical Gram-Schmidt
-    applied twice per column, with element-wise products and sums only."""
-    q = m.clone()
-    for i in range(q.shape[1]):
-        v = q[:, i].clone()
+    applied twice per column, with element-wise products and short row sums only."""
+    q = m.t().contiguous()            # rows are the vectors
+    for i in range(q.shape[0]):
+        v = q[i].clone()
         for _ in range(2):
             if i > 0:
-                coef = (q[:, :i] * v[:, None]).sum(0)
-                v = v - (q[:, :i] * coef[None, :]).sum(1)
-        q[:, i] = v / (v * v).sum().sqrt()
-    return q
+                coef = _sum_last(q[:i] * v[None, :])
+                v = v - (q[:i] * coef[:, None]).sum(0)
+        q[i] = v / _sum_last(v * v).sqrt()
+    return q.t()
 
 
 def scaled_down(sizes: Sequence[int], factor: int, floor: int = 1) -> List[int]:
