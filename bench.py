@@ -34,17 +34,17 @@ TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.md")
 def measured_traffic(workload: str, kernel: str):
     """HBM bytes per launch of `kernel` on `workload` from the tracked counter summary
     (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size).
-    Rows of the table: | workload | kernel | read bytes | written bytes | commit |."""
+    Rows of the table: | workload | kernel | read bytes | written bytes | dispatches | commit |."""
     try:
         text = open(TRAFFIC_TABLE).read()
     except OSError:
         return None
     for line in text.splitlines():
         cells = [c.strip().strip("`") for c in line.strip().strip("|").split("|")]
-        if len(cells) >= 5 and cells[0] == workload and cells[1] == kernel:
+        if len(cells) >= 6 and cells[0] == workload and cells[1] == kernel:
             try:
                 return {"bytes": float(cells[2]) + float(cells[3]), "read_bytes": float(cells[2]),
-                        "written_bytes": float(cells[3]), "measured_at_commit": cells[4],
+                        "written_bytes": float(cells[3]), "measured_at_commit": cells[5],
                         "source": "profiles/hbm_traffic_table.md"}
             except ValueError:
                 return None

@@ -7,7 +7,8 @@
         the library's kernels of a --kernel-trace --stats run as a markdown table
     python -m paper_2006_02924_amd.profile_summary traffic --workload config4 --commit <hash> \\
             --fetch <FETCH_SIZE csv> --write <WRITE_SIZE csv> --copy-fetch <csv> --copy-write <csv>
-        rows of profiles/hbm_traffic_table.md: HBM bytes per dispatch of each streaming kernel.
+        rows of profiles/hbm_traffic_table.md: HBM bytes per dispatch of each streaming kernel
+        (| workload | kernel | read bytes | written bytes | dispatches averaged | commit |).
         FETCH_SIZE / WRITE_SIZE count in units that a plain copy of known size calibrates: the
         --copy-* files come from ``bench.py --workload copy``, whose PyTorch kernel y = g * 1
         reads and writes exactly 2^30 bytes per dispatch.
@@ -99,17 +100,25 @@ def cmd_traffic(args):
     write_unit = _yardstick(args.copy_write, "WRITE_SIZE")
     print(f"<!-- yardstick: one FETCH_SIZE unit = {fetch_unit:.3f} bytes, one WRITE_SIZE unit = {write_unit:.3f} bytes "
           f"(PyTorch y = g * 1 over 2^28 fp32: 2^30 bytes each way) -->")
-    fetch = read_counters(args.fetch)
-    write = read_counters(args.write)
-    for key, counters in fetch.items():
-        name, _grid = key
-        if name == "torch_copy" or not (name.startswith("gram<") or name.startswith("combine<")):
+    # per kernel name: the mean over all its dispatches (a name launched at several sizes in one
+    # step, as the pair passes of radix 2 are, gets the mean over those sizes, like bench.py's
+    # per-launch averages)
+    def by_name(path, counter):
+        acc = collections.OrderedDict()
+        for (name, _grid), counters in read_counters(path).items():
+            if counter in counters and (name.startswith("gram<") or name.startswith("combine<")):
+                a = acc.setdefault(name, [0, 0.0])
+                a[0] += counters[counter][0]
+                a[1] += counters[counter][1]
+        return acc
+    fetch = by_name(args.fetch, "FETCH_SIZE")
+    write = by_name(args.write, "WRITE_SIZE")
+    for name, (n, tot) in fetch.items():
+        if name not in write:
             continue
-        if key not in write:
-            continue
-        rd = counters["FETCH_SIZE"][1] / counters["FETCH_SIZE"][0] * fetch_unit
-        wr = write[key]["WRITE_SIZE"][1] / write[key]["WRITE_SIZE"][0] * write_unit
-        print(f"| {args.workload} | `{name}` | {rd:.4e} | {wr:.4e} | {args.commit} |")
+        rd = tot / n * fetch_unit
+        wr = write[name][1] / write[name][0] * write_unit
+        print(f"| {args.workload} | `{name}` | {rd:.4e} | {wr:.4e} | {n} | {args.commit} |")
 
 
 def main(argv=None):

@@ -17,3 +17,17 @@ def test_help_lists_the_contract_flags():
     assert r.returncode == 0
     for flag in ("--gpus", "--steps", "--warmup", "--workload"):
         assert flag in r.stdout
+
+
+def test_traffic_table_is_readable_and_names_its_commit():
+    """roofline.traffic comes from the tracked counter summary, not from constants in bench.py."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    t = bench.measured_traffic("config4", "combine<bf16,f32,R=16>")
+    assert t is not None and t["source"] == "profiles/hbm_traffic_table.md"
+    # 64 bf16 leaves read and 4 fp32 nodes written over N = 335 141 888, give or take a few per cent
+    assert 0.99 < t["bytes"] / (64 * 335141888 * 2 + 4 * 335141888 * 4) < 1.05
+    assert len(t["measured_at_commit"]) >= 7
+    assert bench.measured_traffic("config4", "no such kernel") is None
+    assert bench.pair_per_level_bytes(64, 335141888, 2, 2) == 1002 * 335141888
