@@ -20,6 +20,16 @@
  * Reading where the paper is silent: an operand whose squared norm is exactly 0
  * gets coefficient 1, so Adasum(0, g) = g and Adasum(0, 0) = 0.
  *
+ * Supported magnitudes.  Products of two stored values are formed and summed in fp32
+ * lanes (fp64 for fp64 storage), so for fp32 and bf16 storage a layer's values must
+ * keep their squares inside the fp32 range: root-mean-square magnitude of a layer
+ * between about 1e-17 and 1e+17 (checked against the oracle at 1e-15 and 1e+15).
+ * fp16 storage cannot leave that range; fp64 storage has fp64's (1e-150 .. 1e+150).
+ * Outside it the result of THAT layer is not the operator's: squares that underflow
+ * to zero put the layer on (or near) the zero-norm convention, a plain sum of the
+ * workers; squares that overflow make it NaN.  Other layers are unaffected.  Gradients, with
+ * or without loss scaling, are many orders of magnitude inside the range.
+ *
  * Conventions for every entry point
  *   - returns ADASUM_OK (0) or a negative ADASUM_ERR_* code; never throws,
  *     aborts or prints.  All argument validation happens before any device

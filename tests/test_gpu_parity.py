@@ -921,3 +921,31 @@ def test_binding_rejects_buffers_the_kernels_would_overrun():
     dplan.destroy()
     with pytest.raises(ValueError):
         B.adasum_reduce(w.grads, w.layer_offsets, layer_stats=torch.zeros(len(sizes), 2, dtype=torch.float64))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K,radix", [(8, 0), (64, 0), (16, 2)])
+def test_supported_magnitude_range(K, radix, dtype):
+    """Layers at the ends of the documented magnitude range (rms 1e-15 and 1e+15) beside ordinary
+    ones: products are formed in fp32 lanes, so the squares (1e-30, 1e+30) must stay inside fp32.
+    A layer far outside (1e-25: its squares underflow; 1e+25: they overflow) does not have the
+    operator's result but leaves its neighbours alone."""
+    say(f"magnitude range K={K} radix={radix} {dtype}")
+    sizes = [5000, 70000, 300, 20000]
+    w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=600 + K, scale=[1e-15, 1e15, 1.0, 1e-15])
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, radix=radix, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    err = assert_parity(out, ref, w.layer_offsets, what="in range")
+    say(f"  rel-L2 per layer {err}")
+    w2 = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=700 + K, scale=[1e-25, 1.0, 1e25, 1.0])
+    ref2 = oracle_reduce(w2.grads, w2.layer_offsets)
+    out2 = B.adasum_reduce(w2.grads, w2.layer_offsets, radix=radix, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    offs = w2.layer_offsets
+    for l in (1, 3):
+        lo, hi = offs[l], offs[l + 1]
+        e = float(O.rel_l2_per_layer(to_f64(out2[lo:hi]), ref2[lo:hi], [0, hi - lo])[0])
+        assert e <= TOL_F32, (l, e)
+    # the underflowing layer stays finite (it falls on the zero-norm convention)
+    assert np.all(np.isfinite(to_f64(out2[offs[0]:offs[1]])))
