@@ -2,7 +2,9 @@
 // away: R streams of bf16 read with one 16-byte non-temporal load per lane and stream, an
 // optional fp32 stream written (two 16-byte stores per lane), workgroups that do one such step
 // and end, direct indexing (no tile table, no weights table, constant weights), buffers of the
-// headline workload's size.  A measuring tool for the roofline discussion: not part of
+// headline workload's size.  A third variant writes a narrow stream instead (16 bytes per lane,
+// as a bf16 result would be): it shows that what a written stream costs does not depend on how
+// much is written.  A measuring tool for the roofline discussion: not part of
 // libadasum, shares no code with it.
 //
 //   pattern_ceiling [elements per stream, default 335141888] [repetitions, default 5]
@@ -28,7 +30,7 @@ struct Streams {
     const u4* p[kMaxStreams];
 };
 
-template <int R, int LANES, bool WRITE>
+template <int R, int LANES, int WRITE>   // 0: read only, 1: fp32 stream written, 2: 16-bit stream written
 __global__ void __launch_bounds__(LANES) step_kernel(const Streams in, u4* __restrict__ out, float* __restrict__ sink,
                                                      size_t granules) {
     const size_t i = static_cast<size_t>(blockIdx.x) * LANES + threadIdx.x;
@@ -49,7 +51,14 @@ __global__ void __launch_bounds__(LANES) step_kernel(const Streams in, u4* __res
             z[2 * k + 1] = __builtin_fmaf(c, __uint_as_float(w[k] & 0xffff0000u), z[2 * k + 1]);
         }
     }
-    if (WRITE) {
+    if (WRITE == 2) {
+        u4 a;
+        a.x = __float_as_uint(z[0]) ^ __float_as_uint(z[4]);
+        a.y = __float_as_uint(z[1]) ^ __float_as_uint(z[5]);
+        a.z = __float_as_uint(z[2]) ^ __float_as_uint(z[6]);
+        a.w = __float_as_uint(z[3]) ^ __float_as_uint(z[7]);
+        __builtin_nontemporal_store(a, out + i);
+    } else if (WRITE == 1) {
         u4 a, b;
         a.x = __float_as_uint(z[0]); a.y = __float_as_uint(z[1]); a.z = __float_as_uint(z[2]); a.w = __float_as_uint(z[3]);
         b.x = __float_as_uint(z[4]); b.y = __float_as_uint(z[5]); b.z = __float_as_uint(z[6]); b.w = __float_as_uint(z[7]);
@@ -62,7 +71,7 @@ __global__ void __launch_bounds__(LANES) step_kernel(const Streams in, u4* __res
     }
 }
 
-template <int R, int LANES, bool WRITE>
+template <int R, int LANES, int WRITE>
 void run(const Streams& in, u4* out, float* sink, size_t granules, int reps) {
     hipEvent_t a, b;
     CK(hipEventCreate(&a));
@@ -80,9 +89,10 @@ void run(const Streams& in, u4* out, float* sink, size_t granules, int reps) {
     float ms = 0.f;
     CK(hipEventElapsedTime(&ms, a, b));
     ms /= reps;
-    const double bytes = static_cast<double>(granules) * 16 * R + (WRITE ? static_cast<double>(granules) * 32 : 0.0);
-    std::printf("streams %2d  lanes %3d  %-10s %8.3f ms  %6.0f GB/s  %5.1f %% of 8 TB/s\n", R, LANES,
-                WRITE ? "read+write" : "read only", ms, bytes / ms / 1e6, bytes / ms / 1e6 / 80.0);
+    const double bytes = static_cast<double>(granules) * 16 * R + static_cast<double>(granules) * (WRITE == 1 ? 32 : WRITE == 2 ? 16 : 0);
+    std::printf("streams %2d  lanes %3d  %-18s %8.3f ms  %6.0f GB/s  %5.1f %% of 8 TB/s\n", R, LANES,
+                WRITE == 1 ? "read + fp32 written" : WRITE == 2 ? "read + bf16 written" : "read only", ms,
+                bytes / ms / 1e6, bytes / ms / 1e6 / 80.0);
     std::fflush(stdout);
     CK(hipEventDestroy(a));
     CK(hipEventDestroy(b));
@@ -90,10 +100,11 @@ void run(const Streams& in, u4* out, float* sink, size_t granules, int reps) {
 
 template <int R>
 void run_all(const Streams& in, u4* out, float* sink, size_t granules, int reps) {
-    run<R, 64, false>(in, out, sink, granules, reps);
-    run<R, 256, false>(in, out, sink, granules, reps);
-    run<R, 64, true>(in, out, sink, granules, reps);
-    run<R, 256, true>(in, out, sink, granules, reps);
+    run<R, 64, 0>(in, out, sink, granules, reps);
+    run<R, 256, 0>(in, out, sink, granules, reps);
+    run<R, 64, 1>(in, out, sink, granules, reps);
+    run<R, 256, 1>(in, out, sink, granules, reps);
+    run<R, 64, 2>(in, out, sink, granules, reps);
 }
 
 int main(int argc, char** argv) {
