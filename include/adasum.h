@@ -106,7 +106,13 @@ typedef struct adasum_options {
     int32_t  use_graph;        /* 1 = replay the level ladder as one hipGraph launch: captured
                                   once per distinct set of buffers (grads, out, workspace,
                                   layer_stats), cached in the plan, relaunched while they match */
-    int32_t  reserved0;
+    int32_t  fuse_siblings;    /* radix 2, ADASUM_ORDER_TREE, no delta_start (else ADASUM_ERR_UNSUPPORTED):
+                                  1 = the combine of a level handles the two sibling pairs of an element
+                                  range together and also leaves the dot product of the two nodes it
+                                  writes (Section 3.4's recursion taken one level ahead), so only the
+                                  first level makes a reduce pass of its own.  Same tree, same result up
+                                  to rounding, a quarter fewer bytes than plain radix 2.  (This field was
+                                  reserved and had to be 0 before.) */
     void*    workspace;        /* DEVICE, 256-byte aligned, or NULL = library-owned, cached per plan */
     size_t   workspace_bytes;  /* size of `workspace`; see adasum_workspace_bytes */
     double*  layer_stats;      /* DEVICE or NULL: n_layers x 2 doubles written per call,
@@ -164,8 +170,8 @@ ADASUM_API int adasum_reduce_ex(const void* const* grads, int K,
 
 /* Bytes of DEVICE workspace adasum_reduce_ex needs for this problem (intermediate
  * tree nodes, per-tile partial sums, coefficient tables, the compact copy of the
- * small layers).  Depends on dtype, radix, order and on whether delta_start is set
- * (any non-NULL value).  Host-only. */
+ * small layers).  Depends on dtype, radix, order, fuse_siblings and on whether
+ * delta_start is set (any non-NULL value).  Host-only. */
 ADASUM_API int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
                            int dtype, const adasum_options* opts, size_t* bytes);
 

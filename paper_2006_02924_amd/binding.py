@@ -48,7 +48,7 @@ class Options(C.Structure):
         ("radix", C.c_int32),
         ("order", C.c_int32),
         ("use_graph", C.c_int32),
-        ("reserved0", C.c_int32),
+        ("fuse_siblings", C.c_int32),
         ("workspace", C.c_void_p),
         ("workspace_bytes", C.c_size_t),
         ("layer_stats", C.c_void_p),
@@ -174,7 +174,8 @@ def _check_inputs(tensors, N):
 
 def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, out_dtype=None,
                   radix: int = 0, order: int = ORDER_TREE, layer_stats=None, workspace=None,
-                  use_graph: bool = False, delta_start=None, stream=None, noalloc: bool = False):
+                  use_graph: bool = False, delta_start=None, stream=None, noalloc: bool = False,
+                  fuse_siblings: bool = False):
     """Per-layer Adasum tree of ``grads`` (K device tensors of N elements).
     Returns ``out`` (allocated here when None).  With ``delta_start`` (a tensor
     like one of ``grads``) the tensors in ``grads`` are parameters after a local
@@ -198,7 +199,8 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
         raise ValueError("out has the wrong dtype, size, layout or device")
     ptrs = _ptr_array(grads)
     plain = (out_code == in_code and radix == 0 and order == ORDER_TREE and layer_stats is None
-             and workspace is None and not use_graph and delta_start is None and not noalloc)
+             and workspace is None and not use_graph and delta_start is None and not noalloc
+             and not fuse_siblings)
     if plain:
         check(lib.adasum_reduce(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()), _stream(stream)))
         return out
@@ -208,6 +210,7 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
     o.radix = radix
     o.order = order
     o.use_graph = 1 if use_graph else 0
+    o.fuse_siblings = 1 if fuse_siblings else 0
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -231,7 +234,8 @@ class Plan:
     problem shape; ``execute`` reduces K tensors of that shape."""
 
     def __init__(self, K: int, layer_offsets: Sequence[int], dtype, *, out_dtype=None, radix: int = 0,
-                 order: int = ORDER_TREE, use_graph: bool = False, workspace=None, delta: bool = False):
+                 order: int = ORDER_TREE, use_graph: bool = False, workspace=None, delta: bool = False,
+                 fuse_siblings: bool = False):
         lib = load()
         offs, L = _offsets(layer_offsets)
         self.K, self.N, self.n_layers = K, int(layer_offsets[-1]), L
@@ -245,6 +249,7 @@ class Plan:
         o.radix = radix
         o.order = order
         o.use_graph = 1 if use_graph else 0
+        o.fuse_siblings = 1 if fuse_siblings else 0
         if workspace is not None:
             o.workspace = workspace.data_ptr()
             o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -302,7 +307,8 @@ class Plan:
 
 
 def adasum_workspace_bytes(K: int, layer_offsets: Sequence[int], dtype_code: int, *, radix: int = 0,
-                           out_dtype_code: int = -1, delta: bool = False, order: int = ORDER_TREE) -> int:
+                           out_dtype_code: int = -1, delta: bool = False, order: int = ORDER_TREE,
+                           fuse_siblings: bool = False) -> int:
     lib = load()
     offs, L = _offsets(layer_offsets)
     o = Options()
@@ -310,6 +316,7 @@ def adasum_workspace_bytes(K: int, layer_offsets: Sequence[int], dtype_code: int
     o.out_dtype = out_dtype_code
     o.radix = radix
     o.order = order
+    o.fuse_siblings = 1 if fuse_siblings else 0
     if delta:
         o.delta_start = 0x100   # only "set or not" matters for the size
     n = C.c_size_t(0)

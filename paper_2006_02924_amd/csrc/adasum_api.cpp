@@ -53,6 +53,7 @@ struct Opts {
     int radix;
     int order;
     int use_graph;
+    int fuse;        // radix 2: sibling pairs combined together, one level ahead
     void* workspace;
     size_t workspace_bytes;
     double* layer_stats;
@@ -68,6 +69,7 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     r.radix = 0;
     r.order = ADASUM_ORDER_TREE;
     r.use_graph = 0;
+    r.fuse = 0;
     r.workspace = nullptr;
     r.workspace_bytes = 0;
     r.layer_stats = nullptr;
@@ -79,6 +81,7 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
         r.radix = o->radix;
         r.order = o->order;
         r.use_graph = o->use_graph;
+        r.fuse = o->fuse_siblings != 0;
         r.workspace = o->workspace;
         r.workspace_bytes = o->workspace_bytes;
         r.layer_stats = o->layer_stats;
@@ -87,6 +90,8 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
     if (r.radix > max_radix(dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
+    if (r.fuse && (r.radix != 2 || r.order != ADASUM_ORDER_TREE || r.delta_start != nullptr))
+        return ADASUM_ERR_UNSUPPORTED;
     if (r.delta_start != nullptr) {
         if (r.order != ADASUM_ORDER_TREE || r.out_dtype != dtype) return ADASUM_ERR_UNSUPPORTED;
         if (!aligned16(r.delta_start)) return ADASUM_ERR_MISALIGNED;
@@ -174,6 +179,7 @@ struct Plan {
     // cache key of library-owned plans beyond the shape: calls that differ in any of these get
     // plans (and workspaces) of their own
     int in_dtype = -1, out_dtype = -1, delta = 0;
+    int fuse = 0;                         // laid out for the sibling-fused radix-2 schedule
     std::vector<int64_t> offsets;
     TileTable gram_tiles;                 // capacity kTile
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
@@ -248,7 +254,7 @@ std::vector<std::unique_ptr<Plan>> g_plans;   // least recently used first
 constexpr size_t kMaxPlans = 64;
 
 // Builds a plan (host tables, their device copies; no workspace yet) on the current device.
-int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets, int n_layers,
+int make_plan(int K, int radix, int order, int node_type, bool fuse, const int64_t* offsets, int n_layers,
               std::unique_ptr<Plan>& out) {
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
@@ -260,6 +266,7 @@ int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets
         p->radix = radix;
         p->order = order;
         p->node_type = node_type;
+        p->fuse = fuse ? 1 : 0;
         p->offsets.assign(offsets, offsets + n_layers + 1);
         p->gram_tiles.capacity = gram_tile_capacity(offsets, n_layers);
         build_tiles(offsets, n_layers, p->gram_tiles.capacity, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
@@ -271,7 +278,8 @@ int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets
         const int64_t small_elems = K > 1 ? find_small_layers(offsets, n_layers, p->small) : 0;
         p->lay = make_layout(Kv, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
                              norm_entries_bound(Kv, offsets, n_layers, p->radices, node_type), p->radices, order,
-                             K + 1, small_elems, node_type);
+                             K + 1, small_elems, node_type,
+                             fuse ? dot_entries_bound(Kv, offsets, n_layers, p->radices, node_type) : 0);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
@@ -291,8 +299,8 @@ int make_plan(int K, int radix, int order, int node_type, const int64_t* offsets
 // The library's own cache of plans, keyed by shape.
 // `order` is a tree order or kStepPlans (the step entry points keep plans of their own).
 constexpr int kStepPlans = 100;
-int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, bool delta, const int64_t* offsets,
-                      int n_layers, Plan** out) {
+int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, bool delta, bool fuse,
+                      const int64_t* offsets, int n_layers, Plan** out) {
     const int node_type = node_dtype(in_dtype);
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
@@ -300,6 +308,7 @@ int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, 
         Plan* p = g_plans[i].get();
         if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
             p->in_dtype == in_dtype && p->out_dtype == out_dtype && p->delta == (delta ? 1 : 0) &&
+            p->fuse == (fuse ? 1 : 0) &&
             static_cast<int>(p->offsets.size()) == n_layers + 1 &&
             std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
             // most recently used last
@@ -311,7 +320,8 @@ int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, 
     // a bounded cache: the least recently used plan goes (hipFree waits for work in flight)
     while (g_plans.size() >= kMaxPlans) g_plans.erase(g_plans.begin());
     std::unique_ptr<Plan> p;
-    const int rc = make_plan(K, radix, order == kStepPlans ? ADASUM_ORDER_TREE : order, node_type, offsets, n_layers, p);
+    const int rc = make_plan(K, radix, order == kStepPlans ? ADASUM_ORDER_TREE : order, node_type, fuse, offsets,
+                             n_layers, p);
     if (rc != ADASUM_OK) return rc;
     p->order = order;
     p->in_dtype = in_dtype;
@@ -477,8 +487,13 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     double* normcoarse = reinterpret_cast<double*>(ws + lay.off_normcoarse);
     double* gram = reinterpret_cast<double*>(ws + lay.off_gram);
     double* weights = reinterpret_cast<double*>(ws + lay.off_weights);
+    double* dotparts = reinterpret_cast<double*>(ws + lay.off_dotparts);
     const long long slot_bytes = static_cast<long long>(lay.slot_elems) * lay.node_bytes;
     char namebuf[48];
+    // sibling-fused radix 2 (fuse_siblings): the combine of every level but the last also leaves the
+    // dot products the next level needs
+    const bool fuse = o.fuse != 0 && p->fuse != 0;
+    bool dots_ready = false;   // the previous combine left this level's dot products
 
     int nodes = virtual_leaves(p->radices);   // tree nodes alive before this pass (leaves: padded count)
     const int depth0 = first_depth(p->radices);   // the first pass's groups are the sub-trees of this depth
@@ -543,16 +558,23 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
             return hi2 - lo;
         };
 
-        // step 1: partial Gram entries
-        for (int g0 = 0; g0 < groups; g0 += batch) {
-            const int ng = std::min(batch, groups - g0);
-            Operands ops;
-            fill_operands(ops, g0, ng);
-            kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
-            ADASUM_TIMED(namebuf, gram_bytes(real_leaves(g0, ng), ng), stream,
-                         launch_gram(in_dtype, first, ops, gt, ng, R, partials + static_cast<int64_t>(g0) * np * T,
-                                     sub_in, stream));
+        // step 1: partial Gram entries -- from a pass over the operands, or (sibling-fused) already
+        // left per combine tile by the combine that wrote them: one entry per pair, summed per Gram tile
+        if (dots_ready) {
+            ADASUM_TIMED("dot_coarsen", 0.0, stream,
+                         launch_norm_coarsen(dotparts, groups, norm_tiles, gt, partials, stream));
+        } else {
+            for (int g0 = 0; g0 < groups; g0 += batch) {
+                const int ng = std::min(batch, groups - g0);
+                Operands ops;
+                fill_operands(ops, g0, ng);
+                kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
+                ADASUM_TIMED(namebuf, gram_bytes(real_leaves(g0, ng), ng), stream,
+                             launch_gram(in_dtype, first, ops, gt, ng, R, partials + static_cast<int64_t>(g0) * np * T,
+                                         sub_in, stream));
+            }
         }
+        const bool fuse_here = fuse && R == 2 && !last && groups % 2 == 0;
         // step 2: finish the sums, then the tree's scalars
         if (!first) {
             ADASUM_TIMED("norm_coarsen", 0.0, stream,
@@ -582,6 +604,17 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                 outs.slot_bytes = slot_bytes;
                 outs.stride = ostride;
             }
+            if (fuse_here) {
+                char base[40];
+                kernel_name("combine", in_dtype, st_dtype, R, false, base, sizeof(base));
+                std::snprintf(namebuf, sizeof(namebuf), "%s+dot", base);
+                ADASUM_TIMED(namebuf, comb_bytes(real_leaves(g0, ng), ng), stream,
+                             launch_combine_siblings(in_dtype, st_dtype, ops, outs, ct, L, ng,
+                                                     weights + static_cast<int64_t>(g0) * L * R,
+                                                     normparts + static_cast<int64_t>(g0) * ct.n_tiles,
+                                                     dotparts + static_cast<int64_t>(g0 / 2) * ct.n_tiles, stream));
+                continue;
+            }
             kernel_name("combine", in_dtype, st_dtype, R, false, namebuf, sizeof(namebuf));
             ADASUM_TIMED(namebuf, comb_bytes(real_leaves(g0, ng), ng), stream,
                          launch_combine(in_dtype, st_dtype, ops, outs, ct, L, ng, R,
@@ -589,6 +622,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                                         want_norm ? normparts + static_cast<int64_t>(g0) * ct.n_tiles : nullptr,
                                         sub_in, add_out, stream));
         }
+        dots_ready = fuse_here;
         stride = first ? 1 : R * stride;
         nodes = groups;
         norm_tiles = ct;
@@ -896,7 +930,7 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
     rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, dtype, o.out_dtype,
-                           o.delta_start != nullptr, layer_offsets, n_layers, &p);
+                           o.delta_start != nullptr, o.fuse != 0, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     return execute_plan(p, grads, dtype, out, o, stream);
 }
@@ -961,8 +995,10 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
         }
         gcap = gram_tile_capacity(layer_offsets, L);
         n_gram = count_tiles(layer_offsets, L, gcap);
+        plan.fuse = o.fuse;
         plan.lay = make_layout(Kv, N, L, n_gram, norm_entries_bound(Kv, layer_offsets, L, plan.radices, node_type),
-                               plan.radices, o.order, K + 1, small_elems, node_type);
+                               plan.radices, o.order, K + 1, small_elems, node_type,
+                               o.fuse ? dot_entries_bound(Kv, layer_offsets, L, plan.radices, node_type) : 0);
         // the combine tables this reduction reads: one per distinct tile capacity
         std::vector<int> caps;
         if (K == 1) caps.push_back(combine_tile_capacity(dtype, 1));
@@ -1076,7 +1112,7 @@ int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dt
     h->opts.radix = o.radix == 0 ? default_radix(o) : o.radix;
     h->opts.delta_start = nullptr;
     if (layer_offsets[n_layers] > 0) {
-        rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), layer_offsets, n_layers, h->plan);
+        rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), o.fuse != 0, layer_offsets, n_layers, h->plan);
         if (rc != ADASUM_OK) return rc;
         if (o.workspace != nullptr && o.workspace_bytes < h->plan->lay.total) return ADASUM_ERR_WORKSPACE;
         // everything execute needs exists from here on: it allocates nothing
@@ -1158,7 +1194,9 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
         const Layout lay = make_layout(Kv, layer_offsets[n_layers], n_layers,
                                        count_tiles(layer_offsets, n_layers, gram_tile_capacity(layer_offsets, n_layers)),
                                        norm_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype)),
-                                       radices, o.order, K + 1, small_elems, node_dtype(dtype));
+                                       radices, o.order, K + 1, small_elems, node_dtype(dtype),
+                                       o.fuse ? dot_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype))
+                                              : 0);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -1183,7 +1221,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     if (n_layers == 0) return ADASUM_OK;
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, false, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;
@@ -1236,7 +1274,7 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     }
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, false, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;

@@ -149,6 +149,9 @@ struct Layout {
     size_t  off_small = 0;    // doubles [K + 1][small_elems]: the small layers of every worker, widened
                               // (row K: those of delta_start)
     int64_t small_elems = 0;
+    size_t  off_dotparts = 0; // doubles [sibling pair][combine tile]: dot product of the two nodes a
+                              // sibling-fused combine wrote (only with fuse_siblings)
+    int64_t dot_entries = 0;
     size_t  total = 0;
 };
 // `norm_entries`: doubles needed for the squared norms the combines leave
@@ -157,7 +160,11 @@ struct Layout {
 // reserved for the compact copy of the small layers.
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices, int order = ADASUM_ORDER_TREE, int64_t small_rows = 0,
-                   int64_t small_elems = 0, int node_type = ADASUM_F32);
+                   int64_t small_elems = 0, int node_type = ADASUM_F32, int64_t dot_entries = 0);
+// Doubles a sibling-fused radix-2 schedule needs for the dot products its combines leave: the most
+// any level but the last writes, pairs of groups x combine tiles of that level.
+int64_t dot_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
+                          int node_type = ADASUM_F32);
 // Number of tiles build_tiles would produce.
 int64_t count_tiles(const int64_t* layer_offsets, int n_layers, int64_t capacity);
 // Gram tile capacity for a layer table: kTile, or kTileSmall for a small problem.
@@ -222,6 +229,14 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
                    const double* weights /* or null: unit weights */, double* normparts,
                    const void* sub_in /* type of the operands, or null */,
                    const void* add_out /* type of the output, or null */, void* stream);
+// Step 3 for the sibling pairs of one radix-2 level at once (the tree recursion of Section 3.4 taken two
+// pairs at a time): group 2j combines operands (4j, 4j+1) into node P, group 2j+1 combines (4j+2, 4j+3) into
+// node Q, one workgroup does both for a tile and also leaves P.Q, so that the level above needs no pass of
+// its own over P and Q: dotparts[j * ct.n_tiles + tile], normparts[(2j | 2j+1) * ct.n_tiles + tile].
+// n_groups must be even; `ct` the table of capacity combine_tile_capacity(dtype, 2).
+int launch_combine_siblings(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                            int n_layers, int n_groups, const double* weights, double* normparts, double* dotparts,
+                            void* stream);
 // Steps 1 and 3 for one group whose operand 0 is stored as fp32 while operands 1..R-1 are
 // 16-bit (`dtype`): the running result of the left-to-right order folded with the next leaves.
 // Always the full Gram matrix (diagonal included); tiles as for `dtype`.

@@ -856,6 +856,120 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
 }
 
 // ---------------------------------------------------------------------------
+// Step 3 for two sibling pairs at once (radix 2 with fuse_siblings): the recursion of Section 3.4
+// taken one level ahead.  Workgroup (tile, j) reads the tile of operands A, B (group 2j) and C, D
+// (group 2j+1), writes P = a A + b B and Q = c C + d D, and leaves |P|^2, |Q|^2 and P.Q of the
+// tile, so the level above -- whose operands are exactly P and Q -- needs no pass over them
+// before its own combine.  Tile capacity: 256 lanes x one 16-byte load per operand.
+// normparts[(2j | 2j+1) * n_tiles + tile], dotparts[j * n_tiles + tile].
+// ---------------------------------------------------------------------------
+template <typename TI, typename TO>
+__global__ void __launch_bounds__(combine_threads(2))
+combine_siblings_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles, int n_tiles,
+                        int n_layers, const double* __restrict__ weights, double* __restrict__ normparts,
+                        double* __restrict__ dotparts) {
+    constexpr int G = 16 / (int)sizeof(TI);
+    constexpr int THREADS = combine_threads(2);
+    typedef typename Traits<TI>::acc_t acc_t;
+    typedef typename Traits<TO>::acc_t out_acc_t;
+    // plain stores where half of the traffic is written (16-bit leaves -> fp32 nodes), as in the pair
+    // kernel; measured on the K = 64 BERT-Large case: 16.5 ms against 18.1 ms with non-temporal ones
+    constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4);
+
+    const int tid = threadIdx.x;
+    const unsigned v = blockIdx.x;
+    const int tile_id = static_cast<int>(v % static_cast<unsigned>(n_tiles));
+    const int j = static_cast<int>(v / static_cast<unsigned>(n_tiles));
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
+
+    const TI* x[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) x[r] = static_cast<const TI*>(ops.pack[4 * j + r]);
+    TO* out[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        out[h] = reinterpret_cast<TO*>(outs.base + static_cast<long long>(2 * j + h) * outs.stride * outs.slot_bytes);
+
+    const long long idx = s.bs + static_cast<long long>(tid) * G;
+    Granule<TI, G> raw[4];
+    if (tid < s.ng) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) load_raw(raw[r], x[r] + idx);
+    }
+    // weights[(group * n_layers + layer) * 2 + operand], groups 2j and 2j+1
+    double wd[4];
+    acc_t w[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        wd[r] = weights[(static_cast<long long>(2 * j + (r >> 1)) * n_layers + t.layer) * 2 + (r & 1)];
+        w[r] = static_cast<acc_t>(wd[r]);
+    }
+
+    acc_t acc[3] = {0, 0, 0};   // |P|^2, |Q|^2, P.Q
+    if (tid < s.ng) {
+        acc_t z[2][G];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            acc_t a[G], b[G];
+            unpack(raw[2 * h], a);
+            unpack(raw[2 * h + 1], b);
+#pragma unroll
+            for (int k = 0; k < G; ++k) z[h][k] = fma_t(w[2 * h + 1], b[k], w[2 * h] * a[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            acc[0] = fma_t(z[0][k], z[0][k], acc[0]);
+            acc[1] = fma_t(z[1][k], z[1][k], acc[1]);
+            acc[2] = fma_t(z[0][k], z[1][k], acc[2]);
+        }
+        store_granule<NTS>(out[0] + idx, z[0]);
+        store_granule<NTS>(out[1] + idx, z[1]);
+    }
+
+    // ragged head/tail elements: fp64 arithmetic, one rounding at the store
+    const int lane = tid & 63, wave = tid >> 6;
+    const int nedge = s.nh + s.nt;
+    double edge[3] = {0.0, 0.0, 0.0};
+    if (nedge > 0 && wave == 0) {
+        if (lane < nedge) {
+            const long long e = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
+            double zs[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const double z = __builtin_fma(wd[2 * h + 1], static_cast<double>(load_elem(x[2 * h + 1] + e)),
+                                               wd[2 * h] * static_cast<double>(load_elem(x[2 * h] + e)));
+                const out_acc_t stored = static_cast<out_acc_t>(z);
+                zs[h] = static_cast<double>(stored);
+                store_elem(out[h] + e, stored);
+            }
+            edge[0] = zs[0] * zs[0];
+            edge[1] = zs[1] * zs[1];
+            edge[2] = zs[0] * zs[1];
+        }
+#pragma unroll
+        for (int q = 0; q < 3; ++q) edge[q] = wave_sum(edge[q]);
+    }
+
+    __shared__ double sh[3][THREADS / 64];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        const acc_t ws = wave_sum(acc[q]);
+        if (lane == 0) sh[q][wave] = static_cast<double>(ws);
+    }
+    __syncthreads();
+    if (tid < 3) {
+        double tot = sh[tid][0];
+#pragma unroll
+        for (int k = 1; k < THREADS / 64; ++k) tot += sh[tid][k];
+        // (threads 0..2 are lanes of wave 0, every lane of which holds the edge sums)
+        if (nedge > 0) tot += tid == 0 ? edge[0] : (tid == 1 ? edge[1] : edge[2]);
+        if (tid < 2) normparts[static_cast<long long>(2 * j + tid) * n_tiles + tile_id] = tot;
+        else dotparts[static_cast<long long>(j) * n_tiles + tile_id] = tot;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Small layers (at most kSmallLayer elements), by the definition itself: the
 // operator of Section 3 applied pair by pair over all K workers in fp64, in the
 // order of Section 3.4's recursion, nothing stored in between.
@@ -1285,7 +1399,38 @@ int launch_combine_head32_r(const Operands& ops, const Outputs& outs, const Tile
     return check_launch();
 }
 
+template <typename TI, typename TO>
+int launch_combine_siblings_t(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
+                              const double* weights, double* normparts, double* dotparts, hipStream_t st) {
+    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups / 2);
+    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
+    hipLaunchKernelGGL((combine_siblings_kernel<TI, TO>), dim3(static_cast<unsigned>(blocks)), dim3(combine_threads(2)),
+                       0, st, ops, outs, ct.tiles, static_cast<int>(ct.n_tiles), n_layers, weights, normparts, dotparts);
+    return check_launch();
+}
+
 }  // namespace
+
+int launch_combine_siblings(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                            int n_layers, int n_groups, const double* weights, double* normparts, double* dotparts,
+                            void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (ct.n_tiles == 0 || n_groups == 0) return 0;
+    if (n_groups % 2 != 0 || 2 * n_groups > kMaxPack || weights == nullptr || normparts == nullptr || dotparts == nullptr ||
+        ct.capacity != combine_tile_capacity(dtype, 2))
+        return static_cast<int>(hipErrorInvalidValue);
+    // the nodes a fused level writes are never the root: always the node type of the input
+    if (dtype == ADASUM_F64 && out_dtype == ADASUM_F64)
+        return launch_combine_siblings_t<double, double>(ops, out, ct, n_layers, n_groups, weights, normparts, dotparts, st);
+    if (out_dtype != ADASUM_F32) return static_cast<int>(hipErrorInvalidValue);
+    if (dtype == ADASUM_BF16)
+        return launch_combine_siblings_t<bf16_t, float>(ops, out, ct, n_layers, n_groups, weights, normparts, dotparts, st);
+    if (dtype == ADASUM_F16)
+        return launch_combine_siblings_t<f16_t, float>(ops, out, ct, n_layers, n_groups, weights, normparts, dotparts, st);
+    if (dtype == ADASUM_F32)
+        return launch_combine_siblings_t<float, float>(ops, out, ct, n_layers, n_groups, weights, normparts, dotparts, st);
+    return static_cast<int>(hipErrorInvalidValue);
+}
 
 int launch_gram_head32(int dtype, const Operands& ops, const TileSet& gt, int R, double* partials, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);

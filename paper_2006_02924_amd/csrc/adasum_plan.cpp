@@ -131,9 +131,22 @@ int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, co
     return need;
 }
 
+int64_t dot_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
+                          int node_type) {
+    int64_t need = 0;
+    int groups = K;
+    for (size_t lv = 0; lv + 1 < radices.size(); ++lv) {
+        groups /= radices[lv];
+        if (radices[lv] != 2) continue;
+        const int64_t t = count_tiles(layer_offsets, n_layers, combine_tile_capacity(node_type, 2));
+        need = std::max<int64_t>(need, static_cast<int64_t>(groups / 2) * t);
+    }
+    return need;
+}
+
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices, int order, int64_t small_rows, int64_t small_elems,
-                   int node_type) {
+                   int node_type, int64_t dot_entries) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
@@ -177,6 +190,9 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
     lay.off_small = off;
     lay.small_elems = small_elems;
     off = align_up(off + static_cast<size_t>(small_rows) * static_cast<size_t>(small_elems) * sizeof(double), 256);
+    lay.off_dotparts = off;
+    lay.dot_entries = dot_entries;
+    off = align_up(off + static_cast<size_t>(dot_entries) * sizeof(double), 256);
     lay.total = off;
     return lay;
 }

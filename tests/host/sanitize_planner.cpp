@@ -97,15 +97,18 @@ static void check_schedule(int K, int radix, int order, const std::vector<int64_
     CHECK(gcap == kTile || gcap == kTileSmall);
     const int64_t n_tiles = count_tiles(offs.data(), L, gcap);
     const int64_t ne = norm_entries_bound(Kv, offs.data(), L, radices, node_type);
-    const Layout lay = make_layout(Kv, offs[L], L, n_tiles, ne, radices, order, K + 1, small_elems, node_type);
+    const int64_t de = order == ADASUM_ORDER_TREE ? dot_entries_bound(Kv, offs.data(), L, radices, node_type) : 0;
+    const Layout lay = make_layout(Kv, offs[L], L, n_tiles, ne, radices, order, K + 1, small_elems, node_type, de);
     const size_t sections[] = {lay.off_slots, lay.off_partials, lay.off_normparts, lay.off_normcoarse, lay.off_gram,
-                               lay.off_weights, lay.off_leafnorm, lay.off_small, lay.total};
+                               lay.off_weights, lay.off_leafnorm, lay.off_small, lay.off_dotparts, lay.total};
+    CHECK(lay.total - lay.off_dotparts >= static_cast<size_t>(de) * sizeof(double));
+    CHECK(de <= ne);
     for (size_t i = 0; i + 1 < sizeof(sections) / sizeof(sections[0]); ++i) {
         CHECK(sections[i] % 256 == 0 && sections[i] <= sections[i + 1]);
     }
     CHECK(lay.off_partials - lay.off_slots >= static_cast<size_t>(lay.n_slots) * lay.slot_elems * lay.node_bytes);
     CHECK(lay.off_normcoarse - lay.off_normparts >= static_cast<size_t>(ne) * sizeof(double));
-    CHECK(lay.total - lay.off_small >= static_cast<size_t>(K + 1) * static_cast<size_t>(small_elems) * sizeof(double));
+    CHECK(lay.off_dotparts - lay.off_small >= static_cast<size_t>(K + 1) * static_cast<size_t>(small_elems) * sizeof(double));
     // every pass's squared norms fit the reserved entries, for every storage type the pass may read
     int groups = Kv;
     for (size_t lv = 0; lv < radices.size(); ++lv) {

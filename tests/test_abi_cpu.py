@@ -113,6 +113,27 @@ def test_options_validation(lib):
     assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, bad) == B.ERR_INVALID_ARG
 
 
+def test_sibling_fusion_option_validation(lib):
+    """fuse_siblings goes with radix 2, the tree order and no delta form; it needs room for the
+    dot products its combines leave."""
+    good = [0x1000, 0x2000, 0x3000, 0x4000]
+    offs = [0, 8]
+    assert _call_reduce(lib, good, 4, [0], B.F32, 0x9000, _opts(radix=2, fuse_siblings=1)) == B.OK
+    assert _call_reduce(lib, good, 4, offs, B.F32, 0x9000, _opts(radix=0, fuse_siblings=1)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 4, offs, B.F32, 0x9000, _opts(radix=4, fuse_siblings=1)) == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 4, offs, B.F32, 0x9000, _opts(radix=2, fuse_siblings=1, order=B.ORDER_LINEAR)) \
+        == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 4, offs, B.F32, 0x9000, _opts(radix=2, fuse_siblings=1, delta_start=0x5000)) \
+        == B.ERR_UNSUPPORTED
+    big = [0, 70632]
+    plain = B.adasum_workspace_bytes(16, big, B.F32, radix=2)
+    fused = B.adasum_workspace_bytes(16, big, B.F32, radix=2, fuse_siblings=True)
+    # 4 pairs of groups x 69 combine tiles of 1024 elements, one double each
+    assert plain < fused <= plain + 4 * 70 * 8 + 256
+    # a single pair has no level above its first: nothing to leave
+    assert B.adasum_workspace_bytes(2, big, B.F32, radix=2, fuse_siblings=True) == B.adasum_workspace_bytes(2, big, B.F32, radix=2)
+
+
 def test_fp64_storage_limits(lib):
     good = [0x1000, 0x2000]
     offs = [0, 8]

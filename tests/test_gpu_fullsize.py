@@ -50,15 +50,24 @@ def test_config4_full_size_sampled_layers(config4):
     say("oracle done")
     stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
     outs = {}
-    for radix, out_dtype in ((0, torch.bfloat16), (0, torch.float32), (2, torch.bfloat16)):
-        say(f"adasum_reduce radix={radix} -> {out_dtype}")
-        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix,
+    for radix, out_dtype, fuse in ((0, torch.bfloat16, False), (0, torch.float32, False), (2, torch.bfloat16, False),
+                                   (2, torch.bfloat16, True)):
+        say(f"adasum_reduce radix={radix} -> {out_dtype}{' (sibling-fused)' if fuse else ''}")
+        out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=radix, fuse_siblings=fuse,
                               layer_stats=stats if (radix == 0 and out_dtype == torch.float32) else None)
         torch.cuda.synchronize()
         err = assert_parity(out, ref, w.layer_offsets, layers=layers, what=f"config4 radix {radix} {out_dtype}")
         say(f"  max rel-L2 on sampled layers {err.max():.3e}")
         if out_dtype == torch.bfloat16:
             assert_bf16_rounding(out, ref, w.layer_offsets, layers=layers)
+        if fuse:
+            # the same tree as plain radix 2: the bf16 results differ in the few elements whose
+            # rounding the last bits of the dot products decide
+            differ = float((out.float() != outs[(2, torch.bfloat16)].float()).float().mean())
+            say(f"  sibling-fused vs plain radix 2 bf16 outputs differ in {differ:.2e} of the elements")
+            assert differ < 1e-2
+            B.shutdown()
+            continue
         outs[(radix, out_dtype)] = out
     # properties that hold for every layer: finite output; |Adasum(g1,g2)|^2 <= |g1|^2 + |g2|^2 at every
     # node, so the Section 3.6 metric is at most 1 (and positive here: the workers are positively

@@ -943,3 +943,85 @@ def test_supported_magnitude_range(K, radix, dtype):
         assert e <= TOL_F32, (l, e)
     # the underflowing layer stays finite (it falls on the zero-norm convention)
     assert np.all(np.isfinite(to_f64(out2[offs[0]:offs[1]])))
+
+
+# ---------------------------------------------------------------------------
+# radix 2 with sibling pairs combined together (the recursion of Section 3.4 taken one level ahead)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.float64])
+@pytest.mark.parametrize("K", [2, 3, 4, 5, 8, 13, 16, 64, 100, 256])
+def test_sibling_fused_radix2(K, dtype):
+    """fuse_siblings: from the second level on, the dot product of a pair comes from the combine that
+    wrote its two nodes instead of from a pass of its own.  Same tree: checked against the oracle,
+    against plain radix 2 (equal up to the rounding of the dot products), with statistics, and for
+    identical bits on a rerun."""
+    say(f"sibling-fused radix 2 K={K} {dtype}")
+    sizes = np.diff(RAGGED).tolist()
+    if dtype == torch.float64:
+        w = _fp64_workload(sizes, K, 950 + K)
+    elif dtype == torch.float16:
+        w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=950 + K,
+                                  scale=W.log_uniform_scales(len(sizes), 79, lo_exp=-2.0, hi_exp=0.0))
+    else:
+        w = W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=950 + K)
+    ref = oracle_reduce(w.grads, w.layer_offsets)
+    before = [g.clone() for g in w.grads]
+    wide = torch.float64 if dtype == torch.float64 else torch.float32
+    stats = torch.full((w.n_layers, 2), -1.0, dtype=torch.float64, device=DEV)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, fuse_siblings=True, out_dtype=wide, layer_stats=stats)
+    plain_stats = torch.full((w.n_layers, 2), -1.0, dtype=torch.float64, device=DEV)
+    plain = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, out_dtype=wide, layer_stats=plain_stats)
+    torch.cuda.synchronize()
+    for g, b in zip(w.grads, before):
+        assert torch.equal(g, b), "inputs must not be modified"
+    assert_parity(out, ref, w.layer_offsets, what="sibling-fused")
+    # against the schedule it replaces: the two differ only in how the dot products were summed
+    got, want = to_f64(out), to_f64(plain)
+    offs = w.layer_offsets
+    for l in range(w.n_layers):
+        lo, hi = offs[l], offs[l + 1]
+        if hi > lo and not np.isnan(ref[lo:hi]).any():
+            den = np.linalg.norm(want[lo:hi])
+            assert np.linalg.norm(got[lo:hi] - want[lo:hi]) <= (1e-12 if dtype == torch.float64 else 2e-6) * den, l
+    np.testing.assert_allclose(stats.cpu().numpy()[:, 1], plain_stats.cpu().numpy()[:, 1], rtol=1e-12)
+    np.testing.assert_allclose(stats.cpu().numpy()[:, 0], plain_stats.cpu().numpy()[:, 0], rtol=1e-5, atol=1e-300)
+    if dtype != wide:
+        narrow = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, fuse_siblings=True)
+        torch.cuda.synchronize()
+        assert_parity(narrow, ref, w.layer_offsets, what="sibling-fused, narrow result")
+        assert_bf16_rounding(narrow, ref, w.layer_offsets)
+    again = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, fuse_siblings=True, out_dtype=wide)
+    torch.cuda.synchronize()
+    assert torch.equal(again, out)
+
+
+def test_sibling_fused_options():
+    """Only with radix 2, the tree order and no delta form; caller-owned plans, graph replay and the
+    entry point without allocation take the option as well."""
+    w = W.correlated_gaussian([3, 5000, 70001, 1], 16, dtype=torch.bfloat16, device=DEV, seed=77)
+    for kw in ({"radix": 0}, {"radix": 16}, {"radix": 2, "order": B.ORDER_LINEAR}):
+        with pytest.raises(B.AdasumError) as e:
+            B.adasum_reduce(w.grads, w.layer_offsets, fuse_siblings=True, **kw)
+        assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.AdasumError) as e:
+        B.adasum_reduce(w.grads, w.layer_offsets, radix=2, fuse_siblings=True, delta_start=w.grads[0])
+    assert e.value.code == B.ERR_UNSUPPORTED
+    want = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, fuse_siblings=True)
+    torch.cuda.synchronize()
+    assert_parity(want, oracle_reduce(w.grads, w.layer_offsets), w.layer_offsets)
+    plan = B.Plan(16, w.layer_offsets, torch.bfloat16, radix=2, fuse_siblings=True)
+    assert plan.workspace_bytes() == B.adasum_workspace_bytes(16, w.layer_offsets, B.BF16, radix=2, fuse_siblings=True)
+    assert plan.workspace_bytes() > B.adasum_workspace_bytes(16, w.layer_offsets, B.BF16, radix=2)
+    got = plan.execute(w.grads)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    plan.destroy()
+    out = torch.empty_like(want)
+    B.adasum_reduce(w.grads, w.layer_offsets, out, radix=2, fuse_siblings=True, noalloc=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+    for _ in range(3):
+        g = B.adasum_reduce(w.grads, w.layer_offsets, radix=2, fuse_siblings=True, use_graph=True)
+        torch.cuda.synchronize()
+        assert torch.equal(g, want)
