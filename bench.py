@@ -75,6 +75,10 @@ def parse_args():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-profile", action="store_true",
                    help="do not bracket kernels with HIP events in the timed region")
+    p.add_argument("--combine-norms-ab", action="store_true",
+                   help="instead of a reduction: time the combine step alone (adasum_group_combine over the first 16 "
+                        "workers of the workload, fp32 result) with and without the per-tile squared norms it can "
+                        "leave, and print both")
     p.add_argument("--headline-only", action="store_true",
                    help="only the workload named by --workload: skip the other configurations "
                         "(they run by default when nothing but --steps / --warmup is given)")
@@ -281,6 +285,38 @@ def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False):
     return row
 
 
+def combine_norms_ab(B, w, steps, warmup):
+    """The radix-16 combine step alone through the C-ABI, with and without the squared norms of the
+    result per tile (the stores a later pass reads its diagonal from): what those stores cost."""
+    import torch
+    R = min(16, w.K)
+    xs = w.grads[:R]
+    weights = torch.full((w.n_layers, R), 1.0 / R, dtype=torch.float64, device=xs[0].device)
+    out = torch.empty(w.N, dtype=torch.float32, device=xs[0].device)
+    es = xs[0].element_size()
+    res = {}
+    for want in (True, False, True, False):
+        for _ in range(warmup):
+            B.adasum_group_combine(xs, w.layer_offsets, weights, out=out, out_dtype=torch.float32, want_sqnorm=want)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            B.adasum_group_combine(xs, w.layer_offsets, weights, out=out, out_dtype=torch.float32, want_sqnorm=want)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / steps
+        res.setdefault(want, []).append(ms)
+    nbytes = w.N * (R * es + 4)
+    line = {"what": f"adasum_group_combine, R={R}, {w.name}, N={w.N}, {str(w.dtype).replace('torch.', '')} -> float32",
+            "bytes_per_call": nbytes, "steps": steps,
+            "with_norms_ms": res[True], "without_norms_ms": res[False],
+            "with_norms_GBps": [nbytes / m / 1e6 for m in res[True]],
+            "without_norms_GBps": [nbytes / m / 1e6 for m in res[False]],
+            "note": "with norms the call also runs two small kernels that sum the per-tile norms per layer"}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -315,6 +351,9 @@ def main():
         w.dtype = to
         torch.cuda.synchronize()
     out_dtype = {"same": w.dtype, "f32": torch.float32, "bf16": torch.bfloat16}[args.out_dtype]
+    if args.combine_norms_ab:
+        combine_norms_ab(B, w, args.steps, args.warmup)
+        return
     out = torch.empty(w.N, dtype=out_dtype, device=dev)
 
     start = None

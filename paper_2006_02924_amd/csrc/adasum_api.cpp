@@ -867,9 +867,13 @@ int begin_on_stream(Plan* p, void* stream, bool* eager) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     *eager = false;
     if (p->done == nullptr) return ADASUM_OK;
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    ADASUM_HIP(hipStreamIsCapturing(st, &cs));
-    if (cs != hipStreamCaptureStatusNone) return ADASUM_OK;
+    // (the default stream cannot be captured; asking about it could even disturb a capture that
+    // another thread has under way in the global mode)
+    if (st != nullptr) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        ADASUM_HIP(hipStreamIsCapturing(st, &cs));
+        if (cs != hipStreamCaptureStatusNone) return ADASUM_OK;
+    }
     *eager = true;
     if (p->has_last && p->last_stream != st) ADASUM_HIP(hipStreamWaitEvent(st, p->done, 0));
     return ADASUM_OK;
