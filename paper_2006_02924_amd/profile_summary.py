@@ -45,6 +45,8 @@ def library_name(kernel_name: str):
         head = "+f32 head" if len(args) >= 5 and args[4] == "true" else ""
         delta = " (delta)" if len(args) >= 4 and args[3] == "true" else ""
         return f"combine<{args[0]},{args[1]},R={args[2]}>{head}{delta}"
+    if kind == "combine_siblings" and len(args) >= 2:
+        return f"combine<{args[0]},{args[1]},R=2>+dot"
     if kind == "gram_finish" and len(args) >= 2:
         return f"gram_finish<R={args[0]},{'diag' if args[1] == 'true' else 'offdiag'}>"
     return kind + (f"<{','.join(args)}>" if args else "")
