@@ -66,6 +66,19 @@ def test_random_cases(block):
                               order=B.ORDER_TREE if order == "tree" else B.ORDER_LINEAR, layer_stats=stats)
         torch.cuda.synchronize()
         assert_parity(out, ref, offs, what=f"case {case}")
+        # the entry point that allocates nothing runs the same kernels on tables built on the device
+        stats2 = torch.full((len(sizes), 2), -1.0, dtype=torch.float64, device=DEV) if stats_on else None
+        out2 = torch.full_like(out, float("nan"))
+        B.adasum_reduce(grads, offs, out2, out_dtype=out_dtype, radix=radix, noalloc=True,
+                        order=B.ORDER_TREE if order == "tree" else B.ORDER_LINEAR, layer_stats=stats2)
+        torch.cuda.synchronize()
+        assert torch.equal(out2.view(torch.uint8), out.view(torch.uint8)), f"case {case}: noalloc differs"
+        if stats_on:
+            assert torch.equal(stats2, stats), f"case {case}: noalloc statistics differ"
+        if radix == 2 and order == "tree":
+            fused = B.adasum_reduce(grads, offs, out_dtype=out_dtype, radix=2, fuse_siblings=True)
+            torch.cuda.synchronize()
+            assert_parity(fused, ref, offs, what=f"case {case}, sibling-fused")
         if not stats_on:
             continue
         f64 = [to_f64(x) for x in grads]
