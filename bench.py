@@ -63,6 +63,8 @@ def parse_args():
     p.add_argument("--radix", type=int, default=0, help="0 = library default")
     p.add_argument("--fuse-siblings", action="store_true",
                    help="with --radix 2: the combine of a level also leaves the next level's dot products")
+    p.add_argument("--separate-passes", action="store_true",
+                   help="every pass makes a reduce pass of its own (no combine leaves the next pass's Gram matrix)")
     p.add_argument("--out-dtype", default="same", choices=["same", "f32", "bf16"])
     p.add_argument("--storage", default="same", choices=["same", "f16", "f64"],
                    help="convert the generated gradients to this storage type before timing")
@@ -192,14 +194,15 @@ def cpu_baseline(w, budget_elems=40_000_000):
             "seconds": tn, "host_cpus": os.cpu_count()}
 
 
-def timed_steps(B, w, out, *, out_dtype, radix, order, graph, start, steps, warmup, profile, fuse=False):
+def timed_steps(B, w, out, *, out_dtype, radix, order, graph, start, steps, warmup, profile, fuse=False,
+                separate=False):
     """`warmup` untimed steps, then exactly `steps` timed ones between device synchronisations.
     Returns (seconds for the timed steps, per-kernel HIP-event records or [])."""
     import torch
 
     def step():
         B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=radix,
-                        use_graph=graph, delta_start=start, fuse_siblings=fuse,
+                        use_graph=graph, delta_start=start, fuse_siblings=fuse, separate_passes=separate,
                         order=B.ORDER_LINEAR if order == "linear" else B.ORDER_TREE)
 
     for _ in range(warmup):
@@ -241,7 +244,7 @@ def kernel_summary(prof, steps, ms_per_step, workload, verbose_tag=None):
             "schedule_bytes": total_bytes}
 
 
-def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False):
+def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False, separate=False):
     """One more configuration, default options: the step time from an event-free loop, the kernel
     breakdown from a second, event-bracketed loop of the same steps."""
     import torch
@@ -253,11 +256,12 @@ def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False):
         torch.cuda.synchronize()
     gen_s = time.perf_counter() - t0
     out = torch.empty(w.N, dtype=w.dtype, device=dev)
-    kw = dict(out_dtype=w.dtype, radix=radix, order="tree", graph=False, start=None, fuse=fuse)
+    kw = dict(out_dtype=w.dtype, radix=radix, order="tree", graph=False, start=None, fuse=fuse, separate=separate)
     dt, _ = timed_steps(B, w, out, steps=steps, warmup=warmup, profile=False, **kw)
     ms = dt / steps * 1e3
     dtp, prof = timed_steps(B, w, out, steps=steps, warmup=0, profile=True, **kw)
-    tag = f"{name}{' radix ' + str(radix) if radix else ''}{' sibling-fused' if fuse else ''}"
+    tag = f"{name}{' radix ' + str(radix) if radix else ''}{' sibling-fused' if fuse else ''}" \
+          f"{' separate passes' if separate else ''}"
     roof = kernel_summary(prof, steps, dtp / steps * 1e3, name, verbose_tag=tag + ": ")
     es = w.grads[0].element_size()
     row = {"workload": f"{name}: K={w.K}, {w.n_layers} tensors, N={w.N}, stored and output "
@@ -272,7 +276,8 @@ def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False):
                     "dominant_kernel": roof["kernel"], "dominant_kernel_avg_ms": roof["kernel_avg_ms"],
                     "dominant_kernel_GBps": roof["achieved"], "dominant_kernel_frac": roof["frac"],
                     "ms_per_step_with_events": dtp / steps * 1e3})
-        t = measured_traffic((name if not radix else f"{name}_radix{radix}") + ("_fused" if fuse else ""), roof["kernel"])
+        t = measured_traffic((name if not radix else f"{name}_radix{radix}") + ("_fused" if fuse else "")
+                             + ("_separate" if separate else ""), roof["kernel"])
         row["dominant_kernel_traffic"] = t["bytes"] if t else None
     if w.K & (w.K - 1) == 0 and w.K > 1:
         row["pair_per_level_bytes"] = pair_per_level_bytes(w.K, w.N, es, es)
@@ -334,7 +339,8 @@ def main():
     torch.cuda.set_device(0)
     plain = (args.workload == "config4" and not args.workers and args.order == "tree" and args.radix == 0
              and args.out_dtype == "same" and args.storage == "same" and not args.graph and not args.delta
-             and not args.single_layer and not args.no_profile and not args.fuse_siblings)
+             and not args.single_layer and not args.no_profile and not args.fuse_siblings
+             and not args.separate_passes)
     with_others = plain and not args.headline_only
     t0 = time.perf_counter()
     w = make_workload(args.workload, dev, args.workers)
@@ -362,7 +368,7 @@ def main():
 
     dt, prof = timed_steps(B, w, out, out_dtype=out_dtype, radix=args.radix, order=args.order, graph=args.graph,
                            start=start, steps=args.steps, warmup=args.warmup, profile=not args.no_profile,
-                           fuse=args.fuse_siblings)
+                           fuse=args.fuse_siblings, separate=args.separate_passes)
 
     ms_per_step = dt / args.steps * 1e3
     value = w.input_bytes / (dt / args.steps) / 1e9
@@ -371,7 +377,8 @@ def main():
 
     roofline = kernel_summary(prof, args.steps, ms_per_step, args.workload, verbose_tag="")
     if roofline is not None:
-        key = args.workload if not args.radix else f"{args.workload}_radix{args.radix}"
+        key = (args.workload if not args.radix else f"{args.workload}_radix{args.radix}") + \
+              ("_fused" if args.fuse_siblings else "") + ("_separate" if args.separate_passes else "")
         t = measured_traffic(key, roofline["kernel"]) if (args.order == "tree" and not args.delta) else None
         if t is not None:
             roofline["traffic"] = t["bytes"]
@@ -395,6 +402,7 @@ def main():
                                f"{str(out_dtype).replace('torch.', '')}",
                    "passes": levels, "radix": args.radix, "graph": bool(args.graph), "delta_form": bool(args.delta),
                    "order": args.order, "fuse_siblings": bool(args.fuse_siblings),
+                   "separate_passes": bool(args.separate_passes),
                    "input_GB": w.input_bytes / 1e9},
         "roofline": roofline,
     }
@@ -410,27 +418,31 @@ def main():
         torch.cuda.empty_cache()
         # the one-pair-per-level schedule on the headline workload, then the other four configurations
         # (the headline workload is dropped before the first of them is generated)
-        todo = [("config4", 2, 10, 2, False), ("config4", 2, 10, 2, True), ("config1", 0, 200, 20, False),
-                ("config2", 0, 50, 5, False), ("config3", 0, 20, 3, False), ("config5", 0, 10, 2, False)]
-        for name, radix, steps, warmup, fuse in todo:
-            reuse = w if radix else None
+        # (name, radix, steps, warm-up, fuse_siblings, separate_passes); the first three reuse the headline buffers
+        todo = [("config4", 0, 20, 5, False, True), ("config4", 2, 10, 2, False, True), ("config4", 2, 10, 2, True, False),
+                ("config1", 0, 200, 20, False, False), ("config2", 0, 50, 5, False, False),
+                ("config3", 0, 20, 3, False, False), ("config5", 0, 10, 2, False, False)]
+        for name, radix, steps, warmup, fuse, separate in todo:
+            reuse = w if (radix or separate) else None
             if reuse is None and w is not None:
                 w = None
                 gc.collect()
                 torch.cuda.empty_cache()
             try:
                 t0 = time.perf_counter()
-                row = run_other(B, name, radix=radix, steps=steps, warmup=warmup, w=reuse, fuse=fuse)
-                print(f"[bench] {name}{' radix 2' if radix else ''}{' sibling-fused' if fuse else ''}: "
+                row = run_other(B, name, radix=radix, steps=steps, warmup=warmup, w=reuse, fuse=fuse, separate=separate)
+                print(f"[bench] {name}{' radix 2' if radix else ''}{' sibling-fused' if fuse else ''}"
+                      f"{' separate passes' if separate else ''}: "
                       f"{row['ms_per_step']:.4f} ms/step, "
                       f"{row['input_GBps']:.0f} GB/s of input ({time.perf_counter() - t0:.1f} s in all)",
                       file=sys.stderr, flush=True)
             except Exception as exc:  # keep the headline line whatever happens here
                 row = {"workload": name, "error": f"{type(exc).__name__}: {exc}"}
             del reuse
-            if radix:
+            if radix or separate:
                 row["radix"] = radix
                 row["fuse_siblings"] = fuse
+                row["separate_passes"] = separate
             others.append(row)
         line["other_configs"] = others
     print(json.dumps(line), flush=True)

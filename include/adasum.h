@@ -133,6 +133,14 @@ typedef struct adasum_options {
                                   buffer as delta_start (in-place parameter update); any other
                                   overlap is ADASUM_ERR_ALIAS.  A struct_bytes that ends before
                                   this field (the struct as it was without it) reads as NULL. */
+    int32_t  separate_passes;  /* 0 (default): in the tree order, the combine of a pass also leaves the
+                                  Gram matrix of the next pass's group (it handles the sibling groups of
+                                  a tile in one workgroup, one wave each, and the waves exchange what they
+                                  wrote), so that only the first pass reads its operands twice;
+                                  1: every pass makes a reduce pass of its own over its operands (for
+                                  measurements; the result is the same up to rounding).  A struct_bytes
+                                  that ends before this field reads as 0. */
+    int32_t  reserved1;        /* must be 0 */
 } adasum_options;
 
 /*
@@ -170,8 +178,8 @@ ADASUM_API int adasum_reduce_ex(const void* const* grads, int K,
 
 /* Bytes of DEVICE workspace adasum_reduce_ex needs for this problem (intermediate
  * tree nodes, per-tile partial sums, coefficient tables, the compact copy of the
- * small layers).  Depends on dtype, radix, order, fuse_siblings and on whether
- * delta_start is set (any non-NULL value).  Host-only. */
+ * small layers).  Depends on dtype, radix, order, fuse_siblings, separate_passes and on
+ * whether delta_start is set (any non-NULL value).  Host-only. */
 ADASUM_API int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers,
                            int dtype, const adasum_options* opts, size_t* bytes);
 

@@ -53,6 +53,8 @@ class Options(C.Structure):
         ("workspace_bytes", C.c_size_t),
         ("layer_stats", C.c_void_p),
         ("delta_start", C.c_void_p),
+        ("separate_passes", C.c_int32),
+        ("reserved1", C.c_int32),
     ]
 
 
@@ -175,7 +177,7 @@ def _check_inputs(tensors, N):
 def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, out_dtype=None,
                   radix: int = 0, order: int = ORDER_TREE, layer_stats=None, workspace=None,
                   use_graph: bool = False, delta_start=None, stream=None, noalloc: bool = False,
-                  fuse_siblings: bool = False):
+                  fuse_siblings: bool = False, separate_passes: bool = False):
     """Per-layer Adasum tree of ``grads`` (K device tensors of N elements).
     Returns ``out`` (allocated here when None).  With ``delta_start`` (a tensor
     like one of ``grads``) the tensors in ``grads`` are parameters after a local
@@ -200,7 +202,7 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
     ptrs = _ptr_array(grads)
     plain = (out_code == in_code and radix == 0 and order == ORDER_TREE and layer_stats is None
              and workspace is None and not use_graph and delta_start is None and not noalloc
-             and not fuse_siblings)
+             and not fuse_siblings and not separate_passes)
     if plain:
         check(lib.adasum_reduce(ptrs, len(grads), offs, L, in_code, C.c_void_p(out.data_ptr()), _stream(stream)))
         return out
@@ -211,6 +213,7 @@ def adasum_reduce(grads: Sequence, layer_offsets: Sequence[int], out=None, *, ou
     o.order = order
     o.use_graph = 1 if use_graph else 0
     o.fuse_siblings = 1 if fuse_siblings else 0
+    o.separate_passes = 1 if separate_passes else 0
     if workspace is not None:
         o.workspace = workspace.data_ptr()
         o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -235,7 +238,7 @@ class Plan:
 
     def __init__(self, K: int, layer_offsets: Sequence[int], dtype, *, out_dtype=None, radix: int = 0,
                  order: int = ORDER_TREE, use_graph: bool = False, workspace=None, delta: bool = False,
-                 fuse_siblings: bool = False):
+                 fuse_siblings: bool = False, separate_passes: bool = False):
         lib = load()
         offs, L = _offsets(layer_offsets)
         self.K, self.N, self.n_layers = K, int(layer_offsets[-1]), L
@@ -250,6 +253,7 @@ class Plan:
         o.order = order
         o.use_graph = 1 if use_graph else 0
         o.fuse_siblings = 1 if fuse_siblings else 0
+        o.separate_passes = 1 if separate_passes else 0
         if workspace is not None:
             o.workspace = workspace.data_ptr()
             o.workspace_bytes = workspace.numel() * workspace.element_size()
@@ -308,7 +312,7 @@ class Plan:
 
 def adasum_workspace_bytes(K: int, layer_offsets: Sequence[int], dtype_code: int, *, radix: int = 0,
                            out_dtype_code: int = -1, delta: bool = False, order: int = ORDER_TREE,
-                           fuse_siblings: bool = False) -> int:
+                           fuse_siblings: bool = False, separate_passes: bool = False) -> int:
     lib = load()
     offs, L = _offsets(layer_offsets)
     o = Options()
@@ -317,6 +321,7 @@ def adasum_workspace_bytes(K: int, layer_offsets: Sequence[int], dtype_code: int
     o.radix = radix
     o.order = order
     o.fuse_siblings = 1 if fuse_siblings else 0
+    o.separate_passes = 1 if separate_passes else 0
     if delta:
         o.delta_start = 0x100   # only "set or not" matters for the size
     n = C.c_size_t(0)

@@ -54,14 +54,16 @@ struct Opts {
     int order;
     int use_graph;
     int fuse;        // radix 2: sibling pairs combined together, one level ahead
+    int separate;    // every pass makes its own reduce pass (no pass feeds the next)
     void* workspace;
     size_t workspace_bytes;
     double* layer_stats;
     const void* delta_start;
 };
 
-// adasum_options as it was before delta_start was appended: still accepted.
+// adasum_options as it was before delta_start, and before separate_passes, were appended: still accepted.
 constexpr uint32_t kOptionsBytesV1 = offsetof(adasum_options, delta_start);
+constexpr uint32_t kOptionsBytesV2 = offsetof(adasum_options, separate_passes);
 
 int read_opts(const adasum_options* o, int dtype, Opts& r) {
     r.dtype = dtype;
@@ -70,13 +72,18 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
     r.order = ADASUM_ORDER_TREE;
     r.use_graph = 0;
     r.fuse = 0;
+    r.separate = 0;
     r.workspace = nullptr;
     r.workspace_bytes = 0;
     r.layer_stats = nullptr;
     r.delta_start = nullptr;
     if (o != nullptr) {
         if (o->struct_bytes < kOptionsBytesV1) return ADASUM_ERR_INVALID_ARG;
-        if (o->struct_bytes >= sizeof(adasum_options)) r.delta_start = o->delta_start;
+        if (o->struct_bytes >= kOptionsBytesV2) r.delta_start = o->delta_start;
+        if (o->struct_bytes >= sizeof(adasum_options)) {
+            if (o->reserved1 != 0) return ADASUM_ERR_INVALID_ARG;
+            r.separate = o->separate_passes != 0;
+        }
         if (o->out_dtype >= 0) r.out_dtype = o->out_dtype;
         r.radix = o->radix;
         r.order = o->order;
@@ -180,6 +187,9 @@ struct Plan {
     // plans (and workspaces) of their own
     int in_dtype = -1, out_dtype = -1, delta = 0;
     int fuse = 0;                         // laid out for the sibling-fused radix-2 schedule
+    int separate = 0;                     // cache key: made with separate_passes
+    int feed = 0;                         // passes leave the next pass's Gram entries where they can
+                                          // (pass_feeds_next): tree order, no delta form, no fuse
     std::vector<int64_t> offsets;
     TileTable gram_tiles;                 // capacity kTile
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
@@ -254,7 +264,14 @@ std::vector<std::unique_ptr<Plan>> g_plans;   // least recently used first
 constexpr size_t kMaxPlans = 64;
 
 // Builds a plan (host tables, their device copies; no workspace yet) on the current device.
-int make_plan(int K, int radix, int order, int node_type, bool fuse, const int64_t* offsets, int n_layers,
+// Radix whose combine tile table pass lv uses: a pass that feeds the next one works with one wave per
+// group, like radix 16.
+int table_radix(bool feed, const std::vector<int>& radices, size_t lv) {
+    return feed && pass_feeds_next(radices, lv) ? 16 : radices[lv];
+}
+
+// `no_feed`: the delta form, the step plans and separate_passes: no pass feeds the next.
+int make_plan(int K, int radix, int order, int node_type, bool fuse, bool no_feed, const int64_t* offsets, int n_layers,
               std::unique_ptr<Plan>& out) {
     int device = 0;
     ADASUM_HIP(hipGetDevice(&device));
@@ -267,6 +284,7 @@ int make_plan(int K, int radix, int order, int node_type, bool fuse, const int64
         p->order = order;
         p->node_type = node_type;
         p->fuse = fuse ? 1 : 0;
+        p->feed = (order == ADASUM_ORDER_TREE && !fuse && !no_feed) ? 1 : 0;
         p->offsets.assign(offsets, offsets + n_layers + 1);
         p->gram_tiles.capacity = gram_tile_capacity(offsets, n_layers);
         build_tiles(offsets, n_layers, p->gram_tiles.capacity, p->gram_tiles.tiles, p->gram_tiles.layer_begin);
@@ -279,7 +297,9 @@ int make_plan(int K, int radix, int order, int node_type, bool fuse, const int64
         p->lay = make_layout(Kv, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
                              norm_entries_bound(Kv, offsets, n_layers, p->radices, node_type), p->radices, order,
                              K + 1, small_elems, node_type,
-                             fuse ? dot_entries_bound(Kv, offsets, n_layers, p->radices, node_type) : 0);
+                             fuse      ? dot_entries_bound(Kv, offsets, n_layers, p->radices, node_type)
+                             : p->feed ? next_entries_bound(Kv, offsets, n_layers, p->radices, node_type)
+                                       : 0);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
@@ -299,7 +319,7 @@ int make_plan(int K, int radix, int order, int node_type, bool fuse, const int64
 // The library's own cache of plans, keyed by shape.
 // `order` is a tree order or kStepPlans (the step entry points keep plans of their own).
 constexpr int kStepPlans = 100;
-int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, bool delta, bool fuse,
+int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, bool delta, bool fuse, bool separate,
                       const int64_t* offsets, int n_layers, Plan** out) {
     const int node_type = node_dtype(in_dtype);
     int device = 0;
@@ -308,7 +328,7 @@ int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, 
         Plan* p = g_plans[i].get();
         if (p->device == device && p->K == K && p->radix == radix && p->order == order && p->node_type == node_type &&
             p->in_dtype == in_dtype && p->out_dtype == out_dtype && p->delta == (delta ? 1 : 0) &&
-            p->fuse == (fuse ? 1 : 0) &&
+            p->fuse == (fuse ? 1 : 0) && p->separate == (separate ? 1 : 0) &&
             static_cast<int>(p->offsets.size()) == n_layers + 1 &&
             std::memcmp(p->offsets.data(), offsets, sizeof(int64_t) * (n_layers + 1)) == 0) {
             // most recently used last
@@ -320,13 +340,14 @@ int find_or_make_plan(int K, int radix, int order, int in_dtype, int out_dtype, 
     // a bounded cache: the least recently used plan goes (hipFree waits for work in flight)
     while (g_plans.size() >= kMaxPlans) g_plans.erase(g_plans.begin());
     std::unique_ptr<Plan> p;
-    const int rc = make_plan(K, radix, order == kStepPlans ? ADASUM_ORDER_TREE : order, node_type, fuse, offsets,
-                             n_layers, p);
+    const int rc = make_plan(K, radix, order == kStepPlans ? ADASUM_ORDER_TREE : order, node_type, fuse,
+                             delta || separate || order == kStepPlans, offsets, n_layers, p);
     if (rc != ADASUM_OK) return rc;
     p->order = order;
     p->in_dtype = in_dtype;
     p->out_dtype = out_dtype;
     p->delta = delta ? 1 : 0;
+    p->separate = separate ? 1 : 0;
     *out = p.get();
     g_plans.push_back(std::move(p));
     return ADASUM_OK;
@@ -494,6 +515,10 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     // dot products the next level needs
     const bool fuse = o.fuse != 0 && p->fuse != 0;
     bool dots_ready = false;   // the previous combine left this level's dot products
+    // passes that feed the next one: the combine leaves the next pass's whole Gram matrix per tile
+    const bool feed = p->feed != 0 && !fuse && o.delta_start == nullptr;
+    double* nextparts = dotparts;   // (the two schemes exclude each other and share the section)
+    bool fed = false;          // the previous combine left this level's Gram entries
 
     int nodes = virtual_leaves(p->radices);   // tree nodes alive before this pass (leaves: padded count)
     const int depth0 = first_depth(p->radices);   // the first pass's groups are the sub-trees of this depth
@@ -504,7 +529,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     // nothing below may allocate, so the ladder can be captured into a graph.
     std::vector<TileSet> comb_sets(n_levels);
     for (int lv = 0; lv < n_levels; ++lv) {
-        const int rc = p->comb_tiles(lv == 0 ? dtype : node_dtype(dtype), p->radices[lv], &comb_sets[lv]);
+        const int rc = p->comb_tiles(lv == 0 ? dtype : node_dtype(dtype), table_radix(feed, p->radices, lv),
+                                     &comb_sets[lv]);
         if (rc != ADASUM_OK) return rc;
     }
     {
@@ -560,7 +586,13 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
 
         // step 1: partial Gram entries -- from a pass over the operands, or (sibling-fused) already
         // left per combine tile by the combine that wrote them: one entry per pair, summed per Gram tile
-        if (dots_ready) {
+        const bool feeds = feed && pass_feeds_next(p->radices, static_cast<size_t>(lv));
+        if (fed) {
+            // whole Gram matrices per combine tile, left by the combine below us: sum them per Gram tile
+            ADASUM_TIMED("gram_from_combine", 0.0, stream,
+                         launch_parts_coarsen(nextparts, groups, gram_entries(R, true), norm_tiles, gt, partials,
+                                              stream));
+        } else if (dots_ready) {
             ADASUM_TIMED("dot_coarsen", 0.0, stream,
                          launch_norm_coarsen(dotparts, groups, norm_tiles, gt, partials, stream));
         } else {
@@ -576,14 +608,14 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         }
         const bool fuse_here = fuse && R == 2 && !last && groups % 2 == 0;
         // step 2: finish the sums, then the tree's scalars
-        if (!first) {
+        if (!first && !fed) {
             ADASUM_TIMED("norm_coarsen", 0.0, stream,
                          launch_norm_coarsen(normparts, nodes, norm_tiles, gt, normcoarse, stream));
         }
-        // (the tree's weights come out of the same launch)
-        kernel_name("gram_finish", 0, 0, R, first, namebuf, sizeof(namebuf));
+        // (the tree's weights come out of the same launch; a fed pass has its diagonal in the partials)
+        kernel_name("gram_finish", 0, 0, R, first || fed, namebuf, sizeof(namebuf));
         ADASUM_TIMED(namebuf, 0.0, stream,
-                     launch_gram_finish(first, gt, L, groups, R, partials, normcoarse, gram, weights, o.order,
+                     launch_gram_finish(first || fed, gt, L, groups, R, partials, normcoarse, gram, weights, o.order,
                                         first ? p->K : 0, depth0, stream));
         if (first && o.layer_stats != nullptr) {
             ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, p->K, depth0, 0, false, o.layer_stats + 1, 2, stream));
@@ -604,6 +636,19 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                 outs.slot_bytes = slot_bytes;
                 outs.stride = ostride;
             }
+            if (feeds) {
+                const int R2 = p->radices[lv + 1];
+                char base[40];
+                kernel_name("combine", in_dtype, st_dtype, R, false, base, sizeof(base));
+                std::snprintf(namebuf, sizeof(namebuf), "%s+gram%d", base, R2);
+                ADASUM_TIMED(namebuf, comb_bytes(real_leaves(g0, ng), ng), stream,
+                             launch_combine_feed(in_dtype, st_dtype, ops, outs, ct, L, ng, R, R2,
+                                                 weights + static_cast<int64_t>(g0) * L * R,
+                                                 nextparts + static_cast<int64_t>(g0 / R2) * ct.n_tiles *
+                                                                 gram_entries(R2, true),
+                                                 stream));
+                continue;
+            }
             if (fuse_here) {
                 char base[40];
                 kernel_name("combine", in_dtype, st_dtype, R, false, base, sizeof(base));
@@ -623,6 +668,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                                         sub_in, add_out, stream));
         }
         dots_ready = fuse_here;
+        fed = feeds;
         stride = first ? 1 : R * stride;
         nodes = groups;
         norm_tiles = ct;
@@ -768,7 +814,7 @@ int prebuild_tables(Plan* p, int dtype, int order) {
         TileSet ct;
         // (the left-to-right order reads leaves, in their storage type, in every pass)
         const bool leaves = lv == 0 || order == ADASUM_ORDER_LINEAR;
-        const int rc = p->comb_tiles(leaves ? dtype : node_dtype(dtype), p->radices[lv], &ct);
+        const int rc = p->comb_tiles(leaves ? dtype : node_dtype(dtype), table_radix(p->feed != 0, p->radices, lv), &ct);
         if (rc != ADASUM_OK) return rc;
     }
     return ADASUM_OK;
@@ -934,7 +980,7 @@ int reduce_impl(const void* const* grads, int K, const int64_t* layer_offsets, i
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
     rc = find_or_make_plan(K, o.radix == 0 ? default_radix(o) : o.radix, o.order, dtype, o.out_dtype,
-                           o.delta_start != nullptr, o.fuse != 0, layer_offsets, n_layers, &p);
+                           o.delta_start != nullptr, o.fuse != 0, o.separate != 0, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     return execute_plan(p, grads, dtype, out, o, stream);
 }
@@ -1000,15 +1046,19 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
         gcap = gram_tile_capacity(layer_offsets, L);
         n_gram = count_tiles(layer_offsets, L, gcap);
         plan.fuse = o.fuse;
+        plan.feed = (o.order == ADASUM_ORDER_TREE && !o.fuse && !o.separate && o.delta_start == nullptr) ? 1 : 0;
         plan.lay = make_layout(Kv, N, L, n_gram, norm_entries_bound(Kv, layer_offsets, L, plan.radices, node_type),
                                plan.radices, o.order, K + 1, small_elems, node_type,
-                               o.fuse ? dot_entries_bound(Kv, layer_offsets, L, plan.radices, node_type) : 0);
+                               o.fuse      ? dot_entries_bound(Kv, layer_offsets, L, plan.radices, node_type)
+                               : plan.feed ? next_entries_bound(Kv, layer_offsets, L, plan.radices, node_type)
+                                           : 0);
         // the combine tables this reduction reads: one per distinct tile capacity
         std::vector<int> caps;
         if (K == 1) caps.push_back(combine_tile_capacity(dtype, 1));
         for (size_t lv = 0; lv < plan.radices.size(); ++lv) {
             const bool leaves = lv == 0 || o.order == ADASUM_ORDER_LINEAR;
-            caps.push_back(combine_tile_capacity(leaves ? dtype : node_type, plan.radices[lv]));
+            caps.push_back(combine_tile_capacity(leaves ? dtype : node_type,
+                                                 table_radix(plan.feed != 0, plan.radices, lv)));
         }
         off_offsets = carve.take(sizeof(int64_t) * (static_cast<size_t>(L) + 1));
         off_gram_tiles = carve.take(sizeof(adasum_tile) * static_cast<size_t>(n_gram));
@@ -1116,7 +1166,8 @@ int adasum_plan_create(int K, const int64_t* layer_offsets, int n_layers, int dt
     h->opts.radix = o.radix == 0 ? default_radix(o) : o.radix;
     h->opts.delta_start = nullptr;
     if (layer_offsets[n_layers] > 0) {
-        rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), o.fuse != 0, layer_offsets, n_layers, h->plan);
+        rc = make_plan(K, h->opts.radix, o.order, node_dtype(dtype), o.fuse != 0, h->for_delta || o.separate != 0,
+                       layer_offsets, n_layers, h->plan);
         if (rc != ADASUM_OK) return rc;
         if (o.workspace != nullptr && o.workspace_bytes < h->plan->lay.total) return ADASUM_ERR_WORKSPACE;
         // everything execute needs exists from here on: it allocates nothing
@@ -1200,7 +1251,9 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
                                        norm_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype)),
                                        radices, o.order, K + 1, small_elems, node_dtype(dtype),
                                        o.fuse ? dot_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype))
-                                              : 0);
+                                       : (o.order == ADASUM_ORDER_TREE && !o.separate && o.delta_start == nullptr)
+                                           ? next_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype))
+                                           : 0);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -1225,7 +1278,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     if (n_layers == 0) return ADASUM_OK;
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, false, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, false, false, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;
@@ -1278,7 +1331,7 @@ int adasum_group_combine(const void* const* x, int R, const int64_t* layer_offse
     }
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* p = nullptr;
-    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, false, layer_offsets, n_layers, &p);
+    rc = find_or_make_plan(R, R, kStepPlans, dtype, dtype, false, false, false, layer_offsets, n_layers, &p);
     if (rc != ADASUM_OK) return rc;
     Opts o{};
     char* ws = nullptr;

@@ -107,6 +107,18 @@ inline int first_depth(const std::vector<int>& radices) {
 // leaves fill.  E.g. K = 64, radix 16 -> {16, 16, 16, 16, 4}.
 int build_linear_passes(int K, int radix, std::vector<int>& passes);
 
+// A pass of the tree order can leave the next pass's Gram entries itself: its combine then takes
+// the radices[lv + 1] sibling groups of a tile in one workgroup (one wave per group), the waves
+// exchange what they wrote through LDS, and the squared norms and dot products of those nodes --
+// the whole Gram matrix of the next pass's group -- go out per tile, so the next pass makes no
+// reduce pass of its own.  Possible when the operand pointers of the sibling groups fit one launch.
+inline bool pass_feeds_next(const std::vector<int>& radices, size_t lv) {
+    return lv + 1 < radices.size() && radices[lv] * radices[lv + 1] <= kMaxPack;
+}
+// Lanes per group in such a combine (one wave), hence its tile capacity.
+constexpr int kFeedLanes = 64;
+inline int feed_tile_capacity(int dtype) { return kFeedLanes * (16 / elem_bytes(dtype)); }
+
 // Number of Gram entries a pass of radix R accumulates per tile: all pairs
 // i < j, plus the R diagonal entries when `diag` (the first pass; later passes
 // get their squared norms from the previous combine).
@@ -161,6 +173,10 @@ struct Layout {
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices, int order = ADASUM_ORDER_TREE, int64_t small_rows = 0,
                    int64_t small_elems = 0, int node_type = ADASUM_F32, int64_t dot_entries = 0);
+// Doubles the passes that feed the next one (pass_feeds_next) need for the Gram entries they leave:
+// the most any of them writes, next pass's groups x combine tiles x entries of a full Gram matrix.
+int64_t next_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
+                           int node_type = ADASUM_F32);
 // Doubles a sibling-fused radix-2 schedule needs for the dot products its combines leave: the most
 // any level but the last writes, pairs of groups x combine tiles of that level.
 int64_t dot_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
@@ -237,6 +253,18 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
 int launch_combine_siblings(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
                             int n_layers, int n_groups, const double* weights, double* normparts, double* dotparts,
                             void* stream);
+// Step 3 of a pass that feeds the next one (pass_feeds_next): workgroup (tile, s) combines the R2
+// sibling groups s * R2 .. s * R2 + R2 - 1 of the tile, one wave each, and leaves the full Gram
+// matrix of the nodes it wrote: nextparts[(s * ct.n_tiles + tile) * NP2 + entry], entries in the
+// Gram pass's order with the diagonal, NP2 = R2 (R2 + 1) / 2.  n_groups must be a multiple of R2
+// and n_groups * R at most kMaxPack; `ct` the table of capacity feed_tile_capacity(dtype).
+int launch_combine_feed(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                        int n_layers, int n_groups, int R, int R2, const double* weights, double* nextparts,
+                        void* stream);
+// coarse[(s * gt.n_tiles + t) * NP + e] = sum of fine[(s * ct.n_tiles + c) * NP + e] over the combine
+// tiles c inside Gram tile t (the rows are whole sets of NP Gram entries).
+int launch_parts_coarsen(const double* fine, int n_rows, int NP, const TileSet& ct, const TileSet& gt,
+                         double* coarse, void* stream);
 // Steps 1 and 3 for one group whose operand 0 is stored as fp32 while operands 1..R-1 are
 // 16-bit (`dtype`): the running result of the left-to-right order folded with the next leaves.
 // Always the full Gram matrix (diagonal included); tiles as for `dtype`.

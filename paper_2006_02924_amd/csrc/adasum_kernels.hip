@@ -970,6 +970,134 @@ combine_siblings_kernel(const Operands ops, const Outputs outs, const adasum_til
 }
 
 // ---------------------------------------------------------------------------
+// Step 3 of a pass that feeds the next one.  Workgroup (tile, s) has R2 waves; wave w combines
+// group s * R2 + w for the tile exactly as combine_kernel does (one 16-byte load per lane and
+// operand, fp64 edges), then the waves put what they wrote into LDS and wave w forms, for every
+// sibling b >= w, the dot product of its node with b's over the tile (b = w: the squared norm).
+// Those R2 (R2 + 1) / 2 sums are the tile's share of the next pass's Gram matrix, in the Gram
+// pass's entry order: nextparts[(s * n_tiles + tile) * NP2 + entry].  The next pass starts from
+// them and reads its operands only once, in its own combine.
+// ---------------------------------------------------------------------------
+template <typename TI, typename TO, int R, int R2>
+__global__ void __launch_bounds__(kFeedLanes * R2)
+combine_feed_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles, int n_tiles,
+                    int n_layers, const double* __restrict__ weights, double* __restrict__ nextparts) {
+    constexpr int G = 16 / (int)sizeof(TI);
+    constexpr int NP2 = R2 * (R2 + 1) / 2;
+    typedef typename Traits<TI>::acc_t acc_t;
+    typedef typename Traits<TO>::acc_t out_acc_t;
+    static_assert(std::is_same<acc_t, out_acc_t>::value, "the nodes of a pass that is not the last have the node type");
+    constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);   // as combine_kernel
+
+    const int lane = threadIdx.x & 63;
+    // the wave's number, as a scalar: the group's operand pointers and weights then live in scalar
+    // registers, as in combine_kernel (60 vector registers fewer, one more wave per SIMD)
+    const int w = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    const unsigned v = blockIdx.x;
+    const int tile_id = static_cast<int>(v % static_cast<unsigned>(n_tiles));
+    const int super = static_cast<int>(v / static_cast<unsigned>(n_tiles));
+    const int g = super * R2 + w;
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
+
+    const TI* x[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
+    TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
+
+    const long long idx = s.bs + static_cast<long long>(lane) * G;
+    Granule<TI, G> raw[R];
+    if (lane < s.ng) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+    }
+    double wd[R];
+    acc_t wt[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        wd[r] = weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r];
+        wt[r] = static_cast<acc_t>(wd[r]);
+    }
+
+    __shared__ acc_t sh[R2][G][kFeedLanes];
+    __shared__ double sh_edge[R2][kFeedLanes];
+    acc_t z[G];
+#pragma unroll
+    for (int k = 0; k < G; ++k) z[k] = 0;
+    if (lane < s.ng) {
+        {
+            acc_t a[G];
+            unpack(raw[0], a);
+#pragma unroll
+            for (int k = 0; k < G; ++k) z[k] = wt[0] * a[k];
+        }
+#pragma unroll
+        for (int r = 1; r < R; ++r) {
+            acc_t a[G];
+            unpack(raw[r], a);
+#pragma unroll
+            for (int k = 0; k < G; ++k) z[k] = fma_t(wt[r], a[k], z[k]);
+        }
+        store_granule<NTS>(out + idx, z);
+    }
+#pragma unroll
+    for (int k = 0; k < G; ++k) sh[w][k][lane] = z[k];
+
+    // ragged head/tail elements: fp64 arithmetic, one rounding at the store; the stored value goes
+    // into the sums
+    const int nedge = s.nh + s.nt;
+    double ze = 0.0;
+    if (nedge > 0) {
+        if (lane < nedge) {
+            const long long e = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
+            double acc = wd[0] * static_cast<double>(load_elem(x[0] + e));
+#pragma unroll
+            for (int r = 1; r < R; ++r) acc = __builtin_fma(wd[r], static_cast<double>(load_elem(x[r] + e)), acc);
+            const out_acc_t stored = static_cast<out_acc_t>(acc);
+            store_elem(out + e, stored);
+            ze = static_cast<double>(stored);
+        }
+        sh_edge[w][lane] = ze;
+    }
+    __syncthreads();
+
+    // entry (i, j), i <= j, of the Gram pass's order with the diagonal: i * R2 - i (i - 1) / 2 + (j - i)
+    double* dst = nextparts + (static_cast<long long>(super) * n_tiles + tile_id) * NP2 + (w * R2 - w * (w - 1) / 2);
+    for (int b = w; b < R2; ++b) {
+        acc_t acc = 0;
+#pragma unroll
+        for (int k = 0; k < G; ++k) acc = fma_t(z[k], sh[b][k][lane], acc);
+        double tot = static_cast<double>(wave_sum(acc));
+        if (nedge > 0) tot += wave_sum(ze * sh_edge[b][lane]);
+        if (lane == 0) dst[b - w] = tot;
+    }
+}
+
+// rows of NP Gram entries per combine tile -> per Gram tile.  One wave per (row set, Gram tile); lane e
+// (and e + 64, ...) sums entry e over the combine tiles of the Gram tile in table order.
+__global__ void __launch_bounds__(64)
+parts_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles, const int32_t* __restrict__ first_in_gram,
+                     int n_gram_tiles, int NP, double* __restrict__ coarse) {
+    const int t = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_gram_tiles));
+    const int row = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_gram_tiles));
+    const int b = first_in_gram[t], e = first_in_gram[t + 1];
+    const double* src = fine + static_cast<long long>(row) * n_fine_tiles * NP;
+    double* dst = coarse + (static_cast<long long>(row) * n_gram_tiles + t) * NP;
+    for (int q = threadIdx.x; q < NP; q += 64) {
+        double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;   // four chains so that loads overlap; fixed order
+        int i = b;
+        for (; i + 4 <= e; i += 4) {
+            v0 += src[static_cast<long long>(i) * NP + q];
+            v1 += src[static_cast<long long>(i + 1) * NP + q];
+            v2 += src[static_cast<long long>(i + 2) * NP + q];
+            v3 += src[static_cast<long long>(i + 3) * NP + q];
+        }
+        for (; i < e; ++i) v0 += src[static_cast<long long>(i) * NP + q];
+        dst[q] = (v0 + v1) + (v2 + v3);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Small layers (at most kSmallLayer elements), by the definition itself: the
 // operator of Section 3 applied pair by pair over all K workers in fp64, in the
 // order of Section 3.4's recursion, nothing stored in between.
@@ -1409,7 +1537,77 @@ int launch_combine_siblings_t(const Operands& ops, const Outputs& outs, const Ti
     return check_launch();
 }
 
+template <typename TI, typename TO, int R>
+int launch_combine_feed_r(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
+                          int R2, const double* weights, double* nextparts, hipStream_t st) {
+    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups / R2);
+    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(blocks));
+    const int nt = static_cast<int>(ct.n_tiles);
+#define ADASUM_FEED(RR2)                                                                                   \
+    hipLaunchKernelGGL((combine_feed_kernel<TI, TO, R, RR2>), grid, dim3(kFeedLanes * RR2), 0, st, ops, outs, \
+                       ct.tiles, nt, n_layers, weights, nextparts)
+    switch (R2) {
+        case 2: ADASUM_FEED(2); break;
+        case 4: ADASUM_FEED(4); break;
+        case 8: ADASUM_FEED(8); break;
+        case 16:
+            if constexpr (R * 16 <= kMaxPack) ADASUM_FEED(16);
+            else return static_cast<int>(hipErrorInvalidValue);
+            break;
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+#undef ADASUM_FEED
+    return check_launch();
+}
+
+template <typename TI, typename TO>
+int launch_combine_feed_t(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
+                          int R, int R2, const double* weights, double* nextparts, hipStream_t st) {
+    switch (R) {
+        case 2: return launch_combine_feed_r<TI, TO, 2>(ops, outs, ct, n_layers, n_groups, R2, weights, nextparts, st);
+        case 4: return launch_combine_feed_r<TI, TO, 4>(ops, outs, ct, n_layers, n_groups, R2, weights, nextparts, st);
+        case 8: return launch_combine_feed_r<TI, TO, 8>(ops, outs, ct, n_layers, n_groups, R2, weights, nextparts, st);
+        case 16:
+            if constexpr (std::is_same<TI, double>::value) return static_cast<int>(hipErrorInvalidValue);
+            else return launch_combine_feed_r<TI, TO, 16>(ops, outs, ct, n_layers, n_groups, R2, weights, nextparts, st);
+        default: return static_cast<int>(hipErrorInvalidValue);
+    }
+}
+
 }  // namespace
+
+int launch_combine_feed(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
+                        int n_layers, int n_groups, int R, int R2, const double* weights, double* nextparts,
+                        void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (ct.n_tiles == 0 || n_groups == 0) return 0;
+    if (R2 < 2 || n_groups % R2 != 0 || n_groups * R > kMaxPack || weights == nullptr || nextparts == nullptr ||
+        ct.capacity != feed_tile_capacity(dtype))
+        return static_cast<int>(hipErrorInvalidValue);
+    // the nodes such a pass writes are never the root: always the node type of the input
+    if (dtype == ADASUM_F64 && out_dtype == ADASUM_F64)
+        return launch_combine_feed_t<double, double>(ops, out, ct, n_layers, n_groups, R, R2, weights, nextparts, st);
+    if (out_dtype != ADASUM_F32) return static_cast<int>(hipErrorInvalidValue);
+    if (dtype == ADASUM_BF16)
+        return launch_combine_feed_t<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, R2, weights, nextparts, st);
+    if (dtype == ADASUM_F16)
+        return launch_combine_feed_t<f16_t, float>(ops, out, ct, n_layers, n_groups, R, R2, weights, nextparts, st);
+    if (dtype == ADASUM_F32)
+        return launch_combine_feed_t<float, float>(ops, out, ct, n_layers, n_groups, R, R2, weights, nextparts, st);
+    return static_cast<int>(hipErrorInvalidValue);
+}
+
+int launch_parts_coarsen(const double* fine, int n_rows, int NP, const TileSet& ct, const TileSet& gt, double* coarse,
+                         void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const long long blocks = static_cast<long long>(n_rows) * gt.n_tiles;
+    if (blocks == 0) return 0;
+    if (!grid_fits(blocks) || ct.first_in_gram == nullptr || NP < 1) return static_cast<int>(hipErrorInvalidConfiguration);
+    hipLaunchKernelGGL(parts_coarsen_kernel, dim3(static_cast<unsigned>(blocks)), dim3(64), 0, st, fine,
+                       static_cast<int>(ct.n_tiles), ct.first_in_gram, static_cast<int>(gt.n_tiles), NP, coarse);
+    return check_launch();
+}
 
 int launch_combine_siblings(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
                             int n_layers, int n_groups, const double* weights, double* normparts, double* dotparts,

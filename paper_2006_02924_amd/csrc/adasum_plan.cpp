@@ -131,6 +131,21 @@ int64_t norm_entries_bound(int K, const int64_t* layer_offsets, int n_layers, co
     return need;
 }
 
+int64_t next_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
+                           int node_type) {
+    int64_t need = 0;
+    int groups = K;
+    for (size_t lv = 0; lv + 1 < radices.size(); ++lv) {
+        groups /= radices[lv];
+        if (!pass_feeds_next(radices, lv)) continue;
+        const int R2 = radices[lv + 1];
+        // the widest storage type a pass may read gives its finest table
+        const int64_t t = count_tiles(layer_offsets, n_layers, feed_tile_capacity(node_type));
+        need = std::max<int64_t>(need, static_cast<int64_t>(groups / R2) * t * gram_entries(R2, true));
+    }
+    return need;
+}
+
 int64_t dot_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
                           int node_type) {
     int64_t need = 0;
@@ -166,7 +181,8 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
     for (size_t lv = 0; lv < radices.size(); ++lv) {
         const int R = radices[lv];
         groups = order == ADASUM_ORDER_LINEAR ? 1 : groups / R;
-        const size_t np = static_cast<size_t>(gram_entries(R, lv == 0 || order == ADASUM_ORDER_LINEAR));
+        // (with the diagonal: a pass fed by the combine below it finds its whole matrix in the partials)
+        const size_t np = static_cast<size_t>(gram_entries(R, true));
         max_partials = std::max(max_partials, static_cast<size_t>(groups) * np * static_cast<size_t>(n_tiles));
         max_gram = std::max(max_gram, static_cast<size_t>(groups) * n_layers * R * R);
         max_weights = std::max(max_weights, static_cast<size_t>(groups) * n_layers * R);

@@ -2,6 +2,7 @@
 // layout) over seeded random inputs and checks its invariants.  Built by
 // tests/test_host_sanitizers_cpu.py with AddressSanitizer and UndefinedBehaviorSanitizer on
 // the CPU; exits non-zero on the first violated invariant (the sanitizers abort on their own).
+#include <algorithm>
 #include <cinttypes>
 #include <cstdio>
 #include <cstdlib>
@@ -97,12 +98,25 @@ static void check_schedule(int K, int radix, int order, const std::vector<int64_
     CHECK(gcap == kTile || gcap == kTileSmall);
     const int64_t n_tiles = count_tiles(offs.data(), L, gcap);
     const int64_t ne = norm_entries_bound(Kv, offs.data(), L, radices, node_type);
-    const int64_t de = order == ADASUM_ORDER_TREE ? dot_entries_bound(Kv, offs.data(), L, radices, node_type) : 0;
+    // (room for what the combines leave for the pass above: the larger of the two schemes)
+    int64_t de = 0;
+    if (order == ADASUM_ORDER_TREE) {
+        de = std::max(dot_entries_bound(Kv, offs.data(), L, radices, node_type),
+                      next_entries_bound(Kv, offs.data(), L, radices, node_type));
+        int g = Kv;
+        for (size_t lv = 0; lv + 1 < radices.size(); ++lv) {
+            g /= radices[lv];
+            if (!pass_feeds_next(radices, lv)) continue;
+            CHECK(radices[lv] * radices[lv + 1] <= kMaxPack && g % radices[lv + 1] == 0);
+            const int in = lv == 0 ? dtype : node_type;
+            const int64_t ct = count_tiles(offs.data(), L, feed_tile_capacity(in));
+            CHECK(static_cast<int64_t>(g / radices[lv + 1]) * ct * gram_entries(radices[lv + 1], true) <= de);
+        }
+    }
     const Layout lay = make_layout(Kv, offs[L], L, n_tiles, ne, radices, order, K + 1, small_elems, node_type, de);
     const size_t sections[] = {lay.off_slots, lay.off_partials, lay.off_normparts, lay.off_normcoarse, lay.off_gram,
                                lay.off_weights, lay.off_leafnorm, lay.off_small, lay.off_dotparts, lay.total};
     CHECK(lay.total - lay.off_dotparts >= static_cast<size_t>(de) * sizeof(double));
-    CHECK(de <= ne);
     for (size_t i = 0; i + 1 < sizeof(sections) / sizeof(sections[0]); ++i) {
         CHECK(sections[i] % 256 == 0 && sections[i] <= sections[i + 1]);
     }

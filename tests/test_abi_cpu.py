@@ -126,10 +126,15 @@ def test_sibling_fusion_option_validation(lib):
     assert _call_reduce(lib, good, 4, offs, B.F32, 0x9000, _opts(radix=2, fuse_siblings=1, delta_start=0x5000)) \
         == B.ERR_UNSUPPORTED
     big = [0, 70632]
-    plain = B.adasum_workspace_bytes(16, big, B.F32, radix=2)
+    # the delta form leaves nothing for the pass above (no such extra section): the size to compare with
+    bare = B.adasum_workspace_bytes(16, big, B.F32, radix=2, delta=True)
     fused = B.adasum_workspace_bytes(16, big, B.F32, radix=2, fuse_siblings=True)
     # 4 pairs of groups x 69 combine tiles of 1024 elements, one double each
-    assert plain < fused <= plain + 4 * 70 * 8 + 256
+    assert bare < fused <= bare + 4 * 70 * 8 + 256
+    # plain radix 2: every pass but the last leaves the next one's 2 x 2 Gram matrix (3 entries) per
+    # 256-element combine tile: 4 next-pass groups x 276 tiles x 3 doubles
+    plain = B.adasum_workspace_bytes(16, big, B.F32, radix=2)
+    assert bare + 4 * 276 * 3 * 8 <= plain <= bare + 4 * 277 * 3 * 8 + 256
     # a single pair has no level above its first: nothing to leave
     assert B.adasum_workspace_bytes(2, big, B.F32, radix=2, fuse_siblings=True) == B.adasum_workspace_bytes(2, big, B.F32, radix=2)
 
@@ -164,6 +169,14 @@ def test_delta_options_validation(lib):
     old = _opts(delta_start=0x5004)
     old.struct_bytes = B.Options.delta_start.offset
     assert _call_reduce(lib, good, 2, [0], B.F32, 0x9000, old) == B.OK
+    # ... and one that ends before separate_passes (the layout with delta_start but without it) reads it as 0
+    mid = _opts(delta_start=0x5004, separate_passes=1, reserved1=7)
+    mid.struct_bytes = B.Options.separate_passes.offset
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, mid) == B.ERR_MISALIGNED   # delta_start is read
+    assert _call_reduce(lib, good, 2, offs, B.F32, 0x9000, _opts(reserved1=1)) == B.ERR_INVALID_ARG
+    # every pass reducing its own operands needs no room for what a combine leaves the next pass
+    big4 = [0, 70632]
+    assert B.adasum_workspace_bytes(64, big4, B.BF16, separate_passes=True) < B.adasum_workspace_bytes(64, big4, B.BF16)
     # the delta form defaults to radix 8: K = 16 takes two passes and needs intermediate nodes
     big = [0, 70632]
     assert B.adasum_workspace_bytes(16, big, B.F32, delta=True) > B.adasum_workspace_bytes(16, big, B.F32) + 70632 * 4
