@@ -101,7 +101,15 @@ typedef struct adasum_options {
                                   4 / 8 / 16 = two / three / four levels per pass (the pass
                                   computes the group's Gram matrix, the tree's scalars follow
                                   from it);
-                                  0 = library default.  The result is the same binary tree. */
+                                  32 / 64 = five / six levels in the first pass, for bf16 and fp16
+                                  inputs in ADASUM_ORDER_TREE without delta_start (else
+                                  ADASUM_ERR_UNSUPPORTED): with 528 or 2080 entries per group the
+                                  Gram matrix is a dense contraction X X^T and is computed on the
+                                  matrix cores (exact 16-bit products, fp32 sums of 64 or 128 of
+                                  them, fp64 above); K = 64 is then a single pass.  Later passes,
+                                  over fp32 nodes, stay at 16 or less;
+                                  0 = library default (16; 8 for fp64 and the delta form).
+                                  The result is the same binary tree. */
     int32_t  order;            /* ADASUM_ORDER_TREE (default) | ADASUM_ORDER_LINEAR */
     int32_t  use_graph;        /* 1 = replay the level ladder as one hipGraph launch: captured
                                   once per distinct set of buffers (grads, out, workspace,
@@ -249,7 +257,7 @@ ADASUM_API int adasum_reduce_noalloc(const void* const* grads, int K,
  * operands, G[i][j] = x_i . x_j (the pair case R = 2 is the triple
  * [a.b, a.a, b.b]).
  *   x      HOST array of R DEVICE pointers (N elements of `dtype` each)
- *   R      2, 4, 8 or 16
+ *   R      2, 4, 8 or 16 (fp64: up to 8); 32 or 64 for bf16 and fp16 operands
  *   gram   DEVICE, n_layers x R x R doubles, row-major per layer, symmetric
  */
 ADASUM_API int adasum_group_gram(const void* const* x, int R,

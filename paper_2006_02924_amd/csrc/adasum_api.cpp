@@ -94,9 +94,12 @@ int read_opts(const adasum_options* o, int dtype, Opts& r) {
         r.layer_stats = o->layer_stats;
     }
     if (!dtype_pair_ok(dtype, r.out_dtype)) return ADASUM_ERR_UNSUPPORTED;
-    if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16) return ADASUM_ERR_UNSUPPORTED;
+    if (r.radix != 0 && r.radix != 2 && r.radix != 4 && r.radix != 8 && r.radix != 16 && r.radix != 32 && r.radix != 64)
+        return ADASUM_ERR_UNSUPPORTED;
     if (r.radix > max_radix(dtype)) return ADASUM_ERR_UNSUPPORTED;
     if (r.order != ADASUM_ORDER_TREE && r.order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
+    // the wide first pass: tree order over 16-bit leaves as they are
+    if (wide_radix(r.radix) && (r.order != ADASUM_ORDER_TREE || r.delta_start != nullptr)) return ADASUM_ERR_UNSUPPORTED;
     if (r.fuse && (r.radix != 2 || r.order != ADASUM_ORDER_TREE || r.delta_start != nullptr))
         return ADASUM_ERR_UNSUPPORTED;
     if (r.delta_start != nullptr) {
@@ -125,9 +128,12 @@ struct TileTable {
     std::vector<adasum_tile> tiles;
     std::vector<int32_t> layer_begin;
     std::vector<int32_t> first_in_gram;   // combine tables only
+    std::vector<int32_t> part_begin;      // span tables (wide first pass) only
     adasum_tile* d_tiles = nullptr;
     int32_t* d_layer_begin = nullptr;
     int32_t* d_first_in_gram = nullptr;
+    int32_t* d_part_begin = nullptr;
+    int n_parts = 0;
     // >= 0: the device tables are borrowed (built on the device inside someone else's memory,
     // no host copy, never freed here) and hold this many tiles
     int64_t n_borrowed = -1;
@@ -139,6 +145,8 @@ struct TileTable {
         t.first_in_gram = d_first_in_gram;
         t.n_tiles = n_borrowed >= 0 ? n_borrowed : static_cast<int64_t>(tiles.size());
         t.capacity = capacity;
+        t.part_begin = d_part_begin;
+        t.n_parts = n_parts;
         return t;
     }
     // Both tables are sorted by start and a combine tile never straddles a Gram tile.
@@ -164,6 +172,11 @@ struct TileTable {
             ADASUM_HIP(hipMemcpy(d_first_in_gram, first_in_gram.data(), first_in_gram.size() * sizeof(int32_t),
                                  hipMemcpyHostToDevice));
         }
+        if (!part_begin.empty()) {
+            ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&d_part_begin), part_begin.size() * sizeof(int32_t)));
+            ADASUM_HIP(hipMemcpy(d_part_begin, part_begin.data(), part_begin.size() * sizeof(int32_t),
+                                 hipMemcpyHostToDevice));
+        }
         return ADASUM_OK;
     }
     void release() {
@@ -171,6 +184,8 @@ struct TileTable {
         if (d_tiles) (void)hipFree(d_tiles);
         if (d_layer_begin) (void)hipFree(d_layer_begin);
         if (d_first_in_gram) (void)hipFree(d_first_in_gram);
+        if (d_part_begin) (void)hipFree(d_part_begin);
+        d_part_begin = nullptr;
         d_tiles = nullptr;
         d_layer_begin = nullptr;
         d_first_in_gram = nullptr;
@@ -192,6 +207,7 @@ struct Plan {
                                           // (pass_feeds_next): tree order, no delta form, no fuse
     std::vector<int64_t> offsets;
     TileTable gram_tiles;                 // capacity kTile
+    TileTable wide_spans;                 // the span table of a wide first pass (else empty)
     std::map<int, TileTable> comb_tables; // by capacity, built on first use
     std::vector<int> radices;
     std::vector<SmallLayer> small;        // layers reduced by the definition in fp64 (see kSmallLayer)
@@ -252,6 +268,7 @@ struct Plan {
         if (capture_stream) (void)hipStreamDestroy(capture_stream);
         if (done) (void)hipEventDestroy(done);
         gram_tiles.release();
+        wide_spans.release();
         for (auto& kv : comb_tables) kv.second.release();
         if (borrowed) return;
         if (d_small) (void)hipFree(d_small);
@@ -294,17 +311,27 @@ int make_plan(int K, int radix, int order, int node_type, bool fuse, bool no_fee
         // the tree order lays its nodes out for the padded (power of two) leaf count
         const int Kv = order == ADASUM_ORDER_LINEAR ? K : virtual_leaves(p->radices);
         const int64_t small_elems = K > 1 ? find_small_layers(offsets, n_layers, p->small) : 0;
+        if (!p->radices.empty() && wide_radix(p->radices[0])) {
+            p->wide_spans.n_parts = wide_part_count(offsets[n_layers]);
+            build_spans(offsets, n_layers, p->wide_spans.n_parts, p->wide_spans.tiles, p->wide_spans.part_begin,
+                        p->wide_spans.layer_begin);
+        }
         p->lay = make_layout(Kv, offsets[n_layers], n_layers, static_cast<int64_t>(p->gram_tiles.tiles.size()),
                              norm_entries_bound(Kv, offsets, n_layers, p->radices, node_type), p->radices, order,
                              K + 1, small_elems, node_type,
                              fuse      ? dot_entries_bound(Kv, offsets, n_layers, p->radices, node_type)
                              : p->feed ? next_entries_bound(Kv, offsets, n_layers, p->radices, node_type)
-                                       : 0);
+                                       : 0,
+                             static_cast<int64_t>(p->wide_spans.tiles.size()));
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
     }
     int rc = p->gram_tiles.upload();
     if (rc != ADASUM_OK) return rc;
+    if (p->wide_spans.n_parts > 0) {
+        rc = p->wide_spans.upload();
+        if (rc != ADASUM_OK) return rc;
+    }
     if (!p->small.empty()) {
         const size_t bytes = p->small.size() * sizeof(SmallLayer);
         ADASUM_HIP(hipMalloc(reinterpret_cast<void**>(&p->d_small), bytes));
@@ -543,7 +570,10 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         const bool first = lv == 0, last = lv == n_levels - 1;
         const int in_dtype = first ? dtype : node_dtype(dtype);
         const int st_dtype = last ? o.out_dtype : node_dtype(dtype);
-        const int np = gram_entries(R, first);
+        // a wide pass walks the span table and leaves whole blocks per span; every other pass the Gram tiles
+        const bool wide = wide_radix(R);
+        const TileSet rt = wide ? p->wide_spans.view() : gt;
+        const int np = wide ? gram_partial_entries(R) : gram_entries(R, first);
         const bool want_norm = !last || o.layer_stats != nullptr;
         const TileSet ct = comb_sets[lv];
 
@@ -602,8 +632,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
                 fill_operands(ops, g0, ng);
                 kernel_name("gram", in_dtype, 0, R, first, namebuf, sizeof(namebuf));
                 ADASUM_TIMED(namebuf, gram_bytes(real_leaves(g0, ng), ng), stream,
-                             launch_gram(in_dtype, first, ops, gt, ng, R, partials + static_cast<int64_t>(g0) * np * T,
-                                         sub_in, stream));
+                             launch_gram(in_dtype, first, ops, rt, ng, R,
+                                         partials + static_cast<int64_t>(g0) * np * rt.n_tiles, sub_in, stream));
             }
         }
         const bool fuse_here = fuse && R == 2 && !last && groups % 2 == 0;
@@ -615,7 +645,7 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
         // (the tree's weights come out of the same launch; a fed pass has its diagonal in the partials)
         kernel_name("gram_finish", 0, 0, R, first || fed, namebuf, sizeof(namebuf));
         ADASUM_TIMED(namebuf, 0.0, stream,
-                     launch_gram_finish(first || fed, gt, L, groups, R, partials, normcoarse, gram, weights, o.order,
+                     launch_gram_finish(first || fed, rt, L, groups, R, partials, normcoarse, gram, weights, o.order,
                                         first ? p->K : 0, depth0, stream));
         if (first && o.layer_stats != nullptr) {
             ADASUM_LAUNCH(launch_trace_sums(gram, R, groups, L, p->K, depth0, 0, false, o.layer_stats + 1, 2, stream));
@@ -1026,6 +1056,7 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
     std::vector<CombTable> combs;
     Carver carve;
     size_t off_offsets = 0, off_gram_tiles = 0, off_gram_begin = 0, off_small = 0, off_ws = 0;
+    size_t off_span_tiles = 0, off_span_begin = 0, off_span_parts = 0;
     int gcap = 0;
     int64_t n_gram = 0;
     try {
@@ -1047,11 +1078,18 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
         n_gram = count_tiles(layer_offsets, L, gcap);
         plan.fuse = o.fuse;
         plan.feed = (o.order == ADASUM_ORDER_TREE && !o.fuse && !o.separate && o.delta_start == nullptr) ? 1 : 0;
+        // the span table of a wide first pass is small (a few hundred entries): built here, on the host
+        if (!plan.radices.empty() && wide_radix(plan.radices[0])) {
+            plan.wide_spans.n_parts = wide_part_count(N);
+            build_spans(layer_offsets, L, plan.wide_spans.n_parts, plan.wide_spans.tiles, plan.wide_spans.part_begin,
+                        plan.wide_spans.layer_begin);
+        }
         plan.lay = make_layout(Kv, N, L, n_gram, norm_entries_bound(Kv, layer_offsets, L, plan.radices, node_type),
                                plan.radices, o.order, K + 1, small_elems, node_type,
                                o.fuse      ? dot_entries_bound(Kv, layer_offsets, L, plan.radices, node_type)
                                : plan.feed ? next_entries_bound(Kv, layer_offsets, L, plan.radices, node_type)
-                                           : 0);
+                                           : 0,
+                               static_cast<int64_t>(plan.wide_spans.tiles.size()));
         // the combine tables this reduction reads: one per distinct tile capacity
         std::vector<int> caps;
         if (K == 1) caps.push_back(combine_tile_capacity(dtype, 1));
@@ -1077,6 +1115,11 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
             combs.push_back(c);
         }
         off_small = carve.take(sizeof(SmallLayer) * static_cast<size_t>(plan.n_small));
+        if (plan.wide_spans.n_parts > 0) {
+            off_span_tiles = carve.take(sizeof(adasum_tile) * plan.wide_spans.tiles.size());
+            off_span_begin = carve.take(sizeof(int64_t) * ((static_cast<size_t>(L) + 2) / 2));
+            off_span_parts = carve.take(sizeof(int64_t) * ((static_cast<size_t>(plan.wide_spans.n_parts) + 2) / 2));
+        }
         off_ws = carve.take(plan.lay.total);
     } catch (const std::bad_alloc&) {
         return ADASUM_ERR_OUT_OF_MEMORY;
@@ -1115,6 +1158,32 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
     }
     plan.d_small = reinterpret_cast<SmallLayer*>(base + off_small);
     ADASUM_LAUNCH(launch_build_small(d_offsets, L, plan.n_small, plan.d_small, stream));
+    if (plan.wide_spans.n_parts > 0) {
+        // the host-built span table travels like the layer table: as 8-byte words in kernel arguments
+        TileTable& w = plan.wide_spans;
+        w.n_borrowed = static_cast<int64_t>(w.tiles.size());
+        w.d_tiles = reinterpret_cast<adasum_tile*>(base + off_span_tiles);
+        w.d_layer_begin = reinterpret_cast<int32_t*>(base + off_span_begin);
+        w.d_part_begin = reinterpret_cast<int32_t*>(base + off_span_parts);
+        try {
+            static_assert(sizeof(adasum_tile) == 2 * sizeof(int64_t), "a span is two words");
+            std::vector<int64_t> words(2 * w.tiles.size());
+            std::memcpy(words.data(), w.tiles.data(), words.size() * sizeof(int64_t));
+            ADASUM_LAUNCH(launch_put_words(words.data(), words.size(), reinterpret_cast<int64_t*>(w.d_tiles), stream));
+            auto put_ints = [&](const std::vector<int32_t>& v, int32_t* dst) -> int {
+                std::vector<int64_t> packed((v.size() + 1) / 2, 0);
+                std::memcpy(packed.data(), v.data(), v.size() * sizeof(int32_t));
+                ADASUM_LAUNCH(launch_put_words(packed.data(), packed.size(), reinterpret_cast<int64_t*>(dst), stream));
+                return ADASUM_OK;
+            };
+            rc = put_ints(w.layer_begin, w.d_layer_begin);
+            if (rc != ADASUM_OK) return rc;
+            rc = put_ints(w.part_begin, w.d_part_begin);
+            if (rc != ADASUM_OK) return rc;
+        } catch (const std::bad_alloc&) {
+            return ADASUM_ERR_OUT_OF_MEMORY;
+        }
+    }
 
     // per-kernel timing would create events: not here
     struct NoProfile {
@@ -1253,6 +1322,9 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
                                        o.fuse ? dot_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype))
                                        : (o.order == ADASUM_ORDER_TREE && !o.separate && o.delta_start == nullptr)
                                            ? next_entries_bound(Kv, layer_offsets, n_layers, radices, node_dtype(dtype))
+                                           : 0,
+                                       !radices.empty() && wide_radix(radices[0])
+                                           ? count_spans(layer_offsets, n_layers, wide_part_count(layer_offsets[n_layers]))
                                            : 0);
         *bytes = lay.total;
     } catch (const std::bad_alloc&) {
@@ -1262,7 +1334,7 @@ int adasum_workspace_bytes(int K, const int64_t* layer_offsets, int n_layers, in
 }
 
 static int step_common(const void* const* x, int R, const int64_t* layer_offsets, int n_layers, int dtype) {
-    if (R != 2 && R != 4 && R != 8 && R != 16) return ADASUM_ERR_UNSUPPORTED;
+    if (R != 2 && R != 4 && R != 8 && R != 16 && R != 32 && R != 64) return ADASUM_ERR_UNSUPPORTED;
     int rc = check_layer_table(layer_offsets, n_layers);
     if (rc != ADASUM_OK) return rc;
     if (!known_dtype(dtype) || R > max_radix(dtype)) return ADASUM_ERR_UNSUPPORTED;
@@ -1289,7 +1361,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
     if (rc != ADASUM_OK) return rc;
     auto enqueue = [&]() -> int {
         double* partials = reinterpret_cast<double*>(ws + p->lay.off_partials);
-        const TileSet gt = p->gram_tiles.view();
+        const TileSet gt = wide_radix(R) ? p->wide_spans.view() : p->gram_tiles.view();
         Operands ops;
         std::memset(&ops, 0, sizeof(ops));
         for (int r = 0; r < R; ++r) ops.pack[r] = x[r];
@@ -1301,7 +1373,7 @@ int adasum_group_gram(const void* const* x, int R, const int64_t* layer_offsets,
 }
 
 int adasum_group_weights(const double* gram, int R, int n_layers, int order, double* weights, void* stream) {
-    if (R != 2 && R != 4 && R != 8 && R != 16) return ADASUM_ERR_UNSUPPORTED;
+    if (R != 2 && R != 4 && R != 8 && R != 16 && R != 32 && R != 64) return ADASUM_ERR_UNSUPPORTED;
     if (n_layers < 0) return ADASUM_ERR_INVALID_ARG;
     if (order != ADASUM_ORDER_TREE && order != ADASUM_ORDER_LINEAR) return ADASUM_ERR_UNSUPPORTED;
     if ((gram == nullptr || weights == nullptr) && n_layers > 0) return ADASUM_ERR_INVALID_ARG;
@@ -1451,7 +1523,7 @@ const char* adasum_strerror(int code) {
     switch (code) {
         case ADASUM_OK: return "ok";
         case ADASUM_ERR_INVALID_ARG: return "invalid argument";
-        case ADASUM_ERR_UNSUPPORTED: return "unsupported (dtype f32/bf16/f16/f64; output the input type or f32, f64 only with f64; radix 2/4/8/16, f64 up to 8; the delta form only in tree order)";
+        case ADASUM_ERR_UNSUPPORTED: return "unsupported (dtype f32/bf16/f16/f64; output the input type or f32, f64 only with f64; radix 2/4/8/16, f64 up to 8, 32/64 for bf16/f16 in tree order without the delta form; the delta form only in tree order)";
         case ADASUM_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
         case ADASUM_ERR_OUT_OF_MEMORY: return "out of memory";
         case ADASUM_ERR_HIP: return "HIP call failed (see adasum_last_hip_error)";

@@ -37,7 +37,13 @@ inline int combine_tile_capacity(int dtype, int R) { return combine_threads(R) *
 
 // Largest number of explicit operand pointers one launch carries by value.
 constexpr int kMaxPack = 128;
+// Widest pass of the vector-unit kernels (136 Gram entries per lane), and of the wide first pass
+// (16-bit leaves only), whose Gram entries are 32 x 32 blocks from the matrix cores.
 constexpr int kMaxRadix = 16;
+constexpr int kMaxWideRadix = 64;
+inline bool wide_radix(int R) { return R > kMaxRadix; }
+// 32 x 32 blocks a wide Gram pass keeps per tile: the three distinct ones of a 64 x 64 matrix, or one.
+constexpr int wide_blocks(int R) { return R == 64 ? 3 : 1; }
 // Radix used when the caller asks for 0: the widest pass moves the fewest bytes.
 constexpr int kDefaultRadix = 16;
 
@@ -45,7 +51,9 @@ inline bool known_dtype(int dtype) { return dtype == ADASUM_F32 || dtype == ADAS
 // Storage type of the intermediate tree nodes for an input type.
 inline int node_dtype(int dtype) { return dtype == ADASUM_F64 ? ADASUM_F64 : ADASUM_F32; }
 // Widest radix a storage type is instantiated for.
-inline int max_radix(int dtype) { return dtype == ADASUM_F64 ? 8 : 16; }
+inline int max_radix(int dtype) {
+    return dtype == ADASUM_F64 ? 8 : (dtype == ADASUM_BF16 || dtype == ADASUM_F16) ? kMaxWideRadix : kMaxRadix;
+}
 // Output storage types a combine supports for an input type: the same type or fp32; any type from fp32.
 inline bool dtype_pair_ok(int in, int out) {
     if (!known_dtype(in) || !known_dtype(out)) return false;
@@ -113,7 +121,7 @@ int build_linear_passes(int K, int radix, std::vector<int>& passes);
 // the whole Gram matrix of the next pass's group -- go out per tile, so the next pass makes no
 // reduce pass of its own.  Possible when the operand pointers of the sibling groups fit one launch.
 inline bool pass_feeds_next(const std::vector<int>& radices, size_t lv) {
-    return lv + 1 < radices.size() && radices[lv] * radices[lv + 1] <= kMaxPack;
+    return lv + 1 < radices.size() && radices[lv] <= kMaxRadix && radices[lv] * radices[lv + 1] <= kMaxPack;
 }
 // Lanes per group in such a combine (one wave), hence its tile capacity.
 constexpr int kFeedLanes = 64;
@@ -123,6 +131,22 @@ inline int feed_tile_capacity(int dtype) { return kFeedLanes * (16 / elem_bytes(
 // i < j, plus the R diagonal entries when `diag` (the first pass; later passes
 // get their squared norms from the previous combine).
 inline int gram_entries(int R, bool diag) { return R * (R - 1) / 2 + (diag ? R : 0); }
+// Doubles a pass of radix R may leave per (group, Gram tile): its entries with the diagonal, or the
+// whole blocks of a wide pass.
+inline int gram_partial_entries(int R) { return wide_radix(R) ? wide_blocks(R) * 1024 : gram_entries(R, true); }
+
+// The wide first pass (radix 32 and 64) walks spans instead of fixed-size tiles: the elements are cut
+// into `n_parts` equal parts (one workgroup each; boundaries at multiples of kWidePartAlign), and a part
+// into spans at the layer boundaries.  One set of Gram blocks is written per span, so the pass stores
+// as rarely as it can.  spans[part_begin[p]] .. [part_begin[p + 1]] are the spans of part p, and
+// layer_begin[l] .. [l + 1] those of layer l (both runs are contiguous: the spans are sorted by start).
+constexpr int kWideParts = 512;          // two workgroups of the wide Gram kernel fit a compute unit: 2 x 256
+constexpr int kWidePartAlign = 2048;     // elements; a part holds at least this many
+int wide_part_count(int64_t N);
+int64_t wide_part_elems(int64_t N, int n_parts);
+void build_spans(const int64_t* layer_offsets, int n_layers, int n_parts, std::vector<adasum_tile>& spans,
+                 std::vector<int32_t>& part_begin, std::vector<int32_t>& layer_begin);
+int64_t count_spans(const int64_t* layer_offsets, int n_layers, int n_parts);
 
 // Layers of at most kSmallLayer elements are reduced a second time by the definition
 // itself, pair by pair in fp64 over all K workers with no stored intermediate, and that
@@ -170,9 +194,11 @@ struct Layout {
 // (max over passes of nodes written x combine tiles of that pass).
 // `K` is the padded leaf count in the tree order; `small_rows` x `small_elems` doubles are
 // reserved for the compact copy of the small layers.
+// `wide_spans`: spans of a wide first pass (count_spans), which sizes that pass's partials.
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices, int order = ADASUM_ORDER_TREE, int64_t small_rows = 0,
-                   int64_t small_elems = 0, int node_type = ADASUM_F32, int64_t dot_entries = 0);
+                   int64_t small_elems = 0, int node_type = ADASUM_F32, int64_t dot_entries = 0,
+                   int64_t wide_spans = 0);
 // Doubles the passes that feed the next one (pass_feeds_next) need for the Gram entries they leave:
 // the most any of them writes, next pass's groups x combine tiles x entries of a full Gram matrix.
 int64_t next_entries_bound(int K, const int64_t* layer_offsets, int n_layers, const std::vector<int>& radices,
@@ -214,11 +240,16 @@ struct TileSet {
     const int32_t* first_in_gram = nullptr;
     int64_t n_tiles = 0;
     int capacity = 0;                        // elements a tile holds at most
+    // span tables (wide first pass) only: device, n_parts + 1
+    const int32_t* part_begin = nullptr;
+    int n_parts = 0;
 };
 
 // All launchers return a hipError_t as int (0 = success) and enqueue on `stream`.
 // partials[(group * gt.n_tiles + tile) * entries + entry]
 // delta_start (or null): operands are x_r - delta_start, same storage type as the operands; diag only.
+// A wide pass (R = 32, 64; 16-bit `dtype`, diag, no delta) takes the span table for `gt` and writes
+// partials[(group * gt.n_tiles + span) * gram_partial_entries(R) + ...].
 int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, int n_groups, int R,
                 double* partials, const void* delta_start, void* stream);
 // coarse[node * gt.n_tiles + t] = sum of fine[node * ct.n_tiles + c] over the combine tiles c inside
@@ -303,6 +334,8 @@ int static_scratch(char** base, size_t* bytes);
 // Copies a host layer table (n_layers + 1 entries) to `d_offsets` through kernel arguments,
 // a few hundred entries per launch: no copy engine, no staging buffer.
 int launch_put_offsets(const int64_t* layer_offsets, int n_layers, int64_t* d_offsets, void* stream);
+// The same for any small host table of 8-byte words.
+int launch_put_words(const int64_t* words, size_t n_words, int64_t* d_words, void* stream);
 // The device-side twin of build_tiles: writes the tile table of `capacity` elements for the
 // layer table at d_offsets.  `n_tiles` must be count_tiles(...) for the same table.
 int launch_build_tiles(const int64_t* d_offsets, int n_layers, int64_t capacity, int64_t n_tiles,

@@ -607,6 +607,52 @@ __device__ __forceinline__ void wave_tree_weights(const double* G, double* w, in
     }
 }
 
+// The same walk by a whole workgroup of NW waves (the wide first pass: 63 merges of up to 32 x 32 terms
+// are slow one after the other): the nodes of one depth are independent, so their 3 quadratic forms
+// each are spread over the waves, then every leaf takes its node's coefficient.  Tree order only.
+// Every thread of the workgroup must call it; q is LDS scratch of 3 * R / 2 doubles.
+template <int R, int NW>
+__device__ __forceinline__ void block_tree_weights(const double* G, double* w, double* q, int r) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < R) w[tid] = tid < r ? 1.0 : 0.0;
+    int levels = 0;
+    while ((1 << levels) < r) ++levels;
+    for (int d = levels - 1; d >= 0; --d) {
+        __syncthreads();
+        const int nodes = 1 << d;
+        for (int job = wave; job < 3 * nodes; job += NW) {
+            const int j = job / 3, what = job - 3 * j;
+            int lo, hi;
+            leaf_range(r, d, j, lo, hi);
+            const int mid = lo + (hi - lo) / 2;
+            double v = 0.0;
+            if (hi - lo >= 2)
+                v = what == 0   ? wave_quadratic<R>(G, w, lo, mid, lo, mid, lane)
+                    : what == 1 ? wave_quadratic<R>(G, w, mid, hi, mid, hi, lane)
+                                : wave_quadratic<R>(G, w, lo, mid, mid, hi, lane);
+            if (lane == 0) q[job] = v;
+        }
+        __syncthreads();
+        if (tid < r) {
+            // the node of this depth that holds leaf tid: walk down from the root
+            int lo = 0, hi = r, j = 0;
+            for (int b = 0; b < d; ++b) {
+                const int mid = lo + (hi - lo) / 2;
+                j = 2 * j + (tid >= mid ? 1 : 0);
+                if (tid >= mid) lo = mid; else hi = mid;
+            }
+            if (hi - lo >= 2) {
+                const int mid = lo + (hi - lo) / 2;
+                const double n1 = q[3 * j], n2 = q[3 * j + 1], dd = q[3 * j + 2];
+                const double ca = n1 > 0.0 ? 1.0 - dd / (2.0 * n1) : 1.0;
+                const double cb = n2 > 0.0 ? 1.0 - dd / (2.0 * n2) : 1.0;
+                w[tid] *= tid < mid ? ca : cb;
+            }
+        }
+    }
+    __syncthreads();
+}
+
 // One workgroup per (group, layer).  When !DIAG the diagonal comes from the
 // coarsened squared norms normparts[(group * R + i) * n_tiles + tile].
 // Threads of a finish workgroup: enough rows of entries side by side to keep many loads in
@@ -1098,6 +1144,355 @@ parts_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles, const in
 }
 
 // ---------------------------------------------------------------------------
+// Wide first pass (radix 32 and 64, 16-bit leaves): with 528 or 2080 Gram entries per group the
+// "partial dot products" step is a dense contraction, G = X X^T over a tile of R rows, more
+// multiply-adds per byte than the vector units have at the memory's speed, so it runs on the
+// matrix cores.  v_mfma_f32_32x32x16 takes, per lane, eight consecutive 16-bit elements of row
+// lane % 32 (k-half lane / 32) for either operand -- the layout a 16-byte load of one row yields
+// -- and multiplying a block of rows with itself or with the other block gives a 32 x 32 block
+// of G.  R = 64: rows 0..31 are P, rows 32..63 are Q, blocks P P^T, P Q^T, Q Q^T; R = 32: P P^T only.
+//
+// The elements are cut into as many equal parts as the chip holds workgroups of this kernel (two
+// per compute unit), and a part into spans at the layer boundaries; a workgroup (four waves) takes
+// one part and leaves one set of blocks per span.  (Per fixed-size tile, as the other passes do it,
+// the pass would write 24 KB every 8 MB it reads: 0.3 % of the traffic, and yet stores sprinkled
+// over a stream of loads cost it 9 % of its speed, 6.9 instead of 6.3 ms on the K = 64 BERT-Large
+// case.  With spans the stores are as few as they can be.)
+// A span is walked in blocks of R rows x 2048 / R granules (32 KB).  How the rows are read decides
+// the speed as well: a wave that fetches 128 bytes of each of 64 rows per step streams at 6.0 TB/s,
+// one that fetches 512 bytes or more of 16 rows at 7.0 (measured on the bare access pattern), so
+// wave w loads rows w, w + 4, ... of the block, 512 bytes or 1 KB of a row per load instruction,
+// two blocks ahead of the multiplies.  The block goes through LDS (two buffers, one barrier per
+// block) to reach the operand layout; every wave then multiplies its quarter of the block's columns
+// for all rows.  The products are exact; the matrix cores add the 64 of a wave's quarter in fp32,
+// the blocks' sums are added with ordinary fp32 additions (round to nearest), fp64 above the wave.
+// partials[(group * n_spans + span) * NPW + (block * 16 + v) * 64 + lane], NPW = blocks * 1024:
+// accumulator v of a lane is row 8 (v / 4) + 4 (lane / 32) + v % 4, column lane % 32 of the block.
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// A 16-byte streaming load through a pointer that was kept in LDS: such a pointer has lost its
+// address space, and a load through it would be a flat one, which counts against the LDS counter
+// too and makes every wait for LDS a wait for all of memory.  These pointers are device memory.
+typedef const u32x4 __attribute__((address_space(1)))* global_u32x4_ptr;
+__device__ __forceinline__ u32x4 stream_load_global(const void* p) {
+#if ADASUM_NT_LOAD
+    return __builtin_nontemporal_load((global_u32x4_ptr)p);
+#else
+    return *(global_u32x4_ptr)p;
+#endif
+}
+
+template <typename T>
+__device__ __forceinline__ f32x16_t mfma_rows(const u32x4& a, const u32x4& b, const f32x16_t& c) {
+    if constexpr (std::is_same<T, bf16_t>::value)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                       c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b),
+                                                      c, 0, 0, 0);
+}
+
+template <typename T, int R>
+__global__ void __launch_bounds__(kThreads, 2)   // (second figure: waves per SIMD the register budget must allow)
+gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, const int32_t* __restrict__ part_begin,
+                 int n_parts, int n_spans, double* __restrict__ partials) {
+    static_assert(sizeof(T) == 2 && (R == 32 || R == 64), "16-bit leaves, 32 or 64 rows");
+    static_assert(kThreads == 256, "four waves per tile");
+    constexpr int G = 8;                          // elements per 16-byte granule
+    constexpr int NB = wide_blocks(R);            // 32 x 32 blocks of the matrix a wave accumulates
+    constexpr int CH = 2048 / R;                  // granules per row and block: 32 (R = 64) or 64 (R = 32)
+    constexpr int RPI = 64 / CH;                  // rows one load instruction covers: 2 or 1
+    constexpr int NLD = R / 4 / RPI;              // load instructions per wave and block: 8
+    constexpr int KW = CH / 8;                    // 16-element multiply steps per wave and block: 4 or 8
+    constexpr int PITCH = CH * 16 + 16;           // bytes per row in LDS (padded: conflict-free operand reads)
+    constexpr int BUF = R * PITCH;
+    constexpr int NPW = NB * 1024;
+    static_assert(NLD == 8 && 2 * BUF >= NB * 16 * 64 * (int)sizeof(double), "LDS is reused for the waves' sums");
+
+    __shared__ __align__(16) unsigned char lds[2 * BUF];
+    __shared__ const T* rowptr[R];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int part = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_parts));
+    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_parts));
+
+    if (tid == 0) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) rowptr[r] = static_cast<const T*>(operand_ptr<R>(ops, g, r));
+    }
+    __syncthreads();
+
+    // what this lane loads: granule `chunk` of rows (lrow + RPI i) * 4 + wave, i = 0 .. NLD - 1
+    const int chunk = lane % CH, lrow = lane / CH;
+    const T* row[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) row[i] = rowptr[(i * RPI + lrow) * 4 + wave];
+    const int wr = (lrow * 4 + wave) * PITCH + chunk * 16;
+    // what it multiplies: row m of P (and of Q), k-half h of the wave's multiply steps
+    const int m = lane & 31, h = lane >> 5;
+    const int rdP = m * PITCH + (2 * KW * wave + h) * 16;
+    const int rdQ = rdP + 32 * PITCH;
+
+    float sum[NB][16];
+
+    auto multiply_add = [&](const u32x4& p, const u32x4& q, f32x16_t (&acc)[NB]) {
+        acc[0] = mfma_rows<T>(p, p, acc[0]);
+        if constexpr (NB == 3) {
+            acc[1] = mfma_rows<T>(p, q, acc[1]);
+            acc[2] = mfma_rows<T>(q, q, acc[2]);
+        }
+    };
+    auto flush = [&](f32x16_t (&acc)[NB]) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                sum[b][v] += acc[b][v];
+                acc[b][v] = 0.f;
+            }
+    };
+
+    for (int sp = part_begin[part]; sp < part_begin[part + 1]; ++sp) {   // (uniform: the barriers below match)
+        const Split s = split_tile<G>(spans[sp]);
+        const T* src[NLD];
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) src[i] = row[i] + s.bs + chunk * G;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum[b][v] = 0.f;
+        const int nsteps = (s.ng + CH - 1) / CH;      // the same for every wave
+        u32x4 stage[2][NLD];                          // the loads of two blocks in flight per wave
+        // No branch around a load (the waits between loads and their use are then counted exactly, and
+        // younger loads stay in flight): a lane past the end of the tile's granules re-reads the last
+        // granule, and what it fetched is replaced by zeros when it is stored to LDS.
+        auto fetch = [&](u32x4 (&into)[NLD], int step) {
+            const int gi = step * CH + chunk;
+            const long long off = static_cast<long long>((gi < s.ng ? gi : s.ng - 1) - chunk) * G;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) into[i] = stream_load_global(src[i] + off);
+        };
+        auto store_block = [&](unsigned char* buf, const u32x4 (&from)[NLD], int step) {
+            const bool live = step * CH + chunk < s.ng;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                u32x4 v = from[i];
+                v.x = live ? v.x : 0u;
+                v.y = live ? v.y : 0u;
+                v.z = live ? v.z : 0u;
+                v.w = live ? v.w : 0u;
+                *reinterpret_cast<u32x4*>(buf + wr + i * (RPI * 4 * PITCH)) = v;
+            }
+        };
+        f32x16_t acc[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+
+        if (nsteps > 0) {
+            fetch(stage[0], 0);
+            fetch(stage[1], 1);
+        }
+        for (int step0 = 0; step0 < nsteps; step0 += 2) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                // block step0 + a (one past the end multiplies zeros) through buffer a: the buffer's last
+                // readers, two blocks back, passed the barrier of the block in between
+                unsigned char* buf = lds + a * BUF;
+                store_block(buf, stage[a], step0 + a);
+                fetch(stage[a], step0 + a + 2);
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < KW; ++j) {
+                    const u32x4 p = *reinterpret_cast<const u32x4*>(buf + rdP + j * 32);
+                    u32x4 q = p;
+                    if constexpr (NB == 3) q = *reinterpret_cast<const u32x4*>(buf + rdQ + j * 32);
+                    multiply_add(p, q, acc);
+                }
+                flush(acc);
+            }
+        }
+
+        // the at most 2 * 7 elements of a ragged head and tail: one more multiply step by wave 0, the
+        // elements fetched one by one straight into the operand layout (k = 8 h .. 8 h + 7)
+        const int nedge = s.nh + s.nt;
+        if (nedge > 0 && wave == 0) {
+            unsigned int pw[4] = {0u, 0u, 0u, 0u}, qw[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int e = 8 * h + k;
+                if (e < nedge) {
+                    const long long idx = e < s.nh ? s.start + e : s.ts + (e - s.nh);
+                    pw[k / 2] |= static_cast<unsigned int>(rowptr[m][idx].v) << (16 * (k & 1));
+                    if constexpr (NB == 3) qw[k / 2] |= static_cast<unsigned int>(rowptr[32 + m][idx].v) << (16 * (k & 1));
+                }
+            }
+            u32x4 p, q;
+            p.x = pw[0]; p.y = pw[1]; p.z = pw[2]; p.w = pw[3];
+            q.x = qw[0]; q.y = qw[1]; q.z = qw[2]; q.w = qw[3];
+            multiply_add(p, q, acc);
+            flush(acc);
+        }
+
+        // the four waves' sums, added in a fixed order through LDS (the staging area, now free)
+        double* red = reinterpret_cast<double*>(lds);
+        double* out = partials + (static_cast<long long>(g) * n_spans + sp) * NPW;
+        __syncthreads();
+#pragma unroll 1
+        for (int w = 0; w < 4; ++w) {
+            if (wave == w) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int i = (b * 16 + v) * 64 + lane;
+                        const double mine = static_cast<double>(sum[b][v]);
+                        if (w == 0) red[i] = mine;
+                        else if (w < 3) red[i] += mine;
+                        else out[i] = red[i] + mine;
+                    }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Step 2 after a wide first pass: sums the per-tile blocks of a (group, layer) in a fixed order,
+// spreads them into the full R x R matrix and walks the tree (wave_tree_weights).
+template <int R>
+__global__ void __launch_bounds__(1024)
+gram_finish_wide_kernel(const double* __restrict__ partials, const int32_t* __restrict__ layer_tile_begin, int n_tiles,
+                        int n_layers, double* __restrict__ gram, double* __restrict__ weights, int order, int K_leaves,
+                        int depth) {
+    constexpr int NB = wide_blocks(R);
+    constexpr int NPW = NB * 1024;
+    constexpr int kAhead = 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_layers));
+    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_layers));
+    const int tb = layer_tile_begin[l], te = layer_tile_begin[l + 1];
+    double* out = gram + (static_cast<long long>(g) * n_layers + l) * (R * R);
+    __shared__ double shG[R * R];
+    __shared__ double shW[R];
+
+    // thread tid owns accumulator v = tid / 64 of lane tid % 64 in every block; one workgroup sums all
+    // tiles of a layer, so it keeps many loads in flight (branch-free: a tile past the end re-reads the
+    // layer's last tile and its value is dropped)
+    const double* base = partials + static_cast<long long>(g) * n_tiles * NPW + tid;
+    double tots[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) tots[b] = 0.0;
+    for (int t0 = tb; t0 < te; t0 += kAhead) {
+        double x[NB][kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int t = t0 + u;
+            const double* row = base + static_cast<long long>(t < te ? t : te - 1) * NPW;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) x[b][u] = row[b * 1024];
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) tots[b] += (t0 + u < te) ? x[b][u] : 0.0;
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const double tot = tots[b];
+        const int v = wave, i = 8 * (v / 4) + 4 * (lane / 32) + v % 4, j = lane % 32;
+        // block 0: rows and columns 0..31; block 1: rows 0..31 against 32..63; block 2: rows and columns 32..63
+        const int row = b == 2 ? 32 + i : i, col = b == 0 ? j : 32 + j;
+        shG[row * R + col] = tot;
+        out[row * R + col] = tot;
+        if (b == 1) {
+            shG[col * R + row] = tot;
+            out[col * R + row] = tot;
+        }
+    }
+    if (weights != nullptr) {
+        __shared__ double shQ[3 * R / 2];
+        int r = R;
+        if (K_leaves > 0) {
+            int lo, hi;
+            leaf_range(K_leaves, depth, g, lo, hi);
+            r = hi - lo;
+        }
+        (void)order;   // (a wide pass exists in the tree order only)
+        block_tree_weights<R, 16>(shG, shW, shQ, r);
+        if (tid < R) weights[(static_cast<long long>(g) * n_layers + l) * R + tid] = shW[tid];
+    }
+}
+
+// Step 3 after a wide first pass: out = sum_r w_r x_r over R = 32 or 64 16-bit operands, sixteen at a
+// time (as many loads in flight per lane as the radix-16 combine has), one 16-byte granule per lane, one
+// wave per tile.  normparts[group * n_tiles + tile] (or null).
+template <typename TI, typename TO, int R>
+__global__ void __launch_bounds__(64)
+combine_wide_kernel(const Operands ops, const Outputs outs, const adasum_tile* __restrict__ tiles, int n_tiles,
+                    int n_layers, const double* __restrict__ weights, double* __restrict__ normparts) {
+    static_assert(sizeof(TI) == 2 && (R == 32 || R == 64), "16-bit leaves, 32 or 64 operands");
+    constexpr int G = 8, C = 16;
+    typedef typename Traits<TO>::acc_t out_acc_t;
+    const int lane = threadIdx.x;
+    const int tile_id = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_tiles));
+    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_tiles));
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
+    TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
+    const double* wl = weights + (static_cast<long long>(g) * n_layers + t.layer) * R;
+    const long long idx = s.bs + static_cast<long long>(lane) * G;
+
+    float nacc = 0.f;
+    if (lane < s.ng) {
+        float z[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) z[k] = 0.f;
+#pragma unroll 1
+        for (int c = 0; c < R / C; ++c) {
+            Granule<TI, G> raw[C];
+#pragma unroll
+            for (int r = 0; r < C; ++r) load_raw(raw[r], static_cast<const TI*>(ops.pack[g * R + c * C + r]) + idx);
+#pragma unroll
+            for (int r = 0; r < C; ++r) {
+                const float w = static_cast<float>(wl[c * C + r]);
+                float v[G];
+                unpack(raw[r], v);
+#pragma unroll
+                for (int k = 0; k < G; ++k) z[k] = fma_t(w, v[k], z[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < G; ++k) nacc = fma_t(z[k], z[k], nacc);
+        store_granule<true>(out + idx, z);
+    }
+    // ragged head/tail elements: fp64 arithmetic, one rounding at the store
+    const int nedge = s.nh + s.nt;
+    double enorm = 0.0;
+    if (nedge > 0) {
+        if (lane < nedge) {
+            const long long e = lane < s.nh ? s.start + lane : s.ts + (lane - s.nh);
+            double z = 0.0;
+#pragma unroll 1
+            for (int r = 0; r < R; ++r)
+                z = __builtin_fma(wl[r], static_cast<double>(load_elem(static_cast<const TI*>(ops.pack[g * R + r]) + e)), z);
+            const out_acc_t zs = static_cast<out_acc_t>(z);
+            enorm = static_cast<double>(zs) * static_cast<double>(zs);
+            store_elem(out + e, zs);
+        }
+        if (normparts != nullptr) enorm = wave_sum(enorm);
+    }
+    if (normparts != nullptr) {
+        const float ws = wave_sum(nacc);
+        if (lane == 0) normparts[static_cast<long long>(g) * n_tiles + tile_id] = static_cast<double>(ws) + enorm;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Small layers (at most kSmallLayer elements), by the definition itself: the
 // operator of Section 3 applied pair by pair over all K workers in fp64, in the
 // order of Section 3.4's recursion, nothing stored in between.
@@ -1575,6 +1970,42 @@ int launch_combine_feed_t(const Operands& ops, const Outputs& outs, const TileSe
     }
 }
 
+// The wide first pass (gram_wide_kernel and what follows it): 16-bit leaves, R = 32 or 64.
+template <typename T>
+int launch_gram_wide_t(const Operands& ops, const TileSet& spans, int n_groups, int R, double* partials, hipStream_t st) {
+    if (spans.part_begin == nullptr || spans.n_parts < 1) return static_cast<int>(hipErrorInvalidValue);   // not a span table
+    const long long blocks = spans.n_parts * static_cast<long long>(n_groups);
+    if (!grid_fits(blocks) || n_groups * R > kMaxPack) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const int ns = static_cast<int>(spans.n_tiles);
+    if (R == 64)
+        hipLaunchKernelGGL((gram_wide_kernel<T, 64>), grid, block, 0, st, ops, spans.tiles, spans.part_begin, spans.n_parts,
+                           ns, partials);
+    else if (R == 32)
+        hipLaunchKernelGGL((gram_wide_kernel<T, 32>), grid, block, 0, st, ops, spans.tiles, spans.part_begin, spans.n_parts,
+                           ns, partials);
+    else return static_cast<int>(hipErrorInvalidValue);
+    return check_launch();
+}
+
+template <typename TI, typename TO>
+int launch_combine_wide_t(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups, int R,
+                          const double* weights, double* normparts, hipStream_t st) {
+    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups);
+    if (!grid_fits(blocks) || n_groups * R > kMaxPack) return static_cast<int>(hipErrorInvalidConfiguration);
+    if (weights == nullptr || ct.capacity != combine_tile_capacity(ADASUM_BF16, R)) return static_cast<int>(hipErrorInvalidValue);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(64);
+    const int nt = static_cast<int>(ct.n_tiles);
+    if (R == 64)
+        hipLaunchKernelGGL((combine_wide_kernel<TI, TO, 64>), grid, block, 0, st, ops, outs, ct.tiles, nt, n_layers, weights,
+                           normparts);
+    else if (R == 32)
+        hipLaunchKernelGGL((combine_wide_kernel<TI, TO, 32>), grid, block, 0, st, ops, outs, ct.tiles, nt, n_layers, weights,
+                           normparts);
+    else return static_cast<int>(hipErrorInvalidValue);
+    return check_launch();
+}
+
 }  // namespace
 
 int launch_combine_feed(int dtype, int out_dtype, const Operands& ops, const Outputs& out, const TileSet& ct,
@@ -1657,6 +2088,13 @@ int launch_gram(int dtype, bool diag, const Operands& ops, const TileSet& gt, in
                 double* partials, const void* delta_start, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (gt.n_tiles == 0 || n_groups == 0) return 0;
+    if (wide_radix(R)) {
+        // leaves only: the whole matrix, no delta form
+        if (!diag || delta_start != nullptr) return static_cast<int>(hipErrorInvalidValue);
+        if (dtype == ADASUM_BF16) return launch_gram_wide_t<bf16_t>(ops, gt, n_groups, R, partials, st);
+        if (dtype == ADASUM_F16) return launch_gram_wide_t<f16_t>(ops, gt, n_groups, R, partials, st);
+        return static_cast<int>(hipErrorInvalidValue);
+    }
     if (dtype == ADASUM_BF16) return launch_gram_t<bf16_t>(diag, ops, gt, n_groups, R, partials, delta_start, st);
     if (dtype == ADASUM_F16) return launch_gram_t<f16_t>(diag, ops, gt, n_groups, R, partials, delta_start, st);
     if (dtype == ADASUM_F64) return launch_gram_t<double>(diag, ops, gt, n_groups, R, partials, delta_start, st);
@@ -1681,8 +2119,20 @@ int launch_gram_finish(bool diag, const TileSet& gt, int n_layers, int n_groups,
     const long long blocks = static_cast<long long>(n_groups) * n_layers;
     if (blocks == 0) return 0;
     if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
-    const dim3 grid(static_cast<unsigned>(blocks)), block(finish_threads(R));
     const int ngt = static_cast<int>(gt.n_tiles);
+    if (wide_radix(R)) {
+        if (!diag) return static_cast<int>(hipErrorInvalidValue);
+        const dim3 wgrid(static_cast<unsigned>(blocks)), wblock(1024);
+        if (R == 64)
+            hipLaunchKernelGGL((gram_finish_wide_kernel<64>), wgrid, wblock, 0, st, partials, gt.layer_begin, ngt, n_layers,
+                               gram, weights, order, K_leaves, depth);
+        else if (R == 32)
+            hipLaunchKernelGGL((gram_finish_wide_kernel<32>), wgrid, wblock, 0, st, partials, gt.layer_begin, ngt, n_layers,
+                               gram, weights, order, K_leaves, depth);
+        else return static_cast<int>(hipErrorInvalidValue);
+        return check_launch();
+    }
+    const dim3 grid(static_cast<unsigned>(blocks)), block(finish_threads(R));
 #define ADASUM_FINISH(RR, DD)                                                                      \
     hipLaunchKernelGGL((gram_finish_kernel<RR, DD>), grid, block, 0, st, partials, normparts,      \
                        gt.layer_begin, ngt, n_layers, gram, weights, order, K_leaves, depth)
@@ -1711,6 +2161,8 @@ int launch_weights(const double* gram, int R, int64_t n_items, int order, int n_
         case 4: hipLaunchKernelGGL((weights_kernel<4>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
         case 8: hipLaunchKernelGGL((weights_kernel<8>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
         case 16: hipLaunchKernelGGL((weights_kernel<16>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
+        case 32: hipLaunchKernelGGL((weights_kernel<32>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
+        case 64: hipLaunchKernelGGL((weights_kernel<64>), grid, block, 0, st, gram, n, order, nl, K_leaves, depth, weights); break;
         default: return static_cast<int>(hipErrorInvalidValue);
     }
     return check_launch();
@@ -1721,6 +2173,19 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
                    const void* sub_in, const void* add_out, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ct.n_tiles == 0 || n_groups == 0) return 0;
+    if (wide_radix(R)) {
+        // 16-bit leaves into fp32 or their own type; no delta form
+        if (sub_in != nullptr || add_out != nullptr) return static_cast<int>(hipErrorInvalidValue);
+        if (dtype == ADASUM_BF16 && out_dtype == ADASUM_BF16)
+            return launch_combine_wide_t<bf16_t, bf16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        if (dtype == ADASUM_BF16 && out_dtype == ADASUM_F32)
+            return launch_combine_wide_t<bf16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        if (dtype == ADASUM_F16 && out_dtype == ADASUM_F16)
+            return launch_combine_wide_t<f16_t, f16_t>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        if (dtype == ADASUM_F16 && out_dtype == ADASUM_F32)
+            return launch_combine_wide_t<f16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
+        return static_cast<int>(hipErrorInvalidValue);
+    }
     // supported pairs: T -> fp32, fp32 -> T, T -> T; fp64 only with itself
     if (dtype == ADASUM_F64 || out_dtype == ADASUM_F64) {
         if (dtype != out_dtype) return static_cast<int>(hipErrorInvalidValue);
@@ -1826,19 +2291,23 @@ int static_scratch(char** base, size_t* bytes) {
     return 0;
 }
 
-int launch_put_offsets(const int64_t* layer_offsets, int n_layers, int64_t* d_offsets, void* stream) {
+int launch_put_words(const int64_t* words, size_t n_words, int64_t* d_words, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int64_t n = static_cast<int64_t>(n_layers) + 1;
+    const int64_t n = static_cast<int64_t>(n_words);
     for (int64_t i0 = 0; i0 < n; i0 += kOffsetsPerLaunch) {
         const int m = static_cast<int>(std::min<int64_t>(kOffsetsPerLaunch, n - i0));
         OffsetChunk c;
-        for (int i = 0; i < kOffsetsPerLaunch; ++i) c.v[i] = i < m ? layer_offsets[i0 + i] : 0;
+        for (int i = 0; i < kOffsetsPerLaunch; ++i) c.v[i] = i < m ? words[i0 + i] : 0;
         hipLaunchKernelGGL(put_offsets_kernel, dim3(1), dim3(kOffsetsPerLaunch), 0, st, c, m,
-                           reinterpret_cast<long long*>(d_offsets) + i0);
+                           reinterpret_cast<long long*>(d_words) + i0);
         const int rc = check_launch();
         if (rc != 0) return rc;
     }
     return 0;
+}
+
+int launch_put_offsets(const int64_t* layer_offsets, int n_layers, int64_t* d_offsets, void* stream) {
+    return launch_put_words(layer_offsets, static_cast<size_t>(n_layers) + 1, d_offsets, stream);
 }
 
 int launch_build_tiles(const int64_t* d_offsets, int n_layers, int64_t capacity, int64_t n_tiles,

@@ -47,7 +47,7 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     radices.clear();
     if (K < 1) return ADASUM_ERR_INVALID_ARG;
     if (radix == 0) radix = kDefaultRadix;
-    if (radix != 2 && radix != 4 && radix != 8 && radix != 16) return ADASUM_ERR_UNSUPPORTED;
+    if (radix != 2 && radix != 4 && radix != 8 && radix != 16 && radix != 32 && radix != 64) return ADASUM_ERR_UNSUPPORTED;
     if (K == 1) return ADASUM_OK;
     // the shallowest depth whose sub-trees have at most `radix` leaves
     int depth = 0;
@@ -58,7 +58,8 @@ int build_levels(int K, int radix, std::vector<int>& radices) {
     radices.push_back(first);
     int rest = 1 << depth;
     while (rest > 1) {
-        int r = std::min(rest, radix);
+        // (only the first pass, over the 16-bit leaves, can be wider than kMaxRadix)
+        int r = std::min(rest, std::min(radix, kMaxRadix));
         radices.push_back(r);
         rest /= r;
     }
@@ -82,6 +83,36 @@ int build_linear_passes(int K, int radix, std::vector<int>& passes) {
         rest -= r - 1;
     }
     return ADASUM_OK;
+}
+
+int wide_part_count(int64_t N) {
+    int64_t parts = (N + kWidePartAlign - 1) / kWidePartAlign;
+    if (parts > kWideParts) parts = kWideParts;
+    if (parts < 1) parts = 1;
+    // (a span's length is a 32-bit count)
+    while (wide_part_elems(N, static_cast<int>(parts)) > (int64_t{1} << 30)) parts *= 2;
+    return static_cast<int>(parts);
+}
+
+int64_t wide_part_elems(int64_t N, int n_parts) {
+    const int64_t e = (N + n_parts - 1) / n_parts;
+    return (e + kWidePartAlign - 1) / kWidePartAlign * kWidePartAlign;
+}
+
+void build_spans(const int64_t* layer_offsets, int n_layers, int n_parts, std::vector<adasum_tile>& spans,
+                 std::vector<int32_t>& part_begin, std::vector<int32_t>& layer_begin) {
+    // tiles whose capacity is a part: cut at the part boundaries and at the layer boundaries, sorted by
+    // start, so the spans of a part are one contiguous run as those of a layer are
+    const int64_t E = wide_part_elems(layer_offsets[n_layers], n_parts);
+    build_tiles(layer_offsets, n_layers, E, spans, layer_begin);
+    part_begin.assign(static_cast<size_t>(n_parts) + 1, 0);
+    for (const adasum_tile& t : spans) ++part_begin[static_cast<size_t>(t.start / E) + 1];
+    for (int p = 0; p < n_parts; ++p) part_begin[p + 1] += part_begin[p];
+}
+
+int64_t count_spans(const int64_t* layer_offsets, int n_layers, int n_parts) {
+    const int64_t E = wide_part_elems(layer_offsets[n_layers], n_parts);
+    return count_tiles(layer_offsets, n_layers, E);
 }
 
 int64_t find_small_layers(const int64_t* layer_offsets, int n_layers, std::vector<SmallLayer>& small) {
@@ -161,7 +192,7 @@ int64_t dot_entries_bound(int K, const int64_t* layer_offsets, int n_layers, con
 
 Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm_entries,
                    const std::vector<int>& radices, int order, int64_t small_rows, int64_t small_elems,
-                   int node_type, int64_t dot_entries) {
+                   int node_type, int64_t dot_entries, int64_t wide_spans) {
     Layout lay;
     lay.N = N;
     lay.n_tiles = n_tiles;
@@ -182,8 +213,10 @@ Layout make_layout(int K, int64_t N, int n_layers, int64_t n_tiles, int64_t norm
         const int R = radices[lv];
         groups = order == ADASUM_ORDER_LINEAR ? 1 : groups / R;
         // (with the diagonal: a pass fed by the combine below it finds its whole matrix in the partials)
-        const size_t np = static_cast<size_t>(gram_entries(R, true));
-        max_partials = std::max(max_partials, static_cast<size_t>(groups) * np * static_cast<size_t>(n_tiles));
+        const size_t np = static_cast<size_t>(gram_partial_entries(R));
+        // (a wide pass -- always the first -- leaves its blocks per span, every other pass per Gram tile)
+        const size_t rows = wide_radix(R) ? static_cast<size_t>(wide_spans) : static_cast<size_t>(n_tiles);
+        max_partials = std::max(max_partials, static_cast<size_t>(groups) * np * rows);
         max_gram = std::max(max_gram, static_cast<size_t>(groups) * n_layers * R * R);
         max_weights = std::max(max_weights, static_cast<size_t>(groups) * n_layers * R);
         max_nodes = std::max(max_nodes, static_cast<size_t>(groups));

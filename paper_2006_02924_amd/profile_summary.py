@@ -47,6 +47,14 @@ def library_name(kernel_name: str):
         return f"combine<{args[0]},{args[1]},R={args[2]}>{head}{delta}"
     if kind == "combine_siblings" and len(args) >= 2:
         return f"combine<{args[0]},{args[1]},R=2>+dot"
+    if kind == "gram_wide" and len(args) >= 2:
+        return f"gram<{args[0]},R={args[1]},diag>"
+    if kind == "combine_wide" and len(args) >= 3:
+        return f"combine<{args[0]},{args[1]},R={args[2]}>"
+    if kind == "gram_finish_wide" and len(args) >= 1:
+        return f"gram_finish<R={args[0]},diag>"
+    if kind == "combine_feed" and len(args) >= 4:
+        return f"combine<{args[0]},{args[1]},R={args[2]}>+gram{args[3]}"
     if kind == "gram_finish" and len(args) >= 2:
         return f"gram_finish<R={args[0]},{'diag' if args[1] == 'true' else 'offdiag'}>"
     return kind + (f"<{','.join(args)}>" if args else "")

@@ -28,8 +28,12 @@ def say(msg):
 RAGGED = [0, 1, 2, 9, 9, 40, 41, 1064, 1064 + 16384, 1064 + 16384 + 33000, 60000, 60001]
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("R", [2, 4, 8, 16])
+# (32 and 64 operands: the wide first pass, 16-bit storage only, Gram blocks from the matrix cores)
+_STEP_CASES = ([(R, dt) for R in (2, 4, 8, 16) for dt in (torch.float32, torch.bfloat16)] +
+               [(R, dt) for R in (32, 64) for dt in (torch.bfloat16, torch.float16)])
+
+
+@pytest.mark.parametrize("R,dtype", _STEP_CASES)
 def test_group_gram_matches_dot_products(R, dtype):
     say(f"group_gram R={R} {dtype}")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=11)
@@ -51,7 +55,7 @@ def test_group_gram_matches_dot_products(R, dtype):
         np.testing.assert_allclose([got[-2][0, 1], got[-2][0, 0], got[-2][1, 1]], [d, n1, n2], rtol=2e-6)
 
 
-@pytest.mark.parametrize("R", [2, 4, 8, 16])
+@pytest.mark.parametrize("R", [2, 4, 8, 16, 32, 64])
 def test_group_weights_reproduce_the_tree(R):
     say(f"group_weights R={R}")
     rng = np.random.default_rng(R)
@@ -89,9 +93,9 @@ def test_group_weights_reproduce_the_tree(R):
         assert np.linalg.norm(wl[l] @ X[l] - want) / np.linalg.norm(want) < 1e-6
 
 
-@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("R", [2, 4, 8, 16])
+@pytest.mark.parametrize("R,dtype,out_dtype", [(R, dt, od) for R, dt in _STEP_CASES
+                                               for od in ((torch.float32, dt) if dt != torch.float32
+                                                          else (torch.float32, torch.bfloat16))])
 def test_group_combine_matches_weighted_sum(R, dtype, out_dtype):
     say(f"group_combine R={R} {dtype}->{out_dtype}")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), R, dtype=dtype, device=DEV, seed=12)
@@ -108,10 +112,11 @@ def test_group_combine_matches_weighted_sum(R, dtype, out_dtype):
     for l in range(L):
         lo, hi = RAGGED[l], RAGGED[l + 1]
         ref[lo:hi] = wt64[l] @ X[:, lo:hi]
-    assert_parity(out, ref, w.layer_offsets, tol=2e-6 if out_dtype == torch.float32 else TOL_BF16)
+    assert_parity(out, ref, w.layer_offsets, tol=2e-6 if out_dtype == torch.float32 else
+                  (1e-3 if out_dtype == torch.float16 else TOL_BF16))
     want_sq = np.array([np.dot(ref[RAGGED[l]:RAGGED[l + 1]], ref[RAGGED[l]:RAGGED[l + 1]]) for l in range(L)])
     np.testing.assert_allclose(sq.cpu().numpy(), want_sq, rtol=1e-5, atol=0)
-    if out_dtype == torch.bfloat16:
+    if out_dtype in (torch.bfloat16, torch.float16):
         assert_bf16_rounding(out, ref, w.layer_offsets)
 
 
@@ -119,6 +124,14 @@ def test_group_combine_in_place_on_first_operand():
     say("group_combine in place")
     w = W.correlated_gaussian(np.diff(RAGGED).tolist(), 4, dtype=torch.float32, device=DEV, seed=13)
     wt = torch.rand(w.n_layers, 4, generator=torch.Generator().manual_seed(6), dtype=torch.float64).to(DEV)
+    ref, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt)
+    got, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt, out=w.grads[0])
+    torch.cuda.synchronize()
+    assert got.data_ptr() == w.grads[0].data_ptr()
+    assert torch.equal(got, ref)
+    # 64 operands, sixteen at a time: a lane still reads all of its element before it writes it
+    w = W.correlated_gaussian(np.diff(RAGGED).tolist(), 64, dtype=torch.bfloat16, device=DEV, seed=14)
+    wt = torch.rand(w.n_layers, 64, generator=torch.Generator().manual_seed(7), dtype=torch.float64).to(DEV)
     ref, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt)
     got, _ = B.adasum_group_combine(w.grads, w.layer_offsets, wt, out=w.grads[0])
     torch.cuda.synchronize()

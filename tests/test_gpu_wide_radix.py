@@ -1,0 +1,114 @@
+"""GPU parity of the wide first pass (radix 32 and 64 over bf16 / fp16 leaves, the group's Gram
+matrix from the matrix cores) against the fp64 CPU oracle, through the C-ABI.
+
+Tolerances (per layer, relative L2): 1e-5 for fp32 output, 2e-3 for bf16 output, 1e-3 for fp16.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2006_02924_amd import binding as B
+from paper_2006_02924_amd import workloads as W
+from tests.gpu_util import assert_parity, assert_bf16_rounding, oracle_reduce, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+# empty layers, layers of a few elements (redone in fp64), ragged heads and tails at every alignment,
+# layers that span several Gram tiles of 16384 and one that crosses many
+SIZES = [0, 1, 7, 9, 0, 31, 1, 1023, 16384, 33000, 26935, 1, 100003]
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _workload(K, dtype, seed):
+    if dtype == torch.float16:
+        return W.correlated_gaussian(SIZES, K, dtype=dtype, device=DEV, seed=seed,
+                                     scale=W.log_uniform_scales(len(SIZES), 81, lo_exp=-2.0, hi_exp=0.0))
+    return W.correlated_gaussian(SIZES, K, dtype=dtype, device=DEV, seed=seed)
+
+
+_CASES = [(K, radix, dtype)
+          for K, radix in [(17, 32), (24, 64), (32, 32), (32, 64), (33, 64), (48, 64), (64, 32), (64, 64), (100, 64),
+                           (128, 64), (128, 32), (256, 64), (1024, 64)]
+          for dtype in (torch.bfloat16, torch.float16)]
+
+
+@pytest.mark.parametrize("K,radix,dtype", _CASES)
+def test_wide_first_pass(K, radix, dtype):
+    """The same tree as every other radix: against the oracle, against the default schedule to the
+    rounding of the scalars, statistics alike, reruns identical, and through the entry point that
+    allocates nothing."""
+    say(f"wide first pass K={K} radix={radix} {dtype}; passes {B.plan_levels(K, radix)}")
+    assert B.plan_levels(K, radix)[0] in (32, 64)
+    w = _workload(K, dtype, 1300 + K)
+    offs = w.layer_offsets
+    ref = oracle_reduce(w.grads, offs)
+    s_wide = torch.full((w.n_layers, 2), -1.0, dtype=torch.float64, device=DEV)
+    s_def = torch.full((w.n_layers, 2), -1.0, dtype=torch.float64, device=DEV)
+    wide = B.adasum_reduce(w.grads, offs, radix=radix, out_dtype=torch.float32, layer_stats=s_wide)
+    base = B.adasum_reduce(w.grads, offs, out_dtype=torch.float32, layer_stats=s_def)
+    torch.cuda.synchronize()
+    assert_parity(wide, ref, offs, what=f"radix {radix}")
+    a, b = to_f64(wide), to_f64(base)
+    for l in range(w.n_layers):
+        lo, hi = offs[l], offs[l + 1]
+        if hi > lo and not np.isnan(ref[lo:hi]).any():
+            assert np.linalg.norm(a[lo:hi] - b[lo:hi]) <= 2e-6 * np.linalg.norm(b[lo:hi]), l
+    np.testing.assert_allclose(s_wide.cpu().numpy()[:, 1], s_def.cpu().numpy()[:, 1], rtol=1e-6)
+    np.testing.assert_allclose(s_wide.cpu().numpy()[:, 0], s_def.cpu().numpy()[:, 0], rtol=1e-5, atol=1e-300)
+    again = B.adasum_reduce(w.grads, offs, radix=radix, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(again, wide)
+    narrow = B.adasum_reduce(w.grads, offs, radix=radix)
+    torch.cuda.synchronize()
+    assert narrow.dtype == dtype
+    assert_parity(narrow, ref, offs, what=f"radix {radix}, narrow result")
+    assert_bf16_rounding(narrow, ref, offs)
+    noalloc = torch.empty_like(narrow)
+    B.adasum_reduce(w.grads, offs, out=noalloc, radix=radix, noalloc=True)
+    torch.cuda.synchronize()
+    assert torch.equal(noalloc, narrow)
+
+
+def test_wide_first_pass_in_a_graph_and_with_a_plan():
+    K, radix = 64, 64
+    w = _workload(K, torch.bfloat16, 1401)
+    offs = w.layer_offsets
+    eager = B.adasum_reduce(w.grads, offs, radix=radix)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        replay = B.adasum_reduce(w.grads, offs, radix=radix, use_graph=True)
+        torch.cuda.synchronize()
+        assert torch.equal(replay, eager)
+        (w.grads[0] + 1).sum().item()      # the program's own work between replays
+    plan = B.Plan(K, offs, torch.bfloat16, radix=radix)
+    out = torch.empty_like(eager)
+    plan.execute(w.grads, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager)
+    plan.destroy()
+
+
+def test_wide_first_pass_where_it_is_not_offered():
+    offs = [0, 100, 5000]
+    g32 = [torch.randn(5000, device=DEV) for _ in range(64)]
+    g16 = [g.to(torch.bfloat16) for g in g32]
+    for radix in (32, 64):
+        with pytest.raises(B.AdasumError) as e:
+            B.adasum_reduce(g32, offs, radix=radix)                      # fp32 leaves
+        assert e.value.code == B.ERR_UNSUPPORTED
+        with pytest.raises(B.AdasumError) as e:
+            B.adasum_reduce(g16, offs, radix=radix, order=B.ORDER_LINEAR)   # left-to-right order
+        assert e.value.code == B.ERR_UNSUPPORTED
+        with pytest.raises(B.AdasumError) as e:
+            B.adasum_reduce(g16, offs, radix=radix, delta_start=g16[0].clone())   # the delta form
+        assert e.value.code == B.ERR_UNSUPPORTED
+    # few workers: the first pass is as wide as they need, the vector-unit kernels
+    assert B.plan_levels(12, 64) == [16] and B.plan_levels(2, 64) == [2]
+    out = B.adasum_reduce(g16[:12], offs, radix=64, out_dtype=torch.float32)
+    ref = B.adasum_reduce(g16[:12], offs, radix=16, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
