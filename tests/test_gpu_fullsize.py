@@ -51,8 +51,10 @@ def test_config4_full_size_sampled_layers(config4):
     stats = torch.zeros(w.n_layers, 2, dtype=torch.float64, device=DEV)
     outs = {}
     # (radix, output, fuse_siblings, separate_passes): the default path (passes feed the next one), the same
-    # with every pass reducing its own operands, and the three radix-2 schedules
+    # with every pass reducing its own operands, the wide first passes (radix 64: a single pass; radix 32:
+    # passes [32, 2]; Gram matrix from the matrix cores), and the three radix-2 schedules
     variants = ((0, torch.bfloat16, False, False), (0, torch.float32, False, False), (0, torch.bfloat16, False, True),
+                (64, torch.bfloat16, False, False), (64, torch.float32, False, False), (32, torch.bfloat16, False, False),
                 (2, torch.bfloat16, False, True), (2, torch.bfloat16, False, False), (2, torch.bfloat16, True, False))
     for radix, out_dtype, fuse, separate in variants:
         what = f"radix={radix} -> {out_dtype}{' (sibling-fused)' if fuse else ''}{' (separate passes)' if separate else ''}"
@@ -286,7 +288,8 @@ def test_config5_full_size_edge_layers():
     ref = oracle_reduce(w.grads, offs, layers=layers)
     say("oracle done")
     # the default path (the first pass leaves the second one's 8 x 8 Gram matrix), and every pass on its own
-    for radix, out_dtype, separate in ((0, torch.bfloat16, True), (0, torch.bfloat16, False), (0, torch.float32, False)):
+    for radix, out_dtype, separate in ((0, torch.bfloat16, True), (0, torch.bfloat16, False), (0, torch.float32, False),
+                                       (64, torch.bfloat16, False), (64, torch.float32, False)):
         out = B.adasum_reduce(w.grads, offs, out_dtype=out_dtype, radix=radix, separate_passes=separate)
         torch.cuda.synchronize()
         err = assert_parity(out, ref, offs, layers=layers, what=f"config5 radix {radix} {out_dtype}")
