@@ -418,20 +418,27 @@ def main():
         torch.cuda.empty_cache()
         # the one-pair-per-level schedule on the headline workload, then the other four configurations
         # (the headline workload is dropped before the first of them is generated)
-        # (name, radix, steps, warm-up, fuse_siblings, separate_passes); the first three reuse the headline buffers
-        todo = [("config4", 0, 20, 5, False, True), ("config4", 2, 10, 2, False, True), ("config4", 2, 10, 2, True, False),
+        # (name, radix, steps, warm-up, fuse_siblings, separate_passes); the first five reuse the headline
+        # buffers (radix 64 and 32: the opt-in wide first pass, whose Gram matrix comes from the matrix cores)
+        todo = [("config4", 64, 20, 5, False, False), ("config4", 32, 20, 5, False, False),
+                ("config4", 0, 20, 5, False, True), ("config4", 2, 10, 2, False, True), ("config4", 2, 10, 2, True, False),
                 ("config1", 0, 200, 20, False, False), ("config2", 0, 50, 5, False, False),
-                ("config3", 0, 20, 3, False, False), ("config5", 0, 10, 2, False, False)]
+                ("config3", 0, 20, 3, False, False), ("config5", 0, 10, 2, False, False),
+                ("config5", 64, 10, 2, False, False)]
+        w5 = None
         for name, radix, steps, warmup, fuse, separate in todo:
-            reuse = w if (radix or separate) else None
-            if reuse is None and w is not None:
+            reuse = w if (name == "config4" and (radix or separate)) else w5 if (name == "config5" and radix) else None
+            if name != "config4" and w is not None:
                 w = None
                 gc.collect()
                 torch.cuda.empty_cache()
+            if name == "config5" and w5 is None:
+                w5 = reuse = make_workload("config5", "cuda:0")
+                torch.cuda.synchronize()
             try:
                 t0 = time.perf_counter()
                 row = run_other(B, name, radix=radix, steps=steps, warmup=warmup, w=reuse, fuse=fuse, separate=separate)
-                print(f"[bench] {name}{' radix 2' if radix else ''}{' sibling-fused' if fuse else ''}"
+                print(f"[bench] {name}{f' radix {radix}' if radix else ''}{' sibling-fused' if fuse else ''}"
                       f"{' separate passes' if separate else ''}: "
                       f"{row['ms_per_step']:.4f} ms/step, "
                       f"{row['input_GBps']:.0f} GB/s of input ({time.perf_counter() - t0:.1f} s in all)",

@@ -113,7 +113,47 @@ static void check_schedule(int K, int radix, int order, const std::vector<int64_
             CHECK(static_cast<int64_t>(g / radices[lv + 1]) * ct * gram_entries(radices[lv + 1], true) <= de);
         }
     }
-    const Layout lay = make_layout(Kv, offs[L], L, n_tiles, ne, radices, order, K + 1, small_elems, node_type, de);
+    // a wide first pass (tree order, 16-bit leaves): its span table and what it leaves per span
+    int64_t n_spans = 0;
+    if (!radices.empty() && wide_radix(radices[0])) {
+        CHECK(order == ADASUM_ORDER_TREE && elem_bytes(dtype) == 2 && radices[0] <= kMaxWideRadix);
+        for (size_t lv = 1; lv < radices.size(); ++lv) CHECK(radices[lv] <= kMaxRadix);
+        const int n_parts = wide_part_count(offs[L]);
+        CHECK(n_parts >= 1 && (n_parts <= kWideParts || wide_part_elems(offs[L], n_parts / 2) > (int64_t{1} << 30)));
+        const int64_t E = wide_part_elems(offs[L], n_parts);
+        CHECK(E % kWidePartAlign == 0 && E * n_parts >= offs[L] && E <= (int64_t{1} << 30));
+        std::vector<adasum_tile> spans;
+        std::vector<int32_t> part_begin, layer_begin;
+        build_spans(offs.data(), L, n_parts, spans, part_begin, layer_begin);
+        n_spans = static_cast<int64_t>(spans.size());
+        CHECK(n_spans == count_spans(offs.data(), L, n_parts) && n_spans <= static_cast<int64_t>(n_parts) + L);
+        CHECK(static_cast<int>(part_begin.size()) == n_parts + 1 && part_begin[0] == 0 && part_begin[n_parts] == n_spans);
+        CHECK(static_cast<int>(layer_begin.size()) == L + 1 && layer_begin[L] == n_spans);
+        int64_t pos = 0;
+        for (int p = 0; p < n_parts; ++p) {
+            CHECK(part_begin[p] <= part_begin[p + 1]);
+            for (int32_t i = part_begin[p]; i < part_begin[p + 1]; ++i) {
+                const adasum_tile& t = spans[static_cast<size_t>(i)];
+                // inside its part and its layer, and the spans tile the elements in order
+                CHECK(t.len >= 1 && t.start == pos && t.start >= p * E && t.start + t.len <= (p + 1) * E);
+                CHECK(t.layer >= 0 && t.layer < L && t.start >= offs[t.layer] && t.start + t.len <= offs[t.layer + 1]);
+                CHECK(i >= layer_begin[t.layer] && i < layer_begin[t.layer + 1]);
+                pos = t.start + t.len;
+            }
+        }
+        CHECK(pos == offs[L]);
+    }
+    const Layout lay = make_layout(Kv, offs[L], L, n_tiles, ne, radices, order, K + 1, small_elems, node_type, de, n_spans);
+    {
+        // room for the widest pass's partials
+        int g = Kv;
+        for (size_t lv = 0; lv < radices.size(); ++lv) {
+            g = order == ADASUM_ORDER_LINEAR ? 1 : g / radices[lv];
+            const int64_t rows = wide_radix(radices[lv]) ? n_spans : n_tiles;
+            CHECK(lay.off_normparts - lay.off_partials >=
+                  static_cast<size_t>(g) * gram_partial_entries(radices[lv]) * static_cast<size_t>(rows) * sizeof(double));
+        }
+    }
     const size_t sections[] = {lay.off_slots, lay.off_partials, lay.off_normparts, lay.off_normcoarse, lay.off_gram,
                                lay.off_weights, lay.off_leafnorm, lay.off_small, lay.off_dotparts, lay.total};
     CHECK(lay.total - lay.off_dotparts >= static_cast<size_t>(de) * sizeof(double));
@@ -136,7 +176,7 @@ static void check_schedule(int K, int radix, int order, const std::vector<int64_
 int main(int argc, char** argv) {
     const int rounds = argc > 1 ? std::atoi(argv[1]) : 300;
     std::mt19937_64 rng(20060292);
-    const int radix_choices[] = {0, 2, 4, 8, 16};
+    const int radix_choices[] = {0, 2, 4, 8, 16, 32, 64};
     const int dtypes[] = {ADASUM_F32, ADASUM_BF16, ADASUM_F16, ADASUM_F64};
     const int64_t caps[] = {1, 7, 64, 512, 2048, kTileSmall, kTile};
     for (int it = 0; it < rounds; ++it) {
@@ -161,9 +201,10 @@ int main(int argc, char** argv) {
                 default: K = 1 + static_cast<int>(rng() % (1 << 20)); break;
             }
             const int dtype = dtypes[rng() % 4];
-            int radix = radix_choices[rng() % 5];
+            int radix = radix_choices[rng() % 7];
             if (radix > max_radix(dtype) || (radix == 0 && dtype == ADASUM_F64)) radix = 8;
-            const int order = (K <= 4096 && rng() % 2) ? ADASUM_ORDER_LINEAR : ADASUM_ORDER_TREE;
+            // (the wide radices exist in the tree order only)
+            const int order = (K <= 4096 && !wide_radix(radix) && rng() % 2) ? ADASUM_ORDER_LINEAR : ADASUM_ORDER_TREE;
             check_schedule(K, radix, order, offs, dtype);
         }
     }

@@ -139,6 +139,39 @@ def test_sibling_fusion_option_validation(lib):
     assert B.adasum_workspace_bytes(2, big, B.F32, radix=2, fuse_siblings=True) == B.adasum_workspace_bytes(2, big, B.F32, radix=2)
 
 
+def test_wide_radix_option_validation(lib):
+    """Radix 32 and 64 (the first pass's Gram matrix from the matrix cores): bf16 and fp16 inputs, the
+    tree order, no delta form; the passes above stay at 16 or less; the pass leaves its blocks per span."""
+    good = [0x1000 * (i + 1) for i in range(64)]
+    offs = [0, 8]
+    for radix in (32, 64):
+        assert _call_reduce(lib, good, 64, [0], B.BF16, 0x90000, _opts(radix=radix)) == B.OK
+        assert _call_reduce(lib, good, 64, offs, B.F32, 0x90000, _opts(radix=radix)) == B.ERR_UNSUPPORTED
+        assert _call_reduce(lib, good, 64, offs, B.F64, 0x90000, _opts(radix=radix)) == B.ERR_UNSUPPORTED
+        assert _call_reduce(lib, good, 64, offs, B.BF16, 0x90000, _opts(radix=radix, order=B.ORDER_LINEAR)) \
+            == B.ERR_UNSUPPORTED
+        assert _call_reduce(lib, good, 64, offs, B.F16, 0x90000, _opts(radix=radix, delta_start=0x80000)) \
+            == B.ERR_UNSUPPORTED
+    assert _call_reduce(lib, good, 64, offs, B.BF16, 0x90000, _opts(radix=128)) == B.ERR_UNSUPPORTED
+    assert B.plan_levels(64, 64) == [64] and B.plan_levels(64, 32) == [32, 2] and B.plan_levels(32, 64) == [32]
+    assert B.plan_levels(128, 64) == [64, 2] and B.plan_levels(4096, 64) == [64, 16, 4]
+    assert B.plan_levels(48, 64) == [64] and B.plan_levels(24, 64) == [32] and B.plan_levels(12, 64) == [16]
+    # a single pass keeps no nodes: blocks of 3 x 1024 doubles per span (here 35 parts of 2048 elements,
+    # one more span where the layer boundary cuts a part), nothing per element
+    big = [0, 1000, 70632]
+    n64 = B.adasum_workspace_bytes(64, big, B.BF16, radix=64)
+    assert 36 * 3072 * 8 <= n64 <= 36 * 3072 * 8 + (1 << 20)
+    assert n64 < B.adasum_workspace_bytes(64, big, B.BF16)
+    # step entry points: 32 and 64 operands for 16-bit storage only
+    x = (C.c_void_p * 64)(*good)
+    o = (C.c_int64 * 2)(0, 8)
+    assert lib.adasum_group_gram(x, 64, o, 1, B.F32, 0x90000, None) == B.ERR_UNSUPPORTED
+    assert lib.adasum_group_gram(x, 64, o, 1, B.BF16, None, None) == B.ERR_INVALID_ARG
+    assert lib.adasum_group_combine(x, 32, o, 1, B.F32, 0xa0000, 0x90000, B.F32, None, None) == B.ERR_UNSUPPORTED
+    assert lib.adasum_group_weights(0x9000, 64, 0, 0, 0xa000, None) == B.OK
+    assert lib.adasum_group_weights(0x9000, 128, 1, 0, 0xa000, None) == B.ERR_UNSUPPORTED
+
+
 def test_fp64_storage_limits(lib):
     good = [0x1000, 0x2000]
     offs = [0, 8]
