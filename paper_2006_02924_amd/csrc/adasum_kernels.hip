@@ -47,6 +47,12 @@
 #define ADASUM_BF16_DOT2 1
 #endif
 
+// Blocks the wide Gram pass (radix 32, 64) loads ahead of the one it multiplies: 1 or 2.  Measured
+// alike (6.21 and 6.24 ms on the K = 64 BERT-Large case); 1 leaves the compiler 32 registers more.
+#ifndef ADASUM_WIDE_AHEAD
+#define ADASUM_WIDE_AHEAD 1
+#endif
+
 // Scratch memory of the entry point that allocates nothing (adasum_reduce_noalloc): tile
 // tables and workspace of one reduction.  One copy per GPU, held until the process ends; its
 // device address comes from hipGetSymbolAddress (static_scratch below), never from this name.
@@ -1162,7 +1168,7 @@ parts_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles, const in
 // the speed as well: a wave that fetches 128 bytes of each of 64 rows per step streams at 6.0 TB/s,
 // one that fetches 512 bytes or more of 16 rows at 7.0 (measured on the bare access pattern), so
 // wave w loads rows w, w + 4, ... of the block, 512 bytes or 1 KB of a row per load instruction,
-// two blocks ahead of the multiplies.  The block goes through LDS (two buffers, one barrier per
+// one block ahead of the multiplies.  The block goes through LDS (two buffers, one barrier per
 // block) to reach the operand layout; every wave then multiplies its quarter of the block's columns
 // for all rows.  The products are exact; the matrix cores add the 64 of a wave's quarter in fp32,
 // the blocks' sums are added with ordinary fp32 additions (round to nearest), fp64 above the wave.
@@ -1207,10 +1213,12 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
     constexpr int RPI = 64 / CH;                  // rows one load instruction covers: 2 or 1
     constexpr int NLD = R / 4 / RPI;              // load instructions per wave and block: 8
     constexpr int KW = CH / 8;                    // 16-element multiply steps per wave and block: 4 or 8
+    constexpr int AHEAD = ADASUM_WIDE_AHEAD;      // blocks whose loads are in flight while one is multiplied
+    static_assert(AHEAD == 1 || AHEAD == 2, "");
     constexpr int PITCH = CH * 16 + 16;           // bytes per row in LDS (padded: conflict-free operand reads)
     constexpr int BUF = R * PITCH;
     constexpr int NPW = NB * 1024;
-    static_assert(NLD == 8 && 2 * BUF >= NB * 16 * 64 * (int)sizeof(double), "LDS is reused for the waves' sums");
+    static_assert(NLD == 8 && 2 * BUF >= 4 * NPW * (int)sizeof(float), "LDS is reused for the waves' sums");
 
     __shared__ __align__(16) unsigned char lds[2 * BUF];
     __shared__ const T* rowptr[R];
@@ -1228,9 +1236,6 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
 
     // what this lane loads: granule `chunk` of rows (lrow + RPI i) * 4 + wave, i = 0 .. NLD - 1
     const int chunk = lane % CH, lrow = lane / CH;
-    const T* row[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) row[i] = rowptr[(i * RPI + lrow) * 4 + wave];
     const int wr = (lrow * 4 + wave) * PITCH + chunk * 16;
     // what it multiplies: row m of P (and of Q), k-half h of the wave's multiply steps
     const int m = lane & 31, h = lane >> 5;
@@ -1258,23 +1263,21 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
 
     for (int sp = part_begin[part]; sp < part_begin[part + 1]; ++sp) {   // (uniform: the barriers below match)
         const Split s = split_tile<G>(spans[sp]);
-        const T* src[NLD];
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) src[i] = row[i] + s.bs + chunk * G;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) sum[b][v] = 0.f;
         const int nsteps = (s.ng + CH - 1) / CH;      // the same for every wave
-        u32x4 stage[2][NLD];                          // the loads of two blocks in flight per wave
+        u32x4 stage[AHEAD][NLD];                      // the loads of AHEAD blocks in flight per wave
         // No branch around a load (the waits between loads and their use are then counted exactly, and
         // younger loads stay in flight): a lane past the end of the tile's granules re-reads the last
         // granule, and what it fetched is replaced by zeros when it is stored to LDS.
+        // (the row pointers are read from LDS every time: eight more registers per lane would spill)
         auto fetch = [&](u32x4 (&into)[NLD], int step) {
             const int gi = step * CH + chunk;
-            const long long off = static_cast<long long>((gi < s.ng ? gi : s.ng - 1) - chunk) * G;
+            const long long off = s.bs + static_cast<long long>(gi < s.ng ? gi : s.ng - 1) * G;
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) into[i] = stream_load_global(src[i] + off);
+            for (int i = 0; i < NLD; ++i) into[i] = stream_load_global(rowptr[(i * RPI + lrow) * 4 + wave] + off);
         };
         auto store_block = [&](unsigned char* buf, const u32x4 (&from)[NLD], int step) {
             const bool live = step * CH + chunk < s.ng;
@@ -1295,8 +1298,8 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
             for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
         if (nsteps > 0) {
-            fetch(stage[0], 0);
-            fetch(stage[1], 1);
+#pragma unroll
+            for (int a = 0; a < AHEAD; ++a) fetch(stage[a], a);
         }
         for (int step0 = 0; step0 < nsteps; step0 += 2) {
 #pragma unroll
@@ -1304,8 +1307,8 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
                 // block step0 + a (one past the end multiplies zeros) through buffer a: the buffer's last
                 // readers, two blocks back, passed the barrier of the block in between
                 unsigned char* buf = lds + a * BUF;
-                store_block(buf, stage[a], step0 + a);
-                fetch(stage[a], step0 + a + 2);
+                store_block(buf, stage[a % AHEAD], step0 + a);
+                fetch(stage[a % AHEAD], step0 + a + AHEAD);
                 __syncthreads();
 #pragma unroll
                 for (int j = 0; j < KW; ++j) {
@@ -1339,26 +1342,20 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
             flush(acc);
         }
 
-        // the four waves' sums, added in a fixed order through LDS (the staging area, now free)
-        double* red = reinterpret_cast<double*>(lds);
+        // the four waves' sums go through LDS (the staging area, now free) and are added in a fixed
+        // order, in fp64, by all lanes: entry e of wave w sits at w * NPW + e
+        float* red = reinterpret_cast<float*>(lds);
         double* out = partials + (static_cast<long long>(g) * n_spans + sp) * NPW;
         __syncthreads();
-#pragma unroll 1
-        for (int w = 0; w < 4; ++w) {
-            if (wave == w) {
 #pragma unroll
-                for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int i = (b * 16 + v) * 64 + lane;
-                        const double mine = static_cast<double>(sum[b][v]);
-                        if (w == 0) red[i] = mine;
-                        else if (w < 3) red[i] += mine;
-                        else out[i] = red[i] + mine;
-                    }
-            }
-            __syncthreads();
-        }
+            for (int v = 0; v < 16; ++v) red[wave * NPW + (b * 16 + v) * 64 + lane] = sum[b][v];
+        __syncthreads();
+        for (int e = tid; e < NPW; e += kThreads)
+            out[e] = ((static_cast<double>(red[e]) + static_cast<double>(red[NPW + e])) +
+                      static_cast<double>(red[2 * NPW + e])) + static_cast<double>(red[3 * NPW + e]);
+        __syncthreads();   // (the next span stages into the same memory)
     }
 }
 
