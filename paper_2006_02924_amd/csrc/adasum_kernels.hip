@@ -1267,20 +1267,26 @@ gram_wide_kernel(const Operands ops, const adasum_tile* __restrict__ spans, cons
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) sum[b][v] = 0.f;
-        const int nsteps = (s.ng + CH - 1) / CH;      // the same for every wave
+        // Blocks start at multiples of the block length in the fused buffer, so that a lane group's
+        // 512 bytes or 1 KB of a row are whole 128-byte lines whatever the layer's offset: the span's
+        // granules are numbers g0 .. g0 + ng - 1 of that grid.
+        const long long base = s.bs / (CH * G) * (CH * G);
+        const int g0 = static_cast<int>((s.bs - base) / G), g1 = g0 + s.ng;
+        const int nsteps = s.ng > 0 ? (g1 + CH - 1) / CH : 0;   // the same for every wave
         u32x4 stage[AHEAD][NLD];                      // the loads of AHEAD blocks in flight per wave
         // No branch around a load (the waits between loads and their use are then counted exactly, and
-        // younger loads stay in flight): a lane past the end of the tile's granules re-reads the last
-        // granule, and what it fetched is replaced by zeros when it is stored to LDS.
+        // younger loads stay in flight): a lane outside the span's granules re-reads the nearest one,
+        // and what it fetched is replaced by zeros when it is stored to LDS.
         // (the row pointers are read from LDS every time: eight more registers per lane would spill)
         auto fetch = [&](u32x4 (&into)[NLD], int step) {
             const int gi = step * CH + chunk;
-            const long long off = s.bs + static_cast<long long>(gi < s.ng ? gi : s.ng - 1) * G;
+            const long long off = base + static_cast<long long>(gi < g0 ? g0 : gi < g1 ? gi : g1 - 1) * G;
 #pragma unroll
             for (int i = 0; i < NLD; ++i) into[i] = stream_load_global(rowptr[(i * RPI + lrow) * 4 + wave] + off);
         };
         auto store_block = [&](unsigned char* buf, const u32x4 (&from)[NLD], int step) {
-            const bool live = step * CH + chunk < s.ng;
+            const int gi = step * CH + chunk;
+            const bool live = gi >= g0 && gi < g1;
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 u32x4 v = from[i];
