@@ -2,10 +2,10 @@
 """Every layer of one configuration against the CPU oracle, at full size, plus the
 oracle's own time on this host: one row of the results table.
 
-    python -m tests.full_parity_report --config 4 [--threads 16] [--out-dtype same|f32]
+    python -m tests.full_parity_report --config 4 [--threads 16] [--out-dtype same|f32] [--radix 64]
 
-The library reduces the workload once (default path, the launch configuration
-bench.py times).  The oracle then reduces every layer from the stored bits copied
+The library reduces the workload once (default path, or the radix given: the launch
+configuration bench.py times).  The oracle then reduces every layer from the stored bits copied
 back from the device -- first on one thread, then as a plain parallel-for over
 layers on `--threads` threads (NumPy's own threading pinned to 1) -- and each
 layer's relative L2 error is taken.  Prints progress lines and ONE JSON line.
@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--out-dtype", default="same", choices=["same", "f32"])
     ap.add_argument("--skip-single", action="store_true", help="only the parallel oracle pass")
+    ap.add_argument("--radix", type=int, default=0, help="0 = library default")
     args = ap.parse_args()
 
     import torch
@@ -48,12 +49,13 @@ def main():
     torch.cuda.synchronize()
     out_dtype = w.dtype if args.out_dtype == "same" else torch.float32
     print(f"[report] {w.name}: K={w.K} N={w.N} layers={w.n_layers} {w.dtype} -> {out_dtype}", flush=True)
-    out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype)
+    print(f"[report] radix {args.radix}: passes {B.plan_levels(w.K, args.radix)}", flush=True)
+    out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=out_dtype, radix=args.radix)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     reps = 5
     for _ in range(reps):
-        B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype)
+        B.adasum_reduce(w.grads, w.layer_offsets, out, out_dtype=out_dtype, radix=args.radix)
     torch.cuda.synchronize()
     gpu_ms = (time.perf_counter() - t0) / reps * 1e3
     got = U.to_f64(out)
@@ -108,7 +110,7 @@ def main():
     worst = int(np.argmax(err))
     big = sizes >= U.TINY_LAYER
     row = {
-        "config": args.config, "K": w.K, "layers": w.n_layers, "layers_checked": int(w.n_layers - len(skipped)),
+        "config": args.config, "K": w.K, "radix": args.radix, "passes": B.plan_levels(w.K, args.radix), "layers": w.n_layers, "layers_checked": int(w.n_layers - len(skipped)),
         "layers_without_reference": skipped, "out_dtype": str(out_dtype).replace("torch.", ""),
         "gpu_ms": gpu_ms, "input_GBps": w.input_bytes / gpu_ms / 1e6,
         "max_rel_l2": float(err.max()), "max_rel_l2_layer": worst, "max_rel_l2_layer_size": int(sizes[worst]),
