@@ -105,9 +105,9 @@ typedef struct adasum_options {
                                   inputs in ADASUM_ORDER_TREE without delta_start (else
                                   ADASUM_ERR_UNSUPPORTED): with 528 or 2080 entries per group the
                                   Gram matrix is a dense contraction X X^T and is computed on the
-                                  matrix cores (exact 16-bit products, fp32 sums of 64 or 128 of
-                                  them, fp64 above); K = 64 is then a single pass.  Later passes,
-                                  over fp32 nodes, stay at 16 or less;
+                                  matrix cores (exact 16-bit products, summed in fp32 within a
+                                  workgroup's span of a layer, fp64 above); K = 64 is then a single
+                                  pass.  Later passes, over fp32 nodes, stay at 16 or less;
                                   0 = library default (16; 8 for fp64 and the delta form).
                                   The result is the same binary tree. */
     int32_t  order;            /* ADASUM_ORDER_TREE (default) | ADASUM_ORDER_LINEAR */
@@ -239,7 +239,8 @@ ADASUM_API int adasum_plan_destroy(adasum_plan* plan);
  *          (ADASUM_ERR_INVALID_ARG otherwise); NULL = all defaults
  * Limit: tables + workspace of the problem (about adasum_workspace_bytes() plus 16 bytes per
  * 512 elements) must fit the array, else ADASUM_ERR_TOO_LARGE and nothing is enqueued.  That
- * holds for e.g. ResNet-50 (25.6 M elements) at K <= 16, or 3 M elements at K = 64.
+ * holds for e.g. ResNet-50 (25.6 M elements) at K <= 16, or 3 M elements at K = 64 -- and, since a
+ * single pass keeps no intermediate nodes, for BERT-Large (335 M elements) at K <= 64 with radix 64.
  * Every call on one GPU uses the same array and finds the previous call's contents there:
  * each call rebuilds all it reads (nothing needs to start at zero), and two calls that
  * overlap in time on one GPU -- on different streams without an ordering between them -- race.

@@ -8,7 +8,9 @@
 // what it writes so the next pass needs only the cross dot products.  Layers
 // of a few elements are redone by the definition in fp64 (small_*_kernel).
 //
-// The work is HBM-bound streaming: no matrix cores.  Every workgroup owns one
+// The work is HBM-bound streaming on the vector units; only the opt-in wide first pass
+// (radix 32 and 64, gram_wide_kernel below), whose Gram matrix is a dense contraction,
+// uses the matrix cores.  Every workgroup owns one
 // tile (consecutive elements inside one layer): a long one (kTile elements) in
 // the read-only Gram pass, where a workgroup's start-up and its reduction must
 // be amortised, and a short one (one 16-byte load per lane and operand) in the
