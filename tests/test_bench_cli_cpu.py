@@ -24,10 +24,13 @@ def test_traffic_table_is_readable_and_names_its_commit():
     import sys
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.measured_traffic("config4", "combine<bf16,f32,R=16>")
-    assert t is not None and t["source"] == "profiles/hbm_traffic_table.md"
-    # 64 bf16 leaves read and 4 fp32 nodes written over N = 335 141 888, give or take a few per cent
-    assert 0.99 < t["bytes"] / (64 * 335141888 * 2 + 4 * 335141888 * 4) < 1.05
-    assert len(t["measured_at_commit"]) >= 7
+    # the dominant kernel of the default path, of the same with separate passes, and of the single wide pass
+    for key, kernel, out_bytes in (("config4", "combine<bf16,f32,R=16>+gram4", 4 * 4), ("config4_separate", "combine<bf16,f32,R=16>", 4 * 4),
+                                   ("config4_radix64", "combine<bf16,bf16,R=64>", 2)):
+        t = bench.measured_traffic(key, kernel)
+        assert t is not None and t["source"] == "profiles/hbm_traffic_table.md", (key, kernel)
+        # 64 bf16 leaves read and the nodes (or the result) written over N = 335 141 888, give or take a few per cent
+        assert 0.99 < t["bytes"] / (64 * 335141888 * 2 + 335141888 * out_bytes) < 1.05
+        assert len(t["measured_at_commit"]) >= 7
     assert bench.measured_traffic("config4", "no such kernel") is None
     assert bench.pair_per_level_bytes(64, 335141888, 2, 2) == 1002 * 335141888
