@@ -23,7 +23,8 @@
  * Supported magnitudes.  Products of two stored values are formed and summed in fp32
  * lanes (fp64 for fp64 storage), so for fp32 and bf16 storage a layer's values must
  * keep their squares inside the fp32 range: root-mean-square magnitude of a layer
- * between about 1e-17 and 1e+17 (checked against the oracle at 1e-15 and 1e+15).
+ * between about 1e-17 and 1e+17 (checked against the oracle at 1e-15 and 1e+15; a first
+ * pass of radix 32 or 64 sums up to 2^18 products in fp32 before it widens them: 1e+16).
  * fp16 storage cannot leave that range; fp64 storage has fp64's (1e-150 .. 1e+150).
  * Outside it the result of THAT layer is not the operator's: squares that underflow
  * to zero put the layer on (or near) the zero-norm convention, a plain sum of the

@@ -190,8 +190,9 @@ def test_empty_and_degenerate_tables():
             assert_parity(out, oracle_reduce(g, offs), offs, what=str(offs))
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("K,radix", [(8, 0), (8, 2), (64, 0), (5, 0)])
+@pytest.mark.parametrize("K,radix,dtype", [(K, radix, dt) for K, radix in [(8, 0), (8, 2), (64, 0), (5, 0)]
+                                           for dt in (torch.float32, torch.bfloat16)] +
+                         [(64, 64, torch.bfloat16), (40, 64, torch.bfloat16), (128, 32, torch.bfloat16)])
 def test_nan_and_inf_stay_inside_their_layer(K, radix, dtype):
     """IEEE propagation: a NaN or an infinity in one worker's layer makes that layer's result
     NaN in every element (the scalars of the first node that sees it are NaN or Inf - Inf), in the
@@ -930,8 +931,9 @@ def test_binding_rejects_buffers_the_kernels_would_overrun():
         B.adasum_reduce(w.grads, w.layer_offsets, layer_stats=torch.zeros(len(sizes), 2, dtype=torch.float64))
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("K,radix", [(8, 0), (64, 0), (16, 2)])
+@pytest.mark.parametrize("K,radix,dtype", [(K, radix, dt) for K, radix in [(8, 0), (64, 0), (16, 2)]
+                                           for dt in (torch.float32, torch.bfloat16)] +
+                         [(64, 64, torch.bfloat16), (32, 32, torch.bfloat16)])   # (the wide first pass: fp32 sums too)
 def test_supported_magnitude_range(K, radix, dtype):
     """Layers at the ends of the documented magnitude range (rms 1e-15 and 1e+15) beside ordinary
     ones: products are formed in fp32 lanes, so the squares (1e-30, 1e+30) must stay inside fp32.
