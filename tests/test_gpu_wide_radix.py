@@ -112,3 +112,77 @@ def test_wide_first_pass_where_it_is_not_offered():
     ref = B.adasum_reduce(g16[:12], offs, radix=16, out_dtype=torch.float32)
     torch.cuda.synchronize()
     assert torch.equal(out, ref)
+
+
+# ---------------------------------------------------------------------------
+# seeded random cases of the wide first pass: parity, the entry point without allocation, and
+# nothing written outside the result, a caller's workspace and the statistics
+# ---------------------------------------------------------------------------
+
+def _draw_wide_case(case):
+    rng = np.random.default_rng(50_000 + case)
+    K = int(rng.choice([17, 20, 24, 31, 32, 33, 40, 48, 63, 64, 65, 100, 128, 200]))
+    dtype = [torch.bfloat16, torch.float16][int(rng.integers(2))]
+    out_dtype = torch.float32 if rng.random() < 0.5 else dtype
+    radix = int(rng.choice([32, 64]))
+    sizes = []
+    for _ in range(int(rng.integers(1, 12))):
+        kind = int(rng.integers(6))
+        if kind == 0:
+            sizes.append(0)
+        elif kind == 1:
+            sizes.append(int(rng.integers(1, 20)))
+        elif kind == 2:
+            sizes.append(int(rng.integers(20, 3000)))
+        elif kind == 3:
+            sizes.append(int(rng.choice([2048, 16384, 65536]) + rng.integers(-9, 10)))
+        elif kind == 4:
+            sizes.append(int(rng.integers(3000, 200000)))
+        else:
+            sizes.append(int(rng.choice([512, 1024, 4096, 8192])))
+    return K, dtype, out_dtype, radix, sizes, bool(rng.random() < 0.5)
+
+
+def _guarded(nbytes, align, fill=0xA5, guard=4096):
+    whole = torch.full((nbytes + 2 * guard + align,), fill, dtype=torch.uint8, device=DEV)
+    off = guard + (-(whole.data_ptr() + guard)) % align
+    return whole, whole[off:off + nbytes], off
+
+
+def _guards_intact(whole, off, nbytes, fill=0xA5):
+    return bool((whole[:off] == fill).all()) and bool((whole[off + nbytes:] == fill).all())
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_cases_of_the_wide_first_pass(block):
+    for case in range(block * 8, (block + 1) * 8):
+        K, dtype, out_dtype, radix, sizes, stats_on = _draw_wide_case(case)
+        say(f"wide case {case}: K={K} {dtype}->{out_dtype} radix={radix} passes {B.plan_levels(K, radix)} "
+            f"stats={stats_on} sizes={sizes}")
+        scale = W.log_uniform_scales(len(sizes), 90 + case, lo_exp=-2.0, hi_exp=0.0) if dtype == torch.float16 else None
+        w = (W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=60_000 + case, scale=scale)
+             if scale is not None else W.correlated_gaussian(sizes, K, dtype=dtype, device=DEV, seed=60_000 + case))
+        offs = w.layer_offsets
+        ref = oracle_reduce(w.grads, offs)
+        before = [g.clone() for g in w.grads]
+        esize = torch.empty(0, dtype=out_dtype).element_size()
+        out_whole, out_bytes, out_off = _guarded(w.N * esize, 16)
+        out = out_bytes.view(out_dtype)
+        need = B.adasum_workspace_bytes(K, offs, B._code_of(dtype), radix=radix, out_dtype_code=B._code_of(out_dtype))
+        ws_whole, ws, ws_off = _guarded(need, 256)
+        stats_whole, stats_bytes, stats_off = _guarded(len(sizes) * 16, 8)
+        stats = stats_bytes.view(torch.float64).view(len(sizes), 2) if stats_on else None
+        got = B.adasum_reduce(w.grads, offs, out, out_dtype=out_dtype, radix=radix, workspace=ws, layer_stats=stats)
+        torch.cuda.synchronize()
+        assert_parity(got, ref, offs, what=f"wide case {case}")
+        assert _guards_intact(out_whole, out_off, w.N * esize), f"case {case}: wrote outside out"
+        assert _guards_intact(ws_whole, ws_off, need), f"case {case}: wrote outside the workspace"
+        assert _guards_intact(stats_whole, stats_off, len(sizes) * 16), f"case {case}: wrote outside layer_stats"
+        for g, b in zip(w.grads, before):
+            assert torch.equal(g, b), f"case {case}: an input changed"
+        # the library's own workspace and the entry point that allocates nothing: the same bits
+        own = B.adasum_reduce(w.grads, offs, out_dtype=out_dtype, radix=radix)
+        quiet = torch.full_like(own, float("nan"))
+        B.adasum_reduce(w.grads, offs, quiet, out_dtype=out_dtype, radix=radix, noalloc=True)
+        torch.cuda.synchronize()
+        assert torch.equal(own, got) and torch.equal(quiet.view(torch.uint8), got.view(torch.uint8)), case
