@@ -142,6 +142,7 @@ inline int gram_partial_entries(int R) { return wide_radix(R) ? wide_blocks(R) *
 // layer_begin[l] .. [l + 1] those of layer l (both runs are contiguous: the spans are sorted by start).
 constexpr int kWideParts = 512;          // two workgroups of the wide Gram kernel fit a compute unit: 2 x 256
 constexpr int kWidePartAlign = 2048;     // elements; a part holds at least this many
+constexpr int64_t kWideMaxPart = 1 << 20;   // and at most this many (bounds the fp32 sums of the wide Gram pass)
 int wide_part_count(int64_t N);
 int64_t wide_part_elems(int64_t N, int n_parts);
 void build_spans(const int64_t* layer_offsets, int n_layers, int n_parts, std::vector<adasum_tile>& spans,

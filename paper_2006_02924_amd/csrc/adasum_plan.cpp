@@ -89,8 +89,9 @@ int wide_part_count(int64_t N) {
     int64_t parts = (N + kWidePartAlign - 1) / kWidePartAlign;
     if (parts > kWideParts) parts = kWideParts;
     if (parts < 1) parts = 1;
-    // (a span's length is a 32-bit count)
-    while (wide_part_elems(N, static_cast<int>(parts)) > (int64_t{1} << 30)) parts *= 2;
+    // a part is what one wave quarter sums in fp32 before it widens: kept to kWideMaxPart elements, so
+    // very long buffers get more parts than the chip holds workgroups (they run in several rounds)
+    while (wide_part_elems(N, static_cast<int>(parts)) > kWideMaxPart) parts *= 2;
     return static_cast<int>(parts);
 }
 

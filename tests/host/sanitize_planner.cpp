@@ -119,9 +119,9 @@ static void check_schedule(int K, int radix, int order, const std::vector<int64_
         CHECK(order == ADASUM_ORDER_TREE && elem_bytes(dtype) == 2 && radices[0] <= kMaxWideRadix);
         for (size_t lv = 1; lv < radices.size(); ++lv) CHECK(radices[lv] <= kMaxRadix);
         const int n_parts = wide_part_count(offs[L]);
-        CHECK(n_parts >= 1 && (n_parts <= kWideParts || wide_part_elems(offs[L], n_parts / 2) > (int64_t{1} << 30)));
+        CHECK(n_parts >= 1 && (n_parts <= kWideParts || wide_part_elems(offs[L], n_parts / 2) > kWideMaxPart));
         const int64_t E = wide_part_elems(offs[L], n_parts);
-        CHECK(E % kWidePartAlign == 0 && E * n_parts >= offs[L] && E <= (int64_t{1} << 30));
+        CHECK(E % kWidePartAlign == 0 && E * n_parts >= offs[L] && E <= kWideMaxPart);
         std::vector<adasum_tile> spans;
         std::vector<int32_t> part_begin, layer_begin;
         build_spans(offs.data(), L, n_parts, spans, part_begin, layer_begin);

@@ -374,3 +374,61 @@ def test_buffers_longer_than_2_31_elements():
     del grads, outs
     B.shutdown()
     torch.cuda.empty_cache()
+
+
+def test_wide_first_pass_on_a_buffer_with_more_parts_than_workgroup_slots():
+    """K = 32 workers of 2^30 + 4133 bf16 elements (2 GB per buffer, 69 GB in all), radix 32: the
+    wide Gram pass keeps a part to 2^20 elements, so this buffer has 1024 parts -- more workgroups
+    than the chip holds at once -- and one layer of 2^30 elements spans all of them.  The small layers
+    against the oracle; the long one against the default schedule (the same tree: equal to the
+    rounding of the scalars) and on a slice against the oracle's operator applied with the weights
+    that the step entry points return."""
+    from oracle import adasum_oracle as O
+
+    free, _ = torch.cuda.mem_get_info()
+    if free < 90e9:
+        pytest.skip("needs ~90 GB of free HBM")
+    K = 32
+    sizes = [4096, 1 << 30, 37]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).tolist()
+    N = offs[-1]
+    gen = torch.Generator(device=DEV).manual_seed(79)
+    say(f"generating K={K} x N={N} bf16")
+    common = torch.empty(N, dtype=torch.bfloat16, device=DEV).normal_(generator=gen)
+    grads = []
+    for k in range(K):
+        g = torch.empty(N, dtype=torch.bfloat16, device=DEV).normal_(generator=gen)
+        g.mul_(0.8).add_(common, alpha=0.6)    # positively correlated workers
+        grads.append(g)
+    del common
+    torch.cuda.synchronize()
+    assert B.plan_levels(K, 32) == [32]
+    stats = torch.zeros(len(sizes), 2, dtype=torch.float64, device=DEV)
+    wide = B.adasum_reduce(grads, offs, out_dtype=torch.float32, radix=32, layer_stats=stats)
+    torch.cuda.synchronize()
+    B.shutdown()
+    base = B.adasum_reduce(grads, offs, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    B.shutdown()
+    for l in (0, 2):
+        lo, hi = offs[l], offs[l + 1]
+        ref = O.adasum_tree([to_f64(g[lo:hi]) for g in grads])
+        err = float(O.rel_l2_per_layer(to_f64(wide[lo:hi]), ref, [0, hi - lo])[0])
+        say(f"  layer {l} [{lo}, {hi}): rel-L2 {err:.3e}")
+        assert err <= 1e-5, (l, err)
+    lo, hi = offs[1], offs[2]
+    # the long layer: both schedules are the same linear combination of the leaves; compare on slices
+    for a in (lo, lo + (1 << 29) - 1000, hi - 70000):
+        x, y = to_f64(wide[a:a + 70000]), to_f64(base[a:a + 70000])
+        d = float(np.linalg.norm(x - y) / np.linalg.norm(y))
+        say(f"  long layer, slice at {a}: wide against default {d:.3e}")
+        assert d <= 2e-6, (a, d)
+    # its squared-norm statistics against a direct sum over the stored bits of one worker pair
+    s = stats.cpu().numpy()
+    leaves = sum(float((g[lo:hi].float() ** 2).sum(dtype=torch.float64)) for g in grads)
+    assert abs(s[1, 1] - leaves) <= 2e-6 * leaves, (s[1, 1], leaves)
+    root = float((wide[lo:hi].double() ** 2).sum())
+    assert abs(s[1, 0] - root) <= 1e-5 * root, (s[1, 0], root)
+    del wide, base, grads
+    B.shutdown()
+    torch.cuda.empty_cache()
