@@ -1161,8 +1161,8 @@ parts_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles, const in
 // of G.  R = 64: rows 0..31 are P, rows 32..63 are Q, blocks P P^T, P Q^T, Q Q^T; R = 32: P P^T only.
 //
 // The elements are cut into as many equal parts as the chip holds workgroups of this kernel (two
-// per compute unit), and a part into spans at the layer boundaries; a workgroup (four waves) takes
-// one part and leaves one set of blocks per span.  (Per fixed-size tile, as the other passes do it,
+// per compute unit; more, of at most 2^20 elements, for very long buffers), and a part into spans at
+// the layer boundaries; a workgroup (four waves) takes one part and leaves one set of blocks per span.  (Per fixed-size tile, as the other passes do it,
 // the pass would write 24 KB every 8 MB it reads: 0.3 % of the traffic, and yet stores sprinkled
 // over a stream of loads cost it 9 % of its speed, 6.9 instead of 6.3 ms on the K = 64 BERT-Large
 // case.  With spans the stores are as few as they can be.)
