@@ -5,4 +5,4 @@ library ``libadasum.so`` (hand-written gfx950 HIP kernels);
 ``paper_2006_02924_amd.workloads`` makes seeded synthetic inputs.  There is no
 CPU fallback: calling the binding without the built library raises.
 """
-__version__ = "0.2.0"
+__version__ = "0.3.0"

@@ -1536,7 +1536,7 @@ const char* adasum_strerror(int code) {
 
 int adasum_last_hip_error(void) { return g_last_hip_error; }
 
-const char* adasum_version(void) { return "libadasum 0.2.0 (gfx950)"; }
+const char* adasum_version(void) { return "libadasum 0.3.0 (gfx950)"; }
 
 int adasum_shutdown(void) {
     std::lock_guard<std::mutex> lock(g_mutex);
