@@ -235,8 +235,9 @@ struct Plan {
     hipStream_t capture_stream = nullptr;
 
     // The combine tile table for this input dtype and radix (device copy made on first use).
-    int comb_tiles(int dtype, int R, TileSet* out) {
-        const int cap = combine_tile_capacity(dtype, R);
+    int comb_tiles(int dtype, int R, TileSet* out) { return comb_tiles_of(combine_tile_capacity(dtype, R), out); }
+    // ... and the one of a given capacity
+    int comb_tiles_of(int cap, TileSet* out) {
         auto it = comb_tables.find(cap);
         if (it == comb_tables.end()) {
             if (borrowed) return ADASUM_ERR_INVALID_ARG;   // such a plan comes with all its tables
@@ -281,10 +282,11 @@ std::vector<std::unique_ptr<Plan>> g_plans;   // least recently used first
 constexpr size_t kMaxPlans = 64;
 
 // Builds a plan (host tables, their device copies; no workspace yet) on the current device.
-// Radix whose combine tile table pass lv uses: a pass that feeds the next one works with one wave per
-// group, like radix 16.
-int table_radix(bool feed, const std::vector<int>& radices, size_t lv) {
-    return feed && pass_feeds_next(radices, lv) ? 16 : radices[lv];
+// Capacity of the combine tile table pass lv uses, reading operands of type `dtype`: a pass that feeds
+// the next one works with one wave per group whatever its radix.
+int table_capacity(bool feed, const std::vector<int>& radices, size_t lv, int dtype) {
+    return feed && pass_feeds_next(radices, lv) ? feed_tile_capacity(dtype, radices[lv])
+                                                : combine_tile_capacity(dtype, radices[lv]);
 }
 
 // `no_feed`: the delta form, the step plans and separate_passes: no pass feeds the next.
@@ -556,8 +558,8 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     // nothing below may allocate, so the ladder can be captured into a graph.
     std::vector<TileSet> comb_sets(n_levels);
     for (int lv = 0; lv < n_levels; ++lv) {
-        const int rc = p->comb_tiles(lv == 0 ? dtype : node_dtype(dtype), table_radix(feed, p->radices, lv),
-                                     &comb_sets[lv]);
+        const int rc = p->comb_tiles_of(table_capacity(feed, p->radices, lv, lv == 0 ? dtype : node_dtype(dtype)),
+                                        &comb_sets[lv]);
         if (rc != ADASUM_OK) return rc;
     }
     {
@@ -844,7 +846,7 @@ int prebuild_tables(Plan* p, int dtype, int order) {
         TileSet ct;
         // (the left-to-right order reads leaves, in their storage type, in every pass)
         const bool leaves = lv == 0 || order == ADASUM_ORDER_LINEAR;
-        const int rc = p->comb_tiles(leaves ? dtype : node_dtype(dtype), table_radix(p->feed != 0, p->radices, lv), &ct);
+        const int rc = p->comb_tiles_of(table_capacity(p->feed != 0, p->radices, lv, leaves ? dtype : node_dtype(dtype)), &ct);
         if (rc != ADASUM_OK) return rc;
     }
     return ADASUM_OK;
@@ -1095,8 +1097,7 @@ int reduce_noalloc_impl(const void* const* grads, int K, const int64_t* layer_of
         if (K == 1) caps.push_back(combine_tile_capacity(dtype, 1));
         for (size_t lv = 0; lv < plan.radices.size(); ++lv) {
             const bool leaves = lv == 0 || o.order == ADASUM_ORDER_LINEAR;
-            caps.push_back(combine_tile_capacity(leaves ? dtype : node_type,
-                                                 table_radix(plan.feed != 0, plan.radices, lv)));
+            caps.push_back(table_capacity(plan.feed != 0, plan.radices, lv, leaves ? dtype : node_type));
         }
         off_offsets = carve.take(sizeof(int64_t) * (static_cast<size_t>(L) + 1));
         off_gram_tiles = carve.take(sizeof(adasum_tile) * static_cast<size_t>(n_gram));

@@ -783,6 +783,8 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, in
 // 16-byte load per lane and operand, then the workgroup ends.  Short-lived
 // workgroups that walk memory in launch order keep the mixed read/write stream
 // close to sequential, worth 10-20 % of bandwidth over long-lived workgroups.
+// Sixteen 16-bit operands (combine_pairs_operands): 32 granules per tile and two operands per
+// load instruction, so that the wave ends after 8 loads and one store.
 // normparts[group * n_tiles + tile].  weights == nullptr: unit weights.
 // ---------------------------------------------------------------------------
 // HEAD32: operand 0 is stored as fp32 while the others are 16-bit (left-to-right order).
@@ -799,6 +801,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     // Non-temporal stores pay off except where the output is half of the traffic
     // and every lane issues two of them (bf16 pair -> fp32): measured, 13.4 vs 16.4 ms.
     constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);
+    constexpr bool PAIR = combine_pairs_operands(sizeof(TI), R);
 
     const int tid = threadIdx.x;
     const unsigned v = blockIdx.x;
@@ -813,6 +816,95 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     const float* x0 = static_cast<const float*>(operand_ptr<R>(ops, g, 0));   // used with HEAD32 only
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
 
+    acc_t nacc = 0;
+    // fp64 weights as computed; the streaming body uses them rounded to fp32
+    // (fetched after the operand loads are in flight)
+    double wd[R];
+    acc_t w[R];
+    if constexpr (PAIR) {
+        // Two operands per load instruction: lanes 0-31 hold the tile's granules of the operands of one
+        // parity, lanes 32-63 of the other.  Each half sums what it holds, the halves exchange the four
+        // columns the other one stores, and half h stores columns 4 h .. 4 h + 3 of its granule.
+        constexpr int H = G / 2;
+        constexpr int R0 = HEAD32 ? 1 : 0;            // operands from R0 on are paired
+        constexpr int NL = (R - R0 + 1) / 2;          // loads per lane
+        const int half = tid >> 5, c = tid & 31;
+        const bool upper = half != 0;
+        const bool active = c < s.ng;
+        const long long idx = s.bs + static_cast<long long>(c) * G;
+        Granule<TI, G> raw[NL];
+        Granule<float, H> head;
+        if (active) {
+            if constexpr (HEAD32) load_raw(head, x0 + idx + H * half);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                // (an odd count leaves the last operand to the lower half; the upper half's copy is not used)
+                const int r = R0 + 2 * i, r1 = r + 1 < R ? r + 1 : r;
+                load_raw(raw[i], (upper ? x[r1] : x[r]) + idx);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            wd[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0;
+            w[r] = static_cast<acc_t>(wd[r]);
+        }
+        acc_t z[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) z[k] = 0;
+        if (active) {
+            acc_t sv[G];
+            if constexpr (SUB) {
+                Granule<TI, G> sraw;
+                load_raw(sraw, sub_in + idx);
+                unpack(sraw, sv);
+            }
+            if constexpr (HEAD32) {
+                acc_t hv[H];
+                unpack(head, hv);
+#pragma unroll
+                for (int k = 0; k < H; ++k) {
+                    const acc_t pz = w[0] * hv[k];
+                    z[k] = upper ? static_cast<acc_t>(0) : pz;
+                    z[H + k] = upper ? pz : static_cast<acc_t>(0);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int r = R0 + 2 * i, r1 = r + 1 < R ? r + 1 : r;
+                const bool both = r + 1 < R;
+                const acc_t ws = upper ? w[r1] : w[r];
+                acc_t v[G];
+                unpack(raw[i], v);
+                if (both || !upper) {
+#pragma unroll
+                    for (int k = 0; k < G; ++k) {
+                        const acc_t e = SUB ? v[k] - sv[k] : v[k];
+                        z[k] = (i == 0 && !HEAD32) ? ws * e : fma_t(ws, e, z[k]);
+                    }
+                }
+            }
+        }
+        acc_t mine[H];
+#pragma unroll
+        for (int k = 0; k < H; ++k) {
+            const acc_t send = upper ? z[k] : z[H + k];
+            const acc_t keep = upper ? z[H + k] : z[k];
+            mine[k] = keep + __shfl_xor(send, 32, 64);
+        }
+        if (active) {
+#pragma unroll
+            for (int k = 0; k < H; ++k) nacc = fma_t(mine[k], mine[k], nacc);
+            if (add_out != nullptr) {
+                Granule<TO, H> araw;
+                load_raw(araw, add_out + idx + H * half);
+                acc_t av[H];
+                unpack(araw, av);
+#pragma unroll
+                for (int k = 0; k < H; ++k) mine[k] += av[k];
+            }
+            store_granule<NTS>(out + idx + H * half, mine);
+        }
+    } else {
     const long long idx = s.bs + static_cast<long long>(tid) * G;
     Granule<TI, G> raw[R];
     Granule<float, G> head;
@@ -822,10 +914,6 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         for (int r = HEAD32 ? 1 : 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
     }
 
-    // fp64 weights as computed; the streaming body uses them rounded to fp32
-    // (fetched after the operand loads are in flight)
-    double wd[R];
-    acc_t w[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         wd[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0;
@@ -835,7 +923,6 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     // Section 4.1's delta form: with SUB the operands are x_r - sub_in (the parameters
     // before the local step); with add_out the stored result is add_out + z.  The
     // squared norm is that of z either way.
-    acc_t nacc = 0;
     if (tid < s.ng) {
         acc_t sv[G];
         if constexpr (SUB) {
@@ -869,6 +956,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
             for (int k = 0; k < G; ++k) z[k] += av[k];
         }
         store_granule<NTS>(out + idx, z);
+    }
     }
 
     // ragged head/tail elements: fp64 arithmetic, one rounding at the store
@@ -1026,7 +1114,7 @@ combine_siblings_kernel(const Operands ops, const Outputs outs, const adasum_til
 // ---------------------------------------------------------------------------
 // Step 3 of a pass that feeds the next one.  Workgroup (tile, s) has R2 waves; wave w combines
 // group s * R2 + w for the tile exactly as combine_kernel does (one 16-byte load per lane and
-// operand, fp64 edges), then the waves put what they wrote into LDS and wave w forms, for every
+// operand or pair of operands, fp64 edges), then the waves put what they wrote into LDS and wave w forms, for every
 // sibling b >= w, the dot product of its node with b's over the tile (b = w: the squared norm).
 // Those R2 (R2 + 1) / 2 sums are the tile's share of the next pass's Gram matrix, in the Gram
 // pass's entry order: nextparts[(s * n_tiles + tile) * NP2 + entry].  The next pass starts from
@@ -1042,6 +1130,7 @@ combine_feed_kernel(const Operands ops, const Outputs outs, const adasum_tile* _
     typedef typename Traits<TO>::acc_t out_acc_t;
     static_assert(std::is_same<acc_t, out_acc_t>::value, "the nodes of a pass that is not the last have the node type");
     constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);   // as combine_kernel
+    constexpr bool PAIR = combine_pairs_operands(sizeof(TI), R);
 
     const int lane = threadIdx.x & 63;
     // the wave's number, as a scalar: the group's operand pointers and weights then live in scalar
@@ -1059,43 +1148,83 @@ combine_feed_kernel(const Operands ops, const Outputs outs, const adasum_tile* _
     for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
 
-    const long long idx = s.bs + static_cast<long long>(lane) * G;
-    Granule<TI, G> raw[R];
-    if (lane < s.ng) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
-    }
+    // what a lane keeps of the node it wrote: its granule, or with paired operands (as in combine_kernel)
+    // the half of it that the lane stored
+    constexpr int NK = PAIR ? G / 2 : G;
+    __shared__ acc_t sh[R2][NK][kFeedLanes];
+    __shared__ double sh_edge[R2][kFeedLanes];
     double wd[R];
     acc_t wt[R];
+    acc_t z[NK];
+    if constexpr (PAIR) {
+        constexpr int NL = R / 2;
+        const int half = lane >> 5, c = lane & 31;
+        const bool upper = half != 0;
+        const bool active = c < s.ng;
+        const long long idx = s.bs + static_cast<long long>(c) * G;
+        Granule<TI, G> raw[NL];
+        if (active) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        wd[r] = weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r];
-        wt[r] = static_cast<acc_t>(wd[r]);
-    }
-
-    __shared__ acc_t sh[R2][G][kFeedLanes];
-    __shared__ double sh_edge[R2][kFeedLanes];
-    acc_t z[G];
-#pragma unroll
-    for (int k = 0; k < G; ++k) z[k] = 0;
-    if (lane < s.ng) {
-        {
-            acc_t a[G];
-            unpack(raw[0], a);
-#pragma unroll
-            for (int k = 0; k < G; ++k) z[k] = wt[0] * a[k];
+            for (int i = 0; i < NL; ++i) load_raw(raw[i], (upper ? x[2 * i + 1] : x[2 * i]) + idx);
         }
 #pragma unroll
-        for (int r = 1; r < R; ++r) {
-            acc_t a[G];
-            unpack(raw[r], a);
-#pragma unroll
-            for (int k = 0; k < G; ++k) z[k] = fma_t(wt[r], a[k], z[k]);
+        for (int r = 0; r < R; ++r) {
+            wd[r] = weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r];
+            wt[r] = static_cast<acc_t>(wd[r]);
         }
-        store_granule<NTS>(out + idx, z);
+        acc_t part[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) part[k] = 0;
+        if (active) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const acc_t ws = upper ? wt[2 * i + 1] : wt[2 * i];
+                acc_t a[G];
+                unpack(raw[i], a);
+#pragma unroll
+                for (int k = 0; k < G; ++k) part[k] = i == 0 ? ws * a[k] : fma_t(ws, a[k], part[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NK; ++k) {
+            const acc_t send = upper ? part[k] : part[NK + k];
+            const acc_t keep = upper ? part[NK + k] : part[k];
+            z[k] = keep + __shfl_xor(send, 32, 64);
+        }
+        if (active) store_granule<NTS>(out + idx + NK * half, z);
+    } else {
+        const long long idx = s.bs + static_cast<long long>(lane) * G;
+        Granule<TI, G> raw[R];
+        if (lane < s.ng) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            wd[r] = weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r];
+            wt[r] = static_cast<acc_t>(wd[r]);
+        }
+#pragma unroll
+        for (int k = 0; k < G; ++k) z[k] = 0;
+        if (lane < s.ng) {
+            {
+                acc_t a[G];
+                unpack(raw[0], a);
+#pragma unroll
+                for (int k = 0; k < G; ++k) z[k] = wt[0] * a[k];
+            }
+#pragma unroll
+            for (int r = 1; r < R; ++r) {
+                acc_t a[G];
+                unpack(raw[r], a);
+#pragma unroll
+                for (int k = 0; k < G; ++k) z[k] = fma_t(wt[r], a[k], z[k]);
+            }
+            store_granule<NTS>(out + idx, z);
+        }
     }
 #pragma unroll
-    for (int k = 0; k < G; ++k) sh[w][k][lane] = z[k];
+    for (int k = 0; k < NK; ++k) sh[w][k][lane] = z[k];
 
     // ragged head/tail elements: fp64 arithmetic, one rounding at the store; the stored value goes
     // into the sums
@@ -1120,7 +1249,7 @@ combine_feed_kernel(const Operands ops, const Outputs outs, const adasum_tile* _
     for (int b = w; b < R2; ++b) {
         acc_t acc = 0;
 #pragma unroll
-        for (int k = 0; k < G; ++k) acc = fma_t(z[k], sh[b][k][lane], acc);
+        for (int k = 0; k < NK; ++k) acc = fma_t(z[k], sh[b][k][lane], acc);
         double tot = static_cast<double>(wave_sum(acc));
         if (nedge > 0) tot += wave_sum(ze * sh_edge[b][lane]);
         if (lane == 0) dst[b - w] = tot;
@@ -2019,7 +2148,7 @@ int launch_combine_feed(int dtype, int out_dtype, const Operands& ops, const Out
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ct.n_tiles == 0 || n_groups == 0) return 0;
     if (R2 < 2 || n_groups % R2 != 0 || n_groups * R > kMaxPack || weights == nullptr || nextparts == nullptr ||
-        ct.capacity != feed_tile_capacity(dtype))
+        ct.capacity != feed_tile_capacity(dtype, R))
         return static_cast<int>(hipErrorInvalidValue);
     // the nodes such a pass writes are never the root: always the node type of the input
     if (dtype == ADASUM_F64 && out_dtype == ADASUM_F64)
@@ -2078,6 +2207,7 @@ int launch_combine_head32(int dtype, int out_dtype, const Operands& ops, const O
                           int n_layers, int R, const double* weights, double* normparts, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ct.n_tiles == 0) return 0;
+    if (ct.capacity != combine_tile_capacity(dtype, R)) return static_cast<int>(hipErrorInvalidValue);
     if (dtype == ADASUM_BF16 && out_dtype == ADASUM_BF16)
         return launch_combine_head32_r<bf16_t, bf16_t>(ops, out, ct, n_layers, R, weights, normparts, st);
     if (dtype == ADASUM_BF16 && out_dtype == ADASUM_F32)
@@ -2191,6 +2321,8 @@ int launch_combine(int dtype, int out_dtype, const Operands& ops, const Outputs&
             return launch_combine_wide_t<f16_t, float>(ops, out, ct, n_layers, n_groups, R, weights, normparts, st);
         return static_cast<int>(hipErrorInvalidValue);
     }
+    // (a kernel of another tile capacity would skip part of every tile)
+    if (ct.capacity != combine_tile_capacity(dtype, R)) return static_cast<int>(hipErrorInvalidValue);
     // supported pairs: T -> fp32, fp32 -> T, T -> T; fp64 only with itself
     if (dtype == ADASUM_F64 || out_dtype == ADASUM_F64) {
         if (dtype != out_dtype) return static_cast<int>(hipErrorInvalidValue);

@@ -172,7 +172,7 @@ int64_t next_entries_bound(int K, const int64_t* layer_offsets, int n_layers, co
         if (!pass_feeds_next(radices, lv)) continue;
         const int R2 = radices[lv + 1];
         // the widest storage type a pass may read gives its finest table
-        const int64_t t = count_tiles(layer_offsets, n_layers, feed_tile_capacity(node_type));
+        const int64_t t = count_tiles(layer_offsets, n_layers, feed_tile_capacity(node_type, radices[lv]));
         need = std::max<int64_t>(need, static_cast<int64_t>(groups / R2) * t * gram_entries(R2, true));
     }
     return need;

@@ -109,7 +109,7 @@ static void check_schedule(int K, int radix, int order, const std::vector<int64_
             if (!pass_feeds_next(radices, lv)) continue;
             CHECK(radices[lv] * radices[lv + 1] <= kMaxPack && g % radices[lv + 1] == 0);
             const int in = lv == 0 ? dtype : node_type;
-            const int64_t ct = count_tiles(offs.data(), L, feed_tile_capacity(in));
+            const int64_t ct = count_tiles(offs.data(), L, feed_tile_capacity(in, radices[lv]));
             CHECK(static_cast<int64_t>(g / radices[lv + 1]) * ct * gram_entries(radices[lv + 1], true) <= de);
         }
     }
