@@ -777,6 +777,21 @@ weights_kernel(const double* __restrict__ gram, long long n_items, int order, in
     if (lane < R) weights[item * R + lane] = shW[lane];
 }
 
+// The R weights of a (group, layer) item, or ones without a table: one branch, so that the loads are
+// issued together.
+template <int R, typename A>
+__device__ __forceinline__ void load_weights(const double* __restrict__ wp, double (&wd)[R], A (&w)[R]) {
+    if (wp != nullptr) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) wd[r] = wp[r];
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) wd[r] = 1.0;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) w[r] = static_cast<A>(wd[r]);
+}
+
 // ---------------------------------------------------------------------------
 // Step 3: out = sum_r w_r x_r per element, squared norm of the result per tile.
 // One workgroup per combine tile: combine_threads(R) granules of 16 input bytes, i.e. one
@@ -803,18 +818,18 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
     constexpr bool NTS = !(sizeof(TI) == 2 && sizeof(TO) == 4 && R <= 2);
     constexpr bool PAIR = combine_pairs_operands(sizeof(TI), R);
 
+    // grid: (tile, group), tiles fastest -- a group's tiles are walked in memory order
     const int tid = threadIdx.x;
-    const unsigned v = blockIdx.x;
-    const int tile_id = static_cast<int>(v % static_cast<unsigned>(n_tiles));
-    const int g = static_cast<int>(v / static_cast<unsigned>(n_tiles));
-    const adasum_tile t = tiles[tile_id];
-    const Split s = split_tile<G>(t);
-
+    const int tile_id = static_cast<int>(blockIdx.x);
+    const int g = static_cast<int>(blockIdx.y);
     const TI* x[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
     const float* x0 = static_cast<const float*>(operand_ptr<R>(ops, g, 0));   // used with HEAD32 only
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
+    const double* wp = weights ? weights + (static_cast<long long>(g) * n_layers + t.layer) * R : nullptr;
 
     acc_t nacc = 0;
     // fp64 weights as computed; the streaming body uses them rounded to fp32
@@ -843,11 +858,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
                 load_raw(raw[i], (upper ? x[r1] : x[r]) + idx);
             }
         }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            wd[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0;
-            w[r] = static_cast<acc_t>(wd[r]);
-        }
+        load_weights<R>(wp, wd, w);
         acc_t z[G];
 #pragma unroll
         for (int k = 0; k < G; ++k) z[k] = 0;
@@ -914,11 +925,7 @@ combine_kernel(const Operands ops, const Outputs outs, const adasum_tile* __rest
         for (int r = HEAD32 ? 1 : 0; r < R; ++r) load_raw(raw[r], x[r] + idx);
     }
 
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        wd[r] = weights ? weights[(static_cast<long long>(g) * n_layers + t.layer) * R + r] : 1.0;
-        w[r] = static_cast<acc_t>(wd[r]);
-    }
+    load_weights<R>(wp, wd, w);
 
     // Section 4.1's delta form: with SUB the operands are x_r - sub_in (the parameters
     // before the local step); with add_out the stored result is add_out + z.  The
@@ -1136,16 +1143,15 @@ combine_feed_kernel(const Operands ops, const Outputs outs, const adasum_tile* _
     // the wave's number, as a scalar: the group's operand pointers and weights then live in scalar
     // registers, as in combine_kernel (60 vector registers fewer, one more wave per SIMD)
     const int w = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
-    const unsigned v = blockIdx.x;
-    const int tile_id = static_cast<int>(v % static_cast<unsigned>(n_tiles));
-    const int super = static_cast<int>(v / static_cast<unsigned>(n_tiles));
+    // grid: (tile, set of R2 sibling groups), tiles fastest
+    const int tile_id = static_cast<int>(blockIdx.x);
+    const int super = static_cast<int>(blockIdx.y);
     const int g = super * R2 + w;
-    const adasum_tile t = tiles[tile_id];
-    const Split s = split_tile<G>(t);
-
     const TI* x[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) x[r] = static_cast<const TI*>(operand_ptr<R>(ops, g, r));
+    const adasum_tile t = tiles[tile_id];
+    const Split s = split_tile<G>(t);
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
 
     // what a lane keeps of the node it wrote: its granule, or with paired operands (as in combine_kernel)
@@ -1573,8 +1579,8 @@ combine_wide_kernel(const Operands ops, const Outputs outs, const adasum_tile* _
     constexpr int G = 8, C = 16;
     typedef typename Traits<TO>::acc_t out_acc_t;
     const int lane = threadIdx.x;
-    const int tile_id = static_cast<int>(blockIdx.x % static_cast<unsigned>(n_tiles));
-    const int g = static_cast<int>(blockIdx.x / static_cast<unsigned>(n_tiles));
+    const int tile_id = static_cast<int>(blockIdx.x);   // grid: (tile, group)
+    const int g = static_cast<int>(blockIdx.y);
     const adasum_tile t = tiles[tile_id];
     const Split s = split_tile<G>(t);
     TO* out = reinterpret_cast<TO*>(outs.base + static_cast<long long>(g) * outs.stride * outs.slot_bytes);
@@ -1920,6 +1926,7 @@ small_table_kernel(const long long* __restrict__ offs, int n_layers, SmallLayer*
 inline int check_launch() { return static_cast<int>(hipGetLastError()); }
 
 inline bool grid_fits(long long blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
+constexpr int kMaxGridY = 65535;   // second grid dimension (groups)
 
 template <typename T, bool DIAG, bool DELTA>
 int launch_gram_r(const Operands& ops, const TileSet& gt, int n_groups, int R, double* partials, const void* start,
@@ -1970,9 +1977,8 @@ template <typename TI, typename TO>
 int launch_combine_r(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
                      int R, const double* weights, double* normparts, const void* sub_in, const void* add_out,
                      hipStream_t st) {
-    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups);
-    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
-    const dim3 grid(static_cast<unsigned>(blocks)), block(combine_threads(R));
+    if (!grid_fits(ct.n_tiles) || n_groups < 1 || n_groups > kMaxGridY) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(ct.n_tiles), static_cast<unsigned>(n_groups)), block(combine_threads(R));
     const int nt = static_cast<int>(ct.n_tiles);
 #define ADASUM_COMBINE_AS(RR, SUB)                                                                   \
     hipLaunchKernelGGL((combine_kernel<TI, TO, RR, SUB>), grid, block, 0, st, ops, outs, ct.tiles,  \
@@ -2069,9 +2075,8 @@ int launch_combine_siblings_t(const Operands& ops, const Outputs& outs, const Ti
 template <typename TI, typename TO, int R>
 int launch_combine_feed_r(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups,
                           int R2, const double* weights, double* nextparts, hipStream_t st) {
-    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups / R2);
-    if (!grid_fits(blocks)) return static_cast<int>(hipErrorInvalidConfiguration);
-    const dim3 grid(static_cast<unsigned>(blocks));
+    if (!grid_fits(ct.n_tiles) || n_groups / R2 > kMaxGridY) return static_cast<int>(hipErrorInvalidConfiguration);
+    const dim3 grid(static_cast<unsigned>(ct.n_tiles), static_cast<unsigned>(n_groups / R2));
     const int nt = static_cast<int>(ct.n_tiles);
 #define ADASUM_FEED(RR2)                                                                                   \
     hipLaunchKernelGGL((combine_feed_kernel<TI, TO, R, RR2>), grid, dim3(kFeedLanes * RR2), 0, st, ops, outs, \
@@ -2125,10 +2130,9 @@ int launch_gram_wide_t(const Operands& ops, const TileSet& spans, int n_groups, 
 template <typename TI, typename TO>
 int launch_combine_wide_t(const Operands& ops, const Outputs& outs, const TileSet& ct, int n_layers, int n_groups, int R,
                           const double* weights, double* normparts, hipStream_t st) {
-    const long long blocks = ct.n_tiles * static_cast<long long>(n_groups);
-    if (!grid_fits(blocks) || n_groups * R > kMaxPack) return static_cast<int>(hipErrorInvalidConfiguration);
+    if (!grid_fits(ct.n_tiles) || n_groups < 1 || n_groups * R > kMaxPack) return static_cast<int>(hipErrorInvalidConfiguration);
     if (weights == nullptr || ct.capacity != combine_tile_capacity(ADASUM_BF16, R)) return static_cast<int>(hipErrorInvalidValue);
-    const dim3 grid(static_cast<unsigned>(blocks)), block(64);
+    const dim3 grid(static_cast<unsigned>(ct.n_tiles), static_cast<unsigned>(n_groups)), block(64);
     const int nt = static_cast<int>(ct.n_tiles);
     if (R == 64)
         hipLaunchKernelGGL((combine_wide_kernel<TI, TO, 64>), grid, block, 0, st, ops, outs, ct.tiles, nt, n_layers, weights,
