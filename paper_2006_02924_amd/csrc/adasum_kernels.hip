@@ -1262,8 +1262,10 @@ combine_feed_kernel(const Operands ops, const Outputs outs, const adasum_tile* _
     }
 }
 
-// rows of NP Gram entries per combine tile -> per Gram tile.  One wave per (row set, Gram tile); lane e
-// (and e + 64, ...) sums entry e over the combine tiles of the Gram tile in table order.
+// rows of NP Gram entries per combine tile -> per Gram tile.  One wave per (row set, Gram tile).  The wave
+// holds S = 64 / NP slices of NP lanes (one slice and a loop over the entries when NP > 32): slice s sums
+// entry q over every S-th combine tile of the Gram tile, starting at the s-th, then the slices are added
+// up in order.  Consecutive lanes read consecutive doubles; the order is fixed.
 __global__ void __launch_bounds__(64)
 parts_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles, const int32_t* __restrict__ first_in_gram,
                      int n_gram_tiles, int NP, double* __restrict__ coarse) {
@@ -1272,17 +1274,36 @@ parts_coarsen_kernel(const double* __restrict__ fine, int n_fine_tiles, const in
     const int b = first_in_gram[t], e = first_in_gram[t + 1];
     const double* src = fine + static_cast<long long>(row) * n_fine_tiles * NP;
     double* dst = coarse + (static_cast<long long>(row) * n_gram_tiles + t) * NP;
-    for (int q = threadIdx.x; q < NP; q += 64) {
+    const int lane = threadIdx.x;
+    const int S = NP <= 32 ? 64 / NP : 1;
+    __shared__ double sh[64];
+    const int slice = lane / NP;                       // (>= S: a lane with nothing to do when S > 1)
+    for (int q0 = 0; q0 < NP; q0 += 64) {              // one round unless NP > 64
+        const int q = S > 1 ? lane - slice * NP : q0 + lane;
+        const bool active = S > 1 ? slice < S : q < NP;
         double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;   // four chains so that loads overlap; fixed order
-        int i = b;
-        for (; i + 4 <= e; i += 4) {
-            v0 += src[static_cast<long long>(i) * NP + q];
-            v1 += src[static_cast<long long>(i + 1) * NP + q];
-            v2 += src[static_cast<long long>(i + 2) * NP + q];
-            v3 += src[static_cast<long long>(i + 3) * NP + q];
+        if (active) {
+            int i = b + (S > 1 ? slice : 0);
+            for (; i + 3 * S < e; i += 4 * S) {
+                v0 += src[static_cast<long long>(i) * NP + q];
+                v1 += src[static_cast<long long>(i + S) * NP + q];
+                v2 += src[static_cast<long long>(i + 2 * S) * NP + q];
+                v3 += src[static_cast<long long>(i + 3 * S) * NP + q];
+            }
+            for (; i < e; i += S) v0 += src[static_cast<long long>(i) * NP + q];
         }
-        for (; i < e; ++i) v0 += src[static_cast<long long>(i) * NP + q];
-        dst[q] = (v0 + v1) + (v2 + v3);
+        const double mine = (v0 + v1) + (v2 + v3);
+        if (S > 1) {
+            sh[lane] = mine;
+            __syncthreads();
+            if (lane < NP) {
+                double tot = sh[lane];
+                for (int k = 1; k < S; ++k) tot += sh[k * NP + lane];
+                dst[lane] = tot;
+            }
+        } else if (active) {
+            dst[q] = mine;
+        }
     }
 }
 
