@@ -530,7 +530,6 @@ int run_tree(Plan* p, char* ws, const void* const* grads, int dtype, void* out, 
     const int L = lay.n_layers;
     const int64_t N = lay.N;
     const TileSet gt = p->gram_tiles.view();
-    const int64_t T = gt.n_tiles;
     char* slots = ws + lay.off_slots;
     double* partials = reinterpret_cast<double*>(ws + lay.off_partials);
     double* normparts = reinterpret_cast<double*>(ws + lay.off_normparts);

@@ -4,12 +4,15 @@
 // and end, direct indexing (no tile table, no weights table, constant weights), buffers of the
 // headline workload's size.  A third variant writes a narrow stream instead (16 bytes per lane,
 // as a bf16 result would be): it shows that what a written stream costs does not depend on how
-// much is written.  A measuring tool for the roofline discussion: not part of
-// libadasum, shares no code with it.
+// much is written.  A fourth takes two streams per load instruction (lanes 0-31 one stream, lanes
+// 32-63 the next: 512 bytes of each), lets the halves exchange their sums and writes the fp32
+// stream with one 16-byte store per lane: the pattern of the library's 16-operand combine of
+// 16-bit inputs.  A measuring tool for the roofline discussion: not part of libadasum, shares no
+// code with it.
 //
 //   pattern_ceiling [elements per stream, default 335141888] [repetitions, default 5]
 //
-// Prints one line per variant: streams, lanes per workgroup, write or not, ms, GB/s moved.
+// Prints one line per variant: streams, lanes per workgroup, what is written, ms, GB/s moved.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -71,6 +74,67 @@ __global__ void __launch_bounds__(LANES) step_kernel(const Streams in, u4* __res
     }
 }
 
+// Two streams per load instruction: a one-wave workgroup covers 32 granules of R streams with R / 2 loads per lane.
+template <int R>
+__global__ void __launch_bounds__(64) pair_kernel(const Streams in, u4* __restrict__ out, size_t granules) {
+    const int lane = threadIdx.x, half = lane >> 5, c = lane & 31;
+    const size_t i = static_cast<size_t>(blockIdx.x) * 32 + c;
+    const bool active = i < granules;
+    float z[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) z[k] = 0.f;
+    if (active) {
+        u4 v[R / 2];
+#pragma unroll
+        for (int j = 0; j < R / 2; ++j) v[j] = __builtin_nontemporal_load((half ? in.p[2 * j + 1] : in.p[2 * j]) + i);
+#pragma unroll
+        for (int j = 0; j < R / 2; ++j) {
+            const unsigned w[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+            const float cf = 0.25f + 0.01f * (2 * j + half);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                z[2 * k] = __builtin_fmaf(cf, __uint_as_float(w[k] << 16), z[2 * k]);
+                z[2 * k + 1] = __builtin_fmaf(cf, __uint_as_float(w[k] & 0xffff0000u), z[2 * k + 1]);
+            }
+        }
+    }
+    // half h keeps columns 4 h .. 4 h + 3 of its granule and gets the other half's sums for them
+    u4 a;
+    unsigned m[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float send = half ? z[k] : z[4 + k];
+        const float keep = half ? z[4 + k] : z[k];
+        m[k] = __float_as_uint(keep + __shfl_xor(send, 32, 64));
+    }
+    a.x = m[0]; a.y = m[1]; a.z = m[2]; a.w = m[3];
+    if (active) __builtin_nontemporal_store(a, out + 2 * i + half);
+}
+
+template <int R>
+void run_pairs(const Streams& in, u4* out, size_t granules, int reps) {
+    hipEvent_t a, b;
+    CK(hipEventCreate(&a));
+    CK(hipEventCreate(&b));
+    const unsigned blocks = static_cast<unsigned>((granules + 31) / 32);
+    for (int w = 0; w < 2; ++w) hipLaunchKernelGGL((pair_kernel<R>), dim3(blocks), dim3(64), 0, 0, in, out, granules);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(a));
+    for (int w = 0; w < reps; ++w) hipLaunchKernelGGL((pair_kernel<R>), dim3(blocks), dim3(64), 0, 0, in, out, granules);
+    CK(hipEventRecord(b));
+    CK(hipEventSynchronize(b));
+    CK(hipGetLastError());
+    float ms = 0.f;
+    CK(hipEventElapsedTime(&ms, a, b));
+    ms /= reps;
+    const double bytes = static_cast<double>(granules) * 16 * R + static_cast<double>(granules) * 32;
+    std::printf("streams %2d  lanes %3d  %-18s %8.3f ms  %6.0f GB/s  %5.1f %% of 8 TB/s\n", R, 64, "pairs + fp32 written", ms,
+                bytes / ms / 1e6, bytes / ms / 1e6 / 80.0);
+    std::fflush(stdout);
+    CK(hipEventDestroy(a));
+    CK(hipEventDestroy(b));
+}
+
 template <int R, int LANES, int WRITE>
 void run(const Streams& in, u4* out, float* sink, size_t granules, int reps) {
     hipEvent_t a, b;
@@ -105,6 +169,7 @@ void run_all(const Streams& in, u4* out, float* sink, size_t granules, int reps)
     run<R, 64, 1>(in, out, sink, granules, reps);
     run<R, 256, 1>(in, out, sink, granules, reps);
     run<R, 64, 2>(in, out, sink, granules, reps);
+    run_pairs<R>(in, out, granules, reps);
 }
 
 int main(int argc, char** argv) {
