@@ -488,7 +488,7 @@ def _check_after_optimizer(out, start, currents, offs, what):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
-@pytest.mark.parametrize("K,radix", _k_radix([1, 2, 8, 64], [0, 2, 4, 16], 0))
+@pytest.mark.parametrize("K,radix", _k_radix([1, 2, 8, 16, 64], [0, 2, 4, 16], 0))
 def test_after_optimizer_delta_form(K, dtype, radix):
     say(f"delta form K={K} {dtype} radix={radix}")
     sizes = np.diff(RAGGED).tolist()
