@@ -239,7 +239,7 @@ ADASUM_API int adasum_plan_destroy(adasum_plan* plan);
  *   opts   as for adasum_reduce_ex, except workspace must be NULL and use_graph 0
  *          (ADASUM_ERR_INVALID_ARG otherwise); NULL = all defaults
  * Limit: tables + workspace of the problem (about adasum_workspace_bytes() plus 16 bytes per
- * 512 elements) must fit the array, else ADASUM_ERR_TOO_LARGE and nothing is enqueued.  That
+ * 256 to 512 elements) must fit the array, else ADASUM_ERR_TOO_LARGE and nothing is enqueued.  That
  * holds for e.g. ResNet-50 (25.6 M elements) at K <= 16, or 3 M elements at K = 64 -- and, since a
  * single pass keeps no intermediate nodes, for BERT-Large (335 M elements) at K <= 64 with radix 64.
  * Every call on one GPU uses the same array and finds the previous call's contents there:
