@@ -13,10 +13,12 @@
 // uses the matrix cores.  Every workgroup owns one
 // tile (consecutive elements inside one layer): a long one (kTile elements) in
 // the read-only Gram pass, where a workgroup's start-up and its reduction must
-// be amortised, and a short one (one 16-byte load per lane and operand) in the
-// combine pass, where short-lived workgroups keep the mixed read/write stream
-// near sequential.  64-wide waves issue 16-byte non-temporal loads that cover
-// 1 KiB of one operand per instruction; partial sums go lane (fp32; fp64 for
+// be amortised, and a short one (one 16-byte load per lane and operand, or per
+// pair of operands) in the combine pass, where short-lived workgroups keep the
+// mixed read/write stream near sequential.  64-wide waves issue 16-byte
+// non-temporal loads that cover 1 KiB of one operand per instruction (the
+// 16-operand combine of 16-bit inputs: 512 bytes of each of two operands);
+// partial sums go lane (fp32; fp64 for
 // fp64 storage) -> wave (shuffles) -> workgroup (fp64 via LDS) -> per-tile fp64
 // partial in memory, summed later in a fixed order; no atomics anywhere.
 #include <hip/hip_runtime.h>
