@@ -178,7 +178,20 @@ int main(int argc, char** argv) {
     std::mt19937_64 rng(20060292);
     const int radix_choices[] = {0, 2, 4, 8, 16, 32, 64};
     const int dtypes[] = {ADASUM_F32, ADASUM_BF16, ADASUM_F16, ADASUM_F64};
-    const int64_t caps[] = {1, 7, 64, 512, 2048, kTileSmall, kTile};
+    const int64_t caps[] = {1, 7, 64, 256, 512, 2048, kTileSmall, kTile};
+    // tile capacities the combine kernels are written for: lanes (or half-waves) x one 16-byte granule
+    CHECK(combine_tile_capacity(ADASUM_BF16, 16) == 256 && combine_tile_capacity(ADASUM_F16, 16) == 256);
+    CHECK(combine_tile_capacity(ADASUM_F32, 16) == 256 && combine_tile_capacity(ADASUM_BF16, 8) == 1024);
+    CHECK(combine_tile_capacity(ADASUM_BF16, 64) == 512 && combine_tile_capacity(ADASUM_BF16, 32) == 512);
+    CHECK(combine_tile_capacity(ADASUM_F64, 8) == 256 && combine_tile_capacity(ADASUM_F32, 2) == 1024);
+    CHECK(feed_tile_capacity(ADASUM_BF16, 16) == 256 && feed_tile_capacity(ADASUM_BF16, 8) == 512);
+    CHECK(feed_tile_capacity(ADASUM_F32, 16) == 256 && feed_tile_capacity(ADASUM_F64, 8) == 128);
+    for (int dt : dtypes)
+        for (int R : {2, 4, 8, 16}) {
+            // the planner sizes its sections for the node type's tables: never coarser than the input type's
+            CHECK(combine_tile_capacity(node_dtype(dt), R) <= combine_tile_capacity(dt, R));
+            CHECK(feed_tile_capacity(node_dtype(dt), R) <= feed_tile_capacity(dt, R));
+        }
     for (int it = 0; it < rounds; ++it) {
         const int kind = static_cast<int>(rng() % 4);
         const int n_layers = kind == 3 ? static_cast<int>(rng() % 6) : static_cast<int>(rng() % 2000);
