@@ -177,6 +177,34 @@ def test_ragged_tables(K, dtype, out_dtype, radix):
         assert_bf16_rounding(out, ref, w.layer_offsets)
 
 
+# Layer sizes around the 256-element tiles of the 16-operand combine of 16-bit inputs (two operands per load
+# instruction): tiles of 1 .. 32 granules, ragged heads and tails of 1 .. 7 elements on either side of a tile
+# boundary, and layers that start at odd global offsets.
+PAIR_EDGES = [255, 256, 257, 1, 7, 8, 9, 15, 16, 17, 511, 512, 513, 31, 33, 248, 264, 3, 1024, 2, 777, 4096 + 5]
+
+
+@pytest.mark.parametrize("order", ["tree", "linear"])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("K", [16, 21, 64])
+def test_tile_edges_of_the_paired_combine(K, dtype, order):
+    say(f"pair edges K={K} {dtype} {order}")
+    w = W.correlated_gaussian(PAIR_EDGES, K, dtype=dtype, device=DEV, seed=900 + K)
+    ref = oracle_reduce(w.grads, w.layer_offsets, order=order)
+    kw = dict(order=B.ORDER_LINEAR) if order == "linear" else {}
+    out = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=torch.float32, radix=16, **kw)
+    torch.cuda.synchronize()
+    assert_parity(out, ref, w.layer_offsets, what=f"pair edges K={K} {order}")
+    if order == "tree" and K == 64:
+        # every pass on its own: the plain 16-operand combine instead of the one that feeds the next pass
+        sep = B.adasum_reduce(w.grads, w.layer_offsets, out_dtype=torch.float32, radix=16, separate_passes=True)
+        torch.cuda.synchronize()
+        assert_parity(sep, ref, w.layer_offsets, what=f"pair edges K={K} separate passes")
+    # the result in the input's own type: one rounding of the same values
+    low = B.adasum_reduce(w.grads, w.layer_offsets, radix=16, **kw)
+    torch.cuda.synchronize()
+    assert_parity(low, ref, w.layer_offsets, what=f"pair edges K={K} {order} -> {dtype}")
+
+
 def test_empty_and_degenerate_tables():
     say("empty tables")
     for offs in ([0], [0, 0], [0, 0, 0, 5, 5], [0, 1], [0, 7, 7, 8]):
