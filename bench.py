@@ -244,7 +244,8 @@ def kernel_summary(prof, steps, ms_per_step, workload, verbose_tag=None):
             "schedule_bytes": total_bytes}
 
 
-def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False, separate=False, order="tree"):
+def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False, separate=False, order="tree",
+              delta=False):
     """One more configuration, default options: the step time from an event-free loop, the kernel
     breakdown from a second, event-bracketed loop of the same steps."""
     import torch
@@ -256,17 +257,21 @@ def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False, separ
         torch.cuda.synchronize()
     gen_s = time.perf_counter() - t0
     out = torch.empty(w.N, dtype=w.dtype, device=dev)
-    kw = dict(out_dtype=w.dtype, radix=radix, order=order, graph=False, start=None, fuse=fuse, separate=separate)
+    # the Adasum-after-optimizer form (Section 4.1): the buffers stand for parameters after a local step
+    start = (torch.randn(w.N, device=dev, dtype=torch.float32) * 0.02).to(w.dtype) if delta else None
+    kw = dict(out_dtype=w.dtype, radix=radix, order=order, graph=False, start=start, fuse=fuse, separate=separate)
     dt, _ = timed_steps(B, w, out, steps=steps, warmup=warmup, profile=False, **kw)
     ms = dt / steps * 1e3
     dtp, prof = timed_steps(B, w, out, steps=steps, warmup=0, profile=True, **kw)
     tag = f"{name}{' radix ' + str(radix) if radix else ''}{' sibling-fused' if fuse else ''}" \
-          f"{' separate passes' if separate else ''}{' left-to-right order' if order == 'linear' else ''}"
+          f"{' separate passes' if separate else ''}{' left-to-right order' if order == 'linear' else ''}" \
+          f"{' after-optimizer form' if delta else ''}"
     roof = kernel_summary(prof, steps, dtp / steps * 1e3, name, verbose_tag=tag + ": ")
     es = w.grads[0].element_size()
     row = {"workload": f"{name}: K={w.K}, {w.n_layers} tensors, N={w.N}, stored and output "
                        f"{str(w.dtype).replace('torch.', '')}",
-           "passes": B.plan_levels(w.K, radix) if order == "tree" else None, "steps": steps, "warmup": warmup,
+           "passes": B.plan_levels(w.K, radix if (radix or not delta) else 8) if order == "tree" else None,
+           "steps": steps, "warmup": warmup,
            "ms_per_step": ms, "input_GBps": w.input_bytes / (ms * 1e-3) / 1e9, "input_GB": w.input_bytes / 1e9,
            "generated_in_s": gen_s}
     if roof is not None:
@@ -277,11 +282,11 @@ def run_other(B, name, *, radix=0, steps=10, warmup=2, w=None, fuse=False, separ
                     "dominant_kernel_GBps": roof["achieved"], "dominant_kernel_frac": roof["frac"],
                     "ms_per_step_with_events": dtp / steps * 1e3})
         t = measured_traffic((name if not radix else f"{name}_radix{radix}") + ("_fused" if fuse else "")
-                             + ("_separate" if separate else ""), roof["kernel"]) if order == "tree" else None
+                             + ("_separate" if separate else ""), roof["kernel"]) if (order == "tree" and not delta) else None
         row["dominant_kernel_traffic"] = t["bytes"] if t else None
-    if w.K & (w.K - 1) == 0 and w.K > 1 and order == "tree":
+    if w.K & (w.K - 1) == 0 and w.K > 1 and order == "tree" and not delta:
         row["pair_per_level_bytes"] = pair_per_level_bytes(w.K, w.N, es, es)
-    del out
+    del out, start
     if own:
         del w
     B.shutdown()
@@ -420,10 +425,11 @@ def main():
         # (the headline workload is dropped before the first of them is generated)
         # (name, radix, steps, warm-up, fuse_siblings, separate_passes); the first five reuse the headline
         # buffers (radix 64 and 32: the opt-in wide first pass, whose Gram matrix comes from the matrix cores)
-        # (the sixth: the left-to-right order of Section 3.4 on the headline buffers)
+        # (the sixth and seventh: the left-to-right order of Section 3.4 and the after-optimizer form of
+        # Section 4.1 on the headline buffers)
         todo = [("config4", 64, 20, 5, False, False), ("config4", 32, 20, 5, False, False),
                 ("config4", 0, 20, 5, False, True), ("config4", 2, 10, 2, False, True), ("config4", 2, 10, 2, True, False),
-                ("config4", 0, 10, 2, False, False, "linear"),
+                ("config4", 0, 10, 2, False, False, "linear"), ("config4", 0, 10, 2, False, False, "tree", True),
                 ("config1", 0, 200, 20, False, False), ("config2", 0, 50, 5, False, False),
                 ("config3", 0, 20, 3, False, False), ("config5", 0, 10, 2, False, False),
                 ("config5", 64, 10, 2, False, False)]
@@ -431,6 +437,7 @@ def main():
         for item in todo:
             name, radix, steps, warmup, fuse, separate = item[:6]
             order = item[6] if len(item) > 6 else "tree"
+            delta = item[7] if len(item) > 7 else False
             reuse = w if name == "config4" else w5 if (name == "config5" and radix) else None
             if name != "config4" and w is not None:
                 w = None
@@ -442,20 +449,22 @@ def main():
             try:
                 t0 = time.perf_counter()
                 row = run_other(B, name, radix=radix, steps=steps, warmup=warmup, w=reuse, fuse=fuse, separate=separate,
-                                order=order)
+                                order=order, delta=delta)
                 print(f"[bench] {name}{f' radix {radix}' if radix else ''}{' sibling-fused' if fuse else ''}"
-                      f"{' separate passes' if separate else ''}{' left-to-right order' if order == 'linear' else ''}: "
+                      f"{' separate passes' if separate else ''}{' left-to-right order' if order == 'linear' else ''}"
+                      f"{' after-optimizer form' if delta else ''}: "
                       f"{row['ms_per_step']:.4f} ms/step, "
                       f"{row['input_GBps']:.0f} GB/s of input ({time.perf_counter() - t0:.1f} s in all)",
                       file=sys.stderr, flush=True)
             except Exception as exc:  # keep the headline line whatever happens here
                 row = {"workload": name, "error": f"{type(exc).__name__}: {exc}"}
             del reuse
-            if radix or separate or order != "tree":
+            if radix or separate or order != "tree" or delta:
                 row["radix"] = radix
                 row["fuse_siblings"] = fuse
                 row["separate_passes"] = separate
                 row["order"] = order
+                row["delta_form"] = delta
             others.append(row)
         line["other_configs"] = others
     print(json.dumps(line), flush=True)
